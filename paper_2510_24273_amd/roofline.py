@@ -1,0 +1,52 @@
+"""Algorithmic byte / flop accounting of one SALS layer-step (host arithmetic only).
+
+The paper's traffic model (Sec. 4.5) counts s*r_score + 2*k*r cache elements per
+sequence.  The figures used for the roofline add what that model leaves out and
+the path still has to move: the two projectors (read once per layer-step for the
+whole batch) and the fp32 score vector (written once, read once).
+"""
+from __future__ import annotations
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+VALU_F32_PEAK_TFLOPS = 157.3
+
+
+def paper_traffic_elements(s: int, r: int, r_score: int, k: int) -> int:
+    """Sec. 4.5: cache elements SALS moves per sequence, s*r* + 2*k*r."""
+    return s * r_score + 2 * k * r
+
+
+def stage_bytes(w, seq_len=None) -> dict:
+    """Algorithmic HBM bytes per layer-step of workload w, by stage."""
+    e = w.esize
+    S = w.S if seq_len is None else seq_len
+    n_sel = min(S, w.k_tot)
+    small = w.B * (w.H * w.d * e * 2 + w.r * 4 + n_sel * 4)   # q, out, q~, idx
+    return {
+        "project": w.r * w.D_kv * e,                      # U_k, once per batch
+        "scores": w.B * (S * w.rs * e + 4 * S),          # K~ stream + score write
+        "select": w.B * 4 * S,                            # score read
+        "attend_k": w.B * n_sel * w.r * e + w.r * w.D_kv * e,   # gathered K~ rows + U_k
+        "attend_v": w.B * n_sel * w.r * e + w.r * w.D_kv * e,   # gathered V~ rows + U_v
+        "small": small,
+    }
+
+
+def algorithmic_bytes(w, seq_len=None) -> int:
+    """Pipeline bytes: U_k is counted once (projection and reconstruction share it)."""
+    b = stage_bytes(w, seq_len)
+    return b["scores"] + b["select"] + b["attend_k"] + b["attend_v"] + b["small"]
+
+
+def stage_flops(w, seq_len=None) -> dict:
+    S = w.S if seq_len is None else seq_len
+    n_sel = min(S, w.k_tot)
+    return {
+        "project": 2 * w.B * w.r * w.D_kv,
+        "scores": 2 * w.B * S * w.rs,
+        "reconstruct_k": 2 * w.B * n_sel * w.r * w.D_kv,
+        "reconstruct_v_literal": 2 * w.B * n_sel * w.r * w.D_kv,
+        "value_reassociated": 2 * w.B * w.H * (n_sel * w.r + w.r * w.d),
+        "attention": 4 * w.B * n_sel * w.H * w.d,
+    }

@@ -1,0 +1,192 @@
+"""Seeded synthetic decode workloads shaped like the paper's models.
+
+This module only *makes inputs*: projectors, latent caches and queries with
+the shapes of LLaMA2-7B, Mistral-7B and LLaMA3.1-8B decode (Sec. 5.1 of arXiv
+2510.24273), which stand in for the paper's real activations.  It holds none
+of the operator's arithmetic that is under test and produces no expected
+values; both the HIP path and the CPU oracle are fed from here.  The only
+linear algebra it does is to orient a few planted cache rows along the latent
+image of the query, so that the selection stage has known winners.
+
+Storage rounding happens here, so both sides see bit-identical inputs: every
+array is returned in its storage form (float32, or bf16 as uint16 bit
+patterns) and ``widen`` turns either into the float64 the oracle reads.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    cfg_id: int
+    B: int
+    S: int
+    H: int
+    H_kv: int
+    d: int
+    r: int
+    top_k: int
+    dtype: str = "bf16"          # storage type: "bf16" | "f32"
+    r_score: int | None = None   # None -> r
+    n_sink: int = 0
+    n_recent: int = 0
+    theta: float = 10000.0
+    rope_style: int = 0
+    n_layers: int = 1
+    plant: int = 0               # planted high-score tokens per query
+    corr_frac: float = 0.0       # fraction of rows correlated with the query
+    corr_rho: float = 0.3
+    scale: float = 1.0           # extra cache scale (stress cases only)
+
+    @property
+    def D_kv(self):
+        return self.H_kv * self.d
+
+    @property
+    def k_tot(self):
+        return self.top_k + self.n_sink + self.n_recent
+
+    @property
+    def rs(self):
+        return self.r if self.r_score is None else self.r_score
+
+    @property
+    def esize(self):
+        return 2 if self.dtype == "bf16" else 4
+
+
+# The five configurations the build is measured on.
+CONFIGS = {
+    "cfg1": Workload("cfg1_tiny_f32_B1_S1024_r512_k128", 1, 1, 1024, 32, 32, 128, 512, 128,
+                     dtype="f32"),
+    "cfg2": Workload("cfg2_llama2_7b_B1_S4096_r640_k512", 2, 1, 4096, 32, 32, 128, 640, 512,
+                     n_layers=32, plant=3),
+    "cfg3a": Workload("cfg3a_llama2_7b_B16_S4096_r640_k512", 3, 16, 4096, 32, 32, 128, 640,
+                      512, plant=3),
+    "cfg3b": Workload("cfg3b_mistral_7b_gqa8_B16_S4096_r640_k512", 3, 16, 4096, 32, 8, 128,
+                      640, 512, plant=3),
+    "cfg4": Workload("cfg4_long_B4_S32768_r640_k2048", 4, 4, 32768, 32, 32, 128, 640, 2048,
+                     corr_frac=0.01),
+    "cfg5": Workload("cfg5_llama31_8b_gqa8_B1_S131072_r512_k4096_w64", 5, 1, 131072, 32, 8,
+                     128, 512, 4096, n_recent=64, theta=500000.0),
+}
+
+
+def shrink(w: Workload, **kw) -> Workload:
+    return replace(w, **kw)
+
+
+# ---- storage rounding ------------------------------------------------------
+
+def to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """float -> bf16 bit patterns (uint16), round-to-nearest-even."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    return ((u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def store(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Round a float array to its storage form."""
+    if dtype == "bf16":
+        return to_bf16_bits(x)
+    if dtype == "f32":
+        return np.ascontiguousarray(x, dtype=np.float32)
+    raise ValueError(dtype)
+
+
+def widen(x: np.ndarray) -> np.ndarray:
+    """Storage form -> float64 (exact)."""
+    if x.dtype == np.uint16:
+        return bf16_bits_to_f32(x).astype(np.float64)
+    return x.astype(np.float64)
+
+
+# ---- generators ------------------------------------------------------------
+
+def seed_of(w: Workload, layer: int, b: int) -> int:
+    return 10_000 * w.cfg_id + 100 * layer + b
+
+
+def make_projector(rng: np.random.Generator, D: int, r: int) -> np.ndarray:
+    """[D x r] with orthonormal columns (rows of its transpose are the
+    orthonormal rows of the up-projection): Q factor of a Gaussian matrix."""
+    if r <= D:
+        qm, _ = np.linalg.qr(rng.standard_normal((D, r)))
+        return qm
+    # over-complete rank (tests only): orthonormal rows instead
+    qm, _ = np.linalg.qr(rng.standard_normal((r, D)))
+    return qm.T
+
+
+def make_weights(w: Workload, layer: int = 0):
+    """Per-layer projectors U_k, U_v [D_kv x r], storage-rounded."""
+    rng = np.random.default_rng(seed_of(w, layer, 99))
+    Uk = make_projector(rng, w.D_kv, w.r)
+    Uv = make_projector(rng, w.D_kv, w.r)
+    return store(Uk, w.dtype), store(Uv, w.dtype)
+
+
+def make_sequence(w: Workload, layer: int, b: int, Uk_stored: np.ndarray, S: int | None = None):
+    """One sequence's query and latent caches, storage-rounded.
+
+    Cache entries are N(0,1) scaled by the decaying spectrum (c+1)^-1/2 of the
+    latent coordinate c.  Returns dict(q [H,d], Kc [S,r], Vc [S,r], planted)."""
+    S = w.S if S is None else S
+    rng = np.random.default_rng(seed_of(w, layer, b))
+    sigma = (np.arange(1, w.r + 1, dtype=np.float64)) ** -0.5 * w.scale
+    q = rng.standard_normal((w.H, w.d))
+    Kc = rng.standard_normal((S, w.r), dtype=np.float32).astype(np.float64) * sigma
+    Vc = rng.standard_normal((S, w.r), dtype=np.float32).astype(np.float64) * sigma
+    planted = np.zeros(0, dtype=np.int64)
+    if (w.plant or w.corr_frac > 0) and S > 0:
+        # latent image of the (group-summed) query, used only to orient rows
+        G = w.H // w.H_kv
+        q_sum = widen(store(q, w.dtype)).reshape(w.H_kv, G, w.d).sum(axis=1).reshape(-1)
+        qt = widen(Uk_stored).T @ q_sum
+        qn = float(np.linalg.norm(qt))
+        if w.plant:
+            s_max = float(np.max(np.abs(Kc[:, : w.rs] @ qt[: w.rs])))
+            planted = rng.choice(S, size=min(w.plant, S), replace=False)
+            for m, t in enumerate(planted):
+                Kc[t, :] += (2.0 + 0.1 * m) * s_max * qt / (qn * qn)
+        if w.corr_frac > 0:
+            n_c = max(1, int(round(w.corr_frac * S)))
+            planted = rng.choice(S, size=n_c, replace=False)
+            rows = Kc[planted, :]
+            norms = np.linalg.norm(rows, axis=1, keepdims=True)
+            Kc[planted, :] = (w.corr_rho * norms / qn) * qt[None, :] \
+                + np.sqrt(1.0 - w.corr_rho ** 2) * rows
+    return {"q": store(q, w.dtype), "Kc": store(Kc, w.dtype), "Vc": store(Vc, w.dtype),
+            "planted": np.sort(planted)}
+
+
+def make_layer(w: Workload, layer: int = 0, seq_lens=None):
+    """A full batch for one layer: dict of stacked storage arrays.
+
+    q [B,H,d], Kc/Vc [B,S,r] (rows past seq_len[b] are zero), Uk/Uv [D_kv,r],
+    seq_len [B] int32, q_pos [B] int32 (= seq_len: the query follows the cache)."""
+    Uk, Uv = make_weights(w, layer)
+    seq_lens = [w.S] * w.B if seq_lens is None else list(seq_lens)
+    assert len(seq_lens) == w.B and max(seq_lens) <= w.S
+    st = np.uint16 if w.dtype == "bf16" else np.float32
+    q = np.zeros((w.B, w.H, w.d), dtype=st)
+    Kc = np.zeros((w.B, w.S, w.r), dtype=st)
+    Vc = np.zeros((w.B, w.S, w.r), dtype=st)
+    planted = []
+    for b in range(w.B):
+        s = make_sequence(w, layer, b, Uk, seq_lens[b])
+        q[b] = s["q"]
+        Kc[b, : seq_lens[b]] = s["Kc"]
+        Vc[b, : seq_lens[b]] = s["Vc"]
+        planted.append(s["planted"])
+    sl = np.asarray(seq_lens, dtype=np.int32)
+    return {"q": q, "Kc": Kc, "Vc": Vc, "Uk": Uk, "Uv": Uv, "seq_len": sl,
+            "q_pos": sl.copy(), "planted": planted}
