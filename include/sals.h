@@ -1,0 +1,165 @@
+/*
+ * sals.h - C ABI of the SALS decode-step attention library for MI355X (gfx950).
+ *
+ * The operator is Algorithm 1 of "SALS: Sparse Attention in Latent Space for KV
+ * cache Compression" (arXiv 2510.24273): per sequence, project the pre-RoPE
+ * query into the shared single-head latent space (Sec. 4.3), score every cached
+ * token against the latent key cache without RoPE, keep the top-k tokens,
+ * reconstruct only those tokens' keys (and values) through the projector, apply
+ * RoPE at their positions and run softmax attention over the selected set
+ * (Sec. 4.4, Eq. 5).
+ *
+ * General conventions
+ * -------------------
+ * Pointers.  Every `const void*` / `void*` / `float*` / `int32_t*` data argument
+ *   is a DEVICE pointer on the GPU that is current when the call is made; only
+ *   the descriptor, the context handle and out-parameters of the sizing / create
+ *   calls are host pointers.  Data pointers must be 16-byte aligned.
+ * Ownership.  The caller allocates and frees every device buffer, including the
+ *   workspace.  The library never allocates or frees device memory and keeps no
+ *   device pointer beyond a call, except the workspace handed to sals_create,
+ *   which must stay valid until sals_destroy.
+ * Layout.  All arrays are dense and row-major.  Element type `T` is the
+ *   descriptor's storage type: 32-bit float, or bfloat16 (upper 16 bits of a
+ *   float, round-to-nearest-even).  Token t of a sequence has RoPE position t.
+ * Projectors.  `Uk`, `Uv` are the joint projectors U_r of Sec. 4.2 in the paper's
+ *   own orientation, [D_kv x r] with D_kv = H_kv*d: row c holds the r latent
+ *   coefficients of stacked key (value) channel c.  Down-projection is U^T x,
+ *   up-projection (reconstruction) is U x~.  Nothing assumes orthonormality.
+ * Asynchrony.  Each call only enqueues kernels on `hip_stream` (a hipStream_t
+ *   passed as void*, NULL = the default stream) and returns; nothing synchronises
+ *   and no device data is read on the host.  Calls that share one context must be
+ *   ordered on one stream (they share the workspace).
+ * Errors.  Every call returns a sals_status; nothing throws or aborts.  Argument
+ *   and descriptor errors are detected on the host before anything is enqueued.
+ *   A failed launch returns SALS_ERR_HIP.
+ */
+#ifndef SALS_H
+#define SALS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SALS_OK = 0,
+    SALS_ERR_INVALID_ARG = 1,  /* NULL pointer, misaligned pointer, bad descriptor field */
+    SALS_ERR_UNSUPPORTED = 2,  /* valid request outside what the kernels cover */
+    SALS_ERR_WORKSPACE = 3,    /* workspace NULL, misaligned or too small */
+    SALS_ERR_HIP = 4           /* a HIP runtime call or kernel launch failed */
+} sals_status;
+
+enum { SALS_F32 = 0, SALS_BF16 = 1 };                 /* sals_desc.dtype      */
+enum { SALS_ROPE_HALF = 0,        /* pair (i, i+d/2) */
+       SALS_ROPE_INTERLEAVED = 1  /* pair (2i, 2i+1) */ };  /* sals_desc.rope_style */
+
+/* Problem descriptor (plain data, host memory).
+ * Supported by the kernels: d == 128; r a multiple of 64, 64 <= r <= 1024;
+ * r_score a multiple of 8, 8 <= r_score <= r; H_q a multiple of H_kv with
+ * H_q/H_kv <= 8; B >= 1; 1 <= S_max <= 2^24; top_k >= 1; n_sink, n_recent >= 0;
+ * top_k + n_sink + n_recent <= 65536. */
+typedef struct {
+    int32_t B;          /* sequences per call                                         */
+    int32_t S_max;      /* row capacity of each sequence's latent caches              */
+    int32_t H_q;        /* query heads  (the paper's n)                               */
+    int32_t H_kv;       /* key/value heads; query head h reads KV head h/(H_q/H_kv)   */
+    int32_t d;          /* head width                                                 */
+    int32_t r;          /* latent rank                                                */
+    int32_t r_score;    /* leading latent coordinates used for scoring (paper: r*)    */
+    int32_t top_k;      /* critical tokens chosen by score                            */
+    int32_t n_recent;   /* most recent tokens always kept (Sec. 5.2), not candidates  */
+    int32_t n_sink;     /* first tokens always kept (Sec. 5.2), not candidates        */
+    float   rope_theta; /* RoPE base; pair i turns by pos * theta^(-2i/d)             */
+    int32_t rope_style; /* SALS_ROPE_HALF | SALS_ROPE_INTERLEAVED                     */
+    int32_t dtype;      /* SALS_F32 | SALS_BF16: type of q, caches, projectors, out   */
+} sals_desc;
+
+typedef struct sals_ctx sals_ctx;   /* opaque host object: descriptor + workspace pointer */
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* sals_status_string(sals_status s);
+
+/* Bytes of device workspace a context for `desc` needs.  Host-only. */
+sals_status sals_workspace_bytes(const sals_desc* desc, size_t* bytes);
+
+/* Validate `desc`, bind the caller's device workspace (256-byte aligned, at least
+ * sals_workspace_bytes) and return a context in *out.  The workspace must be
+ * zero-filled once by the caller before the first call that uses the context
+ * (the kernels keep their counters at zero afterwards).  Host-only, allocates
+ * only host memory. */
+sals_status sals_create(const sals_desc* desc, void* d_workspace, size_t workspace_bytes,
+                        sals_ctx** out);
+void sals_destroy(sals_ctx* ctx);
+
+/* Stage 1, latent compression of the new token (Eq. 1; Algorithm 1, projection and
+ * append steps):  k~ = Uk^T k_new, v~ = Uv^T v_new, rounded to T and written to
+ * row seq_len[b] of Kc[b] / Vc[b]; then seq_len[b] += 1.  A sequence whose cache is
+ * full (seq_len[b] >= S_max) is left untouched.
+ *   k_new, v_new [B, D_kv] T   pre-RoPE key / value of the new token
+ *   Uk, Uv       [D_kv, r] T
+ *   Kc, Vc       [B, S_max, r] T   in/out
+ *   seq_len      [B] int32         in/out (device) */
+sals_status sals_compress_append(sals_ctx* ctx, const void* k_new, const void* v_new,
+                                 const void* Uk, const void* Uv, void* Kc, void* Vc,
+                                 int32_t* seq_len, void* hip_stream);
+
+/* Stage 2a, query projection and latent scores (Sec. 4.3; Algorithm 1, score step):
+ *   q~ = Uk^T (sum of the query heads of each KV group, stacked)     [r], fp32
+ *   scores[b, j] = sum_{i < r_score} q~[i] * Kc[b, j, i]   for j <  seq_len[b]
+ *   scores[b, j] = -inf                                    for j >= seq_len[b]
+ * Raw dot products (no 1/sqrt(d), no softmax, no RoPE), fp32 accumulation.
+ *   q       [B, H_q, d] T      pre-RoPE query
+ *   Kc      [B, S_max, r] T
+ *   seq_len [B] int32
+ *   scores  [B, S_max] fp32    out */
+sals_status sals_latent_scores(sals_ctx* ctx, const void* q, const void* Uk, const void* Kc,
+                               const int32_t* seq_len, float* scores, void* hip_stream);
+
+/* Stage 2b, critical-token selection (Algorithm 1, TopK step; composition with sink
+ * and recent tokens as in Sec. 5.2).  With S = seq_len[b] and
+ * k_tot = top_k + n_sink + n_recent:
+ *   S <= k_tot : every token is selected, n_sel[b] = S, idx[b, :S] = 0..S-1.
+ *   otherwise  : n_sel[b] = k_tot; idx[b] holds the n_sink first tokens, then the
+ *                top_k candidates j in [n_sink, S-n_recent) with the largest scores
+ *                (equal scores: smaller j wins; -0 equals +0), then the n_recent last
+ *                tokens.  Within the critical block the order is: scores above the
+ *                k-th largest by increasing j, then ties at it by increasing j.
+ * Entries idx[b, n_sel[b]:] are set to 0.  The result is deterministic.
+ *   scores [B, S_max] fp32 (NaN-free)
+ *   idx    [B, k_tot] int32   out
+ *   n_sel  [B] int32          out */
+sals_status sals_topk_select(sals_ctx* ctx, const float* scores, const int32_t* seq_len,
+                             int32_t* idx, int32_t* n_sel, void* hip_stream);
+
+/* Stage 3, selective reconstruction, RoPE and sparse attention (Sec. 4.4, Eq. 5;
+ * Algorithm 1, reconstruction to output steps).  For each sequence and the tokens
+ * t = idx[b, j], j < n_sel[b] (indices in [0, S_max), unique):
+ *   K_C[j] = Uk Kc[b, t]  reshaped [H_kv, d], rotated by RoPE at position t
+ *   V_C[j] = Uv Vc[b, t]  reshaped [H_kv, d]
+ *   out[b, h] = sum_j softmax_j( RoPE(q[b,h], q_pos[b]) . K_C[j, g(h)] / sqrt(d) ) V_C[j, g(h)]
+ * Keys are reconstructed on the matrix cores (bf16 x bf16 -> fp32, or fp32), RoPE,
+ * logits and softmax are fp32; the value product is evaluated in the exact
+ * re-associated order  ((p . V~_C) . Uv^T)  and rounded once to T.  If
+ * n_sel[b] == 0, out[b] is zero.
+ *   q [B,H_q,d] T;  q_pos [B] int32;  Kc, Vc [B,S_max,r] T;  Uk, Uv [D_kv,r] T
+ *   idx [B,k_tot] int32;  n_sel [B] int32;  out [B,H_q,d] T */
+sals_status sals_sparse_attend(sals_ctx* ctx, const void* q, const int32_t* q_pos,
+                               const void* Kc, const void* Vc, const void* Uk, const void* Uv,
+                               const int32_t* idx, const int32_t* n_sel, void* out,
+                               void* hip_stream);
+
+/* The whole decode step of Algorithm 1 on one stream: sals_latent_scores,
+ * sals_topk_select, sals_sparse_attend.  `scores`, `idx`, `n_sel` may each be NULL,
+ * in which case that intermediate lives in the workspace. */
+sals_status sals_decode_step(sals_ctx* ctx, const void* q, const int32_t* q_pos, const void* Kc,
+                             const void* Vc, const void* Uk, const void* Uv,
+                             const int32_t* seq_len, void* out, float* scores, int32_t* idx,
+                             int32_t* n_sel, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SALS_H */

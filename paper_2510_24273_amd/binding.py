@@ -1,0 +1,146 @@
+"""Thin ctypes binding of ``libsals.so`` (see ``include/sals.h``).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.
+PyTorch supplies device memory (``tensor.data_ptr()``) and the current stream.
+Importing this module fails loudly when the library has not been built
+(``python -m paper_2510_24273_amd.build``); there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # noqa: F401  (must be imported first: it brings the HIP runtime in)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsals.so")
+
+SALS_OK = 0
+SALS_ERR_INVALID_ARG = 1
+SALS_ERR_UNSUPPORTED = 2
+SALS_ERR_WORKSPACE = 3
+SALS_ERR_HIP = 4
+SALS_F32, SALS_BF16 = 0, 1
+
+EXPORTS = (
+    "sals_status_string", "sals_workspace_bytes", "sals_create", "sals_destroy",
+    "sals_compress_append", "sals_latent_scores", "sals_topk_select", "sals_sparse_attend",
+    "sals_decode_step",
+)
+
+
+class SalsDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("B", "S_max", "H_q", "H_kv", "d", "r", "r_score", "top_k", "n_recent", "n_sink")] + \
+               [("rope_theta", ctypes.c_float), ("rope_style", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class SalsError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)}")
+
+
+def load_library() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2510_24273_amd.build` "
+            "(hipcc, gfx950). There is no fallback implementation.")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32p, f32p = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+    lib.sals_status_string.restype = ctypes.c_char_p
+    lib.sals_status_string.argtypes = [ctypes.c_int]
+    lib.sals_workspace_bytes.argtypes = [ctypes.POINTER(SalsDesc), ctypes.POINTER(ctypes.c_size_t)]
+    lib.sals_create.argtypes = [ctypes.POINTER(SalsDesc), vp, ctypes.c_size_t, ctypes.POINTER(vp)]
+    lib.sals_destroy.argtypes = [vp]
+    lib.sals_destroy.restype = None
+    lib.sals_compress_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, vp]
+    lib.sals_latent_scores.argtypes = [vp, vp, vp, vp, i32p, f32p, vp]
+    lib.sals_topk_select.argtypes = [vp, f32p, i32p, i32p, i32p, vp]
+    lib.sals_sparse_attend.argtypes = [vp, vp, i32p, vp, vp, vp, vp, i32p, i32p, vp, vp]
+    lib.sals_decode_step.argtypes = [vp, vp, i32p, vp, vp, vp, vp, i32p, vp, f32p, i32p, i32p, vp]
+    for name in EXPORTS[1:]:
+        if name != "sals_destroy":
+            getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
+_lib = load_library()
+
+
+def status_string(code: int) -> str:
+    return _lib.sals_status_string(int(code)).decode()
+
+
+def make_desc(B, S_max, H_q, H_kv, d, r, top_k, dtype, r_score=None, n_recent=0, n_sink=0,
+              rope_theta=10000.0, rope_style=0) -> SalsDesc:
+    dt = {"bf16": SALS_BF16, "f32": SALS_F32, torch.bfloat16: SALS_BF16, torch.float32: SALS_F32}[dtype]
+    return SalsDesc(B, S_max, H_q, H_kv, d, r, r if r_score is None else r_score, top_k, n_recent,
+                    n_sink, rope_theta, rope_style, dt)
+
+
+def workspace_bytes(desc: SalsDesc) -> int:
+    n = ctypes.c_size_t(0)
+    st = _lib.sals_workspace_bytes(ctypes.byref(desc), ctypes.byref(n))
+    if st != SALS_OK:
+        raise SalsError(st, "sals_workspace_bytes")
+    return int(n.value)
+
+
+def _p(t):
+    """Device pointer of a tensor (None -> NULL)."""
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Sals:
+    """One context: descriptor + caller-owned (torch) workspace."""
+
+    def __init__(self, desc: SalsDesc, device="cuda:0"):
+        self.desc = desc
+        self.device = torch.device(device)
+        self.k_tot = desc.top_k + desc.n_sink + desc.n_recent
+        nbytes = workspace_bytes(desc)
+        self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=self.device)
+        h = ctypes.c_void_p()
+        st = _lib.sals_create(ctypes.byref(desc), self.workspace.data_ptr(), nbytes, ctypes.byref(h))
+        if st != SALS_OK:
+            raise SalsError(st, "sals_create")
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.sals_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    @staticmethod
+    def _check(st, where):
+        if st != SALS_OK:
+            raise SalsError(st, where)
+
+    def compress_append(self, k_new, v_new, Uk, Uv, Kc, Vc, seq_len):
+        self._check(_lib.sals_compress_append(self._h, _p(k_new), _p(v_new), _p(Uk), _p(Uv), _p(Kc),
+                                              _p(Vc), _p(seq_len), _stream()), "sals_compress_append")
+
+    def latent_scores(self, q, Uk, Kc, seq_len, scores):
+        self._check(_lib.sals_latent_scores(self._h, _p(q), _p(Uk), _p(Kc), _p(seq_len), _p(scores),
+                                            _stream()), "sals_latent_scores")
+
+    def topk_select(self, scores, seq_len, idx, n_sel):
+        self._check(_lib.sals_topk_select(self._h, _p(scores), _p(seq_len), _p(idx), _p(n_sel),
+                                          _stream()), "sals_topk_select")
+
+    def sparse_attend(self, q, q_pos, Kc, Vc, Uk, Uv, idx, n_sel, out):
+        self._check(_lib.sals_sparse_attend(self._h, _p(q), _p(q_pos), _p(Kc), _p(Vc), _p(Uk), _p(Uv),
+                                            _p(idx), _p(n_sel), _p(out), _stream()), "sals_sparse_attend")
+
+    def decode_step(self, q, q_pos, Kc, Vc, Uk, Uv, seq_len, out, scores=None, idx=None, n_sel=None):
+        self._check(_lib.sals_decode_step(self._h, _p(q), _p(q_pos), _p(Kc), _p(Vc), _p(Uk), _p(Uv),
+                                          _p(seq_len), _p(out), _p(scores), _p(idx), _p(n_sel),
+                                          _stream()), "sals_decode_step")

@@ -1,0 +1,395 @@
+// Selective reconstruction, RoPE and sparse attention (Sec. 4.4, Eq. 5;
+// Algorithm 1, reconstruction to output steps).
+//
+//   attend_prep    cos/sin of (position x frequency) for every selected token, and the
+//                  rotated, 1/sqrt(d)-scaled query, both in fp64-accurate angles
+//   attend_logits  K_C = K~_C U_k^T on the matrix cores, RoPE and q.K in the epilogue;
+//                  the reconstructed keys never leave registers
+//   attend_stats   per (sequence, head) softmax maximum and normaliser
+//   attend_pv      T[h,:] = sum_j exp(l_hj - m_h) V~_C[j,:]      (latent-space value sum)
+//   attend_out     y[h] = (T[h,:] U_v[g(h) block]^T) / Z_h       (one pass over U_v)
+//
+// The value product uses  p (V~_C U_v^T) = (p V~_C) U_v^T : the same sum in another
+// order, which avoids reconstructing V_C.
+//
+// Head dims are handled in "pair order": slot p < 64 is the first element of RoPE pair
+// p, slot 64+p its partner, for either pairing style; the rows of U_k are fetched in
+// that order, so both elements of a pair land in the same lane of the MFMA result.
+#pragma once
+#include "common.hpp"
+
+namespace sals {
+
+__device__ __forceinline__ int pair_first(int p, int style) { return style ? 2 * p : p; }
+__device__ __forceinline__ int pair_second(int p, int style) { return style ? 2 * p + 1 : p + kPairs; }
+__device__ __forceinline__ int slot_to_dim(int slot, int style)
+{
+    return slot < kPairs ? pair_first(slot, style) : pair_second(slot - kPairs, style);
+}
+
+struct InvFreq { double f[kPairs]; };  // theta^(-2p/d), computed on the host in fp64
+
+// ---------------------------------------------------------------------------------
+// prep
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void attend_prep_kernel(const T* __restrict__ q,
+                                                          const int32_t* __restrict__ q_pos,
+                                                          const int32_t* __restrict__ idx,
+                                                          const int32_t* __restrict__ n_sel,
+                                                          float2* __restrict__ cs, float* __restrict__ qR,
+                                                          InvFreq inv, int B, int H, int k_tot,
+                                                          int n_tab_blocks, int style, float scale)
+{
+    const int p = threadIdx.x & 63, sub = threadIdx.x >> 6;
+    if ((int)blockIdx.x < n_tab_blocks) {
+        int slot = blockIdx.x * 4 + sub;  // flat (b, j)
+        if (slot >= B * k_tot) return;
+        int b = slot / k_tot, j = slot - b * k_tot;
+        int pos = j < n_sel[b] ? idx[slot] : 0;
+        double sn, c;
+        sincos((double)pos * inv.f[p], &sn, &c);
+        cs[(size_t)slot * kPairs + p] = make_float2((float)c, (float)sn);
+    } else {
+        int bh = (blockIdx.x - n_tab_blocks) * 4 + sub;  // flat (b, h)
+        if (bh >= B * H) return;
+        int b = bh / H;
+        double sn, c;
+        sincos((double)q_pos[b] * inv.f[p], &sn, &c);
+        float x1 = elem<T>::load(q + (size_t)bh * kHeadDim + pair_first(p, style));
+        float x2 = elem<T>::load(q + (size_t)bh * kHeadDim + pair_second(p, style));
+        float cf = (float)c, sf = (float)sn;
+        qR[(size_t)bh * kHeadDim + p] = (x1 * cf - x2 * sf) * scale;
+        qR[(size_t)bh * kHeadDim + kPairs + p] = (x2 * cf + x1 * sf) * scale;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// logits: gathered-row GEMM on MFMA with RoPE + q.K epilogue
+// ---------------------------------------------------------------------------------
+constexpr int kChunkBytes = 128;             // bytes of the latent axis per pipeline step
+constexpr int kLdsRowBytes = kChunkBytes + 16;  // padded: conflict-free 16-byte column reads
+constexpr int kMaxGroup = 8;                 // query heads per KV head
+
+template <typename T> struct mma_op;
+template <> struct mma_op<bf16_t> {  // one v_mfma_f32_32x32x16_bf16 per 16-byte fragment pair
+    static __device__ __forceinline__ void run(const u32x4& a, const u32x4& b, f32x16& c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                    __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+};
+template <> struct mma_op<float> {   // four v_mfma_f32_32x32x2_f32 per 16-byte fragment pair
+    static __device__ __forceinline__ void run(const u32x4& a, const u32x4& b, f32x16& c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+    }
+};
+
+// Workgroup tile: 128 head dims x (32*NB*NW) tokens of one (sequence, KV head).
+// Each wave owns all 128 dims (4 MFMA row blocks) x NB blocks of 32 tokens; the U_k
+// panel goes through LDS (shared by the waves), the gathered latent rows go straight
+// from global memory to registers (private to a wave).
+template <typename T, int NW, int NB>
+__global__ __launch_bounds__(64 * NW) void attend_logits_kernel(
+    const T* __restrict__ Kc, const T* __restrict__ Uk, const int32_t* __restrict__ idx,
+    const int32_t* __restrict__ n_sel, const float2* __restrict__ cs, const float* __restrict__ qR,
+    float* __restrict__ logits, int S_max, int r, int H, int H_kv, int k_tot, int lk, int style)
+{
+    constexpr int NT = 64 * NW;
+    constexpr int TOK = 32 * NB * NW;
+    constexpr int ES = (int)sizeof(T);
+    constexpr int KE = kChunkBytes / ES;       // latent coordinates per pipeline step
+    constexpr int APT = (128 * 8) / NT;        // 16-byte pieces of the U_k panel per thread
+    const int b = blockIdx.z, g = blockIdx.y, tok0 = blockIdx.x * TOK;
+    const int n = n_sel[b];
+    if (tok0 >= n) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int G = H / H_kv;
+
+    __shared__ __attribute__((aligned(16))) unsigned char As[2][128 * kLdsRowBytes];
+    __shared__ __attribute__((aligned(16))) float sQ[kMaxGroup][kHeadDim];
+
+    for (int t = tid; t < G * kHeadDim; t += NT)
+        sQ[t / kHeadDim][t % kHeadDim] = qR[((size_t)b * H + g * G) * kHeadDim + t];
+
+    // gathered latent rows of this lane's tokens
+    const unsigned char* rowp[NB];
+    int slot[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        slot[nb] = tok0 + (wave * NB + nb) * 32 + l32;
+        int t = idx[(size_t)b * k_tot + (slot[nb] < n ? slot[nb] : 0)];
+        t = min(max(t, 0), S_max - 1);  // stay inside the cache whatever the caller passed
+        rowp[nb] = reinterpret_cast<const unsigned char*>(Kc + ((size_t)b * S_max + t) * r) + hi * 16;
+    }
+    // U_k panel pieces of this thread: piece q -> (row = q/8, 16-byte column q%8)
+    const unsigned char* ap[APT];
+    int a_lds[APT];
+#pragma unroll
+    for (int i = 0; i < APT; ++i) {
+        int qd = tid + i * NT;
+        int row = qd >> 3, pc = qd & 7;
+        ap[i] = reinterpret_cast<const unsigned char*>(Uk + ((size_t)g * kHeadDim + slot_to_dim(row, style)) * r) + pc * 16;
+        a_lds[i] = row * kLdsRowBytes + pc * 16;
+    }
+
+    f32x16 acc[4][NB];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+
+    const int nkc = r / KE;
+    u32x4 areg[APT], bcur[4][NB], bnext[4][NB];
+#pragma unroll
+    for (int i = 0; i < APT; ++i) areg[i] = ld16(ap[i]);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) bcur[ks][nb] = ld16(rowp[nb] + ks * 32);
+#pragma unroll
+    for (int i = 0; i < APT; ++i) *reinterpret_cast<u32x4*>(&As[0][a_lds[i]]) = areg[i];
+    __syncthreads();
+
+    for (int kc = 0; kc < nkc; ++kc) {
+        const int cur = kc & 1;
+        const bool more = kc + 1 < nkc;
+        if (more) {
+            const int off = (kc + 1) * kChunkBytes;
+#pragma unroll
+            for (int i = 0; i < APT; ++i) areg[i] = ld16(ap[i] + off);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) bnext[ks][nb] = ld16(rowp[nb] + off + ks * 32);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) {
+                u32x4 a = *reinterpret_cast<const u32x4*>(&As[cur][(mb * 32 + l32) * kLdsRowBytes + ks * 32 + hi * 16]);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) mma_op<T>::run(a, bcur[ks][nb], acc[mb][nb]);
+            }
+        }
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < APT; ++i) *reinterpret_cast<u32x4*>(&As[cur ^ 1][a_lds[i]]) = areg[i];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) bcur[ks][nb] = bnext[ks][nb];
+        }
+        __syncthreads();
+    }
+
+    // epilogue: lane holds, for token l32 of each block, slots mb*32 + 8a + 4hi + c.
+    // slot < 64 is the first element of pair (slot), slot+64 its partner (mb+2).
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const bool valid = slot[nb] < n;
+        float dot[kMaxGroup];
+#pragma unroll
+        for (int m = 0; m < kMaxGroup; ++m) dot[m] = 0.f;
+        const float2* csrow = cs + ((size_t)b * k_tot + (valid ? slot[nb] : 0)) * kPairs;
+#pragma unroll
+        for (int ml = 0; ml < 2; ++ml) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const int p0 = ml * 32 + a * 8 + hi * 4;
+                f32x4 t0 = *reinterpret_cast<const f32x4*>(csrow + p0);      // (c,s) of pairs p0, p0+1
+                f32x4 t1 = *reinterpret_cast<const f32x4*>(csrow + p0 + 2);  // pairs p0+2, p0+3
+                float cc[4] = {t0.x, t0.z, t1.x, t1.z}, ss[4] = {t0.y, t0.w, t1.y, t1.w};
+                float k1[4], k2[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    float x1 = acc[ml][nb][a * 4 + c], x2 = acc[ml + 2][nb][a * 4 + c];
+                    k1[c] = x1 * cc[c] - x2 * ss[c];
+                    k2[c] = x2 * cc[c] + x1 * ss[c];
+                }
+#pragma unroll
+                for (int m = 0; m < kMaxGroup; ++m) {
+                    if (m < G) {
+                        f32x4 q1 = *reinterpret_cast<const f32x4*>(&sQ[m][p0]);
+                        f32x4 q2 = *reinterpret_cast<const f32x4*>(&sQ[m][kPairs + p0]);
+                        dot[m] += q1.x * k1[0] + q1.y * k1[1] + q1.z * k1[2] + q1.w * k1[3] +
+                                  q2.x * k2[0] + q2.y * k2[1] + q2.z * k2[2] + q2.w * k2[3];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < kMaxGroup; ++m) {
+            if (m < G) {
+                float d = dot[m] + __shfl_xor(dot[m], 32, kWave);
+                if (hi == 0 && slot[nb] < lk)
+                    logits[((size_t)b * H + g * G + m) * lk + slot[nb]] = valid ? d : -INFINITY;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// softmax statistics: one wave per (sequence, head)
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attend_stats_kernel(const float* __restrict__ logits,
+                                                           const int32_t* __restrict__ n_sel,
+                                                           float2* __restrict__ stats, int B, int H, int lk)
+{
+    const int bh = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (bh >= B * H) return;
+    const int lane = lane_id();
+    const int n = n_sel[bh / H];
+    const float* l = logits + (size_t)bh * lk;
+    float m = -INFINITY;
+    for (int j = lane; j < n; j += kWave) m = fmaxf(m, l[j]);
+    m = wave_max(m);
+    float z = 0.f;
+    for (int j = lane; j < n; j += kWave) z += __expf(l[j] - m);
+    z = wave_sum(z);
+    if (lane == 0) stats[bh] = make_float2(m, z);
+}
+
+// ---------------------------------------------------------------------------------
+// latent-space value sum: Tpart[tc][b][h][i] = sum_{j in token chunk tc} e^{l_hj - m_h} V~[C_j][i]
+// ---------------------------------------------------------------------------------
+constexpr int kPvCols = 64;      // latent columns per workgroup
+constexpr int kPvTok = 128;      // tokens staged per step
+constexpr int kPvMaxHeads = 64;  // H_q limit of this kernel
+
+template <typename T>
+__global__ __launch_bounds__(256) void attend_pv_kernel(const T* __restrict__ Vc,
+                                                        const int32_t* __restrict__ idx,
+                                                        const int32_t* __restrict__ n_sel,
+                                                        const float* __restrict__ logits,
+                                                        const float2* __restrict__ stats,
+                                                        float* __restrict__ Tpart, int B, int S_max,
+                                                        int r, int H, int k_tot, int lk, int tok_per_wg)
+{
+    constexpr int HPW = kPvMaxHeads / 4;  // heads per wave (upper bound)
+    __shared__ __attribute__((aligned(16))) float ps[kPvMaxHeads][kPvTok];
+    __shared__ int srow[kPvTok];
+    const int b = blockIdx.z, tc = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = blockIdx.x * kPvCols + lane;
+    const int n = n_sel[b];
+    const int hpw = (H + 3) / 4;
+    const int h0 = wave * hpw;
+    const int j_begin = tc * tok_per_wg, j_end = min(n, j_begin + tok_per_wg);
+
+    float acc[HPW];
+#pragma unroll
+    for (int i = 0; i < HPW; ++i) acc[i] = 0.f;
+
+    for (int j0 = j_begin; j0 < j_end; j0 += kPvTok) {
+        __syncthreads();
+        const int cnt = min(kPvTok, j_end - j0);
+        for (int t = tid; t < kPvTok; t += 256) srow[t] = t < cnt ? min(max(idx[(size_t)b * k_tot + j0 + t], 0), S_max - 1) : 0;
+        for (int t = tid; t < H * kPvTok; t += 256) {
+            int h = t / kPvTok, jj = t - h * kPvTok;
+            float p = 0.f;
+            if (jj < cnt) p = __expf(logits[((size_t)b * H + h) * lk + j0 + jj] - stats[b * H + h].x);
+            ps[h][jj] = p;
+        }
+        __syncthreads();
+        const int cnt4 = (cnt + 3) & ~3;
+        for (int jj = 0; jj < cnt4; jj += 4) {
+            float v[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                v[e] = elem<T>::load(Vc + ((size_t)b * S_max + srow[jj + e]) * r + col);  // p == 0 past cnt
+#pragma unroll
+            for (int i = 0; i < HPW; ++i) {
+                if (i < hpw && h0 + i < H) {
+                    f32x4 p4 = *reinterpret_cast<const f32x4*>(&ps[h0 + i][jj]);
+                    acc[i] = fmaf(p4.x, v[0], acc[i]);
+                    acc[i] = fmaf(p4.y, v[1], acc[i]);
+                    acc[i] = fmaf(p4.z, v[2], acc[i]);
+                    acc[i] = fmaf(p4.w, v[3], acc[i]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < HPW; ++i)
+        if (i < hpw && h0 + i < H)
+            Tpart[(((size_t)tc * B + b) * H + h0 + i) * r + col] = acc[i];
+}
+
+// ---------------------------------------------------------------------------------
+// output projection: y[b,h,c] = (sum_i T[b,h,i] U_v[g*128+c, i]) / Z_bh
+// ---------------------------------------------------------------------------------
+constexpr int kOutRowsLds = 8;   // (b,h) rows of T staged per pass
+
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ Uv,
+                                                         const float* __restrict__ Tpart,
+                                                         const float2* __restrict__ stats,
+                                                         const int32_t* __restrict__ n_sel,
+                                                         T* __restrict__ out, int B, int r, int H,
+                                                         int H_kv, int n_tc)
+{
+    constexpr int VEC = elem<T>::vec;
+    extern __shared__ __attribute__((aligned(16))) float Ts[];  // [kOutRowsLds][r]
+    const int g = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int li = lane & 15, grp = tid >> 4;  // 16 groups of 16 lanes: one output channel each
+    const int c = blockIdx.x * 16 + grp;
+    const int G = H / H_kv;
+    const int n_pieces = r / VEC;
+
+    float uf[NCH][VEC];
+#pragma unroll
+    for (int nn = 0; nn < NCH; ++nn) {
+        int p = li + 16 * nn;
+        u32x4 w = p < n_pieces ? ld16(Uv + ((size_t)g * kHeadDim + c) * r + p * VEC) : u32x4{0, 0, 0, 0};
+        elem<T>::unpack(w, uf[nn]);
+    }
+
+    const int n_rows = B * G;  // (b, m) pairs that read this KV head
+    for (int row0 = 0; row0 < n_rows; row0 += kOutRowsLds) {
+        __syncthreads();
+        const int rows = min(kOutRowsLds, n_rows - row0);
+        for (int t = tid; t < rows * r; t += 256) {
+            int rr = t / r, i = t - rr * r;
+            int b = (row0 + rr) / G, h = g * G + (row0 + rr) % G;
+            float s = 0.f;
+            for (int tc = 0; tc < n_tc; ++tc) s += Tpart[(((size_t)tc * B + b) * H + h) * r + i];
+            Ts[rr * r + i] = s;
+        }
+        __syncthreads();
+        for (int rr = 0; rr < rows; ++rr) {
+            float acc = 0.f;
+#pragma unroll
+            for (int nn = 0; nn < NCH; ++nn) {
+                int p = li + 16 * nn;
+                if (p < n_pieces) {
+#pragma unroll
+                    for (int v = 0; v < VEC; v += 4) {
+                        f32x4 t4 = *reinterpret_cast<const f32x4*>(&Ts[rr * r + p * VEC + v]);
+                        acc = fmaf(uf[nn][v], t4.x, acc);
+                        acc = fmaf(uf[nn][v + 1], t4.y, acc);
+                        acc = fmaf(uf[nn][v + 2], t4.z, acc);
+                        acc = fmaf(uf[nn][v + 3], t4.w, acc);
+                    }
+                }
+            }
+            acc = row16_sum(acc);
+            if (li == 0) {
+                int b = (row0 + rr) / G, h = g * G + (row0 + rr) % G;
+                float z = stats[b * H + h].y;
+                float y = n_sel[b] > 0 ? acc / z : 0.f;
+                elem<T>::store(out + ((size_t)b * H + h) * kHeadDim + c, y);
+            }
+        }
+    }
+}
+
+}  // namespace sals

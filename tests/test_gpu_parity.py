@@ -1,0 +1,203 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by
+element, on seeded synthetic workloads.
+
+Tolerances: selected index sets bit-exact against the oracle's rule applied to the same
+fp32 scores, and against the fp64 oracle wherever its k-th/(k+1)-th score gap exceeds
+1e-3 relative; outputs within max-abs 2e-2 (bf16) / 1e-4 (fp32) and within the tighter
+bound derived in tests/gpu_util.py::out_tolerances.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+from paper_2510_24273_amd import synth  # noqa: E402
+from tests import gpu_util as gu  # noqa: E402
+
+C = synth.CONFIGS
+
+
+def _run(oracle, w, layer=0, seq_lens=None, seqs=None, label=""):
+    print(f"[case] {label or w.name} layer={layer} seq_lens={seq_lens}", flush=True)
+    L = synth.make_layer(w, layer, seq_lens)
+    G = gu.upload(L)
+    ctx = gu.make_ctx(w)
+    R = gu.run_stages(ctx, w, G)
+    # the fused entry point must reproduce the staged calls bit for bit
+    out2 = torch.empty_like(R["out"])
+    idx2 = torch.empty_like(R["idx"])
+    n2 = torch.empty_like(R["n_sel"])
+    ctx.decode_step(G["q"], G["q_pos"], G["Kc"], G["Vc"], G["Uk"], G["Uv"], G["seq_len"], out2,
+                    None, idx2, n2)
+    torch.cuda.synchronize()
+    assert torch.equal(idx2, R["idx"]) and torch.equal(n2, R["n_sel"])
+    assert torch.equal(out2.view(torch.int16) if out2.dtype == torch.bfloat16 else out2,
+                       R["out"].view(torch.int16) if out2.dtype == torch.bfloat16 else R["out"])
+    figs = []
+    for b in (range(w.B) if seqs is None else seqs):
+        figs.append(gu.check_sequence(oracle, w, L, R, b))
+    print("   ", figs[0], flush=True)
+    ctx.close()
+    return L, R, figs
+
+
+# ---- configuration 1: the tiny fp32 case, whole --------------------------------------
+
+def test_cfg1_tiny_f32(oracle):
+    _run(oracle, C["cfg1"])
+
+
+# ---- small cases that span several tiles and ragged tails ----------------------------
+
+SMALL = synth.shrink(C["cfg2"], B=3, S=1000, r=192, top_k=100, n_layers=1, plant=2)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_small_ragged_batch(oracle, dtype):
+    w = synth.shrink(SMALL, dtype=dtype)
+    # full, odd length, shorter than k_tot
+    _run(oracle, w, seq_lens=[1000, 777, 61])
+
+
+def test_empty_and_single_token_sequences(oracle):
+    w = synth.shrink(SMALL, B=4, plant=0)
+    _run(oracle, w, seq_lens=[0, 1, 100, 101])
+
+
+def test_gqa_groups(oracle):
+    for H, H_kv in ((32, 8), (8, 1), (16, 16)):
+        w = synth.shrink(SMALL, H=H, H_kv=H_kv, B=2, S=600)
+        _run(oracle, w, seq_lens=[600, 333], label=f"gqa H={H} H_kv={H_kv}")
+
+
+def test_truncated_scoring_rank(oracle):
+    w = synth.shrink(SMALL, r=256, r_score=128, B=2)
+    _run(oracle, w, seq_lens=[1000, 500])
+    w = synth.shrink(SMALL, r=256, r_score=8, B=1, plant=0)
+    _run(oracle, w)
+
+
+def test_sink_and_recent_window(oracle):
+    w = synth.shrink(SMALL, top_k=432, n_sink=16, n_recent=64, S=2048, B=2)
+    L, R, _ = _run(oracle, w, seq_lens=[2048, 513])
+    idx = gu.from_dev(R["idx"])
+    assert idx[0, :16].tolist() == list(range(16))
+    assert idx[0, -64:].tolist() == list(range(2048 - 64, 2048))
+
+
+def test_interleaved_rope_and_large_theta(oracle):
+    w = synth.shrink(SMALL, rope_style=1, theta=500000.0, B=1)
+    _run(oracle, w)
+
+
+def test_peaky_softmax_stress(oracle):
+    """Caches scaled up so that logits spread over tens of units (near one-hot softmax)."""
+    w = synth.shrink(SMALL, scale=30.0, B=2, plant=0)
+    _run(oracle, w, seq_lens=[1000, 900])
+
+
+def test_exact_ties_resolve_to_smaller_index(oracle):
+    """Duplicate cache rows give bit-equal scores; the cut must keep the smaller indices."""
+    w = synth.shrink(SMALL, B=1, S=512, top_k=64, plant=0)
+    L = synth.make_layer(w)
+    L["Kc"][0, 1::2] = L["Kc"][0, 0::2]          # rows 2m and 2m+1 identical
+    G = gu.upload(L)
+    ctx = gu.make_ctx(w)
+    R = gu.run_stages(ctx, w, G)
+    s = gu.from_dev(R["scores"][0])
+    assert np.array_equal(s[0::2], s[1::2])
+    gu.check_sequence(oracle, w, L, R, 0)
+    # all scores equal: the first top_k tokens win
+    scores = torch.zeros((1, 512), dtype=torch.float32, device=gu.DEV)
+    scores[0, 100] = -0.0
+    idx = torch.empty((1, 64), dtype=torch.int32, device=gu.DEV)
+    n = torch.empty((1,), dtype=torch.int32, device=gu.DEV)
+    ctx.topk_select(scores, G["seq_len"], idx, n)
+    torch.cuda.synchronize()
+    assert sorted(idx[0].tolist()) == list(range(64))
+    ctx.close()
+
+
+def test_compress_append_then_decode(oracle):
+    """Algorithm 1 in order: compress the new token, append, then attend with the query on
+    the appended row (q_pos = seq_len - 1)."""
+    w = synth.shrink(SMALL, B=2, S=400, plant=0)
+    L = synth.make_layer(w, seq_lens=[399, 200])
+    G = gu.upload(L)
+    rng = np.random.default_rng(5)
+    k_new = synth.store(rng.standard_normal((w.B, w.D_kv)), w.dtype)
+    v_new = synth.store(rng.standard_normal((w.B, w.D_kv)), w.dtype)
+    ctx = gu.make_ctx(w)
+    for rep in range(2):           # second call: sequence 0 is full and must be left alone
+        before = G["Kc"].clone()
+        ctx.compress_append(gu.to_dev(k_new), gu.to_dev(v_new), G["Uk"], G["Uv"], G["Kc"], G["Vc"],
+                            G["seq_len"])
+        torch.cuda.synchronize()
+        if rep == 0:
+            assert G["seq_len"].tolist() == [400, 201]
+            for b, row in ((0, 399), (1, 200)):
+                for new, U, cache in ((k_new, "Uk", "Kc"), (v_new, "Uv", "Vc")):
+                    want = oracle.project(synth.widen(new[b]), synth.widen(L[U]))
+                    got = gu.from_dev(G[cache][b, row])
+                    ulp = np.maximum(np.abs(want), 1e-30) * 2.0 ** -7     # one bf16 ulp
+                    assert np.all(np.abs(got - want) <= ulp + 1e-6)
+        else:
+            assert G["seq_len"].tolist() == [400, 202]
+            assert torch.equal(before[0].view(torch.int16), G["Kc"][0].view(torch.int16))
+    # decode with the query sitting on the last appended row
+    L2 = dict(L)
+    for kname in ("Kc", "Vc"):
+        t = G[kname].cpu()
+        L2[kname] = t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+    L2["seq_len"] = G["seq_len"].cpu().numpy()
+    L2["q_pos"] = (L2["seq_len"] - 1).astype(np.int32)
+    G["q_pos"] = gu.to_dev(L2["q_pos"])
+    R = gu.run_stages(ctx, w, G)
+    for b in range(w.B):
+        gu.check_sequence(oracle, w, L2, R, b)
+    ctx.close()
+
+
+def test_repeatable_bit_for_bit(oracle):
+    w = synth.shrink(SMALL, B=2)
+    L = synth.make_layer(w)
+    G = gu.upload(L)
+    ctx = gu.make_ctx(w)
+    first = gu.run_stages(ctx, w, G)
+    for _ in range(5):
+        again = gu.run_stages(ctx, w, G)
+        assert torch.equal(first["scores"], again["scores"])
+        assert torch.equal(first["idx"], again["idx"])
+        assert torch.equal(first["out"].view(torch.int16), again["out"].view(torch.int16))
+    ctx.close()
+
+
+# ---- the measured configurations at full size ----------------------------------------
+
+def test_cfg2_full(oracle):
+    L, R, _ = _run(oracle, C["cfg2"], layer=0)
+    sel = set(gu.from_dev(R["idx"][0]).tolist())
+    assert set(L["planted"][0].tolist()) <= sel
+    _run(oracle, C["cfg2"], layer=17)
+
+
+@pytest.mark.parametrize("name", ["cfg3a", "cfg3b"])
+def test_cfg3_full_sampled_sequences(oracle, name):
+    L, R, _ = _run(oracle, C[name], seqs=[0, 7, 15])
+    for b in (0, 7, 15):
+        assert set(L["planted"][b].tolist()) <= set(gu.from_dev(R["idx"][b]).tolist())
+
+
+def test_cfg4_full_sampled_sequences(oracle):
+    _run(oracle, C["cfg4"], seqs=[0, 3])
+
+
+def test_cfg5_full(oracle):
+    L, R, _ = _run(oracle, C["cfg5"])
+    idx = gu.from_dev(R["idx"][0])
+    S = C["cfg5"].S
+    assert idx[-64:].tolist() == list(range(S - 64, S)) and len(idx) == 4160
