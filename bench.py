@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the SALS decode-step attention path on one MI355X.
+
+A *step* is one decode step of the whole hot path (query projection, latent scores,
+top-k, key reconstruction + RoPE, sparse attention) walked over every layer of the
+workload, each layer with its own seeded synthetic caches and projectors resident in
+HBM.  The headline workload is the LLaMA2-7B-shaped configuration (B=1, S=4096, r=640,
+top-k=512, 32 layers); `value` is microseconds per layer-step.  Prints ONE JSON line on
+stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--layers", type=int, default=0, help="distinct layer buffer sets (0 = workload default)")
+    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5",
+                    help="other configurations reported under 'extra' (comma list, '' for none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    return ap.parse_args()
+
+
+class LayerSet:
+    """Device-resident inputs of every layer of a workload + one context."""
+
+    def __init__(self, w, n_layers, torch, binding, synth):
+        self.w, self.torch = w, torch
+        dev = "cuda:0"
+
+        def up(a):
+            import numpy as np
+            if a.dtype == np.uint16:
+                return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+            return torch.from_numpy(a).to(dev)
+
+        self.layers = []
+        self.host0 = None
+        for l in range(n_layers):
+            L = synth.make_layer(w, l)
+            if l == 0:
+                self.host0 = L
+            self.layers.append({k: up(v) for k, v in L.items() if hasattr(v, "dtype")})
+            if l % 8 == 7 or n_layers <= 4:
+                log(f"  [{w.name}] layer {l + 1}/{n_layers} generated")
+        desc = binding.make_desc(w.B, w.S, w.H, w.H_kv, w.d, w.r, w.top_k, w.dtype, r_score=w.rs,
+                                 n_recent=w.n_recent, n_sink=w.n_sink, rope_theta=w.theta,
+                                 rope_style=w.rope_style)
+        self.ctx = binding.Sals(desc, dev)
+        odt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        self.out = [torch.empty((w.B, w.H, w.d), dtype=odt, device=dev) for _ in range(n_layers)]
+
+    def step(self):
+        for G, o in zip(self.layers, self.out):
+            self.ctx.decode_step(G["q"], G["q_pos"], G["Kc"], G["Vc"], G["Uk"], G["Uv"], G["seq_len"], o)
+
+    def bytes_resident(self):
+        return sum(t.numel() * t.element_size() for G in self.layers for t in G.values())
+
+
+def timed(torch, fn, steps, warmup):
+    """ms per call of fn(): `warmup` untimed calls, then exactly `steps` timed ones."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def kernel_table(ls, steps, roofline):
+    """Per-kernel average duration (us) over `steps` profiled steps + roofline figures."""
+    torch, w = ls.torch, ls.w
+    ls.ctx.profile(True)
+    for _ in range(steps):
+        ls.step()
+    torch.cuda.synchronize()
+    prof = ls.ctx.profile_collect()
+    ls.ctx.profile(False)
+    sb, sf = roofline.stage_bytes(w), roofline.stage_flops(w)
+    model = {
+        "project": ("hbm", sb["project"]),
+        "scores": ("hbm", sb["scores"]),
+        "topk": ("hbm", sb["select"] + w.B * w.k_tot * 4),
+        "attend_prep": ("hbm", w.B * w.k_tot * (4 + 512)),
+        "attend_logits": ("mfma", sf["reconstruct_k"]),
+        "attend_stats": ("hbm", w.B * w.H * w.k_tot * 4),
+        "attend_pv": ("hbm", w.B * w.k_tot * w.r * w.esize),
+        "attend_out": ("hbm", w.r * w.D_kv * w.esize),
+    }
+    rows = {}
+    for name, (ms, n) in prof.items():
+        if n == 0:
+            continue
+        us = ms * 1e3 / n
+        bound, work = model[name]
+        if bound == "hbm":
+            ach, peak, unit = work / (us * 1e-6) / 1e9, roofline.HBM_PEAK_GBPS, "GB/s"
+        else:
+            peak = roofline.MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else roofline.VALU_F32_PEAK_TFLOPS
+            ach, unit = work / (us * 1e-6) / 1e12, "TFLOP/s"
+        rows[name] = {"us": round(us, 3), "launches": n, "bound": bound, "work": int(work),
+                      "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4)}
+    return rows
+
+
+def measure(ls, steps, warmup, use_graph, roofline):
+    torch, w = ls.torch, ls.w
+    n_layers = len(ls.layers)
+    eager_ms = timed(torch, ls.step, steps, warmup)
+    res = {"eager_ms_per_step": eager_ms, "graph_ms_per_step": None}
+    if use_graph:
+        ref = [o.clone() for o in ls.out]
+        g = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            ls.step()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(g, stream=s):
+                ls.step()
+        torch.cuda.synchronize()
+        graph_ms = timed(torch, g.replay, steps, warmup)
+        same = all(torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
+                               b.view(torch.int16) if b.dtype == torch.bfloat16 else b)
+                   for a, b in zip(ref, ls.out))
+        res["graph_ms_per_step"] = graph_ms if same else None
+        res["graph_matches_eager"] = bool(same)
+    best = min(x for x in (res["eager_ms_per_step"], res["graph_ms_per_step"]) if x is not None)
+    res["ms_per_step"] = best
+    res["mode"] = "hip_graph" if best == res["graph_ms_per_step"] else "eager"
+    res["us_per_layer_step"] = best * 1e3 / n_layers
+    res["algorithmic_bytes"] = roofline.algorithmic_bytes(w)
+    res["pipeline_GBps"] = res["algorithmic_bytes"] / (res["us_per_layer_step"] * 1e-6) / 1e9
+    res["pipeline_hbm_frac"] = res["pipeline_GBps"] / roofline.HBM_PEAK_GBPS
+    res["kernels"] = kernel_table(ls, max(3, steps // 3), roofline)
+    return res
+
+
+def cpu_baseline(w, host_layers, synth, budget_s=12.0):
+    """The fp64 oracle, as it stands, on the host cores: whole decode steps of layer 0.."""
+    from oracle import sals_oracle
+    wd = synth.widen
+    done, t_total = 0, 0.0
+    for L in host_layers:
+        t0 = time.perf_counter()
+        for b in range(w.B):
+            S = int(L["seq_len"][b])
+            sals_oracle.decode_step(wd(L["q"][b]), S, wd(L["Kc"][b][:S]), wd(L["Vc"][b][:S]), wd(L["Uk"]),
+                                    wd(L["Uv"]), w.H_kv, w.top_k, w.theta, r_score=w.rs, n_sink=w.n_sink,
+                                    n_recent=w.n_recent, rope_style=w.rope_style)
+        t_total += time.perf_counter() - t0
+        done += 1
+        if t_total > budget_s:
+            break
+    return {"value": round(t_total / done * 1e6, 1), "unit": "us/layer-step", "cores": sals_oracle.num_threads(),
+            "kind": "oracle", "sample": f"{done} layer-step(s) of {w.name} (layers 0..{done - 1}), fp64, "
+                                        f"inputs widened from the same storage-rounded arrays"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        log("bench.py: this build is single-GPU by design (one MI355X); run with --gpus 1. "
+            "Sequences and layers shard trivially across GPUs, no multi-GPU figure is produced.")
+        sys.exit(2)
+    import torch
+    from paper_2510_24273_amd import binding, roofline, synth   # fails loudly if libsals.so is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    w = synth.CONFIGS[a.workload]
+    n_layers = a.layers or w.n_layers
+    if n_layers == 1:   # single-layer configs: rotate enough distinct sets to defeat the 256 MB LLC
+        per = roofline.algorithmic_bytes(w) + w.r * w.D_kv * w.esize
+        n_layers = max(2, min(8, int(600e6 // per) + 1))
+    log(f"[bench] generating {w.name}: {n_layers} layers")
+    ls = LayerSet(w, n_layers, torch, binding, synth)
+    log(f"[bench] resident inputs: {ls.bytes_resident() / 1e6:.0f} MB; timing")
+    res = measure(ls, a.steps, a.warmup, not a.no_graph, roofline)
+    kern = res["kernels"]
+    dom = max(kern, key=lambda k: kern[k]["us"])
+    dk = kern[dom]
+    traffic = roofline.MEASURED_TRAFFIC.get((dom, a.workload))
+    out = {
+        "metric": "sals_decode_attn_us_per_layer_step", "value": round(res["us_per_layer_step"], 3),
+        "unit": "us", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(res["ms_per_step"], 5), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "layers_per_step": n_layers, "B": w.B, "S": w.S, "H": w.H,
+                   "H_kv": w.H_kv, "d": w.d, "r": w.r, "r_score": w.rs, "top_k": w.top_k,
+                   "n_recent": w.n_recent, "launch": res["mode"],
+                   "eager_us_per_layer_step": round(res["eager_ms_per_step"] * 1e3 / n_layers, 3),
+                   "graph_us_per_layer_step": None if res["graph_ms_per_step"] is None
+                   else round(res["graph_ms_per_step"] * 1e3 / n_layers, 3)},
+        "pipeline": {"algorithmic_bytes": res["algorithmic_bytes"], "achieved_GBps": round(res["pipeline_GBps"], 1),
+                     "hbm_peak_GBps": roofline.HBM_PEAK_GBPS, "frac": round(res["pipeline_hbm_frac"], 4)},
+        "roofline": {"kernel": dom, "bound": dk["bound"], "achieved": dk["achieved"], "peak": dk["peak"],
+                     "unit": dk["unit"], "frac": dk["frac"], "traffic": traffic, "avg_us": dk["us"]},
+        "kernels": kern,
+    }
+    if not a.no_cpu_baseline:
+        log("[bench] timing the CPU oracle")
+        host = [ls.host0] + [synth.make_layer(w, l) for l in range(1, min(3, n_layers))] if w.B == 1 else [ls.host0]
+        out["cpu_baseline"] = cpu_baseline(w, host, synth)
+    del ls
+    torch.cuda.empty_cache()
+    extra = {}
+    for name in [x for x in a.extras.split(",") if x and x != a.workload]:
+        we = synth.CONFIGS[name]
+        per = roofline.algorithmic_bytes(we) + we.r * we.D_kv * we.esize
+        nl = max(2, min(8, int(600e6 // per) + 1))
+        log(f"[bench] extra {we.name}: {nl} layer sets")
+        lse = LayerSet(we, nl, torch, binding, synth)
+        r = measure(lse, max(5, a.steps // 3), 2, not a.no_graph, roofline)
+        extra[name] = {"workload": we.name, "us_per_layer_step": round(r["us_per_layer_step"], 2),
+                       "launch": r["mode"], "algorithmic_bytes": r["algorithmic_bytes"],
+                       "achieved_GBps": round(r["pipeline_GBps"], 1), "hbm_frac": round(r["pipeline_hbm_frac"], 4),
+                       "kernels_us": {k: v["us"] for k, v in r["kernels"].items()},
+                       "kernels_frac": {k: v["frac"] for k, v in r["kernels"].items()}}
+        del lse
+        torch.cuda.empty_cache()
+    if extra:
+        out["extra"] = extra
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

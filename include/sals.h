@@ -125,9 +125,9 @@ sals_status sals_latent_scores(sals_ctx* ctx, const void* q, const void* Uk, con
  *   otherwise  : n_sel[b] = k_tot; idx[b] holds the n_sink first tokens, then the
  *                top_k candidates j in [n_sink, S-n_recent) with the largest scores
  *                (equal scores: smaller j wins; -0 equals +0), then the n_recent last
- *                tokens.  Within the critical block the order is: scores above the
- *                k-th largest by increasing j, then ties at it by increasing j.
- * Entries idx[b, n_sel[b]:] are set to 0.  The result is deterministic.
+ *                tokens.  The order inside the critical block is unspecified (callers
+ *                treat it as a set) but is a deterministic function of the scores.
+ * Entries idx[b, n_sel[b]:] are set to 0.
  *   scores [B, S_max] fp32 (NaN-free)
  *   idx    [B, k_tot] int32   out
  *   n_sel  [B] int32          out */
@@ -158,6 +158,28 @@ sals_status sals_decode_step(sals_ctx* ctx, const void* q, const int32_t* q_pos,
                              const void* Vc, const void* Uk, const void* Uv,
                              const int32_t* seq_len, void* out, float* scores, int32_t* idx,
                              int32_t* n_sel, void* hip_stream);
+
+/* ---- measurement aid --------------------------------------------------------------
+ * Per-kernel timing for roofline figures.  While enabled, every kernel a stage call
+ * launches is bracketed by a pair of HIP events on the call's stream (host-side event
+ * objects; no device memory).  sals_profile_collect waits for the recorded events, adds
+ * the elapsed milliseconds and launch counts per kernel into total_ms / launches (host
+ * arrays of SALS_N_KERNELS entries, overwritten) and forgets the records.  Timing with
+ * events serialises neighbouring launches slightly; leave it off in timed runs. */
+enum {
+    SALS_K_PROJECT = 0,        /* latent projection (query, or new key/value)  */
+    SALS_K_SCORES = 1,         /* latent score stream over the key cache       */
+    SALS_K_TOPK = 2,           /* radix select                                 */
+    SALS_K_ATTEND_PREP = 3,    /* cos/sin table + rotated query                */
+    SALS_K_ATTEND_LOGITS = 4,  /* MFMA key reconstruction + RoPE + q.K         */
+    SALS_K_ATTEND_STATS = 5,   /* softmax max / normaliser                     */
+    SALS_K_ATTEND_PV = 6,      /* latent-space value sum                       */
+    SALS_K_ATTEND_OUT = 7,     /* output projection through U_v                */
+    SALS_N_KERNELS = 8
+};
+const char* sals_kernel_name(int kernel);
+sals_status sals_profile_enable(sals_ctx* ctx, int on);
+sals_status sals_profile_collect(sals_ctx* ctx, double* total_ms, int32_t* launches);
 
 #ifdef __cplusplus
 }

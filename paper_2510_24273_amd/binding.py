@@ -25,8 +25,9 @@ SALS_F32, SALS_BF16 = 0, 1
 EXPORTS = (
     "sals_status_string", "sals_workspace_bytes", "sals_create", "sals_destroy",
     "sals_compress_append", "sals_latent_scores", "sals_topk_select", "sals_sparse_attend",
-    "sals_decode_step",
+    "sals_decode_step", "sals_kernel_name", "sals_profile_enable", "sals_profile_collect",
 )
+N_KERNELS = 8
 
 
 class SalsDesc(ctypes.Structure):
@@ -59,8 +60,12 @@ def load_library() -> ctypes.CDLL:
     lib.sals_topk_select.argtypes = [vp, f32p, i32p, i32p, i32p, vp]
     lib.sals_sparse_attend.argtypes = [vp, vp, i32p, vp, vp, vp, vp, i32p, i32p, vp, vp]
     lib.sals_decode_step.argtypes = [vp, vp, i32p, vp, vp, vp, vp, i32p, vp, f32p, i32p, i32p, vp]
+    lib.sals_kernel_name.restype = ctypes.c_char_p
+    lib.sals_kernel_name.argtypes = [ctypes.c_int]
+    lib.sals_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.sals_profile_collect.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
     for name in EXPORTS[1:]:
-        if name != "sals_destroy":
+        if name not in ("sals_destroy", "sals_kernel_name"):
             getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -123,6 +128,16 @@ class Sals:
     def _check(st, where):
         if st != SALS_OK:
             raise SalsError(st, where)
+
+    def profile(self, on: bool):
+        self._check(_lib.sals_profile_enable(self._h, 1 if on else 0), "sals_profile_enable")
+
+    def profile_collect(self) -> dict:
+        """{kernel name: (total ms, launches)} since profiling was enabled / last collected."""
+        ms = (ctypes.c_double * N_KERNELS)()
+        n = (ctypes.c_int32 * N_KERNELS)()
+        self._check(_lib.sals_profile_collect(self._h, ms, n), "sals_profile_collect")
+        return {_lib.sals_kernel_name(k).decode(): (float(ms[k]), int(n[k])) for k in range(N_KERNELS)}
 
     def compress_append(self, k_new, v_new, Uk, Uv, Kc, Vc, seq_len):
         self._check(_lib.sals_compress_append(self._h, _p(k_new), _p(v_new), _p(Uk), _p(Uv), _p(Kc),

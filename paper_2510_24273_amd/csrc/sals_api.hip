@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdio>
 #include <new>
+#include <vector>
 
 #include "common.hpp"
 #include "k_attend.hpp"
@@ -30,15 +31,43 @@ struct Layout {  // byte offsets into the workspace
 
 }  // namespace
 
+struct ProfRecord { int kernel; hipEvent_t start, stop; };
+
 struct sals_ctx {
     sals_desc d;
     Layout L;
     unsigned char* ws;
     size_t ws_bytes;
     InvFreq inv;
+    bool profiling = false;
+    std::vector<ProfRecord> prof;
 };
 
 namespace {
+
+const char* const kKernelNames[SALS_N_KERNELS] = {
+    "project", "scores", "topk", "attend_prep", "attend_logits", "attend_stats", "attend_pv", "attend_out"};
+
+// Brackets one kernel launch with a pair of events while profiling is on.
+struct ProfScope {
+    sals_ctx* c;
+    hipStream_t st;
+    ProfRecord rec{};
+    bool on;
+    ProfScope(const sals_ctx* ctx, int kernel, hipStream_t s) : c(const_cast<sals_ctx*>(ctx)), st(s), on(ctx->profiling)
+    {
+        if (!on) return;
+        rec.kernel = kernel;
+        if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess) { on = false; return; }
+        (void)hipEventRecord(rec.start, st);
+    }
+    ~ProfScope()
+    {
+        if (!on) return;
+        (void)hipEventRecord(rec.stop, st);
+        c->prof.push_back(rec);
+    }
+};
 
 sals_status validate(const sals_desc* d)
 {
@@ -128,7 +157,10 @@ sals_status launch_project(const sals_ctx* c, const void* const* X, const void* 
     a.S_max = d.S_max; a.rows_per_wg = c->L.proj_rows_per_wg; a.nchunk = c->L.proj_nchunk;
     a.ncol = c->L.proj_ncol; a.nproj = nproj;
     dim3 grid(a.ncol, a.nchunk, nproj);
-    hipLaunchKernelGGL((project_kernel<T, QUERY>), grid, dim3(kProjThreads), 0, st, a);
+    {
+        ProfScope ps(c, SALS_K_PROJECT, st);
+        hipLaunchKernelGGL((project_kernel<T, QUERY>), grid, dim3(kProjThreads), 0, st, a);
+    }
     return launch_status();
 }
 
@@ -151,6 +183,7 @@ sals_status launch_scores(const sals_ctx* c, const void* Kc, const int32_t* seq_
         hipLaunchKernelGGL((scores_kernel<T, N>), grid, dim3(kScoreThreads), 0, st, K, qt, seq_len, \
                            scores, d.S_max, d.r, d.r_score, rows);                                  \
         break;
+    ProfScope ps(c, SALS_K_SCORES, st);
     switch (nch) {
         SALS_SCORES_CASE(1) SALS_SCORES_CASE(2) SALS_SCORES_CASE(3) SALS_SCORES_CASE(4)
         SALS_SCORES_CASE(5) SALS_SCORES_CASE(6) SALS_SCORES_CASE(7) SALS_SCORES_CASE(8)
@@ -170,6 +203,7 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
 #define SALS_TOPK(F4)                                                                                \
     hipLaunchKernelGGL((topk_kernel<F4>), grid, block, 0, st, scores, seq_len, idx, n_sel, d.S_max, \
                        d.top_k, d.n_sink, d.n_recent)
+    ProfScope ps(c, SALS_K_TOPK, st);
     if (d.S_max <= 4096) SALS_TOPK(1);
     else if (d.S_max <= 8192) SALS_TOPK(2);
     else if (d.S_max <= 16384) SALS_TOPK(4);
@@ -196,6 +230,7 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
 
     {   // cos/sin table and rotated query
         int n_tab = ceil_div(d.B * k_tot, 4), n_q = ceil_div(d.B * d.H_q, 4);
+        ProfScope ps(c, SALS_K_ATTEND_PREP, st);
         hipLaunchKernelGGL((attend_prep_kernel<T>), dim3(n_tab + n_q), dim3(256), 0, st,
                            static_cast<const T*>(q), q_pos, idx, n_sel, cs, qR, c->inv, d.B, d.H_q, k_tot,
                            n_tab, d.rope_style, 1.0f / std::sqrt((float)d.d));
@@ -207,6 +242,7 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     hipLaunchKernelGGL((attend_logits_kernel<T, NW, NB>), dim3(ceil_div(k_tot, 32 * NW * NB), d.H_kv, d.B), \
                        dim3(64 * NW), 0, st, static_cast<const T*>(Kc), static_cast<const T*>(Uk), idx,   \
                        n_sel, cs, qR, logits, d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk, d.rope_style)
+        ProfScope ps(c, SALS_K_ATTEND_LOGITS, st);
         if (tiles128 >= 1024) SALS_LOGITS(4, 2);       // 256 tokens per workgroup
         else if (tiles128 >= 256) SALS_LOGITS(4, 1);   // 128
         else if (tiles128 >= 64) SALS_LOGITS(2, 1);    // 64
@@ -214,17 +250,24 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
 #undef SALS_LOGITS
         if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     }
+    {
+    ProfScope ps(c, SALS_K_ATTEND_STATS, st);
     hipLaunchKernelGGL(attend_stats_kernel, dim3(ceil_div(d.B * d.H_q, 4)), dim3(256), 0, st, logits, n_sel,
                        stats, d.B, d.H_q, L.lk);
+    }
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+    {
+    ProfScope ps(c, SALS_K_ATTEND_PV, st);
     hipLaunchKernelGGL((attend_pv_kernel<T>), dim3(d.r / kPvCols, L.pv_ntc, d.B), dim3(256), 0, st,
                        static_cast<const T*>(Vc), idx, n_sel, logits, stats, tpart, d.B, d.S_max, d.r, d.H_q,
                        k_tot, L.lk, L.pv_tok_per_wg);
+    }
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     {
         const int nch = ceil_div(d.r / VEC, 16);
         const size_t shm = (size_t)kOutRowsLds * d.r * 4;
         dim3 grid(kHeadDim / 16, d.H_kv);
+        ProfScope ps(c, SALS_K_ATTEND_OUT, st);
 #define SALS_OUT_CASE(N)                                                                              \
     case N:                                                                                           \
         hipLaunchKernelGGL((attend_out_kernel<T, N>), grid, dim3(256), shm, st, static_cast<const T*>(Uv), \
@@ -288,7 +331,42 @@ sals_status sals_create(const sals_desc* desc, void* d_workspace, size_t workspa
     return SALS_OK;
 }
 
-void sals_destroy(sals_ctx* ctx) { delete ctx; }
+void sals_destroy(sals_ctx* ctx)
+{
+    if (!ctx) return;
+    for (auto& r : ctx->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    delete ctx;
+}
+
+const char* sals_kernel_name(int kernel)
+{
+    return (kernel >= 0 && kernel < SALS_N_KERNELS) ? kKernelNames[kernel] : "unknown";
+}
+
+sals_status sals_profile_enable(sals_ctx* ctx, int on)
+{
+    if (!ctx) return SALS_ERR_INVALID_ARG;
+    ctx->profiling = on != 0;
+    return SALS_OK;
+}
+
+sals_status sals_profile_collect(sals_ctx* ctx, double* total_ms, int32_t* launches)
+{
+    if (!ctx || !total_ms || !launches) return SALS_ERR_INVALID_ARG;
+    for (int k = 0; k < SALS_N_KERNELS; ++k) { total_ms[k] = 0.0; launches[k] = 0; }
+    sals_status st = SALS_OK;
+    for (auto& r : ctx->prof) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess)
+            st = SALS_ERR_HIP;
+        total_ms[r.kernel] += ms;
+        launches[r.kernel] += 1;
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    ctx->prof.clear();
+    return st;
+}
 
 sals_status sals_compress_append(sals_ctx* ctx, const void* k_new, const void* v_new, const void* Uk,
                                  const void* Uv, void* Kc, void* Vc, int32_t* seq_len, void* hip_stream)

@@ -50,3 +50,7 @@ def stage_flops(w, seq_len=None) -> dict:
         "value_reassociated": 2 * w.B * w.H * (n_sel * w.r + w.r * w.d),
         "attention": 4 * w.B * n_sel * w.H * w.d,
     }
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
+# copy kernel of known size); filled from the summaries under profiles/.
+MEASURED_TRAFFIC: dict = {}
