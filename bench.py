@@ -52,25 +52,28 @@ class LayerSet:
                 return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
             return torch.from_numpy(a).to(dev)
 
+        desc = binding.make_desc(w.B, w.S, w.H, w.H_kv, w.d, w.r, w.top_k, w.dtype, r_score=w.rs,
+                                 n_recent=w.n_recent, n_sink=w.n_sink, rope_theta=w.theta,
+                                 rope_style=w.rope_style)
+        self.ctx = binding.Sals(desc, dev)
         self.layers = []
         self.host0 = None
         for l in range(n_layers):
             L = synth.make_layer(w, l)
             if l == 0:
                 self.host0 = L
-            self.layers.append({k: up(v) for k, v in L.items() if hasattr(v, "dtype")})
+            G = {k: up(v) for k, v in L.items() if hasattr(v, "dtype")}
+            G["W"] = self.ctx.pack_weights(G.pop("Uk"), G.pop("Uv"))   # one-time repack, as at model load
+            self.layers.append(G)
             if l % 8 == 7 or n_layers <= 4:
                 log(f"  [{w.name}] layer {l + 1}/{n_layers} generated")
-        desc = binding.make_desc(w.B, w.S, w.H, w.H_kv, w.d, w.r, w.top_k, w.dtype, r_score=w.rs,
-                                 n_recent=w.n_recent, n_sink=w.n_sink, rope_theta=w.theta,
-                                 rope_style=w.rope_style)
-        self.ctx = binding.Sals(desc, dev)
+        torch.cuda.synchronize()
         odt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
         self.out = [torch.empty((w.B, w.H, w.d), dtype=odt, device=dev) for _ in range(n_layers)]
 
     def step(self):
         for G, o in zip(self.layers, self.out):
-            self.ctx.decode_step(G["q"], G["q_pos"], G["Kc"], G["Vc"], G["Uk"], G["Uv"], G["seq_len"], o)
+            self.ctx.decode_step(G["q"], G["q_pos"], G["Kc"], G["Vc"], G["W"], G["seq_len"], o)
 
     def bytes_resident(self):
         return sum(t.numel() * t.element_size() for G in self.layers for t in G.values())
@@ -104,7 +107,7 @@ def kernel_table(ls, steps, roofline):
         "topk": ("hbm", sb["select"] + w.B * w.k_tot * 4),
         "attend_prep": ("hbm", w.B * w.k_tot * (4 + 512)),
         "attend_logits": ("mfma", sf["reconstruct_k"]),
-        "attend_stats": ("hbm", w.B * w.H * w.k_tot * 4),
+        "attend_softmax": ("hbm", w.B * w.H * w.k_tot * 8),
         "attend_pv": ("hbm", w.B * w.k_tot * w.r * w.esize),
         "attend_out": ("hbm", w.r * w.D_kv * w.esize),
     }

@@ -16,9 +16,9 @@
  *   the descriptor, the context handle and out-parameters of the sizing / create
  *   calls are host pointers.  Data pointers must be 16-byte aligned.
  * Ownership.  The caller allocates and frees every device buffer, including the
- *   workspace.  The library never allocates or frees device memory and keeps no
- *   device pointer beyond a call, except the workspace handed to sals_create,
- *   which must stay valid until sals_destroy.
+ *   workspace and the packed weights.  The library never allocates or frees
+ *   device memory and keeps no device pointer beyond a call, except the workspace
+ *   handed to sals_create, which must stay valid until sals_destroy.
  * Layout.  All arrays are dense and row-major.  Element type `T` is the
  *   descriptor's storage type: 32-bit float, or bfloat16 (upper 16 bits of a
  *   float, round-to-nearest-even).  Token t of a sequence has RoPE position t.
@@ -26,6 +26,9 @@
  *   own orientation, [D_kv x r] with D_kv = H_kv*d: row c holds the r latent
  *   coefficients of stacked key (value) channel c.  Down-projection is U^T x,
  *   up-projection (reconstruction) is U x~.  Nothing assumes orthonormality.
+ *   The projectors are fixed after calibration, so the decode calls read them from
+ *   a packed copy `W` that sals_pack_weights makes once per layer (transposed
+ *   copies for the projections, a matrix-core tile order for the reconstruction).
  * Asynchrony.  Each call only enqueues kernels on `hip_stream` (a hipStream_t
  *   passed as void*, NULL = the default stream) and returns; nothing synchronises
  *   and no device data is read on the host.  Calls that share one context must be
@@ -59,8 +62,8 @@ enum { SALS_ROPE_HALF = 0,        /* pair (i, i+d/2) */
 /* Problem descriptor (plain data, host memory).
  * Supported by the kernels: d == 128; r a multiple of 64, 64 <= r <= 1024;
  * r_score a multiple of 8, 8 <= r_score <= r; H_q a multiple of H_kv with
- * H_q/H_kv <= 8; B >= 1; 1 <= S_max <= 2^24; top_k >= 1; n_sink, n_recent >= 0;
- * top_k + n_sink + n_recent <= 65536. */
+ * H_q/H_kv <= 8 and H_q <= 64; B >= 1 with B*(H_q/H_kv) <= 128; 1 <= S_max <= 2^24;
+ * top_k >= 1; n_sink, n_recent >= 0; top_k + n_sink + n_recent <= 65536. */
 typedef struct {
     int32_t B;          /* sequences per call                                         */
     int32_t S_max;      /* row capacity of each sequence's latent caches              */
@@ -88,23 +91,35 @@ sals_status sals_workspace_bytes(const sals_desc* desc, size_t* bytes);
 /* Validate `desc`, bind the caller's device workspace (256-byte aligned, at least
  * sals_workspace_bytes) and return a context in *out.  The workspace must be
  * zero-filled once by the caller before the first call that uses the context
- * (the kernels keep their counters at zero afterwards).  Host-only, allocates
- * only host memory. */
+ * (kept as a requirement so that later versions may hold counters there).
+ * Host-only, allocates only host memory. */
 sals_status sals_create(const sals_desc* desc, void* d_workspace, size_t workspace_bytes,
                         sals_ctx** out);
 void sals_destroy(sals_ctx* ctx);
+
+/* Bytes of one layer's packed projectors (4 * D_kv * r elements of T).  Host-only. */
+sals_status sals_packed_weight_bytes(const sals_desc* desc, size_t* bytes);
+
+/* One-time repacking of a layer's projectors (Sec. 4.2: they are computed offline and
+ * never change), outside the decode path.  Writes into `W` (caller-allocated,
+ * 256-byte aligned, sals_packed_weight_bytes): Uk^T and Uv^T [r, D_kv] for the
+ * projections, Uk in the tile order of the reconstruction kernel with each head's
+ * channels in RoPE pair order (the descriptor's rope_style), and Uv unchanged.
+ *   Uk, Uv [D_kv, r] T   (may be freed once the call has completed on the stream) */
+sals_status sals_pack_weights(sals_ctx* ctx, const void* Uk, const void* Uv, void* W,
+                              void* hip_stream);
 
 /* Stage 1, latent compression of the new token (Eq. 1; Algorithm 1, projection and
  * append steps):  k~ = Uk^T k_new, v~ = Uv^T v_new, rounded to T and written to
  * row seq_len[b] of Kc[b] / Vc[b]; then seq_len[b] += 1.  A sequence whose cache is
  * full (seq_len[b] >= S_max) is left untouched.
  *   k_new, v_new [B, D_kv] T   pre-RoPE key / value of the new token
- *   Uk, Uv       [D_kv, r] T
+ *   W                          packed projectors of this layer
  *   Kc, Vc       [B, S_max, r] T   in/out
  *   seq_len      [B] int32         in/out (device) */
 sals_status sals_compress_append(sals_ctx* ctx, const void* k_new, const void* v_new,
-                                 const void* Uk, const void* Uv, void* Kc, void* Vc,
-                                 int32_t* seq_len, void* hip_stream);
+                                 const void* W, void* Kc, void* Vc, int32_t* seq_len,
+                                 void* hip_stream);
 
 /* Stage 2a, query projection and latent scores (Sec. 4.3; Algorithm 1, score step):
  *   q~ = Uk^T (sum of the query heads of each KV group, stacked)     [r], fp32
@@ -115,7 +130,7 @@ sals_status sals_compress_append(sals_ctx* ctx, const void* k_new, const void* v
  *   Kc      [B, S_max, r] T
  *   seq_len [B] int32
  *   scores  [B, S_max] fp32    out */
-sals_status sals_latent_scores(sals_ctx* ctx, const void* q, const void* Uk, const void* Kc,
+sals_status sals_latent_scores(sals_ctx* ctx, const void* q, const void* W, const void* Kc,
                                const int32_t* seq_len, float* scores, void* hip_stream);
 
 /* Stage 2b, critical-token selection (Algorithm 1, TopK step; composition with sink
@@ -144,10 +159,10 @@ sals_status sals_topk_select(sals_ctx* ctx, const float* scores, const int32_t* 
  * logits and softmax are fp32; the value product is evaluated in the exact
  * re-associated order  ((p . V~_C) . Uv^T)  and rounded once to T.  If
  * n_sel[b] == 0, out[b] is zero.
- *   q [B,H_q,d] T;  q_pos [B] int32;  Kc, Vc [B,S_max,r] T;  Uk, Uv [D_kv,r] T
+ *   q [B,H_q,d] T;  q_pos [B] int32;  Kc, Vc [B,S_max,r] T;  W packed projectors
  *   idx [B,k_tot] int32;  n_sel [B] int32;  out [B,H_q,d] T */
 sals_status sals_sparse_attend(sals_ctx* ctx, const void* q, const int32_t* q_pos,
-                               const void* Kc, const void* Vc, const void* Uk, const void* Uv,
+                               const void* Kc, const void* Vc, const void* W,
                                const int32_t* idx, const int32_t* n_sel, void* out,
                                void* hip_stream);
 
@@ -155,9 +170,8 @@ sals_status sals_sparse_attend(sals_ctx* ctx, const void* q, const int32_t* q_po
  * sals_topk_select, sals_sparse_attend.  `scores`, `idx`, `n_sel` may each be NULL,
  * in which case that intermediate lives in the workspace. */
 sals_status sals_decode_step(sals_ctx* ctx, const void* q, const int32_t* q_pos, const void* Kc,
-                             const void* Vc, const void* Uk, const void* Uv,
-                             const int32_t* seq_len, void* out, float* scores, int32_t* idx,
-                             int32_t* n_sel, void* hip_stream);
+                             const void* Vc, const void* W, const int32_t* seq_len, void* out,
+                             float* scores, int32_t* idx, int32_t* n_sel, void* hip_stream);
 
 /* ---- measurement aid --------------------------------------------------------------
  * Per-kernel timing for roofline figures.  While enabled, every kernel a stage call
@@ -172,7 +186,7 @@ enum {
     SALS_K_TOPK = 2,           /* radix select                                 */
     SALS_K_ATTEND_PREP = 3,    /* cos/sin table + rotated query                */
     SALS_K_ATTEND_LOGITS = 4,  /* MFMA key reconstruction + RoPE + q.K         */
-    SALS_K_ATTEND_STATS = 5,   /* softmax max / normaliser                     */
+    SALS_K_ATTEND_SOFTMAX = 5, /* softmax weights over the selected tokens     */
     SALS_K_ATTEND_PV = 6,      /* latent-space value sum                       */
     SALS_K_ATTEND_OUT = 7,     /* output projection through U_v                */
     SALS_N_KERNELS = 8

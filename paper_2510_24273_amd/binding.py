@@ -26,6 +26,7 @@ EXPORTS = (
     "sals_status_string", "sals_workspace_bytes", "sals_create", "sals_destroy",
     "sals_compress_append", "sals_latent_scores", "sals_topk_select", "sals_sparse_attend",
     "sals_decode_step", "sals_kernel_name", "sals_profile_enable", "sals_profile_collect",
+    "sals_packed_weight_bytes", "sals_pack_weights",
 )
 N_KERNELS = 8
 
@@ -55,11 +56,13 @@ def load_library() -> ctypes.CDLL:
     lib.sals_create.argtypes = [ctypes.POINTER(SalsDesc), vp, ctypes.c_size_t, ctypes.POINTER(vp)]
     lib.sals_destroy.argtypes = [vp]
     lib.sals_destroy.restype = None
-    lib.sals_compress_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, vp]
+    lib.sals_packed_weight_bytes.argtypes = [ctypes.POINTER(SalsDesc), ctypes.POINTER(ctypes.c_size_t)]
+    lib.sals_pack_weights.argtypes = [vp, vp, vp, vp, vp]
+    lib.sals_compress_append.argtypes = [vp, vp, vp, vp, vp, vp, i32p, vp]
     lib.sals_latent_scores.argtypes = [vp, vp, vp, vp, i32p, f32p, vp]
     lib.sals_topk_select.argtypes = [vp, f32p, i32p, i32p, i32p, vp]
-    lib.sals_sparse_attend.argtypes = [vp, vp, i32p, vp, vp, vp, vp, i32p, i32p, vp, vp]
-    lib.sals_decode_step.argtypes = [vp, vp, i32p, vp, vp, vp, vp, i32p, vp, f32p, i32p, i32p, vp]
+    lib.sals_sparse_attend.argtypes = [vp, vp, i32p, vp, vp, vp, i32p, i32p, vp, vp]
+    lib.sals_decode_step.argtypes = [vp, vp, i32p, vp, vp, vp, i32p, vp, f32p, i32p, i32p, vp]
     lib.sals_kernel_name.restype = ctypes.c_char_p
     lib.sals_kernel_name.argtypes = [ctypes.c_int]
     lib.sals_profile_enable.argtypes = [vp, ctypes.c_int]
@@ -89,6 +92,14 @@ def workspace_bytes(desc: SalsDesc) -> int:
     st = _lib.sals_workspace_bytes(ctypes.byref(desc), ctypes.byref(n))
     if st != SALS_OK:
         raise SalsError(st, "sals_workspace_bytes")
+    return int(n.value)
+
+
+def packed_weight_bytes(desc: SalsDesc) -> int:
+    n = ctypes.c_size_t(0)
+    st = _lib.sals_packed_weight_bytes(ctypes.byref(desc), ctypes.byref(n))
+    if st != SALS_OK:
+        raise SalsError(st, "sals_packed_weight_bytes")
     return int(n.value)
 
 
@@ -139,23 +150,29 @@ class Sals:
         self._check(_lib.sals_profile_collect(self._h, ms, n), "sals_profile_collect")
         return {_lib.sals_kernel_name(k).decode(): (float(ms[k]), int(n[k])) for k in range(N_KERNELS)}
 
-    def compress_append(self, k_new, v_new, Uk, Uv, Kc, Vc, seq_len):
-        self._check(_lib.sals_compress_append(self._h, _p(k_new), _p(v_new), _p(Uk), _p(Uv), _p(Kc),
-                                              _p(Vc), _p(seq_len), _stream()), "sals_compress_append")
+    def pack_weights(self, Uk, Uv):
+        """One-time repacking of a layer's projectors; returns the packed device buffer W."""
+        W = torch.empty(packed_weight_bytes(self.desc), dtype=torch.uint8, device=self.device)
+        self._check(_lib.sals_pack_weights(self._h, _p(Uk), _p(Uv), _p(W), _stream()), "sals_pack_weights")
+        return W
 
-    def latent_scores(self, q, Uk, Kc, seq_len, scores):
-        self._check(_lib.sals_latent_scores(self._h, _p(q), _p(Uk), _p(Kc), _p(seq_len), _p(scores),
+    def compress_append(self, k_new, v_new, W, Kc, Vc, seq_len):
+        self._check(_lib.sals_compress_append(self._h, _p(k_new), _p(v_new), _p(W), _p(Kc), _p(Vc),
+                                              _p(seq_len), _stream()), "sals_compress_append")
+
+    def latent_scores(self, q, W, Kc, seq_len, scores):
+        self._check(_lib.sals_latent_scores(self._h, _p(q), _p(W), _p(Kc), _p(seq_len), _p(scores),
                                             _stream()), "sals_latent_scores")
 
     def topk_select(self, scores, seq_len, idx, n_sel):
         self._check(_lib.sals_topk_select(self._h, _p(scores), _p(seq_len), _p(idx), _p(n_sel),
                                           _stream()), "sals_topk_select")
 
-    def sparse_attend(self, q, q_pos, Kc, Vc, Uk, Uv, idx, n_sel, out):
-        self._check(_lib.sals_sparse_attend(self._h, _p(q), _p(q_pos), _p(Kc), _p(Vc), _p(Uk), _p(Uv),
-                                            _p(idx), _p(n_sel), _p(out), _stream()), "sals_sparse_attend")
+    def sparse_attend(self, q, q_pos, Kc, Vc, W, idx, n_sel, out):
+        self._check(_lib.sals_sparse_attend(self._h, _p(q), _p(q_pos), _p(Kc), _p(Vc), _p(W), _p(idx),
+                                            _p(n_sel), _p(out), _stream()), "sals_sparse_attend")
 
-    def decode_step(self, q, q_pos, Kc, Vc, Uk, Uv, seq_len, out, scores=None, idx=None, n_sel=None):
-        self._check(_lib.sals_decode_step(self._h, _p(q), _p(q_pos), _p(Kc), _p(Vc), _p(Uk), _p(Uv),
-                                          _p(seq_len), _p(out), _p(scores), _p(idx), _p(n_sel),
-                                          _stream()), "sals_decode_step")
+    def decode_step(self, q, q_pos, Kc, Vc, W, seq_len, out, scores=None, idx=None, n_sel=None):
+        self._check(_lib.sals_decode_step(self._h, _p(q), _p(q_pos), _p(Kc), _p(Vc), _p(W), _p(seq_len),
+                                          _p(out), _p(scores), _p(idx), _p(n_sel), _stream()),
+                    "sals_decode_step")

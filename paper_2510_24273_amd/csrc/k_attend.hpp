@@ -13,8 +13,9 @@
 // order, which avoids reconstructing V_C.
 //
 // Head dims are handled in "pair order": slot p < 64 is the first element of RoPE pair
-// p, slot 64+p its partner, for either pairing style; the rows of U_k are fetched in
-// that order, so both elements of a pair land in the same lane of the MFMA result.
+// p, slot 64+p its partner, for either pairing style; the packed U_k panel (see
+// pack_weights_kernel) already has its rows in that order, so both elements of a pair land
+// in the same lane of the MFMA result.
 #pragma once
 #include "common.hpp"
 
@@ -95,9 +96,9 @@ template <> struct mma_op<float> {   // four v_mfma_f32_32x32x2_f32 per 16-byte 
 // from global memory to registers (private to a wave).
 template <typename T, int NW, int NB>
 __global__ __launch_bounds__(64 * NW) void attend_logits_kernel(
-    const T* __restrict__ Kc, const T* __restrict__ Uk, const int32_t* __restrict__ idx,
+    const T* __restrict__ Kc, const T* __restrict__ UkP, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ n_sel, const float2* __restrict__ cs, const float* __restrict__ qR,
-    float* __restrict__ logits, int S_max, int r, int H, int H_kv, int k_tot, int lk, int style)
+    float* __restrict__ logits, int S_max, int r, int H, int H_kv, int k_tot, int lk)
 {
     constexpr int NT = 64 * NW;
     constexpr int TOK = 32 * NB * NW;
@@ -134,7 +135,8 @@ __global__ __launch_bounds__(64 * NW) void attend_logits_kernel(
     for (int i = 0; i < APT; ++i) {
         int qd = tid + i * NT;
         int row = qd >> 3, pc = qd & 7;
-        ap[i] = reinterpret_cast<const unsigned char*>(Uk + ((size_t)g * kHeadDim + slot_to_dim(row, style)) * r) + pc * 16;
+        // packed panel: [g][latent step][128 slots][128 bytes], head dims already in pair order
+        ap[i] = reinterpret_cast<const unsigned char*>(UkP + (size_t)g * kHeadDim * r) + row * kChunkBytes + pc * 16;
         a_lds[i] = row * kLdsRowBytes + pc * 16;
     }
 
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(64 * NW) void attend_logits_kernel(
         if (more) {
             const int off = (kc + 1) * kChunkBytes;
 #pragma unroll
-            for (int i = 0; i < APT; ++i) areg[i] = ld16(ap[i] + off);
+            for (int i = 0; i < APT; ++i) areg[i] = ld16(ap[i] + (size_t)(kc + 1) * 128 * kChunkBytes);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
@@ -237,156 +239,81 @@ __global__ __launch_bounds__(64 * NW) void attend_logits_kernel(
 }
 
 // ---------------------------------------------------------------------------------
-// softmax statistics: one wave per (sequence, head)
+// softmax over the selected tokens (Eq. 5): one workgroup per (sequence, head) row turns
+// the logits into normalised weights stored for the matrix cores: a bf16 head plane and
+// a bf16 remainder plane (fp32 storage: one fp32 plane), zero past the selected tokens.
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attend_stats_kernel(const float* __restrict__ logits,
-                                                           const int32_t* __restrict__ n_sel,
-                                                           float2* __restrict__ stats, int B, int H, int lk)
-{
-    const int bh = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (bh >= B * H) return;
-    const int lane = lane_id();
-    const int n = n_sel[bh / H];
-    const float* l = logits + (size_t)bh * lk;
-    float m = -INFINITY;
-    for (int j = lane; j < n; j += kWave) m = fmaxf(m, l[j]);
-    m = wave_max(m);
-    float z = 0.f;
-    for (int j = lane; j < n; j += kWave) z += __expf(l[j] - m);
-    z = wave_sum(z);
-    if (lane == 0) stats[bh] = make_float2(m, z);
-}
+constexpr int kSmThreads = 256;
+constexpr int kSmBatch = 8;  // values per thread per round; the first round stays in registers
 
-// ---------------------------------------------------------------------------------
-// latent-space value sum: Tpart[tc][b][h][i] = sum_{j in token chunk tc} e^{l_hj - m_h} V~[C_j][i]
-// ---------------------------------------------------------------------------------
-constexpr int kPvCols = 64;      // latent columns per workgroup
-constexpr int kPvTok = 128;      // tokens staged per step
-constexpr int kPvMaxHeads = 64;  // H_q limit of this kernel
+__device__ __forceinline__ float block_reduce_256(float v, float* sh, bool is_max)
+{
+    v = is_max ? wave_max(v) : wave_sum(v);
+    __syncthreads();
+    if (lane_id() == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float a = sh[0], b = sh[1], c = sh[2], d = sh[3];
+    return is_max ? fmaxf(fmaxf(a, b), fmaxf(c, d)) : (a + b) + (c + d);
+}
 
 template <typename T>
-__global__ __launch_bounds__(256) void attend_pv_kernel(const T* __restrict__ Vc,
-                                                        const int32_t* __restrict__ idx,
-                                                        const int32_t* __restrict__ n_sel,
-                                                        const float* __restrict__ logits,
-                                                        const float2* __restrict__ stats,
-                                                        float* __restrict__ Tpart, int B, int S_max,
-                                                        int r, int H, int k_tot, int lk, int tok_per_wg)
+__global__ __launch_bounds__(kSmThreads) void attend_softmax_kernel(const float* __restrict__ logits,
+                                                                    const int32_t* __restrict__ n_sel,
+                                                                    T* __restrict__ P, int B, int H, int lk)
 {
-    constexpr int HPW = kPvMaxHeads / 4;  // heads per wave (upper bound)
-    __shared__ __attribute__((aligned(16))) float ps[kPvMaxHeads][kPvTok];
-    __shared__ int srow[kPvTok];
-    const int b = blockIdx.z, tc = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int col = blockIdx.x * kPvCols + lane;
-    const int n = n_sel[b];
-    const int hpw = (H + 3) / 4;
-    const int h0 = wave * hpw;
-    const int j_begin = tc * tok_per_wg, j_end = min(n, j_begin + tok_per_wg);
+    __shared__ float sh[4];
+    const int bh = blockIdx.x, tid = threadIdx.x;
+    const int n = n_sel[bh / H];
+    const float* lrow = logits + (size_t)bh * lk;
+    T* p_hi = P + (size_t)bh * lk;
+    T* p_lo = P + (size_t)B * H * lk + (size_t)bh * lk;  // second plane (bf16 storage only)
+    constexpr int SPAN = kSmThreads * kSmBatch;
 
-    float acc[HPW];
+    float first[kSmBatch];
 #pragma unroll
-    for (int i = 0; i < HPW; ++i) acc[i] = 0.f;
-
-    for (int j0 = j_begin; j0 < j_end; j0 += kPvTok) {
-        __syncthreads();
-        const int cnt = min(kPvTok, j_end - j0);
-        for (int t = tid; t < kPvTok; t += 256) srow[t] = t < cnt ? min(max(idx[(size_t)b * k_tot + j0 + t], 0), S_max - 1) : 0;
-        for (int t = tid; t < H * kPvTok; t += 256) {
-            int h = t / kPvTok, jj = t - h * kPvTok;
-            float p = 0.f;
-            if (jj < cnt) p = __expf(logits[((size_t)b * H + h) * lk + j0 + jj] - stats[b * H + h].x);
-            ps[h][jj] = p;
-        }
-        __syncthreads();
-        const int cnt4 = (cnt + 3) & ~3;
-        for (int jj = 0; jj < cnt4; jj += 4) {
-            float v[4];
+    for (int u = 0; u < kSmBatch; ++u) { int j = u * kSmThreads + tid; first[u] = j < n ? lrow[j] : -INFINITY; }
+    float mx = -INFINITY;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                v[e] = elem<T>::load(Vc + ((size_t)b * S_max + srow[jj + e]) * r + col);  // p == 0 past cnt
+    for (int u = 0; u < kSmBatch; ++u) mx = fmaxf(mx, first[u]);
+    for (int j0 = SPAN; j0 < n; j0 += SPAN) {
+        float v[kSmBatch];
 #pragma unroll
-            for (int i = 0; i < HPW; ++i) {
-                if (i < hpw && h0 + i < H) {
-                    f32x4 p4 = *reinterpret_cast<const f32x4*>(&ps[h0 + i][jj]);
-                    acc[i] = fmaf(p4.x, v[0], acc[i]);
-                    acc[i] = fmaf(p4.y, v[1], acc[i]);
-                    acc[i] = fmaf(p4.z, v[2], acc[i]);
-                    acc[i] = fmaf(p4.w, v[3], acc[i]);
-                }
-            }
-        }
+        for (int u = 0; u < kSmBatch; ++u) { int j = j0 + u * kSmThreads + tid; v[u] = j < n ? lrow[j] : -INFINITY; }
+#pragma unroll
+        for (int u = 0; u < kSmBatch; ++u) mx = fmaxf(mx, v[u]);
     }
+    mx = block_reduce_256(mx, sh, true);
+    float z = 0.f;
 #pragma unroll
-    for (int i = 0; i < HPW; ++i)
-        if (i < hpw && h0 + i < H)
-            Tpart[(((size_t)tc * B + b) * H + h0 + i) * r + col] = acc[i];
-}
-
-// ---------------------------------------------------------------------------------
-// output projection: y[b,h,c] = (sum_i T[b,h,i] U_v[g*128+c, i]) / Z_bh
-// ---------------------------------------------------------------------------------
-constexpr int kOutRowsLds = 8;   // (b,h) rows of T staged per pass
-
-template <typename T, int NCH>
-__global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ Uv,
-                                                         const float* __restrict__ Tpart,
-                                                         const float2* __restrict__ stats,
-                                                         const int32_t* __restrict__ n_sel,
-                                                         T* __restrict__ out, int B, int r, int H,
-                                                         int H_kv, int n_tc)
-{
-    constexpr int VEC = elem<T>::vec;
-    extern __shared__ __attribute__((aligned(16))) float Ts[];  // [kOutRowsLds][r]
-    const int g = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int li = lane & 15, grp = tid >> 4;  // 16 groups of 16 lanes: one output channel each
-    const int c = blockIdx.x * 16 + grp;
-    const int G = H / H_kv;
-    const int n_pieces = r / VEC;
-
-    float uf[NCH][VEC];
+    for (int u = 0; u < kSmBatch; ++u) z += first[u] > -INFINITY ? __expf(first[u] - mx) : 0.f;
+    for (int j0 = SPAN; j0 < n; j0 += SPAN) {
+        float v[kSmBatch];
 #pragma unroll
-    for (int nn = 0; nn < NCH; ++nn) {
-        int p = li + 16 * nn;
-        u32x4 w = p < n_pieces ? ld16(Uv + ((size_t)g * kHeadDim + c) * r + p * VEC) : u32x4{0, 0, 0, 0};
-        elem<T>::unpack(w, uf[nn]);
+        for (int u = 0; u < kSmBatch; ++u) { int j = j0 + u * kSmThreads + tid; v[u] = j < n ? lrow[j] : -INFINITY; }
+#pragma unroll
+        for (int u = 0; u < kSmBatch; ++u) z += v[u] > -INFINITY ? __expf(v[u] - mx) : 0.f;
     }
-
-    const int n_rows = B * G;  // (b, m) pairs that read this KV head
-    for (int row0 = 0; row0 < n_rows; row0 += kOutRowsLds) {
-        __syncthreads();
-        const int rows = min(kOutRowsLds, n_rows - row0);
-        for (int t = tid; t < rows * r; t += 256) {
-            int rr = t / r, i = t - rr * r;
-            int b = (row0 + rr) / G, h = g * G + (row0 + rr) % G;
-            float s = 0.f;
-            for (int tc = 0; tc < n_tc; ++tc) s += Tpart[(((size_t)tc * B + b) * H + h) * r + i];
-            Ts[rr * r + i] = s;
+    z = block_reduce_256(z, sh, false);
+    const float zi = z > 0.f ? 1.f / z : 0.f;
+    for (int j0 = 0; j0 < lk; j0 += SPAN) {
+        float v[kSmBatch];
+#pragma unroll
+        for (int u = 0; u < kSmBatch; ++u) {
+            int j = j0 + u * kSmThreads + tid;
+            v[u] = j0 == 0 ? first[u] : (j < n ? lrow[j] : -INFINITY);
         }
-        __syncthreads();
-        for (int rr = 0; rr < rows; ++rr) {
-            float acc = 0.f;
 #pragma unroll
-            for (int nn = 0; nn < NCH; ++nn) {
-                int p = li + 16 * nn;
-                if (p < n_pieces) {
-#pragma unroll
-                    for (int v = 0; v < VEC; v += 4) {
-                        f32x4 t4 = *reinterpret_cast<const f32x4*>(&Ts[rr * r + p * VEC + v]);
-                        acc = fmaf(uf[nn][v], t4.x, acc);
-                        acc = fmaf(uf[nn][v + 1], t4.y, acc);
-                        acc = fmaf(uf[nn][v + 2], t4.z, acc);
-                        acc = fmaf(uf[nn][v + 3], t4.w, acc);
-                    }
+        for (int u = 0; u < kSmBatch; ++u) {
+            int j = j0 + u * kSmThreads + tid;
+            if (j < lk) {
+                float pj = v[u] > -INFINITY ? __expf(v[u] - mx) * zi : 0.f;
+                if constexpr (sizeof(T) == 2) {
+                    bf16_t ph = f32_to_bf16(pj);
+                    p_hi[j] = ph;
+                    p_lo[j] = f32_to_bf16(pj - bf16_to_f32(ph));
+                } else {
+                    p_hi[j] = pj;
                 }
-            }
-            acc = row16_sum(acc);
-            if (li == 0) {
-                int b = (row0 + rr) / G, h = g * G + (row0 + rr) % G;
-                float z = stats[b * H + h].y;
-                float y = n_sel[b] > 0 ? acc / z : 0.f;
-                elem<T>::store(out + ((size_t)b * H + h) * kHeadDim + c, y);
             }
         }
     }

@@ -1,140 +1,184 @@
-// Latent projection  x~ = U^T x  (Sec. 4.3; Algorithm 1, projection step).
+// Latent projection  x~ = U^T x  (Sec. 4.3; Algorithm 1, projection step) and the one-time
+// repacking of the projectors.
 //
-// U is [D x r] row-major, so the reduction runs down the columns: the kernel
-// streams U once for the whole batch (it is the only large operand), each
-// workgroup owning a [rows_per_wg x CW] panel.  Partial sums of the row panels
-// go to a workspace and the last workgroup to finish a column panel adds them
-// up in a fixed order, so the result is bit-reproducible from run to run.
+// The projection reads the TRANSPOSED projector U^T [r x D] (made once by pack_weights),
+// so each output coordinate is a dot product along a contiguous row: a workgroup owns 16
+// latent coordinates, its 8 waves split the D axis, and every wave keeps all of its
+// 16-byte row pieces in flight at once.  The products run on 16x16 MFMA tiles whose
+// columns are the (sequence, query head of the KV group) pairs, so a whole batch costs
+// one pass over U^T; the heads of a group are added in fp32 afterwards, which equals
+// projecting their sum.  Single pass, fixed summation order, bit-reproducible.
 #pragma once
 #include "common.hpp"
 
 namespace sals {
 
-constexpr int kProjThreads = 256;
-constexpr int kProjRowLanes = 32;   // threads along the reduction axis
-constexpr int kProjBT = 4;          // batch entries accumulated per pass
-constexpr int kProjMaxRows = 256;   // max rows per workgroup panel
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
+template <typename T> struct mma16_op;
+template <> struct mma16_op<bf16_t> {  // v_mfma_f32_16x16x32_bf16
+    static __device__ __forceinline__ void run(const u32x4& a, const u32x4& b, f32x4v& c)
+    {
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
+                                                    c, 0, 0, 0);
+    }
+};
+template <> struct mma16_op<float> {   // four v_mfma_f32_16x16x4_f32
+    static __device__ __forceinline__ void run(const u32x4& a, const u32x4& b, f32x4v& c)
+    {
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+    }
+};
+
+constexpr int kProjWaves = 8;
+constexpr int kProjThreads = 64 * kProjWaves;
+constexpr int kProjMaxCols = 128;  // B * (H_q / H_kv) handled per call
+constexpr int kProjBatch = 4;      // row pieces a wave keeps in flight per round
 
 struct ProjArgs {
-    const void* X[2];     // QUERY: q [B,H,d]; else [B,D]
-    const void* U[2];     // [D,r]
-    void* cache[2];       // append: [B,S_max,r]
-    float* out_f32;       // QUERY: [B,r]
-    float* partial;       // [nproj][nchunk][B][r]
-    uint32_t* counters;   // [nproj*ncol] panel counters, then 1 "all done" counter
-    int32_t* seq_len;     // append: [B], incremented at the very end
-    int B, D, r, H, H_kv, d, S_max, rows_per_wg, nchunk, ncol, nproj;
+    const void* UT[2];   // transposed projectors [r, D]
+    const void* X[2];    // QUERY: q [B,H,d] (X[0]); else new key / value [B,D]
+    void* cache[2];      // append: [B,S_max,r]
+    float* out_f32;      // QUERY: q~ [B,r]
+    const int32_t* seq_len;  // append: [B] row to write
+    int B, D, r, H, H_kv, d, S_max, nproj;
 };
 
 template <typename T, bool QUERY>
 __global__ __launch_bounds__(kProjThreads) void project_kernel(ProjArgs a)
 {
     constexpr int VEC = elem<T>::vec;
-    constexpr int CW = 8 * VEC;  // columns per workgroup
-    const int tid = threadIdx.x;
-    const int tx = tid & 7, ty = tid >> 3;
-    const int proj = blockIdx.z;
-    const int col0 = blockIdx.x * CW;
-    const int c_begin = blockIdx.y * a.rows_per_wg;
-    const int c_end = min(a.D, c_begin + a.rows_per_wg);
+    constexpr int KS = 4 * VEC;  // elements of the D axis per MFMA step
+    const int proj = blockIdx.y;
+    const int i0 = blockIdx.x * 16;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, kg = lane >> 4;
+    const int G = QUERY ? a.H / a.H_kv : 1;
+    const int ncols = a.B * G, n_nblk = (ncols + 15) >> 4;
+    const int nks = a.D / KS;
+    const T* UT = static_cast<const T*>(a.UT[proj]);
     const T* X = static_cast<const T*>(a.X[proj]);
-    const T* U = static_cast<const T*>(a.U[proj]);
-    float* partial = a.partial + ((size_t)proj * a.nchunk + blockIdx.y) * a.B * a.r;
+    const T* arow = UT + (size_t)(i0 + l16) * a.D + kg * VEC;
 
-    __shared__ float xs[kProjBT][kProjMaxRows];
-    __shared__ float red[kProjRowLanes][CW + 1];
-    __shared__ int is_last;
+    __shared__ __attribute__((aligned(16))) float red[kProjWaves][64][4];
+    __shared__ float colsum[kProjMaxCols][16];
 
-    const int G = a.H / a.H_kv;
-    for (int b0 = 0; b0 < a.B; b0 += kProjBT) {
-        // stage the slice of x for this row panel (group-summed heads for a query)
-        for (int t = tid; t < kProjBT * a.rows_per_wg; t += kProjThreads) {
-            int bb = t / a.rows_per_wg, cc = t - bb * a.rows_per_wg;
-            int b = b0 + bb, c = c_begin + cc;
-            float v = 0.f;
-            if (b < a.B && c < c_end) {
-                if (QUERY) {
-                    int g = c / a.d, e = c - g * a.d;
-                    for (int m = 0; m < G; ++m)
-                        v += elem<T>::load(X + ((size_t)b * a.H + g * G + m) * a.d + e);
-                } else {
-                    v = elem<T>::load(X + (size_t)b * a.D + c);
+    f32x4v acc[kProjMaxCols / 16];
+#pragma unroll
+    for (int nb = 0; nb < kProjMaxCols / 16; ++nb) acc[nb] = f32x4v{0.f, 0.f, 0.f, 0.f};
+
+    // this wave's steps: wave, wave+8, ... ; kProjBatch steps of loads per round
+    for (int ks0 = wave; ks0 < nks; ks0 += kProjWaves * kProjBatch) {
+        u32x4 af[kProjBatch];
+#pragma unroll
+        for (int u = 0; u < kProjBatch; ++u) {
+            int ks = ks0 + u * kProjWaves;
+            af[u] = ks < nks ? ld16(arow + (size_t)ks * KS) : u32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int nb = 0; nb < kProjMaxCols / 16; ++nb) {
+            if (nb < n_nblk) {
+                const int n = nb * 16 + l16;
+                u32x4 bf[kProjBatch];
+#pragma unroll
+                for (int u = 0; u < kProjBatch; ++u) {
+                    int ks = ks0 + u * kProjWaves;
+                    bf[u] = u32x4{0, 0, 0, 0};
+                    if (ks < nks && n < ncols) {
+                        int c = ks * KS + kg * VEC;
+                        const T* xp;
+                        if (QUERY) {
+                            int b = n / G, m = n - b * G, g = c / a.d;
+                            xp = X + ((size_t)b * a.H + g * G + m) * a.d + (c - g * a.d);
+                        } else {
+                            xp = X + (size_t)n * a.D + c;
+                        }
+                        bf[u] = ld16(xp);
+                    }
                 }
-            }
-            xs[bb][cc] = v;
-        }
-        __syncthreads();
-        float acc[kProjBT][VEC];
 #pragma unroll
-        for (int bb = 0; bb < kProjBT; ++bb)
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) acc[bb][v] = 0.f;
-        for (int c = c_begin + ty; c < c_end; c += kProjRowLanes) {
-            float uf[VEC];
-            elem<T>::unpack(ld16(U + (size_t)c * a.r + col0 + tx * VEC), uf);
-#pragma unroll
-            for (int bb = 0; bb < kProjBT; ++bb) {
-                float xv = xs[bb][c - c_begin];
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) acc[bb][v] = fmaf(xv, uf[v], acc[bb][v]);
+                for (int u = 0; u < kProjBatch; ++u) mma16_op<T>::run(af[u], bf[u], acc[nb]);
             }
         }
-        // reduce over the 32 row lanes, one batch entry at a time
-#pragma unroll
-        for (int bb = 0; bb < kProjBT; ++bb) {
-            __syncthreads();
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) red[ty][tx * VEC + v] = acc[bb][v];
-            __syncthreads();
-            if (tid < CW && b0 + bb < a.B) {
-                float s = 0.f;
-                for (int y = 0; y < kProjRowLanes; ++y) s += red[y][tid];
-                partial[(size_t)(b0 + bb) * a.r + col0 + tid] = s;
-            }
-        }
-        __syncthreads();
     }
 
-    // last workgroup of this column panel adds the row-panel partials
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t old = atomicAdd(&a.counters[proj * a.ncol + blockIdx.x], 1u);
-        is_last = (old == (uint32_t)a.nchunk - 1u);
+    // fold the 8 D-slices in wave order; acc[nb][v] is (coordinate 4*kg+v, column nb*16+l16)
+#pragma unroll
+    for (int nb = 0; nb < kProjMaxCols / 16; ++nb) {
+        if (nb < n_nblk) {  // uniform
+            __syncthreads();
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[wave][lane][v] = acc[nb][v];
+            __syncthreads();
+            if (tid < 256) {
+                int col = tid & 15, rr = tid >> 4;
+                int src_lane = (rr >> 2) * 16 + col, v = rr & 3;
+                float s = 0.f;
+#pragma unroll
+                for (int w = 0; w < kProjWaves; ++w) s += red[w][src_lane][v];
+                colsum[nb * 16 + col][rr] = s;
+            }
+        }
     }
     __syncthreads();
-    if (!is_last) return;
-    __threadfence();
-    const float* pbase = a.partial + (size_t)proj * a.nchunk * a.B * a.r;
-    for (int t = tid; t < a.B * CW; t += kProjThreads) {
-        int b = t / CW, col = col0 + (t - b * CW);
+    // add the heads of each group and write
+    for (int t = tid; t < a.B * 16; t += kProjThreads) {
+        int b = t >> 4, rr = t & 15;
         float s = 0.f;
-        for (int ch = 0; ch < a.nchunk; ++ch)
-            s += __hip_atomic_load(pbase + ((size_t)ch * a.B + b) * a.r + col, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+        for (int m = 0; m < G; ++m) s += colsum[b * G + m][rr];
         if (QUERY) {
-            a.out_f32[(size_t)b * a.r + col] = s;
+            a.out_f32[(size_t)b * a.r + i0 + rr] = s;
         } else {
             int row = a.seq_len[b];
             if (row < a.S_max)
-                elem<T>::store(static_cast<T*>(a.cache[proj]) + ((size_t)b * a.S_max + row) * a.r + col, s);
+                elem<T>::store(static_cast<T*>(a.cache[proj]) + ((size_t)b * a.S_max + row) * a.r + i0 + rr, s);
         }
     }
-    if (tid == 0) a.counters[proj * a.ncol + blockIdx.x] = 0u;
-    if (QUERY) return;
-    // append: the very last panel (over both projections) advances the lengths
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t* done = a.counters + a.nproj * a.ncol;
-        uint32_t old = atomicAdd(done, 1u);
-        is_last = (old == (uint32_t)(a.nproj * a.ncol) - 1u);
-        if (is_last) *done = 0u;
+}
+
+// after an append: advance the sequence lengths (separate launch, so that every cache row
+// has been written before any length changes)
+__global__ void bump_seq_len_kernel(int32_t* __restrict__ seq_len, int B, int S_max)
+{
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B && seq_len[b] < S_max) seq_len[b] += 1;
+}
+
+// ---------------------------------------------------------------------------------
+// one-time weight repacking (model-load time; not on the decode path)
+// ---------------------------------------------------------------------------------
+// section 0: UkT [r, D]      section 1: UvT [r, D]
+// section 2: Uk in reconstruction order: [H_kv][r/KE][128 slots][KE] with the head dims
+//            in RoPE pair order (slot p < 64: first element of pair p; 64+p: its partner)
+// section 3: Uv [D, r] unchanged
+template <typename T>
+__global__ __launch_bounds__(256) void pack_weights_kernel(const T* __restrict__ Uk, const T* __restrict__ Uv,
+                                                           T* __restrict__ packed, size_t section_elems,
+                                                           int D, int r, int style)
+{
+    constexpr int KE = 128 / (int)sizeof(T);
+    const int sec = blockIdx.y;
+    T* dst = packed + (size_t)sec * section_elems;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < section_elems; e += (size_t)gridDim.x * 256) {
+        T v;
+        if (sec == 0 || sec == 1) {
+            size_t i = e / D, c = e - i * D;
+            v = (sec == 0 ? Uk : Uv)[c * r + i];
+        } else if (sec == 2) {
+            size_t per_head = (size_t)kHeadDim * r;
+            size_t g = e / per_head, rem = e - g * per_head;
+            size_t kc = rem / ((size_t)kHeadDim * KE), rem2 = rem - kc * kHeadDim * KE;
+            int slot = (int)(rem2 / KE), ke = (int)(rem2 - (size_t)slot * KE);
+            int dim = slot < kPairs ? (style ? 2 * slot : slot) : (style ? 2 * (slot - kPairs) + 1 : slot);
+            v = Uk[(g * kHeadDim + dim) * r + kc * KE + ke];
+        } else {
+            v = Uv[e];
+        }
+        dst[e] = v;
     }
-    __syncthreads();
-    if (!is_last) return;
-    for (int b = tid; b < a.B; b += kProjThreads)
-        if (a.seq_len[b] < a.S_max) a.seq_len[b] += 1;
 }
 
 }  // namespace sals

@@ -3,6 +3,7 @@
 // stream; nothing here allocates device memory or synchronises.
 #include "../../include/sals.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <new>
@@ -13,6 +14,7 @@
 #include "k_project.hpp"
 #include "k_scores.hpp"
 #include "k_topk.hpp"
+#include "k_value.hpp"
 
 using namespace sals;
 
@@ -23,11 +25,12 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Layout {  // byte offsets into the workspace
-    size_t counters, qt, proj_partial, scores, idx, n_sel, cs, qR, logits, stats, tpart, total;
-    int proj_rows_per_wg, proj_nchunk, proj_ncol;  // projection panels
-    int lk;                                        // logits row stride (floats)
-    int pv_tok_per_wg, pv_ntc;                     // value-sum token chunks
+    size_t qt, scores, idx, n_sel, cs, qR, logits, pw, tpart, tfin, total;
+    int lk;                      // logits row stride (floats)
+    int pv_tok_per_wg, pv_ntr;   // value-sum token ranges
+    size_t w_section;            // elements per section of the packed weights
 };
+
 
 }  // namespace
 
@@ -46,7 +49,7 @@ struct sals_ctx {
 namespace {
 
 const char* const kKernelNames[SALS_N_KERNELS] = {
-    "project", "scores", "topk", "attend_prep", "attend_logits", "attend_stats", "attend_pv", "attend_out"};
+    "project", "scores", "topk", "attend_prep", "attend_logits", "attend_softmax", "attend_pv", "attend_out"};
 
 // Brackets one kernel launch with a pair of events while profiling is on.
 struct ProfScope {
@@ -84,7 +87,8 @@ sals_status validate(const sals_desc* d)
     if (d->r % 64 != 0 || d->r > 1024) return SALS_ERR_UNSUPPORTED;
     if (d->r_score % 8 != 0) return SALS_ERR_UNSUPPORTED;
     if (d->H_q / d->H_kv > kMaxGroup || d->H_q > kPvMaxHeads) return SALS_ERR_UNSUPPORTED;
-    if (d->S_max > (1 << 24) || d->B > 65535) return SALS_ERR_UNSUPPORTED;
+    if (d->S_max > (1 << 24)) return SALS_ERR_UNSUPPORTED;
+    if ((long long)d->B * (d->H_q / d->H_kv) > kProjMaxCols) return SALS_ERR_UNSUPPORTED;
     if ((long long)d->top_k + d->n_recent + d->n_sink > 65536) return SALS_ERR_UNSUPPORTED;
     return SALS_OK;
 }
@@ -94,38 +98,30 @@ Layout make_layout(const sals_desc& d)
     Layout L{};
     const int D = d.H_kv * d.d;
     const int k_tot = d.top_k + d.n_sink + d.n_recent;
-    const int vec = d.dtype == SALS_BF16 ? 8 : 4;
-    // projection panels: about 256..512 workgroups, partial sums kept near 1.5 MB
-    L.proj_ncol = d.r / (8 * vec);
-    int want_chunks = std::max(1, 384 / L.proj_ncol);
-    size_t per_chunk = (size_t)d.B * d.r * 4;
-    int cap_chunks = (int)std::max<size_t>(8, (size_t)(1536 * 1024) / per_chunk);
-    int nchunk = std::min(want_chunks, cap_chunks);
-    int rows = std::min(kProjMaxRows, std::max(kProjRowLanes, ceil_div(D, nchunk)));
-    rows = ceil_div(rows, kProjRowLanes) * kProjRowLanes;
-    L.proj_rows_per_wg = rows;
-    L.proj_nchunk = ceil_div(D, rows);
-    L.lk = (k_tot + 3) & ~3;
-    // value sum: enough workgroups to fill the chip without too many partial sums
-    int colchunks = d.r / kPvCols;
-    int tok = kPvTok;
-    while (tok < k_tot && (long long)colchunks * ceil_div(k_tot, tok) * d.B > 1024) tok *= 2;
-    L.pv_tok_per_wg = tok;
-    L.pv_ntc = ceil_div(k_tot, tok);
-
+    L.lk = ceil_div(k_tot, 64) * 64;
+    L.w_section = (size_t)D * d.r;
+    // value sum: split the selected tokens into ranges until about 256 workgroups exist
+    {
+        int blocks = d.r / kPvCols;
+        int want = ceil_div(256, blocks * d.B);
+        int n_tr = std::max(1, std::min(std::min(want, kMaxRanges), ceil_div(k_tot, 4 * kPvTJ)));
+        int tok = ceil_div(ceil_div(k_tot, n_tr), kPvTJ) * kPvTJ;
+        tok = std::max(tok, ceil_div(ceil_div(k_tot, kMaxRanges), kPvTJ) * kPvTJ);
+        L.pv_tok_per_wg = tok;
+        L.pv_ntr = ceil_div(k_tot, tok);
+    }
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
-    L.counters = take((size_t)(2 * 64 + 1) * 4);
     L.qt = take((size_t)d.B * d.r * 4);
-    L.proj_partial = take((size_t)2 * L.proj_nchunk * d.B * d.r * 4);
     L.scores = take((size_t)d.B * d.S_max * 4);
     L.idx = take((size_t)d.B * k_tot * 4);
     L.n_sel = take((size_t)d.B * 4);
     L.cs = take((size_t)d.B * k_tot * kPairs * 8);
     L.qR = take((size_t)d.B * d.H_q * kHeadDim * 4);
     L.logits = take((size_t)d.B * d.H_q * L.lk * 4);
-    L.stats = take((size_t)d.B * d.H_q * 8);
-    L.tpart = take((size_t)L.pv_ntc * d.B * d.H_q * d.r * 4);
+    L.pw = take((size_t)d.B * d.H_q * L.lk * 4);
+    L.tpart = take((size_t)L.pv_ntr * d.B * d.H_q * d.r * 4);
+    L.tfin = take((size_t)d.B * d.H_q * d.r * 4);
     L.total = o;
     return L;
 }
@@ -138,29 +134,32 @@ inline sals_status launch_status()
     return hipGetLastError() == hipSuccess ? SALS_OK : SALS_ERR_HIP;
 }
 
+template <typename T> inline const T* w_section(const sals_ctx* c, const void* W, int sec)
+{
+    return static_cast<const T*>(W) + (size_t)sec * c->L.w_section;
+}
+
 template <typename T, bool QUERY>
-sals_status launch_project(const sals_ctx* c, const void* const* X, const void* const* U, void* const* cache,
-                           int nproj, int32_t* seq_len, hipStream_t st)
+sals_status launch_project(const sals_ctx* c, const void* W, const void* x0, const void* x1, void* cache0,
+                           void* cache1, int32_t* seq_len, hipStream_t st)
 {
     const sals_desc& d = c->d;
     ProjArgs a{};
-    for (int i = 0; i < nproj; ++i) {
-        a.X[i] = X[i];
-        a.U[i] = U[i];
-        a.cache[i] = cache ? cache[i] : nullptr;
-    }
+    a.UT[0] = w_section<T>(c, W, 0);
+    a.UT[1] = w_section<T>(c, W, 1);
+    a.X[0] = x0; a.X[1] = x1;
+    a.cache[0] = cache0; a.cache[1] = cache1;
     a.out_f32 = reinterpret_cast<float*>(c->ws + c->L.qt);
-    a.partial = reinterpret_cast<float*>(c->ws + c->L.proj_partial);
-    a.counters = reinterpret_cast<uint32_t*>(c->ws + c->L.counters);
     a.seq_len = seq_len;
     a.B = d.B; a.D = d.H_kv * d.d; a.r = d.r; a.H = d.H_q; a.H_kv = d.H_kv; a.d = d.d;
-    a.S_max = d.S_max; a.rows_per_wg = c->L.proj_rows_per_wg; a.nchunk = c->L.proj_nchunk;
-    a.ncol = c->L.proj_ncol; a.nproj = nproj;
-    dim3 grid(a.ncol, a.nchunk, nproj);
+    a.S_max = d.S_max; a.nproj = QUERY ? 1 : 2;
     {
         ProfScope ps(c, SALS_K_PROJECT, st);
-        hipLaunchKernelGGL((project_kernel<T, QUERY>), grid, dim3(kProjThreads), 0, st, a);
+        hipLaunchKernelGGL((project_kernel<T, QUERY>), dim3(d.r / 16, a.nproj), dim3(kProjThreads), 0, st, a);
     }
+    if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+    if (!QUERY)
+        hipLaunchKernelGGL(bump_seq_len_kernel, dim3(ceil_div(d.B, 128)), dim3(128), 0, st, seq_len, d.B, d.S_max);
     return launch_status();
 }
 
@@ -178,12 +177,12 @@ sals_status launch_scores(const sals_ctx* c, const void* Kc, const int32_t* seq_
     dim3 grid(ceil_div(d.S_max, rows), d.B);
     const float* qt = reinterpret_cast<const float*>(c->ws + c->L.qt);
     const T* K = static_cast<const T*>(Kc);
+    ProfScope ps(c, SALS_K_SCORES, st);
 #define SALS_SCORES_CASE(N)                                                                         \
     case N:                                                                                         \
         hipLaunchKernelGGL((scores_kernel<T, N>), grid, dim3(kScoreThreads), 0, st, K, qt, seq_len, \
                            scores, d.S_max, d.r, d.r_score, rows);                                  \
         break;
-    ProfScope ps(c, SALS_K_SCORES, st);
     switch (nch) {
         SALS_SCORES_CASE(1) SALS_SCORES_CASE(2) SALS_SCORES_CASE(3) SALS_SCORES_CASE(4)
         SALS_SCORES_CASE(5) SALS_SCORES_CASE(6) SALS_SCORES_CASE(7) SALS_SCORES_CASE(8)
@@ -200,10 +199,10 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
 {
     const sals_desc& d = c->d;
     dim3 grid(d.B), block(kTopkThreads);
+    ProfScope ps(c, SALS_K_TOPK, st);
 #define SALS_TOPK(F4)                                                                                \
     hipLaunchKernelGGL((topk_kernel<F4>), grid, block, 0, st, scores, seq_len, idx, n_sel, d.S_max, \
                        d.top_k, d.n_sink, d.n_recent)
-    ProfScope ps(c, SALS_K_TOPK, st);
     if (d.S_max <= 4096) SALS_TOPK(1);
     else if (d.S_max <= 8192) SALS_TOPK(2);
     else if (d.S_max <= 16384) SALS_TOPK(4);
@@ -215,18 +214,18 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
 
 template <typename T>
 sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos, const void* Kc,
-                          const void* Vc, const void* Uk, const void* Uv, const int32_t* idx,
-                          const int32_t* n_sel, void* out, hipStream_t st)
+                          const void* Vc, const void* W, const int32_t* idx, const int32_t* n_sel, void* out,
+                          hipStream_t st)
 {
     const sals_desc& d = c->d;
     const Layout& L = c->L;
-    constexpr int VEC = elem<T>::vec;
     const int k_tot = d.top_k + d.n_sink + d.n_recent;
     float2* cs = reinterpret_cast<float2*>(c->ws + L.cs);
     float* qR = reinterpret_cast<float*>(c->ws + L.qR);
     float* logits = reinterpret_cast<float*>(c->ws + L.logits);
-    float2* stats = reinterpret_cast<float2*>(c->ws + L.stats);
+    T* pw = reinterpret_cast<T*>(c->ws + L.pw);
     float* tpart = reinterpret_cast<float*>(c->ws + L.tpart);
+    T* tfin = reinterpret_cast<T*>(c->ws + L.tfin);
 
     {   // cos/sin table and rotated query
         int n_tab = ceil_div(d.B * k_tot, 4), n_q = ceil_div(d.B * d.H_q, 4);
@@ -238,11 +237,11 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     }
     {   // logits: pick the token tile so that the grid covers the chip
         long long tiles128 = (long long)ceil_div(k_tot, 128) * d.H_kv * d.B;
-#define SALS_LOGITS(NW, NB)                                                                           \
-    hipLaunchKernelGGL((attend_logits_kernel<T, NW, NB>), dim3(ceil_div(k_tot, 32 * NW * NB), d.H_kv, d.B), \
-                       dim3(64 * NW), 0, st, static_cast<const T*>(Kc), static_cast<const T*>(Uk), idx,   \
-                       n_sel, cs, qR, logits, d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk, d.rope_style)
         ProfScope ps(c, SALS_K_ATTEND_LOGITS, st);
+#define SALS_LOGITS(NW, NB)                                                                                  \
+    hipLaunchKernelGGL((attend_logits_kernel<T, NW, NB>), dim3(ceil_div(k_tot, 32 * NW * NB), d.H_kv, d.B), \
+                       dim3(64 * NW), 0, st, static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,   \
+                       cs, qR, logits, d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk)
         if (tiles128 >= 1024) SALS_LOGITS(4, 2);       // 256 tokens per workgroup
         else if (tiles128 >= 256) SALS_LOGITS(4, 1);   // 128
         else if (tiles128 >= 64) SALS_LOGITS(2, 1);    // 64
@@ -251,36 +250,23 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
         if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     }
     {
-    ProfScope ps(c, SALS_K_ATTEND_STATS, st);
-    hipLaunchKernelGGL(attend_stats_kernel, dim3(ceil_div(d.B * d.H_q, 4)), dim3(256), 0, st, logits, n_sel,
-                       stats, d.B, d.H_q, L.lk);
+        ProfScope ps(c, SALS_K_ATTEND_SOFTMAX, st);
+        hipLaunchKernelGGL((attend_softmax_kernel<T>), dim3(d.B * d.H_q), dim3(kSmThreads), 0, st, logits, n_sel, pw,
+                           d.B, d.H_q, L.lk);
     }
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     {
-    ProfScope ps(c, SALS_K_ATTEND_PV, st);
-    hipLaunchKernelGGL((attend_pv_kernel<T>), dim3(d.r / kPvCols, L.pv_ntc, d.B), dim3(256), 0, st,
-                       static_cast<const T*>(Vc), idx, n_sel, logits, stats, tpart, d.B, d.S_max, d.r, d.H_q,
-                       k_tot, L.lk, L.pv_tok_per_wg);
+        ProfScope ps(c, SALS_K_ATTEND_PV, st);
+        hipLaunchKernelGGL((attend_pv_kernel<T>), dim3(d.r / kPvCols, L.pv_ntr, d.B), dim3(256), 0, st,
+                           static_cast<const T*>(Vc), idx, n_sel, pw, tpart, tfin, d.B, d.S_max,
+                           d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr);
     }
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     {
-        const int nch = ceil_div(d.r / VEC, 16);
-        const size_t shm = (size_t)kOutRowsLds * d.r * 4;
-        dim3 grid(kHeadDim / 16, d.H_kv);
         ProfScope ps(c, SALS_K_ATTEND_OUT, st);
-#define SALS_OUT_CASE(N)                                                                              \
-    case N:                                                                                           \
-        hipLaunchKernelGGL((attend_out_kernel<T, N>), grid, dim3(256), shm, st, static_cast<const T*>(Uv), \
-                           tpart, stats, n_sel, static_cast<T*>(out), d.B, d.r, d.H_q, d.H_kv, L.pv_ntc);  \
-        break;
-        switch (nch) {
-            SALS_OUT_CASE(1) SALS_OUT_CASE(2) SALS_OUT_CASE(3) SALS_OUT_CASE(4) SALS_OUT_CASE(5)
-            SALS_OUT_CASE(6) SALS_OUT_CASE(7) SALS_OUT_CASE(8) SALS_OUT_CASE(9) SALS_OUT_CASE(10)
-            SALS_OUT_CASE(11) SALS_OUT_CASE(12) SALS_OUT_CASE(13) SALS_OUT_CASE(14) SALS_OUT_CASE(15)
-            SALS_OUT_CASE(16)
-            default: return SALS_ERR_UNSUPPORTED;
-        }
-#undef SALS_OUT_CASE
+        hipLaunchKernelGGL((attend_out_kernel<T>), dim3(kHeadDim / 32, d.H_kv), dim3(256), 0, st,
+                           w_section<T>(c, W, 3), tfin, tpart, static_cast<T*>(out), d.B, d.r, d.H_q, d.H_kv,
+                           L.pv_ntr);
     }
     return launch_status();
 }
@@ -310,6 +296,15 @@ sals_status sals_workspace_bytes(const sals_desc* desc, size_t* bytes)
     return SALS_OK;
 }
 
+sals_status sals_packed_weight_bytes(const sals_desc* desc, size_t* bytes)
+{
+    if (!bytes) return SALS_ERR_INVALID_ARG;
+    sals_status s = validate(desc);
+    if (s != SALS_OK) return s;
+    *bytes = align_up(4 * make_layout(*desc).w_section * (desc->dtype == SALS_BF16 ? 2 : 4));
+    return SALS_OK;
+}
+
 sals_status sals_create(const sals_desc* desc, void* d_workspace, size_t workspace_bytes, sals_ctx** out)
 {
     if (!out) return SALS_ERR_INVALID_ARG;
@@ -336,6 +331,25 @@ void sals_destroy(sals_ctx* ctx)
     if (!ctx) return;
     for (auto& r : ctx->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     delete ctx;
+}
+
+sals_status sals_pack_weights(sals_ctx* ctx, const void* Uk, const void* Uv, void* W, void* hip_stream)
+{
+    if (!ctx || bad(Uk) || bad(Uv) || !W || (reinterpret_cast<uintptr_t>(W) % kAlign) != 0)
+        return SALS_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const sals_desc& d = ctx->d;
+    const size_t n = ctx->L.w_section;
+    dim3 grid((unsigned)std::min<size_t>(2048, (n + 255) / 256), 4);
+    if (d.dtype == SALS_BF16)
+        hipLaunchKernelGGL((pack_weights_kernel<bf16_t>), grid, dim3(256), 0, st, static_cast<const bf16_t*>(Uk),
+                           static_cast<const bf16_t*>(Uv), static_cast<bf16_t*>(W), n, d.H_kv * d.d, d.r,
+                           d.rope_style);
+    else
+        hipLaunchKernelGGL((pack_weights_kernel<float>), grid, dim3(256), 0, st, static_cast<const float*>(Uk),
+                           static_cast<const float*>(Uv), static_cast<float*>(W), n, d.H_kv * d.d, d.r,
+                           d.rope_style);
+    return launch_status();
 }
 
 const char* sals_kernel_name(int kernel)
@@ -368,28 +382,24 @@ sals_status sals_profile_collect(sals_ctx* ctx, double* total_ms, int32_t* launc
     return st;
 }
 
-sals_status sals_compress_append(sals_ctx* ctx, const void* k_new, const void* v_new, const void* Uk,
-                                 const void* Uv, void* Kc, void* Vc, int32_t* seq_len, void* hip_stream)
+sals_status sals_compress_append(sals_ctx* ctx, const void* k_new, const void* v_new, const void* W, void* Kc,
+                                 void* Vc, int32_t* seq_len, void* hip_stream)
 {
-    if (!ctx || bad(k_new) || bad(v_new) || bad(Uk) || bad(Uv) || bad(Kc) || bad(Vc) || !seq_len)
-        return SALS_ERR_INVALID_ARG;
+    if (!ctx || bad(k_new) || bad(v_new) || bad(W) || bad(Kc) || bad(Vc) || !seq_len) return SALS_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const void* X[2] = {k_new, v_new};
-    const void* U[2] = {Uk, Uv};
-    void* cache[2] = {Kc, Vc};
-    return ctx->d.dtype == SALS_BF16 ? launch_project<bf16_t, false>(ctx, X, U, cache, 2, seq_len, st)
-                                     : launch_project<float, false>(ctx, X, U, cache, 2, seq_len, st);
+    return ctx->d.dtype == SALS_BF16
+               ? launch_project<bf16_t, false>(ctx, W, k_new, v_new, Kc, Vc, seq_len, st)
+               : launch_project<float, false>(ctx, W, k_new, v_new, Kc, Vc, seq_len, st);
 }
 
-sals_status sals_latent_scores(sals_ctx* ctx, const void* q, const void* Uk, const void* Kc,
+sals_status sals_latent_scores(sals_ctx* ctx, const void* q, const void* W, const void* Kc,
                                const int32_t* seq_len, float* scores, void* hip_stream)
 {
-    if (!ctx || bad(q) || bad(Uk) || bad(Kc) || !seq_len || bad(scores)) return SALS_ERR_INVALID_ARG;
+    if (!ctx || bad(q) || bad(W) || bad(Kc) || !seq_len || bad(scores)) return SALS_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const void* X[2] = {q, nullptr};
-    const void* U[2] = {Uk, nullptr};
-    sals_status s = ctx->d.dtype == SALS_BF16 ? launch_project<bf16_t, true>(ctx, X, U, nullptr, 1, nullptr, st)
-                                              : launch_project<float, true>(ctx, X, U, nullptr, 1, nullptr, st);
+    sals_status s = ctx->d.dtype == SALS_BF16
+                        ? launch_project<bf16_t, true>(ctx, W, q, nullptr, nullptr, nullptr, nullptr, st)
+                        : launch_project<float, true>(ctx, W, q, nullptr, nullptr, nullptr, nullptr, st);
     if (s != SALS_OK) return s;
     return ctx->d.dtype == SALS_BF16 ? launch_scores<bf16_t>(ctx, Kc, seq_len, scores, st)
                                      : launch_scores<float>(ctx, Kc, seq_len, scores, st);
@@ -403,32 +413,31 @@ sals_status sals_topk_select(sals_ctx* ctx, const float* scores, const int32_t* 
 }
 
 sals_status sals_sparse_attend(sals_ctx* ctx, const void* q, const int32_t* q_pos, const void* Kc,
-                               const void* Vc, const void* Uk, const void* Uv, const int32_t* idx,
-                               const int32_t* n_sel, void* out, void* hip_stream)
+                               const void* Vc, const void* W, const int32_t* idx, const int32_t* n_sel,
+                               void* out, void* hip_stream)
 {
-    if (!ctx || bad(q) || !q_pos || bad(Kc) || bad(Vc) || bad(Uk) || bad(Uv) || !idx || !n_sel || bad(out))
+    if (!ctx || bad(q) || !q_pos || bad(Kc) || bad(Vc) || bad(W) || !idx || !n_sel || bad(out))
         return SALS_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    return ctx->d.dtype == SALS_BF16
-               ? launch_attend<bf16_t>(ctx, q, q_pos, Kc, Vc, Uk, Uv, idx, n_sel, out, st)
-               : launch_attend<float>(ctx, q, q_pos, Kc, Vc, Uk, Uv, idx, n_sel, out, st);
+    return ctx->d.dtype == SALS_BF16 ? launch_attend<bf16_t>(ctx, q, q_pos, Kc, Vc, W, idx, n_sel, out, st)
+                                     : launch_attend<float>(ctx, q, q_pos, Kc, Vc, W, idx, n_sel, out, st);
 }
 
 sals_status sals_decode_step(sals_ctx* ctx, const void* q, const int32_t* q_pos, const void* Kc,
-                             const void* Vc, const void* Uk, const void* Uv, const int32_t* seq_len,
-                             void* out, float* scores, int32_t* idx, int32_t* n_sel, void* hip_stream)
+                             const void* Vc, const void* W, const int32_t* seq_len, void* out, float* scores,
+                             int32_t* idx, int32_t* n_sel, void* hip_stream)
 {
-    if (!ctx || bad(q) || !q_pos || bad(Kc) || bad(Vc) || bad(Uk) || bad(Uv) || !seq_len || bad(out))
+    if (!ctx || bad(q) || !q_pos || bad(Kc) || bad(Vc) || bad(W) || !seq_len || bad(out))
         return SALS_ERR_INVALID_ARG;
     if (scores && !aligned16(scores)) return SALS_ERR_INVALID_ARG;
     if (!scores) scores = reinterpret_cast<float*>(ctx->ws + ctx->L.scores);
     if (!idx) idx = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.idx);
     if (!n_sel) n_sel = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_sel);
-    sals_status s = sals_latent_scores(ctx, q, Uk, Kc, seq_len, scores, hip_stream);
+    sals_status s = sals_latent_scores(ctx, q, W, Kc, seq_len, scores, hip_stream);
     if (s != SALS_OK) return s;
     s = sals_topk_select(ctx, scores, seq_len, idx, n_sel, hip_stream);
     if (s != SALS_OK) return s;
-    return sals_sparse_attend(ctx, q, q_pos, Kc, Vc, Uk, Uv, idx, n_sel, out, hip_stream);
+    return sals_sparse_attend(ctx, q, q_pos, Kc, Vc, W, idx, n_sel, out, hip_stream);
 }
 
 }  // extern "C"

@@ -31,8 +31,12 @@ def make_ctx(w: synth.Workload) -> binding.Sals:
     return binding.Sals(desc, DEV)
 
 
-def upload(L: dict) -> dict:
-    return {k: to_dev(v) for k, v in L.items() if isinstance(v, np.ndarray)}
+def upload(L: dict, ctx=None) -> dict:
+    """Device copies of a layer; with a context, also its packed projectors under "W"."""
+    G = {k: to_dev(v) for k, v in L.items() if isinstance(v, np.ndarray)}
+    if ctx is not None:
+        G["W"] = ctx.pack_weights(G["Uk"], G["Uv"])
+    return G
 
 
 def out_dtype(w):
@@ -45,9 +49,9 @@ def run_stages(ctx, w, G):
     idx = torch.full((w.B, w.k_tot), -7, dtype=torch.int32, device=DEV)
     n_sel = torch.full((w.B,), -7, dtype=torch.int32, device=DEV)
     out = torch.empty((w.B, w.H, w.d), dtype=out_dtype(w), device=DEV)
-    ctx.latent_scores(G["q"], G["Uk"], G["Kc"], G["seq_len"], scores)
+    ctx.latent_scores(G["q"], G["W"], G["Kc"], G["seq_len"], scores)
     ctx.topk_select(scores, G["seq_len"], idx, n_sel)
-    ctx.sparse_attend(G["q"], G["q_pos"], G["Kc"], G["Vc"], G["Uk"], G["Uv"], idx, n_sel, out)
+    ctx.sparse_attend(G["q"], G["q_pos"], G["Kc"], G["Vc"], G["W"], idx, n_sel, out)
     torch.cuda.synchronize()
     return {"scores": scores, "idx": idx, "n_sel": n_sel, "out": out}
 

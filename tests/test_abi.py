@@ -61,6 +61,7 @@ def test_workspace_bytes_and_validation(sb):
         (dict(r=2048), sb.SALS_ERR_UNSUPPORTED),
         (dict(r_score=100), sb.SALS_ERR_UNSUPPORTED),
         (dict(H_q=128, H_kv=8), sb.SALS_ERR_UNSUPPORTED),
+        (dict(B=64), sb.SALS_ERR_UNSUPPORTED),            # B * (H_q/H_kv) > 128
     ]:
         with pytest.raises(sb.SalsError) as e:
             sb.workspace_bytes(_desc(sb, **bad))
@@ -87,9 +88,12 @@ def test_create_checks_workspace_and_calls_check_pointers(sb):
     assert lib.sals_latent_scores(h, ok, ok, ok + 4, ok, ok, None) == sb.SALS_ERR_INVALID_ARG   # misaligned cache
     assert lib.sals_latent_scores(None, ok, ok, ok, ok, ok, None) == sb.SALS_ERR_INVALID_ARG
     assert lib.sals_topk_select(h, ok, ok, None, ok, None) == sb.SALS_ERR_INVALID_ARG
-    assert lib.sals_sparse_attend(h, ok, ok, ok, ok, ok, ok, ok, ok, None, None) == sb.SALS_ERR_INVALID_ARG
-    assert lib.sals_compress_append(h, ok, ok, ok, ok, ok, ok, None, None) == sb.SALS_ERR_INVALID_ARG
-    assert lib.sals_decode_step(h, ok, ok, ok, ok, ok, ok, ok, None, None, None, None, None) \
+    assert lib.sals_sparse_attend(h, ok, ok, ok, ok, ok, ok, ok, None, None) == sb.SALS_ERR_INVALID_ARG
+    assert lib.sals_compress_append(h, ok, ok, ok, ok, ok, None, None) == sb.SALS_ERR_INVALID_ARG
+    assert lib.sals_decode_step(h, ok, ok, ok, ok, ok, ok, None, None, None, None, None) \
         == sb.SALS_ERR_INVALID_ARG
+    assert lib.sals_pack_weights(h, ok, ok, None, None) == sb.SALS_ERR_INVALID_ARG
+    assert lib.sals_pack_weights(h, ok, ok, ok + 16, None) == sb.SALS_ERR_INVALID_ARG   # W not 256-aligned
+    assert sb.packed_weight_bytes(d) == 4 * 8 * 128 * 512 * 2
     lib.sals_destroy(h)
     lib.sals_destroy(None)

@@ -24,14 +24,14 @@ C = synth.CONFIGS
 def _run(oracle, w, layer=0, seq_lens=None, seqs=None, label=""):
     print(f"[case] {label or w.name} layer={layer} seq_lens={seq_lens}", flush=True)
     L = synth.make_layer(w, layer, seq_lens)
-    G = gu.upload(L)
     ctx = gu.make_ctx(w)
+    G = gu.upload(L, ctx)
     R = gu.run_stages(ctx, w, G)
     # the fused entry point must reproduce the staged calls bit for bit
     out2 = torch.empty_like(R["out"])
     idx2 = torch.empty_like(R["idx"])
     n2 = torch.empty_like(R["n_sel"])
-    ctx.decode_step(G["q"], G["q_pos"], G["Kc"], G["Vc"], G["Uk"], G["Uv"], G["seq_len"], out2,
+    ctx.decode_step(G["q"], G["q_pos"], G["Kc"], G["Vc"], G["W"], G["seq_len"], out2,
                     None, idx2, n2)
     torch.cuda.synchronize()
     assert torch.equal(idx2, R["idx"]) and torch.equal(n2, R["n_sel"])
@@ -105,8 +105,8 @@ def test_exact_ties_resolve_to_smaller_index(oracle):
     w = synth.shrink(SMALL, B=1, S=512, top_k=64, plant=0)
     L = synth.make_layer(w)
     L["Kc"][0, 1::2] = L["Kc"][0, 0::2]          # rows 2m and 2m+1 identical
-    G = gu.upload(L)
     ctx = gu.make_ctx(w)
+    G = gu.upload(L, ctx)
     R = gu.run_stages(ctx, w, G)
     s = gu.from_dev(R["scores"][0])
     assert np.array_equal(s[0::2], s[1::2])
@@ -132,9 +132,10 @@ def test_compress_append_then_decode(oracle):
     k_new = synth.store(rng.standard_normal((w.B, w.D_kv)), w.dtype)
     v_new = synth.store(rng.standard_normal((w.B, w.D_kv)), w.dtype)
     ctx = gu.make_ctx(w)
+    G["W"] = ctx.pack_weights(G["Uk"], G["Uv"])
     for rep in range(2):           # second call: sequence 0 is full and must be left alone
         before = G["Kc"].clone()
-        ctx.compress_append(gu.to_dev(k_new), gu.to_dev(v_new), G["Uk"], G["Uv"], G["Kc"], G["Vc"],
+        ctx.compress_append(gu.to_dev(k_new), gu.to_dev(v_new), G["W"], G["Kc"], G["Vc"],
                             G["seq_len"])
         torch.cuda.synchronize()
         if rep == 0:
@@ -165,8 +166,8 @@ def test_compress_append_then_decode(oracle):
 def test_repeatable_bit_for_bit(oracle):
     w = synth.shrink(SMALL, B=2)
     L = synth.make_layer(w)
-    G = gu.upload(L)
     ctx = gu.make_ctx(w)
+    G = gu.upload(L, ctx)
     first = gu.run_stages(ctx, w, G)
     for _ in range(5):
         again = gu.run_stages(ctx, w, G)
