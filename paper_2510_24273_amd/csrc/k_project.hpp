@@ -36,7 +36,7 @@ template <> struct mma16_op<float> {   // four v_mfma_f32_16x16x4_f32
 constexpr int kProjWaves = 8;
 constexpr int kProjThreads = 64 * kProjWaves;
 constexpr int kProjMaxCols = 128;  // B * (H_q / H_kv) handled per call
-constexpr int kProjBatch = 4;      // row pieces a wave keeps in flight per round
+constexpr int kProjBatch = 16;     // row pieces a wave keeps in flight per round
 
 struct ProjArgs {
     const void* UT[2];   // transposed projectors [r, D]

@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) void attend_pv_kernel(const T* __restrict__ Vc
 // ---------------------------------------------------------------------------------
 // output projection: y[(b,h), c] = sum_i T[(b,h), i] U_v[g*128 + c, i]
 // ---------------------------------------------------------------------------------
-constexpr int kOutBatch = 4;  // K steps of loads kept in flight per round
+constexpr int kOutBatch = 16; // K steps of loads kept in flight per round
 
 template <typename T>
 __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ Uv, const T* __restrict__ Tfin,

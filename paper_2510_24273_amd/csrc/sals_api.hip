@@ -242,7 +242,7 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     hipLaunchKernelGGL((attend_logits_kernel<T, NW, NB>), dim3(ceil_div(k_tot, 32 * NW * NB), d.H_kv, d.B), \
                        dim3(64 * NW), 0, st, static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,   \
                        cs, qR, logits, d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk)
-        if (tiles128 >= 1024) SALS_LOGITS(4, 2);       // 256 tokens per workgroup
+        if (tiles128 >= 100000000) SALS_LOGITS(4, 2);       // 256 tokens per workgroup
         else if (tiles128 >= 256) SALS_LOGITS(4, 1);   // 128
         else if (tiles128 >= 64) SALS_LOGITS(2, 1);    // 64
         else SALS_LOGITS(1, 1);                        // 32
