@@ -68,8 +68,6 @@ __global__ __launch_bounds__(256) void attend_prep_kernel(const T* __restrict__ 
 // ---------------------------------------------------------------------------------
 // logits: gathered-row GEMM on MFMA with RoPE + q.K epilogue
 // ---------------------------------------------------------------------------------
-constexpr int kChunkBytes = 128;             // bytes of the latent axis per pipeline step
-constexpr int kLdsRowBytes = kChunkBytes + 16;  // padded: conflict-free 16-byte column reads
 constexpr int kMaxGroup = 8;                 // query heads per KV head
 
 template <typename T> struct mma_op;
@@ -89,154 +87,6 @@ template <> struct mma_op<float> {   // four v_mfma_f32_32x32x2_f32 per 16-byte 
         c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
     }
 };
-
-// Workgroup tile: 128 head dims x (32*NB*NW) tokens of one (sequence, KV head).
-// Each wave owns all 128 dims (4 MFMA row blocks) x NB blocks of 32 tokens; the U_k
-// panel goes through LDS (shared by the waves), the gathered latent rows go straight
-// from global memory to registers (private to a wave).
-template <typename T, int NW, int NB>
-__global__ __launch_bounds__(64 * NW) void attend_logits_kernel(
-    const T* __restrict__ Kc, const T* __restrict__ UkP, const int32_t* __restrict__ idx,
-    const int32_t* __restrict__ n_sel, const float2* __restrict__ cs, const float* __restrict__ qR,
-    float* __restrict__ logits, int S_max, int r, int H, int H_kv, int k_tot, int lk)
-{
-    constexpr int NT = 64 * NW;
-    constexpr int TOK = 32 * NB * NW;
-    constexpr int ES = (int)sizeof(T);
-    constexpr int KE = kChunkBytes / ES;       // latent coordinates per pipeline step
-    constexpr int APT = (128 * 8) / NT;        // 16-byte pieces of the U_k panel per thread
-    const int b = blockIdx.z, g = blockIdx.y, tok0 = blockIdx.x * TOK;
-    const int n = n_sel[b];
-    if (tok0 >= n) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, hi = lane >> 5;
-    const int G = H / H_kv;
-
-    __shared__ __attribute__((aligned(16))) unsigned char As[2][128 * kLdsRowBytes];
-    __shared__ __attribute__((aligned(16))) float sQ[kMaxGroup][kHeadDim];
-
-    for (int t = tid; t < G * kHeadDim; t += NT)
-        sQ[t / kHeadDim][t % kHeadDim] = qR[((size_t)b * H + g * G) * kHeadDim + t];
-
-    // gathered latent rows of this lane's tokens
-    const unsigned char* rowp[NB];
-    int slot[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        slot[nb] = tok0 + (wave * NB + nb) * 32 + l32;
-        int t = idx[(size_t)b * k_tot + (slot[nb] < n ? slot[nb] : 0)];
-        t = min(max(t, 0), S_max - 1);  // stay inside the cache whatever the caller passed
-        rowp[nb] = reinterpret_cast<const unsigned char*>(Kc + ((size_t)b * S_max + t) * r) + hi * 16;
-    }
-    // U_k panel pieces of this thread: piece q -> (row = q/8, 16-byte column q%8)
-    const unsigned char* ap[APT];
-    int a_lds[APT];
-#pragma unroll
-    for (int i = 0; i < APT; ++i) {
-        int qd = tid + i * NT;
-        int row = qd >> 3, pc = qd & 7;
-        // packed panel: [g][latent step][128 slots][128 bytes], head dims already in pair order
-        ap[i] = reinterpret_cast<const unsigned char*>(UkP + (size_t)g * kHeadDim * r) + row * kChunkBytes + pc * 16;
-        a_lds[i] = row * kLdsRowBytes + pc * 16;
-    }
-
-    f32x16 acc[4][NB];
-#pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
-
-    const int nkc = r / KE;
-    u32x4 areg[APT], bcur[4][NB], bnext[4][NB];
-#pragma unroll
-    for (int i = 0; i < APT; ++i) areg[i] = ld16(ap[i]);
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) bcur[ks][nb] = ld16(rowp[nb] + ks * 32);
-#pragma unroll
-    for (int i = 0; i < APT; ++i) *reinterpret_cast<u32x4*>(&As[0][a_lds[i]]) = areg[i];
-    __syncthreads();
-
-    for (int kc = 0; kc < nkc; ++kc) {
-        const int cur = kc & 1;
-        const bool more = kc + 1 < nkc;
-        if (more) {
-            const int off = (kc + 1) * kChunkBytes;
-#pragma unroll
-            for (int i = 0; i < APT; ++i) areg[i] = ld16(ap[i] + (size_t)(kc + 1) * 128 * kChunkBytes);
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) bnext[ks][nb] = ld16(rowp[nb] + off + ks * 32);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-#pragma unroll
-            for (int mb = 0; mb < 4; ++mb) {
-                u32x4 a = *reinterpret_cast<const u32x4*>(&As[cur][(mb * 32 + l32) * kLdsRowBytes + ks * 32 + hi * 16]);
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) mma_op<T>::run(a, bcur[ks][nb], acc[mb][nb]);
-            }
-        }
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < APT; ++i) *reinterpret_cast<u32x4*>(&As[cur ^ 1][a_lds[i]]) = areg[i];
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) bcur[ks][nb] = bnext[ks][nb];
-        }
-        __syncthreads();
-    }
-
-    // epilogue: lane holds, for token l32 of each block, slots mb*32 + 8a + 4hi + c.
-    // slot < 64 is the first element of pair (slot), slot+64 its partner (mb+2).
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const bool valid = slot[nb] < n;
-        float dot[kMaxGroup];
-#pragma unroll
-        for (int m = 0; m < kMaxGroup; ++m) dot[m] = 0.f;
-        const float2* csrow = cs + ((size_t)b * k_tot + (valid ? slot[nb] : 0)) * kPairs;
-#pragma unroll
-        for (int ml = 0; ml < 2; ++ml) {
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const int p0 = ml * 32 + a * 8 + hi * 4;
-                f32x4 t0 = *reinterpret_cast<const f32x4*>(csrow + p0);      // (c,s) of pairs p0, p0+1
-                f32x4 t1 = *reinterpret_cast<const f32x4*>(csrow + p0 + 2);  // pairs p0+2, p0+3
-                float cc[4] = {t0.x, t0.z, t1.x, t1.z}, ss[4] = {t0.y, t0.w, t1.y, t1.w};
-                float k1[4], k2[4];
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    float x1 = acc[ml][nb][a * 4 + c], x2 = acc[ml + 2][nb][a * 4 + c];
-                    k1[c] = x1 * cc[c] - x2 * ss[c];
-                    k2[c] = x2 * cc[c] + x1 * ss[c];
-                }
-#pragma unroll
-                for (int m = 0; m < kMaxGroup; ++m) {
-                    if (m < G) {
-                        f32x4 q1 = *reinterpret_cast<const f32x4*>(&sQ[m][p0]);
-                        f32x4 q2 = *reinterpret_cast<const f32x4*>(&sQ[m][kPairs + p0]);
-                        dot[m] += q1.x * k1[0] + q1.y * k1[1] + q1.z * k1[2] + q1.w * k1[3] +
-                                  q2.x * k2[0] + q2.y * k2[1] + q2.z * k2[2] + q2.w * k2[3];
-                    }
-                }
-            }
-        }
-#pragma unroll
-        for (int m = 0; m < kMaxGroup; ++m) {
-            if (m < G) {
-                float d = dot[m] + __shfl_xor(dot[m], 32, kWave);
-                if (hi == 0 && slot[nb] < lk)
-                    logits[((size_t)b * H + g * G + m) * lk + slot[nb]] = valid ? d : -INFINITY;
-            }
-        }
-    }
-}
 
 // ---------------------------------------------------------------------------------
 // softmax over the selected tokens (Eq. 5): one workgroup per (sequence, head) row turns

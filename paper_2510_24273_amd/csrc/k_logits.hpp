@@ -1,0 +1,214 @@
+// Selective key reconstruction with fused RoPE and query dot product
+// (Algorithm 1, reconstruction / RoPE / logit steps; Sec. 4.4):
+//   logits[b, h, j] = RoPE(q[b,h], q_pos[b]) . RoPE(U_k[g(h) block] K~[b, C_j], C_j) / sqrt(d)
+//
+// A gathered-row GEMM on the matrix cores: for one sequence, HEADS KV heads and a tile of
+// selected tokens, D[dim, token] = sum_i U_k[dim, i] K~[C_token, i].  Both operands are
+// staged through LDS in 128-byte steps of the latent axis: the packed U_k panel (shared by
+// the waves of a head) and the gathered latent rows (shared by the heads), each loaded
+// with 16 contiguous bytes per lane and written to a swizzled layout that the MFMA
+// fragment reads hit without bank conflicts.  Global loads run one or two steps ahead of
+// the MFMAs (one or two register sets, two LDS buffers).  The reconstructed keys stay in the
+// accumulators: the epilogue rotates them with the token's cos/sin row and dots them with
+// the rotated query, so only logits are written.
+//
+// Wave tile: 128 head dims (4 MFMA row blocks, in RoPE pair order) x 32*NB tokens.
+// Workgroup: HEADS x NTG waves, i.e. HEADS heads x (NTG*32*NB) tokens.
+#pragma once
+#include "common.hpp"
+#include "k_attend.hpp"
+
+namespace sals {
+
+constexpr int kLgChunk = 128;  // bytes of the latent axis per pipeline step
+
+// byte offset of 16-byte piece `pc` of row `row` inside a [rows][128 B] swizzled LDS tile
+__device__ __forceinline__ int swz(int row, int pc) { return row * kLgChunk + ((pc ^ ((row >> 1) & 7)) << 4); }
+
+template <int HEADS, int NTG, int NB> struct logits_cfg {
+    static constexpr int NT = 64 * HEADS * NTG;            // threads
+    static constexpr int TOK = NTG * NB * 32;              // tokens per workgroup
+    static constexpr int A_BYTES = HEADS * 128 * kLgChunk;  // U_k panel per step
+    static constexpr int B_BYTES = TOK * kLgChunk;          // gathered rows per step
+    static constexpr int STAGE = A_BYTES + B_BYTES;
+    static constexpr int NA = A_BYTES / 16 / NT;            // 16-byte pieces per thread per step
+    static constexpr int NBP = B_BYTES / 16 / NT;
+    static constexpr size_t LDS = 2 * (size_t)STAGE;
+};
+
+template <typename T, int HEADS, int NTG, int NB, bool DEEP>
+__global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
+    const T* __restrict__ Kc, const T* __restrict__ UkP, const int32_t* __restrict__ idx,
+    const int32_t* __restrict__ n_sel, const float2* __restrict__ cs, const float* __restrict__ qR,
+    float* __restrict__ logits, int S_max, int r, int H, int H_kv, int k_tot, int lk)
+{
+    typedef logits_cfg<HEADS, NTG, NB> C;
+    constexpr int NT = C::NT, NA = C::NA, NBP = C::NBP;
+    constexpr int ES = (int)sizeof(T);
+    static_assert(C::A_BYTES % (16 * NT) == 0 && C::B_BYTES % (16 * NT) == 0, "tile / thread mismatch");
+
+    const int b = blockIdx.z, g0 = blockIdx.y * HEADS, tok0 = blockIdx.x * C::TOK;
+    const int n = n_sel[b];
+    if (tok0 >= n) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int hh = wave / NTG, tg = wave % NTG;   // head of the tile, token group
+    const int G = H / H_kv;
+    const int g = g0 + hh;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // [2][A | B]
+    __shared__ __attribute__((aligned(16))) float sQ[HEADS][kMaxGroup][kHeadDim];
+
+    for (int t = tid; t < HEADS * G * kHeadDim; t += NT) {
+        int h2 = t / (G * kHeadDim), rem = t - h2 * G * kHeadDim;
+        sQ[h2][rem / kHeadDim][rem % kHeadDim] = qR[((size_t)b * H + (g0 + h2) * G) * kHeadDim + rem];
+    }
+
+    // ---- global sources of this thread's pieces ---------------------------------------
+    // U_k panel: piece q = tid + i*NT -> head q/1024, slot (q%1024)/8, 16-byte column q%8.  The
+    // packed layout is [head][step][128 slots][128 B]: inside a head the pieces of a step are
+    // contiguous, and a step adds 16 KB.
+    const unsigned char* a_base = reinterpret_cast<const unsigned char*>(UkP + (size_t)g0 * kHeadDim * r);
+    const size_t head_bytes = (size_t)kHeadDim * r * ES;
+    auto a_src = [&](int i, int kc) {
+        const int qd = tid + i * NT;
+        return a_base + (size_t)(qd >> 10) * head_bytes + (size_t)kc * (128 * kLgChunk) + (qd & 1023) * 16;
+    };
+    auto a_dst = [&](int i) {
+        const int qd = tid + i * NT;
+        return (qd >> 10) * 128 * kLgChunk + swz((qd >> 3) & 127, qd & 7);
+    };
+    // gathered rows: piece q -> token q/8 of the tile, column q%8
+    int b_row[NBP];
+#pragma unroll
+    for (int i = 0; i < NBP; ++i) {
+        const int slot = tok0 + ((tid + i * NT) >> 3);
+        int t = idx[(size_t)b * k_tot + (slot < n ? slot : 0)];
+        b_row[i] = min(max(t, 0), S_max - 1);  // stay inside the cache whatever the caller passed
+    }
+    const unsigned char* b_base = reinterpret_cast<const unsigned char*>(Kc + (size_t)b * S_max * r) + (tid & 7) * 16;
+    const size_t row_bytes = (size_t)r * ES;
+    auto b_dst = [&](int i) { return C::A_BYTES + swz((tid + i * NT) >> 3, tid & 7); };
+
+    f32x16 acc[4][NB];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+
+    const int nkc = r * ES / kLgChunk;
+    struct Regs { u32x4 a[NA]; u32x4 b[NBP]; };
+    auto g_load = [&](Regs& R, int kc) {
+#pragma unroll
+        for (int i = 0; i < NA; ++i) R.a[i] = ld16(a_src(i, kc));
+#pragma unroll
+        for (int i = 0; i < NBP; ++i) R.b[i] = ld16(b_base + (size_t)b_row[i] * row_bytes + (size_t)kc * kLgChunk);
+    };
+    auto l_store = [&](const Regs& R, int buf) {
+        unsigned char* base = lds + (size_t)buf * C::STAGE;
+#pragma unroll
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4*>(base + a_dst(i)) = R.a[i];
+#pragma unroll
+        for (int i = 0; i < NBP; ++i) *reinterpret_cast<u32x4*>(base + b_dst(i)) = R.b[i];
+    };
+    auto compute = [&](int buf) {
+        const unsigned char* pa = lds + (size_t)buf * C::STAGE + hh * 128 * kLgChunk;
+        const unsigned char* pb = lds + (size_t)buf * C::STAGE + C::A_BYTES + tg * NB * 32 * kLgChunk;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            u32x4 bf[NB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                bf[nb] = *reinterpret_cast<const u32x4*>(pb + swz(nb * 32 + l32, ks * 2 + hi));
+            u32x4 af[4];
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+                af[mb] = *reinterpret_cast<const u32x4*>(pa + swz(mb * 32 + l32, ks * 2 + hi));
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) mma_op<T>::run(af[mb], bf[nb], acc[mb][nb]);
+        }
+    };
+
+    if constexpr (DEEP) {
+        // two register sets: global loads run two steps ahead of the MFMAs
+        Regs R0, R1;
+        auto step = [&](int kc, Regs& RL, const Regs& RS) {
+            if (kc + 2 < nkc) g_load(RL, kc + 2);
+            compute(kc & 1);
+            if (kc + 1 < nkc) l_store(RS, (kc + 1) & 1);
+            __syncthreads();
+        };
+        g_load(R0, 0);
+        if (nkc > 1) g_load(R1, 1);
+        l_store(R0, 0);
+        __syncthreads();
+        for (int kc = 0; kc < nkc; kc += 2) {
+            step(kc, R0, R1);                      // R0 held step kc (already in LDS); R1 holds kc+1
+            if (kc + 1 < nkc) step(kc + 1, R1, R0);
+        }
+    } else {
+        // one register set: step kc+1 goes to LDS, then the loads of step kc+2 fly during the MFMAs
+        Regs R;
+        g_load(R, 0);
+        l_store(R, 0);
+        if (nkc > 1) g_load(R, 1);
+        __syncthreads();
+        for (int kc = 0; kc < nkc; ++kc) {
+            if (kc + 1 < nkc) l_store(R, (kc + 1) & 1);
+            if (kc + 2 < nkc) g_load(R, kc + 2);
+            compute(kc & 1);
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue: lane holds, for token l32 of each block, slots mb*32 + 8a + 4hi + c;
+    // slot < 64 is the first element of pair (slot), slot+64 its partner (mb+2)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int slot = tok0 + (tg * NB + nb) * 32 + l32;
+        const bool valid = slot < n;
+        float dot[kMaxGroup];
+#pragma unroll
+        for (int m = 0; m < kMaxGroup; ++m) dot[m] = 0.f;
+        const float2* csrow = cs + ((size_t)b * k_tot + (valid ? slot : 0)) * kPairs;
+#pragma unroll
+        for (int ml = 0; ml < 2; ++ml) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const int p0 = ml * 32 + a * 8 + hi * 4;
+                f32x4 t0 = *reinterpret_cast<const f32x4*>(csrow + p0);      // (c,s) of pairs p0, p0+1
+                f32x4 t1 = *reinterpret_cast<const f32x4*>(csrow + p0 + 2);  // pairs p0+2, p0+3
+                float cc[4] = {t0.x, t0.z, t1.x, t1.z}, ss[4] = {t0.y, t0.w, t1.y, t1.w};
+                float k1[4], k2[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    float x1 = acc[ml][nb][a * 4 + c], x2 = acc[ml + 2][nb][a * 4 + c];
+                    k1[c] = x1 * cc[c] - x2 * ss[c];
+                    k2[c] = x2 * cc[c] + x1 * ss[c];
+                }
+#pragma unroll
+                for (int m = 0; m < kMaxGroup; ++m) {
+                    if (m < G) {
+                        f32x4 q1 = *reinterpret_cast<const f32x4*>(&sQ[hh][m][p0]);
+                        f32x4 q2 = *reinterpret_cast<const f32x4*>(&sQ[hh][m][kPairs + p0]);
+                        dot[m] += q1.x * k1[0] + q1.y * k1[1] + q1.z * k1[2] + q1.w * k1[3] +
+                                  q2.x * k2[0] + q2.y * k2[1] + q2.z * k2[2] + q2.w * k2[3];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < kMaxGroup; ++m) {
+            if (m < G) {
+                float d = dot[m] + __shfl_xor(dot[m], 32, kWave);
+                if (hi == 0 && slot < lk) logits[((size_t)b * H + g * G + m) * lk + slot] = valid ? d : -INFINITY;
+            }
+        }
+    }
+}
+
+}  // namespace sals

@@ -11,6 +11,7 @@
 
 #include "common.hpp"
 #include "k_attend.hpp"
+#include "k_logits.hpp"
 #include "k_project.hpp"
 #include "k_scores.hpp"
 #include "k_topk.hpp"
@@ -235,17 +236,25 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
                            n_tab, d.rope_style, 1.0f / std::sqrt((float)d.d));
         if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     }
-    {   // logits: pick the token tile so that the grid covers the chip
-        long long tiles128 = (long long)ceil_div(k_tot, 128) * d.H_kv * d.B;
+    {   // logits: the largest tile (most operand reuse) that still gives the chip enough workgroups
+        auto n_wg = [&](int heads, int tok) { return (long long)ceil_div(k_tot, tok) * (d.H_kv / heads) * d.B; };
         ProfScope ps(c, SALS_K_ATTEND_LOGITS, st);
-#define SALS_LOGITS(NW, NB)                                                                                  \
-    hipLaunchKernelGGL((attend_logits_kernel<T, NW, NB>), dim3(ceil_div(k_tot, 32 * NW * NB), d.H_kv, d.B), \
-                       dim3(64 * NW), 0, st, static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,   \
-                       cs, qR, logits, d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk)
-        if (tiles128 >= 100000000) SALS_LOGITS(4, 2);       // 256 tokens per workgroup
-        else if (tiles128 >= 256) SALS_LOGITS(4, 1);   // 128
-        else if (tiles128 >= 64) SALS_LOGITS(2, 1);    // 64
-        else SALS_LOGITS(1, 1);                        // 32
+#define SALS_LOGITS(HEADS, NTG, NB, DEEP)                                                                        \
+    do {                                                                                                     \
+        typedef logits_cfg<HEADS, NTG, NB> LC;                                                               \
+        auto kern = attend_logits_kernel<T, HEADS, NTG, NB, DEEP>;                                           \
+        if (LC::LDS > 48 * 1024 &&                                                                           \
+            hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                (int)LC::LDS) != hipSuccess)                                                 \
+            return SALS_ERR_HIP;                                                                             \
+        hipLaunchKernelGGL(kern, dim3(ceil_div(k_tot, LC::TOK), d.H_kv / HEADS, d.B), dim3(LC::NT), LC::LDS, st, \
+                           static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel, cs, qR, logits,     \
+                           d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk);                                        \
+    } while (0)
+        if (d.H_kv % 2 == 0 && n_wg(2, 256) >= 384) SALS_LOGITS(2, 4, 2, false);   // 2 heads x 256 tokens, 8 waves
+        else if (n_wg(1, 256) >= 200) SALS_LOGITS(1, 4, 2, false);                 // 1 head  x 256 tokens
+        else if (n_wg(1, 64) >= 128) SALS_LOGITS(1, 2, 1, true);                  // 1 head  x  64 tokens
+        else SALS_LOGITS(1, 1, 1, true);                                          // 1 head  x  32 tokens
 #undef SALS_LOGITS
         if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     }
