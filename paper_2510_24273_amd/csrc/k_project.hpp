@@ -3,8 +3,9 @@
 //
 // The projection reads the TRANSPOSED projector U^T [r x D] (made once by pack_weights),
 // so each output coordinate is a dot product along a contiguous row: a workgroup owns 16
-// latent coordinates, its 8 waves split the D axis, and every wave keeps all of its
-// 16-byte row pieces in flight at once.  The products run on 16x16 MFMA tiles whose
+// latent coordinates and one slice of the D axis (the slices' partial sums are added by
+// the score kernel, in slice order), its 4 waves split the slice, and every wave keeps all
+// of its 16-byte row pieces in flight at once.  The products run on 16x16 MFMA tiles whose
 // columns are the (sequence, query head of the KV group) pairs, so a whole batch costs
 // one pass over U^T; the heads of a group are added in fp32 afterwards, which equals
 // projecting their sum.  Single pass, fixed summation order, bit-reproducible.
@@ -33,18 +34,18 @@ template <> struct mma16_op<float> {   // four v_mfma_f32_16x16x4_f32
     }
 };
 
-constexpr int kProjWaves = 8;
+constexpr int kProjWaves = 4;
 constexpr int kProjThreads = 64 * kProjWaves;
 constexpr int kProjMaxCols = 128;  // B * (H_q / H_kv) handled per call
-constexpr int kProjBatch = 16;     // row pieces a wave keeps in flight per round
+constexpr int kProjBatch = 8;      // row pieces a wave keeps in flight per round
 
 struct ProjArgs {
     const void* UT[2];   // transposed projectors [r, D]
     const void* X[2];    // QUERY: q [B,H,d] (X[0]); else new key / value [B,D]
     void* cache[2];      // append: [B,S_max,r]
-    float* out_f32;      // QUERY: q~ [B,r]
+    float* out_f32;      // QUERY: partial q~ [np,B,r], one slice of the D axis each
     const int32_t* seq_len;  // append: [B] row to write
-    int B, D, r, H, H_kv, d, S_max, nproj;
+    int B, D, r, H, H_kv, d, S_max, nproj, np;
 };
 
 template <typename T, bool QUERY>
@@ -52,13 +53,14 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(ProjArgs a)
 {
     constexpr int VEC = elem<T>::vec;
     constexpr int KS = 4 * VEC;  // elements of the D axis per MFMA step
-    const int proj = blockIdx.y;
+    const int proj = blockIdx.z, slice = blockIdx.y;
     const int i0 = blockIdx.x * 16;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, kg = lane >> 4;
     const int G = QUERY ? a.H / a.H_kv : 1;
     const int ncols = a.B * G, n_nblk = (ncols + 15) >> 4;
-    const int nks = a.D / KS;
+    const int nks_all = a.D / KS, nks = nks_all / a.np;   // steps of this workgroup's slice
+    const int ks_first = slice * nks;
     const T* UT = static_cast<const T*>(a.UT[proj]);
     const T* X = static_cast<const T*>(a.X[proj]);
     const T* arow = UT + (size_t)(i0 + l16) * a.D + kg * VEC;
@@ -76,7 +78,7 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(ProjArgs a)
 #pragma unroll
         for (int u = 0; u < kProjBatch; ++u) {
             int ks = ks0 + u * kProjWaves;
-            af[u] = ks < nks ? ld16(arow + (size_t)ks * KS) : u32x4{0, 0, 0, 0};
+            af[u] = ks < nks ? ld16(arow + (size_t)(ks_first + ks) * KS) : u32x4{0, 0, 0, 0};
         }
 #pragma unroll
         for (int nb = 0; nb < kProjMaxCols / 16; ++nb) {
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(ProjArgs a)
                     int ks = ks0 + u * kProjWaves;
                     bf[u] = u32x4{0, 0, 0, 0};
                     if (ks < nks && n < ncols) {
-                        int c = ks * KS + kg * VEC;
+                        int c = (ks_first + ks) * KS + kg * VEC;
                         const T* xp;
                         if (QUERY) {
                             int b = n / G, m = n - b * G, g = c / a.d;
@@ -113,7 +115,7 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(ProjArgs a)
 #pragma unroll
             for (int v = 0; v < 4; ++v) red[wave][lane][v] = acc[nb][v];
             __syncthreads();
-            if (tid < 256) {
+            {
                 int col = tid & 15, rr = tid >> 4;
                 int src_lane = (rr >> 2) * 16 + col, v = rr & 3;
                 float s = 0.f;
@@ -130,7 +132,7 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(ProjArgs a)
         float s = 0.f;
         for (int m = 0; m < G; ++m) s += colsum[b * G + m][rr];
         if (QUERY) {
-            a.out_f32[(size_t)b * a.r + i0 + rr] = s;
+            a.out_f32[((size_t)slice * a.B + b) * a.r + i0 + rr] = s;
         } else {
             int row = a.seq_len[b];
             if (row < a.S_max)

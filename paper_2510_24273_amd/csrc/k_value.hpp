@@ -15,6 +15,7 @@
 #pragma once
 #include "common.hpp"
 #include "k_attend.hpp"
+#include "k_project.hpp"
 
 namespace sals {
 
@@ -150,8 +151,13 @@ __global__ __launch_bounds__(256) void attend_pv_kernel(const T* __restrict__ Vc
 
 // ---------------------------------------------------------------------------------
 // output projection: y[(b,h), c] = sum_i T[(b,h), i] U_v[g*128 + c, i]
+//
+// One workgroup per (KV head, 16 output channels): 8 x H_kv workgroups, so that the single
+// pass over U_v is spread over the whole chip.  16x16 MFMA tiles: rows are the (sequence,
+// head of the group) pairs, columns the channels; the latent axis is split over the four
+// waves, every wave issuing all of its loads as one batch.
 // ---------------------------------------------------------------------------------
-constexpr int kOutBatch = 16; // K steps of loads kept in flight per round
+constexpr int kOutBatch = 8;  // latent steps of loads kept in flight per round
 
 template <typename T>
 __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ Uv, const T* __restrict__ Tfin,
@@ -159,108 +165,104 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
                                                          int B, int r, int H, int H_kv, int n_tr)
 {
     constexpr int VEC = elem<T>::vec;
+    constexpr int KS = 4 * VEC;  // latent coordinates per MFMA step
     constexpr bool kSplit = sizeof(T) == 2;
-    __shared__ __attribute__((aligned(16))) float red[3][64][17];
+    __shared__ __attribute__((aligned(16))) float red[3][64][5];
 
     const int g = blockIdx.y, cb = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, hi = lane >> 5;
+    const int l16 = lane & 15, kg = lane >> 4;
     const int G = H / H_kv;
     const int n_rows = B * G;  // (sequence, head of this group) pairs
-    const int nks = r / (2 * VEC), kpw = nks / 4;
-    const T* urow = Uv + ((size_t)g * kHeadDim + cb * 32 + l32) * r + hi * VEC;
+    const int nks = r / KS;
+    const T* urow = Uv + ((size_t)g * kHeadDim + cb * 16 + l16) * r + kg * VEC;
     const T* Thi_arr = Tfin;
     const T* Tlo_arr = Tfin + (size_t)B * H * r;
+    const size_t tstride = (size_t)B * H * r;
 
-    for (int row0 = 0; row0 < n_rows; row0 += 32) {
-        const int row = row0 + l32;
+    for (int row0 = 0; row0 < n_rows; row0 += 16) {
+        const int row = row0 + l16;
         const bool row_ok = row < n_rows;
         const int bb = row_ok ? row / G : 0, h = row_ok ? g * G + row % G : 0;
-        const size_t trow = ((size_t)bb * H + h) * r + hi * VEC;
-        f32x16 acc;
+        const size_t trow = ((size_t)bb * H + h) * r + kg * VEC;
+        f32x4v acc = {0.f, 0.f, 0.f, 0.f};
+        for (int ks0 = wave; ks0 < nks; ks0 += 4 * kOutBatch) {  // this wave: ks0, ks0+4, ...
+            u32x4 bf[kOutBatch], ah[kOutBatch], al[kOutBatch];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-        if (n_tr == 1) {
-            for (int ks0 = wave * kpw; ks0 < (wave + 1) * kpw; ks0 += kOutBatch) {
-                u32x4 bf[kOutBatch], ah[kOutBatch], al[kOutBatch];
+            for (int u = 0; u < kOutBatch; ++u) {
+                const int ks = ks0 + 4 * u;
+                const bool ok = ks < nks;
+                const int i0 = ks * KS;
+                bf[u] = ok ? ld16(urow + i0) : u32x4{0, 0, 0, 0};
+                ah[u] = u32x4{0, 0, 0, 0};
+                al[u] = u32x4{0, 0, 0, 0};
+                if (ok && row_ok) {
+                    if (n_tr == 1) {
+                        ah[u] = ld16(Thi_arr + trow + i0);
+                        if constexpr (kSplit) al[u] = ld16(Tlo_arr + trow + i0);
+                    } else {
+                        // several token ranges: add their fp32 partial sums in range order, then split
+                        float tm[VEC];
 #pragma unroll
-                for (int u = 0; u < kOutBatch; ++u) {
-                    const int ks = ks0 + u;
-                    const bool ok = ks < (wave + 1) * kpw;
-                    const int i0 = ks * 2 * VEC;
-                    bf[u] = ok ? ld16(urow + i0) : u32x4{0, 0, 0, 0};
-                    ah[u] = (ok && row_ok) ? ld16(Thi_arr + trow + i0) : u32x4{0, 0, 0, 0};
-                    if constexpr (kSplit) al[u] = (ok && row_ok) ? ld16(Tlo_arr + trow + i0) : u32x4{0, 0, 0, 0};
-                }
+                        for (int v = 0; v < VEC; ++v) tm[v] = 0.f;
+                        for (int t0 = 0; t0 < n_tr; t0 += 4) {
+                            f32x4 x[4][VEC / 4];
 #pragma unroll
-                for (int u = 0; u < kOutBatch; ++u) {
-                    mma_op<T>::run(ah[u], bf[u], acc);
-                    if constexpr (kSplit) mma_op<T>::run(al[u], bf[u], acc);
+                            for (int w = 0; w < 4; ++w)
+#pragma unroll
+                                for (int v = 0; v < VEC / 4; ++v)
+                                    x[w][v] = t0 + w < n_tr
+                                                  ? *reinterpret_cast<const f32x4*>(Tpart + (size_t)(t0 + w) * tstride +
+                                                                                    trow + i0 + 4 * v)
+                                                  : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                            for (int w = 0; w < 4; ++w)
+#pragma unroll
+                                for (int v = 0; v < VEC / 4; ++v) {
+                                    tm[4 * v] += x[w][v].x; tm[4 * v + 1] += x[w][v].y;
+                                    tm[4 * v + 2] += x[w][v].z; tm[4 * v + 3] += x[w][v].w;
+                                }
+                        }
+                        if constexpr (kSplit) {
+                            uint32_t hw[8], lw[8];
+#pragma unroll
+                            for (int v = 0; v < 8; ++v) {
+                                bf16_t ph = f32_to_bf16(tm[v]);
+                                hw[v] = ph;
+                                lw[v] = f32_to_bf16(tm[v] - bf16_to_f32(ph));
+                            }
+                            ah[u] = u32x4{hw[0] | (hw[1] << 16), hw[2] | (hw[3] << 16), hw[4] | (hw[5] << 16),
+                                          hw[6] | (hw[7] << 16)};
+                            al[u] = u32x4{lw[0] | (lw[1] << 16), lw[2] | (lw[3] << 16), lw[4] | (lw[5] << 16),
+                                          lw[6] | (lw[7] << 16)};
+                        } else {
+                            ah[u] = u32x4{__float_as_uint(tm[0]), __float_as_uint(tm[1]), __float_as_uint(tm[2]),
+                                          __float_as_uint(tm[3])};
+                        }
+                    }
                 }
             }
-        } else {
-            // several token ranges: add their fp32 partial sums in range order, then split
-            const size_t tstride = (size_t)B * H * r;
-            for (int ks = wave * kpw; ks < (wave + 1) * kpw; ++ks) {
-                const int i0 = ks * 2 * VEC;
-                u32x4 bf = ld16(urow + i0);
-                float tm[VEC];
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) tm[v] = 0.f;
-                if (row_ok) {
-                    for (int t0 = 0; t0 < n_tr; t0 += 4) {
-                        f32x4 x[4][VEC / 4];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u)
-#pragma unroll
-                            for (int v = 0; v < VEC / 4; ++v)
-                                x[u][v] = t0 + u < n_tr
-                                              ? *reinterpret_cast<const f32x4*>(Tpart + (size_t)(t0 + u) * tstride +
-                                                                                trow + i0 + 4 * v)
-                                              : f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                        for (int u = 0; u < 4; ++u)
-#pragma unroll
-                            for (int v = 0; v < VEC / 4; ++v) {
-                                tm[4 * v] += x[u][v].x; tm[4 * v + 1] += x[u][v].y;
-                                tm[4 * v + 2] += x[u][v].z; tm[4 * v + 3] += x[u][v].w;
-                            }
-                    }
-                }
-                if constexpr (kSplit) {
-                    uint32_t hw[8], lw[8];
-#pragma unroll
-                    for (int v = 0; v < 8; ++v) {
-                        bf16_t ph = f32_to_bf16(tm[v]);
-                        hw[v] = ph;
-                        lw[v] = f32_to_bf16(tm[v] - bf16_to_f32(ph));
-                    }
-                    u32x4 ah = {hw[0] | (hw[1] << 16), hw[2] | (hw[3] << 16), hw[4] | (hw[5] << 16), hw[6] | (hw[7] << 16)};
-                    u32x4 al = {lw[0] | (lw[1] << 16), lw[2] | (lw[3] << 16), lw[4] | (lw[5] << 16), lw[6] | (lw[7] << 16)};
-                    mma_op<T>::run(ah, bf, acc);
-                    mma_op<T>::run(al, bf, acc);
-                } else {
-                    u32x4 af = {__float_as_uint(tm[0]), __float_as_uint(tm[1]), __float_as_uint(tm[2]),
-                                __float_as_uint(tm[3])};
-                    mma_op<T>::run(af, bf, acc);
-                }
+            for (int u = 0; u < kOutBatch; ++u) {
+                mma16_op<T>::run(ah[u], bf[u], acc);
+                if constexpr (kSplit) mma16_op<T>::run(al[u], bf[u], acc);
             }
         }
-        // fold the four K slices (waves) and write: acc[4a+c] is tile row 8a+4hi+c, column l32
+        // fold the four latent slices (waves) in order; acc[v] is tile row 4*kg+v, channel l16
         __syncthreads();
         if (wave > 0) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) red[wave - 1][lane][v] = acc[v];
+            for (int v = 0; v < 4; ++v) red[wave - 1][lane][v] = acc[v];
         }
         __syncthreads();
         if (wave == 0) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
+            for (int v = 0; v < 4; ++v) {
                 float y = acc[v] + red[0][lane][v] + red[1][lane][v] + red[2][lane][v];
-                int orow = row0 + (v >> 2) * 8 + hi * 4 + (v & 3);
+                int orow = row0 + kg * 4 + v;
                 if (orow < n_rows) {
                     int ob = orow / G, oh = g * G + orow % G;
-                    elem<T>::store(out + ((size_t)ob * H + oh) * kHeadDim + cb * 32 + l32, y);
+                    elem<T>::store(out + ((size_t)ob * H + oh) * kHeadDim + cb * 16 + l16, y);
                 }
             }
         }

@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <new>
 #include <vector>
 
@@ -29,6 +30,7 @@ struct Layout {  // byte offsets into the workspace
     size_t qt, scores, idx, n_sel, cs, qR, logits, pw, tpart, tfin, total;
     int lk;                      // logits row stride (floats)
     int pv_tok_per_wg, pv_ntr;   // value-sum token ranges
+    int proj_np;                 // D-axis slices of the query projection
     size_t w_section;            // elements per section of the packed weights
 };
 
@@ -101,6 +103,12 @@ Layout make_layout(const sals_desc& d)
     const int k_tot = d.top_k + d.n_sink + d.n_recent;
     L.lk = ceil_div(k_tot, 64) * 64;
     L.w_section = (size_t)D * d.r;
+    {   // query projection: slice the D axis until about 256 workgroups stream U_k^T
+        int nks = D / (d.dtype == SALS_BF16 ? 32 : 16);
+        int np = 1;
+        while (np < 8 && (d.r / 16) * np < 256 && nks % (np * 2) == 0 && nks / (np * 2) >= 4) np *= 2;
+        L.proj_np = np;
+    }
     // value sum: split the selected tokens into ranges until about 256 workgroups exist
     {
         int blocks = d.r / kPvCols;
@@ -113,7 +121,7 @@ Layout make_layout(const sals_desc& d)
     }
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
-    L.qt = take((size_t)d.B * d.r * 4);
+    L.qt = take((size_t)L.proj_np * d.B * d.r * 4);
     L.scores = take((size_t)d.B * d.S_max * 4);
     L.idx = take((size_t)d.B * k_tot * 4);
     L.n_sel = take((size_t)d.B * 4);
@@ -153,10 +161,10 @@ sals_status launch_project(const sals_ctx* c, const void* W, const void* x0, con
     a.out_f32 = reinterpret_cast<float*>(c->ws + c->L.qt);
     a.seq_len = seq_len;
     a.B = d.B; a.D = d.H_kv * d.d; a.r = d.r; a.H = d.H_q; a.H_kv = d.H_kv; a.d = d.d;
-    a.S_max = d.S_max; a.nproj = QUERY ? 1 : 2;
+    a.S_max = d.S_max; a.nproj = QUERY ? 1 : 2; a.np = QUERY ? c->L.proj_np : 1;
     {
         ProfScope ps(c, SALS_K_PROJECT, st);
-        hipLaunchKernelGGL((project_kernel<T, QUERY>), dim3(d.r / 16, a.nproj), dim3(kProjThreads), 0, st, a);
+        hipLaunchKernelGGL((project_kernel<T, QUERY>), dim3(d.r / 16, a.np, a.nproj), dim3(kProjThreads), 0, st, a);
     }
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     if (!QUERY)
@@ -171,9 +179,10 @@ sals_status launch_scores(const sals_ctx* c, const void* Kc, const int32_t* seq_
     const sals_desc& d = c->d;
     constexpr int VEC = elem<T>::vec;
     const int nch = ceil_div(d.r_score / VEC, 16);
-    // rows per workgroup: a multiple of 16 giving roughly 2048+ workgroups
+    // rows per workgroup: a multiple of 16 giving roughly 1024 workgroups, 16..128 rows (measured optimum)
     long long total_rows = (long long)d.B * d.S_max;
-    int rows = (int)std::min<long long>(256, std::max<long long>(16, total_rows / 4096));
+    int rows = (int)std::min<long long>(128, std::max<long long>(16, total_rows / 1024));
+    if (const char* e = std::getenv("SALS_TUNE_SCORE_ROWS")) rows = std::atoi(e);  // tuning aid
     rows = ceil_div(rows, kScoreRowsPerIter) * kScoreRowsPerIter;
     dim3 grid(ceil_div(d.S_max, rows), d.B);
     const float* qt = reinterpret_cast<const float*>(c->ws + c->L.qt);
@@ -181,8 +190,8 @@ sals_status launch_scores(const sals_ctx* c, const void* Kc, const int32_t* seq_
     ProfScope ps(c, SALS_K_SCORES, st);
 #define SALS_SCORES_CASE(N)                                                                         \
     case N:                                                                                         \
-        hipLaunchKernelGGL((scores_kernel<T, N>), grid, dim3(kScoreThreads), 0, st, K, qt, seq_len, \
-                           scores, d.S_max, d.r, d.r_score, rows);                                  \
+        hipLaunchKernelGGL((scores_kernel<T, N>), grid, dim3(kScoreThreads), 0, st, K, qt, c->L.proj_np, \
+                           seq_len, scores, d.B, d.S_max, d.r, d.r_score, rows);                       \
         break;
     switch (nch) {
         SALS_SCORES_CASE(1) SALS_SCORES_CASE(2) SALS_SCORES_CASE(3) SALS_SCORES_CASE(4)
@@ -273,7 +282,7 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     {
         ProfScope ps(c, SALS_K_ATTEND_OUT, st);
-        hipLaunchKernelGGL((attend_out_kernel<T>), dim3(kHeadDim / 32, d.H_kv), dim3(256), 0, st,
+        hipLaunchKernelGGL((attend_out_kernel<T>), dim3(kHeadDim / 16, d.H_kv), dim3(256), 0, st,
                            w_section<T>(c, W, 3), tfin, tpart, static_cast<T*>(out), d.B, d.r, d.H_q, d.H_kv,
                            L.pv_ntr);
     }
