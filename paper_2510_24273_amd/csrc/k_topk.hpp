@@ -1,13 +1,22 @@
 // Critical-token selection  C = TopK(s, k)  (Algorithm 1, TopK step), with the
 // sink / recent composition of Sec. 5.2.
 //
-// One workgroup per sequence runs an exact radix select on order-preserving
-// 32-bit keys of the fp32 scores: three passes (12 + 10 + 10 bits) with an LDS
-// histogram find the key of the k-th largest candidate, then one counting pass and
-// a single block-wide prefix sum place every selected index.  Keys live in
-// registers when the sequence fits (up to 32 per thread); longer sequences
-// re-read the scores, which sit in L2.  Equal scores are resolved towards the
-// smaller index, so the output is a deterministic function of the scores.
+// One workgroup per sequence finds the key of the k-th largest candidate exactly and then
+// places every selected index with one block-wide prefix sum.  Scores are handled as
+// order-preserving 32-bit keys, kept in registers when the sequence fits (up to 32 per
+// thread); longer sequences re-read the scores, which sit in L2.
+//
+// Finding the k-th key:
+//   fast path  a 4096-bin histogram over the LINEAR range [min, max] of the candidates (a
+//              monotone map, so bins are ordered like the scores).  Unlike a histogram over
+//              float bit fields it spreads clustered scores over many bins, which matters:
+//              LDS atomics that hit one address from many lanes serialise.  The bin holding
+//              the k-th score usually has a few dozen members; they are copied to LDS and
+//              ranked against each other.
+//   fallback   (degenerate range, or too many members in that bin) an exact radix select
+//              over the key bits, 12 + 10 + 10.
+// Equal scores are resolved towards the smaller index, so the output is a deterministic
+// function of the scores.
 #pragma once
 #include "common.hpp"
 
@@ -16,30 +25,50 @@ namespace sals {
 constexpr int kTopkThreads = 1024;
 constexpr int kTopkWaves = kTopkThreads / kWave;
 constexpr int kTopkBins = 4096;
+constexpr int kTopkCand = 512;  // members of the threshold bin handled by the fast path
 
 struct TopkShared {
     uint32_t hist[kTopkBins];
-    uint32_t wave_tot[kTopkWaves + 1];
-    uint32_t sel_prefix, sel_kk;
+    __attribute__((aligned(16))) uint32_t cand[kTopkCand];
+    uint32_t scan_a[2][kTopkWaves], scan_b[2][kTopkWaves];  // wave totals, double buffered
+    uint32_t wave_a[kTopkWaves], wave_b[kTopkWaves];
+    uint32_t sel_prefix, sel_kk, n_cand;
 };
 
-// exclusive prefix sum of v over the 1024 threads; *total gets the block sum
-__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wave_tot, uint32_t* total)
+__device__ __forceinline__ float key_to_score(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
+}
+
+// Exclusive prefix sums of a and b over the 1024 threads (one barrier); *ta, *tb get the block
+// sums.  `phase` alternates the LDS buffer, so back-to-back calls need no second barrier.
+__device__ __forceinline__ void block_excl_scan2(uint32_t& a, uint32_t& b, TopkShared& sh, int& phase,
+                                                 uint32_t* ta, uint32_t* tb)
 {
     const int lane = lane_id(), wave = threadIdx.x >> 6;
-    uint32_t incl = wave_incl_scan(v);
-    __syncthreads();  // protect wave_tot from the previous use
-    if (lane == kWave - 1) wave_tot[wave] = incl;
+    const uint32_t ia = wave_incl_scan(a), ib = wave_incl_scan(b);
+    if (lane == kWave - 1) { sh.scan_a[phase][wave] = ia; sh.scan_b[phase][wave] = ib; }
     __syncthreads();
-    if (wave == 0) {
-        uint32_t t = lane < kTopkWaves ? wave_tot[lane] : 0u;
-        uint32_t ti = wave_incl_scan(t);
-        if (lane < kTopkWaves) wave_tot[lane] = ti - t;
-        if (lane == kTopkWaves - 1) wave_tot[kTopkWaves] = ti;
-    }
+    static_assert(kTopkWaves == 16, "one DPP row holds the wave totals");
+    const uint32_t wa = sh.scan_a[phase][lane & 15], wb = sh.scan_b[phase][lane & 15];
+    const bool before = (lane & 15) < wave;
+    *ta = row16_sum_u32(wa);
+    *tb = row16_sum_u32(wb);
+    a = row16_sum_u32(before ? wa : 0u) + ia - a;
+    b = row16_sum_u32(before ? wb : 0u) + ib - b;
+    phase ^= 1;
+}
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, TopkShared& sh, int& phase, uint32_t* total)
+{
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const uint32_t iv = wave_incl_scan(v);
+    if (lane == kWave - 1) sh.scan_a[phase][wave] = iv;
     __syncthreads();
-    *total = wave_tot[kTopkWaves];
-    return wave_tot[wave] + incl - v;
+    const uint32_t wv = sh.scan_a[phase][lane & 15];
+    *total = row16_sum_u32(wv);
+    const uint32_t r = row16_sum_u32((lane & 15) < wave ? wv : 0u) + iv - v;
+    phase ^= 1;
+    return r;
 }
 
 // F4 > 0: keys of F4 float4 groups per thread stay in registers.  F4 == 0: stream.
@@ -51,12 +80,35 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
                                                             int top_k, int n_sink, int n_recent)
 {
     __shared__ TopkShared sh;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int b = blockIdx.x;
     const int k_tot = top_k + n_sink + n_recent;
-    const int S = min(seq_len[b], S_max);
     const float* s = scores + (size_t)b * S_max;
     int32_t* out = idx + (size_t)b * k_tot;
+    const bool vec_ok = (((size_t)b * S_max) & 3) == 0;  // this row starts 16-byte aligned
+    constexpr int NREG = F4 > 0 ? F4 * 4 : 4;
+
+    // group c of this thread covers tokens 4*(c*1024 + tid) .. +3  (coalesced float4 loads);
+    // the loads depend on S_max only, so they are in flight together with the length
+    auto load_group = [&](int c, float* f) {
+        const int j = (c * kTopkThreads + tid) << 2;
+        f[0] = f[1] = f[2] = f[3] = 0.f;
+        if (vec_ok && j + 3 < S_max) {
+            f32x4 v = *reinterpret_cast<const f32x4*>(s + j);
+            f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (j + e < S_max) f[e] = s[j + e];
+        }
+    };
+    const int S_in = seq_len[b];
+    float raw[NREG];
+    if (F4 > 0) {
+#pragma unroll
+        for (int c = 0; c < (F4 > 0 ? F4 : 1); ++c) load_group(c, raw + 4 * c);
+    }
+    const int S = min(S_in, S_max);
 
     if (S <= k_tot) {  // short cache: every token is selected
         for (int t = tid; t < k_tot; t += kTopkThreads) out[t] = t < S ? t : 0;
@@ -67,182 +119,184 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
     for (int t = tid; t < n_sink; t += kTopkThreads) out[t] = t;
     for (int t = tid; t < n_recent; t += kTopkThreads) out[n_sink + top_k + t] = hi + t;
     if (tid == 0) n_sel[b] = k_tot;
+    if (top_k <= 0) return;
 
-    // group c of this thread covers tokens 4*(c*1024 + tid) .. +3  (coalesced float4 loads)
-    const int n_groups = (S + 3) >> 2;
-    const bool vec_ok = (((size_t)b * S_max) & 3) == 0;  // this row starts 16-byte aligned
-    const int n_iter = F4 > 0 ? F4 : (n_groups + kTopkThreads - 1) / kTopkThreads;
-    constexpr int NREG = F4 > 0 ? F4 * 4 : 4;
+    // candidates are the tokens lo <= j < hi; every other slot carries key 0 (below -inf)
     uint32_t keys[NREG];
-
-    auto load_group = [&](int c, uint32_t* k4) {
-        int grp = c * kTopkThreads + tid;
-        int j = grp << 2;
-        float f[4] = {0.f, 0.f, 0.f, 0.f};
-        if (grp < n_groups) {
-            if (vec_ok && j + 3 < S_max) {
-                f32x4 v = *reinterpret_cast<const f32x4*>(s + j);
-                f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (j + e < S_max) f[e] = s[j + e];
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            int jj = j + e;
-            k4[e] = (jj >= lo && jj < hi) ? score_key(f[e]) : 0u;  // key 0 sorts below -inf
-        }
-    };
     if (F4 > 0) {
 #pragma unroll
-        for (int c = 0; c < (F4 > 0 ? F4 : 1); ++c) load_group(c, keys + 4 * c);
+        for (int i = 0; i < NREG; ++i) {
+            const int jj = (((i >> 2) * kTopkThreads + tid) << 2) + (i & 3);
+            keys[i] = (jj >= lo && jj < hi) ? score_key(raw[i]) : 0u;
+        }
     }
-
-    // ---- radix select of the top_k-th largest key --------------------------------
-    uint32_t prefix = 0u, mask = 0u, kk = (uint32_t)top_k;
-#pragma unroll 1
-    for (int pass = 0; pass < 3; ++pass) {
-        const int bits = pass == 0 ? 12 : 10;
-        const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
-        const uint32_t nb = 1u << bits;
-        for (uint32_t t = tid; t < nb; t += kTopkThreads) sh.hist[t] = 0u;
-        __syncthreads();
-        // histogram indexed from the top: slot 0 is the largest digit
+    const int n_iter = F4 > 0 ? F4 : (((S + 3) >> 2) + kTopkThreads - 1) / kTopkThreads;
+    // visit every (key, token index) of this thread
+    auto for_each_key = [&](auto&& fn) {
         if (F4 > 0) {
 #pragma unroll
-            for (int i = 0; i < NREG; ++i) {
-                uint32_t k = keys[i];
-                if (k != 0u && (k & mask) == prefix) atomicAdd(&sh.hist[nb - 1u - ((k >> shift) & (nb - 1u))], 1u);
-            }
+            for (int i = 0; i < NREG; ++i) fn(keys[i], (((i >> 2) * kTopkThreads + tid) << 2) + (i & 3));
         } else {
             for (int c = 0; c < n_iter; ++c) {
-                uint32_t k4[4];
-                load_group(c, k4);
+                float f[4];
+                load_group(c, f);
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (k4[e] != 0u && (k4[e] & mask) == prefix)
-                        atomicAdd(&sh.hist[nb - 1u - ((k4[e] >> shift) & (nb - 1u))], 1u);
+                for (int e = 0; e < 4; ++e) {
+                    const int jj = ((c * kTopkThreads + tid) << 2) + e;
+                    fn((jj >= lo && jj < hi) ? score_key(f[e]) : 0u, jj);
+                }
             }
         }
-        __syncthreads();
-        // each thread owns nb/1024 consecutive slots; find the slot where the running
-        // count from the top first reaches kk
-        const int per = (int)(nb / kTopkThreads);  // 4 or 1
-        uint32_t cnt[4] = {0u, 0u, 0u, 0u}, mine = 0u;
-        for (int i = 0; i < per; ++i) { cnt[i] = sh.hist[tid * per + i]; mine += cnt[i]; }
-        uint32_t total;
-        uint32_t above = block_excl_scan(mine, sh.wave_tot, &total);
-        for (int i = 0; i < per; ++i) {
-            if (above < kk && kk <= above + cnt[i]) {
-                uint32_t digit = nb - 1u - (uint32_t)(tid * per + i);
-                sh.sel_prefix = prefix | (digit << shift);
-                sh.sel_kk = kk - above;
-            }
-            above += cnt[i];
+    };
+
+    int phase = 0;
+    uint32_t tau = 0u, need_eq = 0u;  // key of the top_k-th largest candidate; ties taken at it
+    bool found = false;
+
+    // ---- fast path: linear-range histogram ---------------------------------------------
+    {
+        uint32_t kmin = 0xffffffffu, kmax = 0u;
+        for_each_key([&](uint32_t k, int) { if (k != 0u) { kmin = min(kmin, k); kmax = max(kmax, k); } });
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
+            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
         }
+        if (lane == 0) { sh.wave_a[wave] = kmin; sh.wave_b[wave] = kmax; }
+        for (uint32_t t = tid; t < kTopkBins; t += kTopkThreads) sh.hist[t] = 0u;
+        if (tid < kTopkCand) sh.cand[tid] = 0u;  // key 0 ranks below every candidate
+        if (tid == 0) sh.n_cand = 0u;
         __syncthreads();
-        prefix = sh.sel_prefix;
-        kk = sh.sel_kk;
-        mask |= (nb - 1u) << shift;
+#pragma unroll
+        for (int w = 0; w < kTopkWaves; ++w) { kmin = min(kmin, sh.wave_a[w]); kmax = max(kmax, sh.wave_b[w]); }
+        const float flo = key_to_score(kmin), fhi = key_to_score(kmax);
+        const float span = fhi - flo;
+        const float scale = (span > 0.f && span < 3.0e38f) ? (float)kTopkBins / span : 0.f;
+        const float off = -flo * scale;
+        if (scale > 0.f && scale < 3.0e38f && fabsf(off) < 3.0e38f) {  // uniform
+            // a monotone map of the score onto slots; slot 0 is the top of the range
+            auto slot_of = [&](uint32_t k) {
+                int bin = (int)fmaf(key_to_score(k), scale, off);
+                return kTopkBins - 1 - min(max(bin, 0), kTopkBins - 1);
+            };
+            for_each_key([&](uint32_t k, int) { if (k != 0u) atomicAdd(&sh.hist[slot_of(k)], 1u); });
+            __syncthreads();
+            const u32x4 c4 = *reinterpret_cast<const u32x4*>(&sh.hist[tid * 4]);
+            const uint32_t cnt[4] = {c4.x, c4.y, c4.z, c4.w};
+            uint32_t total;
+            uint32_t above = block_excl_scan(c4.x + c4.y + c4.z + c4.w, sh, phase, &total);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (above < (uint32_t)top_k && (uint32_t)top_k <= above + cnt[i]) {
+                    sh.sel_prefix = (uint32_t)(tid * 4 + i);  // slot holding the k-th score
+                    sh.sel_kk = (uint32_t)top_k - above;      // how many of its members are selected
+                }
+                above += cnt[i];
+            }
+            __syncthreads();
+            const int t_slot = (int)sh.sel_prefix;
+            const uint32_t kk = sh.sel_kk;
+            const uint32_t members = sh.hist[t_slot];
+            if (members <= (uint32_t)kTopkCand) {  // uniform
+                for_each_key([&](uint32_t k, int) {
+                    if (k != 0u && slot_of(k) == t_slot) sh.cand[atomicAdd(&sh.n_cand, 1u)] = k;
+                });
+                __syncthreads();
+                // the member with  #(greater) < kk <= #(greater or equal)  carries the k-th key
+                if (tid < (int)members) {
+                    const uint32_t mykey = sh.cand[tid];
+                    uint32_t gt = 0u, ge = 0u;
+                    for (uint32_t c = 0; c < members; c += 4) {
+                        u32x4 o = *reinterpret_cast<const u32x4*>(&sh.cand[c]);
+                        gt += (o.x > mykey) + (o.y > mykey) + (o.z > mykey) + (o.w > mykey);
+                        ge += (o.x >= mykey) + (o.y >= mykey) + (o.z >= mykey) + (o.w >= mykey);
+                    }
+                    if (gt < kk && kk <= ge) { sh.sel_prefix = mykey; sh.sel_kk = kk - gt; }
+                }
+                __syncthreads();
+                tau = sh.sel_prefix;
+                need_eq = sh.sel_kk;
+                found = true;
+            }
+        }
     }
-    const uint32_t tau = prefix;       // key of the top_k-th largest candidate
-    const uint32_t need_eq = kk;       // how many keys equal to tau are selected
+
+    // ---- fallback: radix select over the key bits -----------------------------------------
+    if (!found) {  // uniform
+        uint32_t prefix = 0u, mask = 0u, kk = (uint32_t)top_k;
+#pragma unroll 1
+        for (int pass = 0; pass < 3; ++pass) {
+            const int bits = pass == 0 ? 12 : 10;
+            const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+            const uint32_t nb = 1u << bits;
+            __syncthreads();
+            for (uint32_t t = tid; t < nb; t += kTopkThreads) sh.hist[t] = 0u;
+            __syncthreads();
+            // histogram indexed from the top: slot 0 is the largest digit
+            for_each_key([&](uint32_t k, int) {
+                if (k != 0u && (k & mask) == prefix) atomicAdd(&sh.hist[nb - 1u - ((k >> shift) & (nb - 1u))], 1u);
+            });
+            __syncthreads();
+            const int per = (int)(nb / kTopkThreads);  // 4 or 1
+            uint32_t cnt[4], mine = 0u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { cnt[i] = i < per ? sh.hist[tid * per + i] : 0u; mine += cnt[i]; }
+            uint32_t total;
+            uint32_t above = block_excl_scan(mine, sh, phase, &total);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (i < per && above < kk && kk <= above + cnt[i]) {
+                    uint32_t digit = nb - 1u - (uint32_t)(tid * per + i);
+                    sh.sel_prefix = prefix | (digit << shift);
+                    sh.sel_kk = kk - above;
+                }
+                above += cnt[i];
+            }
+            __syncthreads();
+            prefix = sh.sel_prefix;
+            kk = sh.sel_kk;
+            mask |= (nb - 1u) << shift;
+        }
+        tau = prefix;
+        need_eq = kk;
+    }
     const uint32_t n_gt = (uint32_t)top_k - need_eq;
 
-    // ---- count, then place ----------------------------------------------------------
-    uint32_t my_gt = 0u, my_eq = 0u;
-    if (F4 > 0) {
-#pragma unroll
-        for (int i = 0; i < NREG; ++i) { my_gt += keys[i] > tau; my_eq += keys[i] == tau; }
-    } else {
-        for (int c = 0; c < n_iter; ++c) {
-            uint32_t k4[4];
-            load_group(c, k4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { my_gt += k4[e] > tau; my_eq += k4[e] == tau; }
-        }
-    }
+    // ---- count, then place ----------------------------------------------------------------
+    uint32_t pos_gt = 0u, pos_eq = 0u;
+    for_each_key([&](uint32_t k, int) { pos_gt += k > tau; pos_eq += k == tau; });
     uint32_t tot_gt, tot_eq;
-    uint32_t pos_gt = block_excl_scan(my_gt, sh.wave_tot, &tot_gt);
-    uint32_t pos_eq = block_excl_scan(my_eq, sh.wave_tot, &tot_eq);
+    block_excl_scan2(pos_gt, pos_eq, sh, phase, &tot_gt, &tot_eq);
 
     // ties that straddle the cut: keep the need_eq smallest token indices among them
     int j_cut = hi;  // select ties with index < j_cut
-    if (tot_eq > need_eq) {
+    if (tot_eq > need_eq) {  // uniform
         int lo_j = lo, hi_j = hi;  // smallest J with #(eq && j < J) >= need_eq
         while (lo_j < hi_j) {
             int mid = (lo_j + hi_j) >> 1;
             uint32_t c_mine = 0u;
-            if (F4 > 0) {
-#pragma unroll
-                for (int i = 0; i < NREG; ++i) {
-                    int jj = (((i >> 2) * kTopkThreads + tid) << 2) + (i & 3);
-                    c_mine += (keys[i] == tau && jj < mid);
-                }
-            } else {
-                for (int c = 0; c < n_iter; ++c) {
-                    uint32_t k4[4];
-                    load_group(c, k4);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        int jj = ((c * kTopkThreads + tid) << 2) + e;
-                        c_mine += (k4[e] == tau && jj < mid);
-                    }
-                }
-            }
+            for_each_key([&](uint32_t k, int jj) { c_mine += (k == tau && jj < mid); });
             uint32_t c_tot;
-            block_excl_scan(c_mine, sh.wave_tot, &c_tot);
+            block_excl_scan(c_mine, sh, phase, &c_tot);
             if (c_tot >= need_eq) hi_j = mid; else lo_j = mid + 1;
         }
         j_cut = lo_j;
-        // recount this thread's selected ties and their offsets
-        my_eq = 0u;
-        if (F4 > 0) {
-#pragma unroll
-            for (int i = 0; i < NREG; ++i) {
-                int jj = (((i >> 2) * kTopkThreads + tid) << 2) + (i & 3);
-                my_eq += (keys[i] == tau && jj < j_cut);
-            }
-        } else {
-            for (int c = 0; c < n_iter; ++c) {
-                uint32_t k4[4];
-                load_group(c, k4);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    int jj = ((c * kTopkThreads + tid) << 2) + e;
-                    my_eq += (k4[e] == tau && jj < j_cut);
-                }
-            }
-        }
-        pos_eq = block_excl_scan(my_eq, sh.wave_tot, &tot_eq);
+        uint32_t my_eq = 0u;
+        for_each_key([&](uint32_t k, int jj) { my_eq += (k == tau && jj < j_cut); });
+        pos_eq = block_excl_scan(my_eq, sh, phase, &tot_eq);
     }
 
-    // (the end pointers only guard against out-of-range writes on malformed scores, e.g. NaN)
-    int32_t* out_gt = out + n_sink + pos_gt;
-    int32_t* out_eq = out + n_sink + n_gt + pos_eq;
-    int32_t* const end_gt = out + n_sink + n_gt;
-    int32_t* const end_eq = out + n_sink + top_k;
-    if (F4 > 0) {
-#pragma unroll
-        for (int i = 0; i < NREG; ++i) {
-            int jj = (((i >> 2) * kTopkThreads + tid) << 2) + (i & 3);
-            if (keys[i] > tau) { if (out_gt < end_gt) *out_gt++ = jj; }
-            else if (keys[i] == tau && jj < j_cut) { if (out_eq < end_eq) *out_eq++ = jj; }
-        }
-    } else {
-        for (int c = 0; c < n_iter; ++c) {
-            uint32_t k4[4];
-            load_group(c, k4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                int jj = ((c * kTopkThreads + tid) << 2) + e;
-                if (k4[e] > tau) { if (out_gt < end_gt) *out_gt++ = jj; }
-                else if (k4[e] == tau && jj < j_cut) { if (out_eq < end_eq) *out_eq++ = jj; }
-            }
-        }
-    }
+    // greater-than keys fill [0, n_gt), ties [n_gt, top_k), each in token order.  (The limits
+    // only guard against out-of-range writes on malformed scores, e.g. NaN.)
+    int32_t* const sel = out + n_sink;
+    uint32_t og = pos_gt, oe = n_gt + pos_eq;
+    for_each_key([&](uint32_t k, int jj) {
+        const bool g = k > tau, e = (k == tau) && (jj < j_cut);
+        const uint32_t p = g ? og : oe, lim = g ? n_gt : (uint32_t)top_k;
+        if ((g || e) && p < lim) sel[p] = jj;
+        og += g;
+        oe += e;
+    });
 }
 
 }  // namespace sals
