@@ -105,9 +105,7 @@ def kernel_table(ls, steps, roofline):
         "project": ("hbm", sb["project"]),
         "scores": ("hbm", sb["scores"]),
         "topk": ("hbm", sb["select"] + w.B * w.k_tot * 4),
-        "attend_prep": ("hbm", w.B * w.k_tot * (4 + 512)),
         "attend_logits": ("mfma", sf["reconstruct_k"]),
-        "attend_softmax": ("hbm", w.B * w.H * w.k_tot * 8),
         "attend_pv": ("hbm", w.B * w.k_tot * w.r * w.esize),
         "attend_out": ("hbm", w.r * w.D_kv * w.esize),
     }

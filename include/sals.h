@@ -62,7 +62,7 @@ enum { SALS_ROPE_HALF = 0,        /* pair (i, i+d/2) */
 /* Problem descriptor (plain data, host memory).
  * Supported by the kernels: d == 128; r a multiple of 64, 64 <= r <= 1024;
  * r_score a multiple of 8, 8 <= r_score <= r; H_q a multiple of H_kv with
- * H_q/H_kv <= 8 and H_q <= 64; B >= 1 with B*(H_q/H_kv) <= 128; 1 <= S_max <= 2^24;
+ * H_q/H_kv <= 8 and H_q <= 64; B >= 1 with B*(H_q/H_kv) <= 128; 1 <= S_max <= 2^20;
  * top_k >= 1; n_sink, n_recent >= 0; top_k + n_sink + n_recent <= 65536. */
 typedef struct {
     int32_t B;          /* sequences per call                                         */
@@ -89,10 +89,12 @@ const char* sals_status_string(sals_status s);
 sals_status sals_workspace_bytes(const sals_desc* desc, size_t* bytes);
 
 /* Validate `desc`, bind the caller's device workspace (256-byte aligned, at least
- * sals_workspace_bytes) and return a context in *out.  The workspace must be
- * zero-filled once by the caller before the first call that uses the context
- * (kept as a requirement so that later versions may hold counters there).
- * Host-only, allocates only host memory. */
+ * sals_workspace_bytes) and return a context in *out.  No initial contents are
+ * required; after this call the workspace belongs to the library and the caller
+ * must not write to it.  Part of it holds a constant table (RoPE cos/sin of every
+ * position 0 .. S_max, 512 bytes per position) that the first sals_sparse_attend /
+ * sals_decode_step call on the context fills with one extra kernel on that call's
+ * stream.  Host-only, allocates only host memory. */
 sals_status sals_create(const sals_desc* desc, void* d_workspace, size_t workspace_bytes,
                         sals_ctx** out);
 void sals_destroy(sals_ctx* ctx);
@@ -183,13 +185,11 @@ sals_status sals_decode_step(sals_ctx* ctx, const void* q, const int32_t* q_pos,
 enum {
     SALS_K_PROJECT = 0,        /* latent projection (query, or new key/value)  */
     SALS_K_SCORES = 1,         /* latent score stream over the key cache       */
-    SALS_K_TOPK = 2,           /* radix select                                 */
-    SALS_K_ATTEND_PREP = 3,    /* cos/sin table + rotated query                */
-    SALS_K_ATTEND_LOGITS = 4,  /* MFMA key reconstruction + RoPE + q.K         */
-    SALS_K_ATTEND_SOFTMAX = 5, /* softmax weights over the selected tokens     */
-    SALS_K_ATTEND_PV = 6,      /* latent-space value sum                       */
-    SALS_K_ATTEND_OUT = 7,     /* output projection through U_v                */
-    SALS_N_KERNELS = 8
+    SALS_K_TOPK = 2,           /* exact top-k selection                        */
+    SALS_K_ATTEND_LOGITS = 3,  /* MFMA key reconstruction + RoPE + q.K         */
+    SALS_K_ATTEND_PV = 4,      /* softmax + latent-space value sum             */
+    SALS_K_ATTEND_OUT = 5,     /* output projection through U_v                */
+    SALS_N_KERNELS = 6
 };
 const char* sals_kernel_name(int kernel);
 sals_status sals_profile_enable(sals_ctx* ctx, int on);

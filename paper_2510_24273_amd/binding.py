@@ -28,7 +28,7 @@ EXPORTS = (
     "sals_decode_step", "sals_kernel_name", "sals_profile_enable", "sals_profile_collect",
     "sals_packed_weight_bytes", "sals_pack_weights",
 )
-N_KERNELS = 8
+N_KERNELS = 6
 
 
 class SalsDesc(ctypes.Structure):

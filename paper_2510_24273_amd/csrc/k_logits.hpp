@@ -10,7 +10,9 @@
 // fragment reads hit without bank conflicts.  Global loads run one or two steps ahead of
 // the MFMAs (one or two register sets, two LDS buffers).  The reconstructed keys stay in the
 // accumulators: the epilogue rotates them with the token's cos/sin row and dots them with
-// the rotated query, so only logits are written.
+// the rotated query, so only logits are written, plus each (head, token tile)'s softmax
+// maximum and normaliser for the value kernel.  The query itself is rotated (fp64-accurate angles)
+// and scaled by 1/sqrt(d) in the prologue, while the first tile loads are in flight.
 //
 // Wave tile: 128 head dims (4 MFMA row blocks, in RoPE pair order) x 32*NB tokens.
 // Workgroup: HEADS x NTG waves, i.e. HEADS heads x (NTG*32*NB) tokens.
@@ -39,8 +41,10 @@ template <int HEADS, int NTG, int NB> struct logits_cfg {
 template <typename T, int HEADS, int NTG, int NB, bool DEEP>
 __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
     const T* __restrict__ Kc, const T* __restrict__ UkP, const int32_t* __restrict__ idx,
-    const int32_t* __restrict__ n_sel, const float2* __restrict__ cs, const float* __restrict__ qR,
-    float* __restrict__ logits, int S_max, int r, int H, int H_kv, int k_tot, int lk)
+    const int32_t* __restrict__ n_sel, const T* __restrict__ q, const int32_t* __restrict__ q_pos,
+    const float2* __restrict__ rope, InvFreq inv,
+    float* __restrict__ logits, float2* __restrict__ stats, int S_max, int r, int H, int H_kv, int k_tot,
+    int lk, int style, float scale)
 {
     typedef logits_cfg<HEADS, NTG, NB> C;
     constexpr int NT = C::NT, NA = C::NA, NBP = C::NBP;
@@ -49,20 +53,62 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
 
     const int b = blockIdx.z, g0 = blockIdx.y * HEADS, tok0 = blockIdx.x * C::TOK;
     const int n = n_sel[b];
-    if (tok0 >= n) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
     const int hh = wave / NTG, tg = wave % NTG;   // head of the tile, token group
     const int G = H / H_kv;
     const int g = g0 + hh;
+    const int n_parts = gridDim.x;
+    if (tok0 >= n) {  // no selected token in this tile: neutral statistics
+        if (tid < HEADS * G)
+            stats[((size_t)b * H + (size_t)g0 * G + tid) * n_parts + blockIdx.x] = make_float2(-INFINITY, 0.f);
+        return;
+    }
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // [2][A | B]
     __shared__ __attribute__((aligned(16))) float sQ[HEADS][kMaxGroup][kHeadDim];
 
-    for (int t = tid; t < HEADS * G * kHeadDim; t += NT) {
-        int h2 = t / (G * kHeadDim), rem = t - h2 * G * kHeadDim;
-        sQ[h2][rem / kHeadDim][rem % kHeadDim] = qR[((size_t)b * H + (g0 + h2) * G) * kHeadDim + rem];
+    __shared__ float2 sCS[kPairs];
+    __shared__ float2 sStat[HEADS][NTG][kMaxGroup];
+
+    // raw query pairs of this tile's heads; rotated once the first tile loads are issued
+    constexpr int QP = (HEADS * kMaxGroup * kPairs + NT - 1) / NT;
+    float qa[QP], qb[QP];
+#pragma unroll
+    for (int u = 0; u < QP; ++u) {
+        const int t = tid + u * NT;
+        qa[u] = qb[u] = 0.f;
+        if (t < HEADS * G * kPairs) {
+            const int p = t & (kPairs - 1);
+            const T* qrow = q + ((size_t)b * H + (size_t)g0 * G + (t >> 6)) * kHeadDim;
+            qa[u] = elem<T>::load(qrow + pair_first(p, style));
+            qb[u] = elem<T>::load(qrow + pair_second(p, style));
+        }
     }
+    const int qpos = q_pos[b];
+    auto rotate_query = [&]() {
+        if (tid < kPairs) {
+            if (qpos >= 0 && qpos <= S_max) {  // the table holds exactly these values
+                sCS[tid] = rope[(size_t)qpos * kPairs + tid];
+            } else {
+                double sn, c;
+                sincos((double)qpos * inv.f[tid], &sn, &c);
+                sCS[tid] = make_float2((float)c, (float)sn);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < QP; ++u) {
+            const int t = tid + u * NT;
+            if (t < HEADS * G * kPairs) {
+                const int p = t & (kPairs - 1), hm = t >> 6;
+                const float2 c = sCS[p];
+                float* dst = &sQ[0][0][0] + (size_t)((hm / G) * kMaxGroup + hm % G) * kHeadDim;
+                dst[p] = (qa[u] * c.x - qb[u] * c.y) * scale;
+                dst[kPairs + p] = (qb[u] * c.x + qa[u] * c.y) * scale;
+            }
+        }
+    };
 
     // ---- global sources of this thread's pieces ---------------------------------------
     // U_k panel: piece q = tid + i*NT -> head q/1024, slot (q%1024)/8, 16-byte column q%8.  The
@@ -85,6 +131,12 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
         const int slot = tok0 + ((tid + i * NT) >> 3);
         int t = idx[(size_t)b * k_tot + (slot < n ? slot : 0)];
         b_row[i] = min(max(t, 0), S_max - 1);  // stay inside the cache whatever the caller passed
+    }
+    int pos_e[NB];  // RoPE position of the token this lane finishes in the epilogue
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int slot = tok0 + (tg * NB + nb) * 32 + l32;
+        pos_e[nb] = min(max(idx[(size_t)b * k_tot + (slot < n ? slot : 0)], 0), S_max - 1);
     }
     const unsigned char* b_base = reinterpret_cast<const unsigned char*>(Kc + (size_t)b * S_max * r) + (tid & 7) * 16;
     const size_t row_bytes = (size_t)r * ES;
@@ -144,6 +196,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
         };
         g_load(R0, 0);
         if (nkc > 1) g_load(R1, 1);
+        rotate_query();
         l_store(R0, 0);
         __syncthreads();
         for (int kc = 0; kc < nkc; kc += 2) {
@@ -154,6 +207,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
         // one register set: step kc+1 goes to LDS, then the loads of step kc+2 fly during the MFMAs
         Regs R;
         g_load(R, 0);
+        rotate_query();
         l_store(R, 0);
         if (nkc > 1) g_load(R, 1);
         __syncthreads();
@@ -167,14 +221,17 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
 
     // ---- epilogue: lane holds, for token l32 of each block, slots mb*32 + 8a + 4hi + c;
     // slot < 64 is the first element of pair (slot), slot+64 its partner (mb+2)
+    float dl[kMaxGroup][NB];
+    bool ok[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int slot = tok0 + (tg * NB + nb) * 32 + l32;
         const bool valid = slot < n;
+        ok[nb] = valid;
         float dot[kMaxGroup];
 #pragma unroll
         for (int m = 0; m < kMaxGroup; ++m) dot[m] = 0.f;
-        const float2* csrow = cs + ((size_t)b * k_tot + (valid ? slot : 0)) * kPairs;
+        const float2* csrow = rope + (size_t)pos_e[nb] * kPairs;  // cos/sin of the token's angles
 #pragma unroll
         for (int ml = 0; ml < 2; ++ml) {
 #pragma unroll
@@ -203,11 +260,37 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
         }
 #pragma unroll
         for (int m = 0; m < kMaxGroup; ++m) {
+            dl[m][nb] = 0.f;
             if (m < G) {
                 float d = dot[m] + __shfl_xor(dot[m], 32, kWave);
+                dl[m][nb] = d;
                 if (hi == 0 && slot < lk) logits[((size_t)b * H + g * G + m) * lk + slot] = valid ? d : -INFINITY;
             }
         }
+    }
+
+    // softmax statistics of this tile, per head: the waves' (max, sum exp) merged in wave order
+#pragma unroll
+    for (int m = 0; m < kMaxGroup; ++m) {
+        if (m < G) {  // uniform
+            float mx = -INFINITY;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) mx = ok[nb] ? fmaxf(mx, dl[m][nb]) : mx;
+            mx = wave_max(mx);
+            float se = 0.f;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) se += (ok[nb] && hi == 0) ? __expf(dl[m][nb] - mx) : 0.f;
+            se = wave_sum(se);
+            if (lane == 0) sStat[hh][tg][m] = make_float2(mx, se);
+        }
+    }
+    __syncthreads();
+    if (tid < HEADS * G) {
+        const int h2 = tid / G, m = tid - h2 * G;
+        float2 st = sStat[h2][0][m];
+#pragma unroll
+        for (int t = 1; t < NTG; ++t) st = stat_merge(st, sStat[h2][t][m]);
+        stats[((size_t)b * H + (size_t)(g0 + h2) * G + m) * n_parts + blockIdx.x] = st;
     }
 }
 

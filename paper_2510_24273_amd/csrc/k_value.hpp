@@ -4,9 +4,10 @@
 //
 //   attend_pv   per (sequence, token range, 32 latent columns):
 //               T[h,:] = sum_j p_hj V~[C_j,:]  on the matrix cores, tokens being the
-//               contraction axis (split over the four waves).  The normalised softmax
-//               weights p come from the softmax kernel.  With one range T is written in
-//               matrix-core form; with several, each range writes an fp32 partial sum.
+//               contraction axis (split over the four waves).  The softmax weights are formed
+//               on the fly, p = exp(logit - m_h) / Z_h, with m_h and Z_h merged in the prologue
+//               from the per-tile statistics the logits kernel left.  With one range T is
+//               written in matrix-core form; with several, each range writes an fp32 partial sum.
 //   attend_out  y[(b,h), c] = sum_i T[(b,h), i] U_v[g*128 + c, i]  on the matrix cores; adds the
 //               range partials in order first when there are several.
 //
@@ -38,11 +39,12 @@ __device__ __forceinline__ void store_split(T* hi_arr, T* lo_arr, size_t at, flo
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void attend_pv_kernel(const T* __restrict__ Vc,
+__global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__ Vc,
                                                         const int32_t* __restrict__ idx,
                                                         const int32_t* __restrict__ n_sel,
-                                                        const T* __restrict__ P, float* __restrict__ Tpart,
-                                                        T* __restrict__ Tfin,
+                                                        const float* __restrict__ logits,
+                                                        const float2* __restrict__ stats, int n_parts,
+                                                        float* __restrict__ Tpart, T* __restrict__ Tfin,
                                                         int B, int S_max, int r, int H, int k_tot, int lk,
                                                         int tok_per_wg, int n_tr)
 {
@@ -52,6 +54,7 @@ __global__ __launch_bounds__(256) void attend_pv_kernel(const T* __restrict__ Vc
     constexpr bool kSplit = sizeof(T) == 2;
 
     __shared__ __attribute__((aligned(16))) float red[3][64][33];
+    __shared__ float2 sMZ[kPvMaxHeads];  // per head: softmax maximum, 1 / normaliser
 
     const int b = blockIdx.z, tr = blockIdx.y, cb = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -60,8 +63,25 @@ __global__ __launch_bounds__(256) void attend_pv_kernel(const T* __restrict__ Vc
     const int j_begin = min(n, tr * tok_per_wg), j_end = min(n, j_begin + tok_per_wg);
     const int col = cb * kPvCols + l32;
     const int n_mb = (H + 31) >> 5;
-    const T* P_hi = P + (size_t)b * H * lk;
-    const T* P_lo = P + (size_t)B * H * lk + (size_t)b * H * lk;
+    const float* lg = logits + (size_t)b * H * lk;
+
+    // softmax maximum and normaliser of every head: four lanes share a head's tiles and merge
+    // them in a fixed order
+    {
+        const int h = tid >> 2, sub = tid & 3;
+        float2 st = make_float2(-INFINITY, 0.f);
+        if (h < H) {
+            const float2* sp = stats + ((size_t)b * H + h) * n_parts;
+            for (int t = sub; t < n_parts; t += 4) st = stat_merge(st, sp[t]);
+        }
+        st = stat_merge(st, make_float2(__shfl_xor(st.x, 1, kWave), __shfl_xor(st.y, 1, kWave)));
+        st = stat_merge(st, make_float2(__shfl_xor(st.x, 2, kWave), __shfl_xor(st.y, 2, kWave)));
+        if (sub == 0) sMZ[h] = make_float2(st.x > -INFINITY ? st.x : 0.f, st.y > 0.f ? 1.f / st.y : 0.f);
+    }
+    __syncthreads();
+    float2 mz[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) mz[mb] = sMZ[mb * 32 + l32];
     const T* vbase = Vc + (size_t)b * S_max * r + col;
     const int32_t* ib = idx + (size_t)b * k_tot;
     T* Thi_arr = Tfin;
@@ -94,8 +114,34 @@ __global__ __launch_bounds__(256) void attend_pv_kernel(const T* __restrict__ Vc
                 const int h = mb * 32 + l32;
                 const size_t off = (size_t)h * lk + j0 + ks * KG + hi * VEC;
                 const bool ok = mb < n_mb && h < H;
-                ah[ks][mb] = ok ? ld16(P_hi + off) : u32x4{0, 0, 0, 0};
-                if constexpr (kSplit) al[ks][mb] = ok ? ld16(P_lo + off) : u32x4{0, 0, 0, 0};
+                float pj[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; v += 4) {
+                    const f32x4 x = ok ? *reinterpret_cast<const f32x4*>(lg + off + v)
+                                       : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+                    // slots past the selected tokens carry no weight (their logits may be unwritten)
+                    const int jt = j0 + ks * KG + hi * VEC + v;
+                    pj[v] = jt < n ? __expf(x.x - mz[mb].x) * mz[mb].y : 0.f;
+                    pj[v + 1] = jt + 1 < n ? __expf(x.y - mz[mb].x) * mz[mb].y : 0.f;
+                    pj[v + 2] = jt + 2 < n ? __expf(x.z - mz[mb].x) * mz[mb].y : 0.f;
+                    pj[v + 3] = jt + 3 < n ? __expf(x.w - mz[mb].x) * mz[mb].y : 0.f;
+                }
+                if constexpr (kSplit) {
+                    uint32_t ph[VEC], pl[VEC];
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        const bf16_t hb = f32_to_bf16(pj[v]);
+                        ph[v] = hb;
+                        pl[v] = f32_to_bf16(pj[v] - bf16_to_f32(hb));
+                    }
+                    ah[ks][mb] = u32x4{ph[0] | (ph[1] << 16), ph[2] | (ph[3] << 16), ph[4] | (ph[5] << 16),
+                                       ph[6] | (ph[7] << 16)};
+                    al[ks][mb] = u32x4{pl[0] | (pl[1] << 16), pl[2] | (pl[3] << 16), pl[4] | (pl[5] << 16),
+                                       pl[6] | (pl[7] << 16)};
+                } else {
+                    ah[ks][mb] = u32x4{__float_as_uint(pj[0]), __float_as_uint(pj[1]), __float_as_uint(pj[2]),
+                                       __float_as_uint(pj[3])};
+                }
             }
         u32x4 vfrag[NKG];
 #pragma unroll

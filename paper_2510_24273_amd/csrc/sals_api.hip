@@ -27,8 +27,9 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Layout {  // byte offsets into the workspace
-    size_t qt, scores, idx, n_sel, cs, qR, logits, pw, tpart, tfin, total;
+    size_t qt, scores, idx, n_sel, logits, stats, rope, tpart, tfin, total;
     int lk;                      // logits row stride (floats)
+    int max_parts;               // token tiles per head of the logits kernel, at most
     int pv_tok_per_wg, pv_ntr;   // value-sum token ranges
     int proj_np;                 // D-axis slices of the query projection
     size_t w_section;            // elements per section of the packed weights
@@ -46,13 +47,14 @@ struct sals_ctx {
     size_t ws_bytes;
     InvFreq inv;
     bool profiling = false;
+    bool rope_ready = false;     // the cos/sin table in the workspace has been enqueued
     std::vector<ProfRecord> prof;
 };
 
 namespace {
 
 const char* const kKernelNames[SALS_N_KERNELS] = {
-    "project", "scores", "topk", "attend_prep", "attend_logits", "attend_softmax", "attend_pv", "attend_out"};
+    "project", "scores", "topk", "attend_logits", "attend_pv", "attend_out"};
 
 // Brackets one kernel launch with a pair of events while profiling is on.
 struct ProfScope {
@@ -90,7 +92,7 @@ sals_status validate(const sals_desc* d)
     if (d->r % 64 != 0 || d->r > 1024) return SALS_ERR_UNSUPPORTED;
     if (d->r_score % 8 != 0) return SALS_ERR_UNSUPPORTED;
     if (d->H_q / d->H_kv > kMaxGroup || d->H_q > kPvMaxHeads) return SALS_ERR_UNSUPPORTED;
-    if (d->S_max > (1 << 24)) return SALS_ERR_UNSUPPORTED;
+    if (d->S_max > (1 << 20)) return SALS_ERR_UNSUPPORTED;  // the RoPE table takes 512 B per position
     if ((long long)d->B * (d->H_q / d->H_kv) > kProjMaxCols) return SALS_ERR_UNSUPPORTED;
     if ((long long)d->top_k + d->n_recent + d->n_sink > 65536) return SALS_ERR_UNSUPPORTED;
     return SALS_OK;
@@ -125,10 +127,10 @@ Layout make_layout(const sals_desc& d)
     L.scores = take((size_t)d.B * d.S_max * 4);
     L.idx = take((size_t)d.B * k_tot * 4);
     L.n_sel = take((size_t)d.B * 4);
-    L.cs = take((size_t)d.B * k_tot * kPairs * 8);
-    L.qR = take((size_t)d.B * d.H_q * kHeadDim * 4);
     L.logits = take((size_t)d.B * d.H_q * L.lk * 4);
-    L.pw = take((size_t)d.B * d.H_q * L.lk * 4);
+    L.max_parts = ceil_div(k_tot, 32);
+    L.stats = take((size_t)d.B * d.H_q * L.max_parts * 8);
+    L.rope = take((size_t)(d.S_max + 1) * kPairs * 8);  // positions 0 .. S_max (the query after a full cache)
     L.tpart = take((size_t)L.pv_ntr * d.B * d.H_q * d.r * 4);
     L.tfin = take((size_t)d.B * d.H_q * d.r * 4);
     L.total = o;
@@ -230,20 +232,18 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     const sals_desc& d = c->d;
     const Layout& L = c->L;
     const int k_tot = d.top_k + d.n_sink + d.n_recent;
-    float2* cs = reinterpret_cast<float2*>(c->ws + L.cs);
-    float* qR = reinterpret_cast<float*>(c->ws + L.qR);
     float* logits = reinterpret_cast<float*>(c->ws + L.logits);
-    T* pw = reinterpret_cast<T*>(c->ws + L.pw);
+    float2* stats = reinterpret_cast<float2*>(c->ws + L.stats);
+    const float2* rope = reinterpret_cast<const float2*>(c->ws + L.rope);
     float* tpart = reinterpret_cast<float*>(c->ws + L.tpart);
     T* tfin = reinterpret_cast<T*>(c->ws + L.tfin);
-
-    {   // cos/sin table and rotated query
-        int n_tab = ceil_div(d.B * k_tot, 4), n_q = ceil_div(d.B * d.H_q, 4);
-        ProfScope ps(c, SALS_K_ATTEND_PREP, st);
-        hipLaunchKernelGGL((attend_prep_kernel<T>), dim3(n_tab + n_q), dim3(256), 0, st,
-                           static_cast<const T*>(q), q_pos, idx, n_sel, cs, qR, c->inv, d.B, d.H_q, k_tot,
-                           n_tab, d.rope_style, 1.0f / std::sqrt((float)d.d));
+    int n_parts = 0;
+    if (!c->rope_ready) {  // first use of the context: cos/sin of every cache position, ahead of the logits
+        const size_t n = (size_t)(d.S_max + 1) * kPairs;
+        hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                           reinterpret_cast<float2*>(c->ws + L.rope), c->inv, d.S_max + 1);
         if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+        const_cast<sals_ctx*>(c)->rope_ready = true;
     }
     {   // logits: the largest tile (most operand reuse) that still gives the chip enough workgroups
         auto n_wg = [&](int heads, int tok) { return (long long)ceil_div(k_tot, tok) * (d.H_kv / heads) * d.B; };
@@ -256,9 +256,12 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
             hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                 (int)LC::LDS) != hipSuccess)                                                 \
             return SALS_ERR_HIP;                                                                             \
-        hipLaunchKernelGGL(kern, dim3(ceil_div(k_tot, LC::TOK), d.H_kv / HEADS, d.B), dim3(LC::NT), LC::LDS, st, \
-                           static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel, cs, qR, logits,     \
-                           d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk);                                        \
+        n_parts = ceil_div(k_tot, LC::TOK);                                                                  \
+        hipLaunchKernelGGL(kern, dim3(n_parts, d.H_kv / HEADS, d.B), dim3(LC::NT), LC::LDS, st,              \
+                           static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,                     \
+                           static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats,                     \
+                           d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk, d.rope_style,                           \
+                           1.0f / std::sqrt((float)d.d));                                                    \
     } while (0)
         if (d.H_kv % 2 == 0 && n_wg(2, 256) >= 384) SALS_LOGITS(2, 4, 2, false);   // 2 heads x 256 tokens, 8 waves
         else if (n_wg(1, 256) >= 200) SALS_LOGITS(1, 4, 2, false);                 // 1 head  x 256 tokens
@@ -268,15 +271,9 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
         if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     }
     {
-        ProfScope ps(c, SALS_K_ATTEND_SOFTMAX, st);
-        hipLaunchKernelGGL((attend_softmax_kernel<T>), dim3(d.B * d.H_q), dim3(kSmThreads), 0, st, logits, n_sel, pw,
-                           d.B, d.H_q, L.lk);
-    }
-    if (launch_status() != SALS_OK) return SALS_ERR_HIP;
-    {
         ProfScope ps(c, SALS_K_ATTEND_PV, st);
         hipLaunchKernelGGL((attend_pv_kernel<T>), dim3(d.r / kPvCols, L.pv_ntr, d.B), dim3(256), 0, st,
-                           static_cast<const T*>(Vc), idx, n_sel, pw, tpart, tfin, d.B, d.S_max,
+                           static_cast<const T*>(Vc), idx, n_sel, logits, stats, n_parts, tpart, tfin, d.B, d.S_max,
                            d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr);
     }
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;

@@ -163,6 +163,20 @@ def test_compress_append_then_decode(oracle):
     ctx.close()
 
 
+def test_query_position_beyond_the_cache(oracle):
+    """q_pos far above S_max: the query's angles are then evaluated in the kernel instead of
+    being read from the per-context cos/sin table."""
+    w = synth.shrink(SMALL, B=2)
+    L = synth.make_layer(w)
+    L["q_pos"] = np.array([w.S + 1, 1_000_003], np.int32)
+    ctx = gu.make_ctx(w)
+    G = gu.upload(L, ctx)
+    R = gu.run_stages(ctx, w, G)
+    for b in range(w.B):
+        gu.check_sequence(oracle, w, L, R, b)
+    ctx.close()
+
+
 def test_repeatable_bit_for_bit(oracle):
     w = synth.shrink(SMALL, B=2)
     L = synth.make_layer(w)
