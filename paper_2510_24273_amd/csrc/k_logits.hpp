@@ -23,6 +23,7 @@
 namespace sals {
 
 constexpr int kLgChunk = 128;  // bytes of the latent axis per pipeline step
+constexpr int kXcds = 8;        // accelerator dies, workgroups are dealt to them round-robin
 
 // byte offset of 16-byte piece `pc` of row `row` inside a [rows][128 B] swizzled LDS tile
 __device__ __forceinline__ int swz(int row, int pc) { return row * kLgChunk + ((pc ^ ((row >> 1) & 7)) << 4); }
@@ -43,25 +44,43 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
     const T* __restrict__ Kc, const T* __restrict__ UkP, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ n_sel, const T* __restrict__ q, const int32_t* __restrict__ q_pos,
     const float2* __restrict__ rope, InvFreq inv,
-    float* __restrict__ logits, float2* __restrict__ stats, int S_max, int r, int H, int H_kv, int k_tot,
-    int lk, int style, float scale)
+    float* __restrict__ logits, float2* __restrict__ stats, int B, int S_max, int r, int H, int H_kv,
+    int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale)
 {
     typedef logits_cfg<HEADS, NTG, NB> C;
     constexpr int NT = C::NT, NA = C::NA, NBP = C::NBP;
     constexpr int ES = (int)sizeof(T);
     static_assert(C::A_BYTES % (16 * NT) == 0 && C::B_BYTES % (16 * NT) == 0, "tile / thread mismatch");
 
-    const int b = blockIdx.z, g0 = blockIdx.y * HEADS, tok0 = blockIdx.x * C::TOK;
+    // Workgroup id -> (sequence, token tile, head block).  Consecutive ids are dispatched to
+    // different XCDs, each with its own L2, so every XCD gets one contiguous range of the work
+    // list; the list is ordered so that a range shares the larger operand: heads fastest keeps
+    // the gathered rows of a few token tiles in that L2 (U_k is re-read per XCD), tiles fastest
+    // keeps the U_k panels of a few heads there (the rows are re-read per XCD).
+    int b, g0, part;
+    {
+        const int n_y = H_kv / HEADS, N = n_parts * n_y * B;
+        const int id = blockIdx.x, xcd = id % kXcds, slot = id / kXcds;
+        const int q = N / kXcds, rem = N % kXcds;
+        const int w = (xcd < rem ? xcd * (q + 1) : rem * (q + 1) + (xcd - rem) * q) + slot;
+        if (heads_fastest) {
+            const int bt = w / n_y;
+            g0 = (w - bt * n_y) * HEADS; b = bt / n_parts; part = bt - b * n_parts;
+        } else {
+            const int hb = w / (n_parts * B), bt = w - hb * (n_parts * B);
+            g0 = hb * HEADS; b = bt / n_parts; part = bt - b * n_parts;
+        }
+    }
+    const int tok0 = part * C::TOK;
     const int n = n_sel[b];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
     const int hh = wave / NTG, tg = wave % NTG;   // head of the tile, token group
     const int G = H / H_kv;
     const int g = g0 + hh;
-    const int n_parts = gridDim.x;
     if (tok0 >= n) {  // no selected token in this tile: neutral statistics
         if (tid < HEADS * G)
-            stats[((size_t)b * H + (size_t)g0 * G + tid) * n_parts + blockIdx.x] = make_float2(-INFINITY, 0.f);
+            stats[((size_t)b * H + (size_t)g0 * G + tid) * n_parts + part] = make_float2(-INFINITY, 0.f);
         return;
     }
 
@@ -184,7 +203,6 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
                 for (int nb = 0; nb < NB; ++nb) mma_op<T>::run(af[mb], bf[nb], acc[mb][nb]);
         }
     };
-
     if constexpr (DEEP) {
         // two register sets: global loads run two steps ahead of the MFMAs
         Regs R0, R1;
@@ -218,7 +236,6 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
             __syncthreads();
         }
     }
-
     // ---- epilogue: lane holds, for token l32 of each block, slots mb*32 + 8a + 4hi + c;
     // slot < 64 is the first element of pair (slot), slot+64 its partner (mb+2)
     float dl[kMaxGroup][NB];
@@ -268,7 +285,6 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
             }
         }
     }
-
     // softmax statistics of this tile, per head: the waves' (max, sum exp) merged in wave order
 #pragma unroll
     for (int m = 0; m < kMaxGroup; ++m) {
@@ -290,7 +306,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
         float2 st = sStat[h2][0][m];
 #pragma unroll
         for (int t = 1; t < NTG; ++t) st = stat_merge(st, sStat[h2][t][m]);
-        stats[((size_t)b * H + (size_t)(g0 + h2) * G + m) * n_parts + blockIdx.x] = st;
+        stats[((size_t)b * H + (size_t)(g0 + h2) * G + m) * n_parts + part] = st;
     }
 }
 

@@ -13,6 +13,7 @@
 #include "common.hpp"
 #include "k_attend.hpp"
 #include "k_logits.hpp"
+#include "k_logits_small.hpp"
 #include "k_project.hpp"
 #include "k_scores.hpp"
 #include "k_topk.hpp"
@@ -247,6 +248,9 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     }
     {   // logits: the largest tile (most operand reuse) that still gives the chip enough workgroups
         auto n_wg = [&](int heads, int tok) { return (long long)ceil_div(k_tot, tok) * (d.H_kv / heads) * d.B; };
+        // replicate the smaller operand across the XCDs' L2s: all of U_k, or the gathered rows
+        const size_t a_bytes = (size_t)d.H_kv * kHeadDim * d.r, b_bytes = (size_t)d.B * k_tot * d.r;
+        const int heads_fastest = a_bytes <= b_bytes ? 1 : 0;
         ProfScope ps(c, SALS_K_ATTEND_LOGITS, st);
 #define SALS_LOGITS(HEADS, NTG, NB, DEEP)                                                                        \
     do {                                                                                                     \
@@ -257,16 +261,42 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
                                 (int)LC::LDS) != hipSuccess)                                                 \
             return SALS_ERR_HIP;                                                                             \
         n_parts = ceil_div(k_tot, LC::TOK);                                                                  \
-        hipLaunchKernelGGL(kern, dim3(n_parts, d.H_kv / HEADS, d.B), dim3(LC::NT), LC::LDS, st,              \
+        hipLaunchKernelGGL(kern, dim3(n_parts * (d.H_kv / HEADS) * d.B), dim3(LC::NT), LC::LDS, st,          \
                            static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,                     \
-                           static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats,                     \
-                           d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk, d.rope_style,                           \
+                           static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats, d.B,                \
+                           d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk, n_parts, heads_fastest, d.rope_style,   \
                            1.0f / std::sqrt((float)d.d));                                                    \
     } while (0)
         if (d.H_kv % 2 == 0 && n_wg(2, 256) >= 384) SALS_LOGITS(2, 4, 2, false);   // 2 heads x 256 tokens, 8 waves
         else if (n_wg(1, 256) >= 200) SALS_LOGITS(1, 4, 2, false);                 // 1 head  x 256 tokens
-        else if (n_wg(1, 64) >= 128) SALS_LOGITS(1, 2, 1, true);                  // 1 head  x  64 tokens
-        else SALS_LOGITS(1, 1, 1, true);                                          // 1 head  x  32 tokens
+        else {  // few tiles: 1 head x 64 tokens with the whole latent axis loaded ahead
+            const int nkc = d.r * (int)sizeof(T) / kLgChunk;
+            int nst = kLsMaxChunk;  // steps loaded ahead: the largest divisor of the step count
+            while (nkc % nst != 0) --nst;
+            void (*kern)(const T*, const T*, const int32_t*, const int32_t*, const T*, const int32_t*, const float2*,
+                         InvFreq, float*, float2*, int, int, int, int, int, int, int, int, int, int, float) = nullptr;
+            switch (nst) {
+                case 1: kern = attend_logits_small_kernel<T, 1>; break;
+                case 2: kern = attend_logits_small_kernel<T, 2>; break;
+                case 3: kern = attend_logits_small_kernel<T, 3>; break;
+                case 4: kern = attend_logits_small_kernel<T, 4>; break;
+                case 5: kern = attend_logits_small_kernel<T, 5>; break;
+                case 6: kern = attend_logits_small_kernel<T, 6>; break;
+                case 7: kern = attend_logits_small_kernel<T, 7>; break;
+                case 8: kern = attend_logits_small_kernel<T, 8>; break;
+                case 9: kern = attend_logits_small_kernel<T, 9>; break;
+                default: kern = attend_logits_small_kernel<T, 10>; break;
+            }
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)kLsLds) != hipSuccess)
+                return SALS_ERR_HIP;
+            n_parts = ceil_div(k_tot, kLsTok);
+            hipLaunchKernelGGL(kern, dim3(n_parts * d.H_kv * d.B), dim3(kLsThreads), kLsLds, st,
+                               static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,
+                               static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats, d.B, d.S_max, d.r,
+                               d.H_q, d.H_kv, k_tot, L.lk, n_parts, heads_fastest, d.rope_style,
+                               1.0f / std::sqrt((float)d.d));
+        }
 #undef SALS_LOGITS
         if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     }
