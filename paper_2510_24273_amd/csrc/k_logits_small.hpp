@@ -34,7 +34,7 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale)
 {
     constexpr int ES = (int)sizeof(T);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
     const int ksel = wave & 1, dh = (wave >> 1) & 1, tb = wave >> 2;
     const int G = H / H_kv;
@@ -180,10 +180,15 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
         float* xch = reinterpret_cast<float*>(lds);  // [pair of waves 4][parity 2][16][64]
         float* mine = xch + ((size_t)((wave >> 1) * 2 + ksel) * 16) * 64 + lane;
         const float* theirs = xch + ((size_t)((wave >> 1) * 2 + (ksel ^ 1)) * 16) * 64 + lane;
+        // (static register indices on both sides of a uniform branch: a select between two
+        // accumulator elements would turn into a long chain of per-element selects)
+        float x1[8], x2[8];  // this wave's kept first / second pair elements, index aa*4 + c
+        if (ksel) {
 #pragma unroll
-        for (int v = 0; v < 8; ++v) {
-            mine[v * 64] = ksel ? acc0[v] : acc0[8 + v];
-            mine[(8 + v) * 64] = ksel ? acc1[v] : acc1[8 + v];
+            for (int v = 0; v < 8; ++v) { mine[v * 64] = acc0[v]; mine[(8 + v) * 64] = acc1[v]; x1[v] = acc0[8 + v]; x2[v] = acc1[8 + v]; }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 8; ++v) { mine[v * 64] = acc0[8 + v]; mine[(8 + v) * 64] = acc1[8 + v]; x1[v] = acc0[v]; x2[v] = acc1[v]; }
         }
         __syncthreads();
         float k1[2][4], k2[2][4];
@@ -194,10 +199,10 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int v = aa * 4 + c;
-                const float x1 = (ksel ? acc0[8 + v] : acc0[v]) + theirs[v * 64];
-                const float x2 = (ksel ? acc1[8 + v] : acc1[v]) + theirs[(8 + v) * 64];
-                k1[aa][c] = x1 * cc[c] - x2 * ss[c];
-                k2[aa][c] = x2 * cc[c] + x1 * ss[c];
+                const float y1 = x1[v] + theirs[v * 64];
+                const float y2 = x2[v] + theirs[(8 + v) * 64];
+                k1[aa][c] = y1 * cc[c] - y2 * ss[c];
+                k2[aa][c] = y2 * cc[c] + y1 * ss[c];
             }
         }
         // partial dot products over this wave's 16 pairs, per query head of the group
