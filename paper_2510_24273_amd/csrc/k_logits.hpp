@@ -4,15 +4,19 @@
 //
 // A gathered-row GEMM on the matrix cores: for one sequence, HEADS KV heads and a tile of
 // selected tokens, D[dim, token] = sum_i U_k[dim, i] K~[C_token, i].  Both operands are
-// staged through LDS in 128-byte steps of the latent axis: the packed U_k panel (shared by
+// staged through LDS in 64-byte steps of the latent axis: the packed U_k panel (shared by
 // the waves of a head) and the gathered latent rows (shared by the heads), each loaded
 // with 16 contiguous bytes per lane and written to a swizzled layout that the MFMA
-// fragment reads hit without bank conflicts.  Global loads run one or two steps ahead of
-// the MFMAs (one or two register sets, two LDS buffers).  The reconstructed keys stay in the
-// accumulators: the epilogue rotates them with the token's cos/sin row and dots them with
-// the rotated query, so only logits are written, plus each (head, token tile)'s softmax
-// maximum and normaliser for the value kernel.  The query itself is rotated (fp64-accurate angles)
-// and scaled by 1/sqrt(d) in the prologue, while the first tile loads are in flight.
+// fragment reads hit without bank conflicts.  Global loads run a step ahead of the MFMAs
+// (one register set, two LDS buffers); with 64-byte steps the two buffers take 64 KB, so two
+// workgroups share a compute unit and fill each other's prologue, barrier and epilogue gaps.
+//
+// The reconstructed keys stay in the accumulators.  The epilogue streams the tokens' cos/sin
+// rows through the same LDS buffers, 16 RoPE pairs per pass, rotates the accumulators and
+// dots them with the rotated query, so only logits are written, plus each (head, token
+// tile)'s softmax maximum and normaliser for the value kernel.  The query itself is rotated
+// (fp64-accurate angles) and scaled by 1/sqrt(d) in the prologue, while the first tile loads
+// are in flight.
 //
 // Wave tile: 128 head dims (4 MFMA row blocks, in RoPE pair order) x 32*NB tokens.
 // Workgroup: HEADS x NTG waves, i.e. HEADS heads x (NTG*32*NB) tokens.
@@ -22,25 +26,31 @@
 
 namespace sals {
 
-constexpr int kLgChunk = 128;  // bytes of the latent axis per pipeline step
-constexpr int kXcds = 8;        // accelerator dies, workgroups are dealt to them round-robin
+constexpr int kLgChunk = 128;  // bytes per row of a [rows][128 B] swizzled LDS tile
+constexpr int kLgStep = 64;    // bytes of the latent axis per pipeline step (= one packed U_k block)
+constexpr int kXcds = 8;       // accelerator dies, workgroups are dealt to them round-robin
 
 // byte offset of 16-byte piece `pc` of row `row` inside a [rows][128 B] swizzled LDS tile
 __device__ __forceinline__ int swz(int row, int pc) { return row * kLgChunk + ((pc ^ ((row >> 1) & 7)) << 4); }
+// the same for a [rows][64 B] tile: eight consecutive rows reading one piece index cover
+// all eight 16-byte bank groups
+__device__ __forceinline__ int swz64(int row, int pc) { return row * kLgStep + ((pc ^ ((row >> 1) & 3)) << 4); }
 
 template <int HEADS, int NTG, int NB> struct logits_cfg {
     static constexpr int NT = 64 * HEADS * NTG;            // threads
     static constexpr int TOK = NTG * NB * 32;              // tokens per workgroup
-    static constexpr int A_BYTES = HEADS * 128 * kLgChunk;  // U_k panel per step
-    static constexpr int B_BYTES = TOK * kLgChunk;          // gathered rows per step
+    static constexpr int A_BYTES = HEADS * 128 * kLgStep;  // U_k panel per step
+    static constexpr int B_BYTES = TOK * kLgStep;          // gathered rows per step
     static constexpr int STAGE = A_BYTES + B_BYTES;
-    static constexpr int NA = A_BYTES / 16 / NT;            // 16-byte pieces per thread per step
+    static constexpr int NA = A_BYTES / 16 / NT;           // 16-byte pieces per thread per step
     static constexpr int NBP = B_BYTES / 16 / NT;
-    static constexpr size_t LDS = 2 * (size_t)STAGE;
+    static constexpr int CS_BYTES = TOK * kLgChunk;        // cos/sin of 16 pairs for every token
+    static constexpr int NCS = CS_BYTES / 16 / NT;
+    static constexpr size_t LDS = 2 * (size_t)(STAGE > CS_BYTES ? STAGE : CS_BYTES);
 };
 
-template <typename T, int HEADS, int NTG, int NB, bool DEEP>
-__global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
+template <typename T, int HEADS, int NTG, int NB>
+__global__ __launch_bounds__(64 * HEADS * NTG, 2) void attend_logits_kernel(
     const T* __restrict__ Kc, const T* __restrict__ UkP, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ n_sel, const T* __restrict__ q, const int32_t* __restrict__ q_pos,
     const float2* __restrict__ rope, InvFreq inv,
@@ -48,9 +58,10 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
     int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale)
 {
     typedef logits_cfg<HEADS, NTG, NB> C;
-    constexpr int NT = C::NT, NA = C::NA, NBP = C::NBP;
+    constexpr int NT = C::NT, NA = C::NA, NBP = C::NBP, NCS = C::NCS;
     constexpr int ES = (int)sizeof(T);
-    static_assert(C::A_BYTES % (16 * NT) == 0 && C::B_BYTES % (16 * NT) == 0, "tile / thread mismatch");
+    static_assert(C::A_BYTES % (16 * NT) == 0 && C::B_BYTES % (16 * NT) == 0 && C::CS_BYTES % (16 * NT) == 0,
+                  "tile / thread mismatch");
 
     // Workgroup id -> (sequence, token tile, head block).  Consecutive ids are dispatched to
     // different XCDs, each with its own L2, so every XCD gets one contiguous range of the work
@@ -61,8 +72,8 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
     {
         const int n_y = H_kv / HEADS, N = n_parts * n_y * B;
         const int id = blockIdx.x, xcd = id % kXcds, slot = id / kXcds;
-        const int q = N / kXcds, rem = N % kXcds;
-        const int w = (xcd < rem ? xcd * (q + 1) : rem * (q + 1) + (xcd - rem) * q) + slot;
+        const int qn = N / kXcds, rem = N % kXcds;
+        const int w = (xcd < rem ? xcd * (qn + 1) : rem * (qn + 1) + (xcd - rem) * qn) + slot;
         if (heads_fastest) {
             const int bt = w / n_y;
             g0 = (w - bt * n_y) * HEADS; b = bt / n_parts; part = bt - b * n_parts;
@@ -73,7 +84,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
     }
     const int tok0 = part * C::TOK;
     const int n = n_sel[b];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
     const int hh = wave / NTG, tg = wave % NTG;   // head of the tile, token group
     const int G = H / H_kv;
@@ -84,11 +95,16 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
         return;
     }
 
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // [2][A | B]
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // [2][A | B], later [2][cos/sin]
     __shared__ __attribute__((aligned(16))) float sQ[HEADS][kMaxGroup][kHeadDim];
-
     __shared__ float2 sCS[kPairs];
     __shared__ float2 sStat[HEADS][NTG][kMaxGroup];
+    __shared__ int sPos[C::TOK];  // cache row (= RoPE position) of every token of the tile
+
+    const int32_t* ib = idx + (size_t)b * k_tot;
+    // rows past the selected tokens read the first selected row; they get no weight
+    auto row_of = [&](int slot) { return min(max(ib[slot < n ? slot : 0], 0), S_max - 1); };
+    for (int t = tid; t < C::TOK; t += NT) sPos[t] = row_of(tok0 + t);
 
     // raw query pairs of this tile's heads; rotated once the first tile loads are issued
     constexpr int QP = (HEADS * kMaxGroup * kPairs + NT - 1) / NT;
@@ -130,36 +146,26 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
     };
 
     // ---- global sources of this thread's pieces ---------------------------------------
-    // U_k panel: piece q = tid + i*NT -> head q/1024, slot (q%1024)/8, 16-byte column q%8.  The
-    // packed layout is [head][step][128 slots][128 B]: inside a head the pieces of a step are
-    // contiguous, and a step adds 16 KB.
+    // U_k panel: piece q = tid + i*NT -> head q/512, slot (q%512)/4, 16-byte column q%4.  The
+    // packed layout is [head][step][128 slots][64 B]: inside a head the pieces of a step are
+    // contiguous, and a step adds 8 KB.
     const unsigned char* a_base = reinterpret_cast<const unsigned char*>(UkP + (size_t)g0 * kHeadDim * r);
     const size_t head_bytes = (size_t)kHeadDim * r * ES;
     auto a_src = [&](int i, int kc) {
         const int qd = tid + i * NT;
-        return a_base + (size_t)(qd >> 10) * head_bytes + (size_t)kc * (128 * kLgChunk) + (qd & 1023) * 16;
+        return a_base + (size_t)(qd >> 9) * head_bytes + (size_t)kc * (128 * kLgStep) + (qd & 511) * 16;
     };
     auto a_dst = [&](int i) {
         const int qd = tid + i * NT;
-        return (qd >> 10) * 128 * kLgChunk + swz((qd >> 3) & 127, qd & 7);
+        return (qd >> 9) * 128 * kLgStep + swz64((qd >> 2) & 127, qd & 3);
     };
-    // gathered rows: piece q -> token q/8 of the tile, column q%8
+    // gathered rows: piece q -> token q/4 of the tile, column q%4
     int b_row[NBP];
 #pragma unroll
-    for (int i = 0; i < NBP; ++i) {
-        const int slot = tok0 + ((tid + i * NT) >> 3);
-        int t = idx[(size_t)b * k_tot + (slot < n ? slot : 0)];
-        b_row[i] = min(max(t, 0), S_max - 1);  // stay inside the cache whatever the caller passed
-    }
-    int pos_e[NB];  // RoPE position of the token this lane finishes in the epilogue
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const int slot = tok0 + (tg * NB + nb) * 32 + l32;
-        pos_e[nb] = min(max(idx[(size_t)b * k_tot + (slot < n ? slot : 0)], 0), S_max - 1);
-    }
-    const unsigned char* b_base = reinterpret_cast<const unsigned char*>(Kc + (size_t)b * S_max * r) + (tid & 7) * 16;
+    for (int i = 0; i < NBP; ++i) b_row[i] = row_of(tok0 + ((tid + i * NT) >> 2));
+    const unsigned char* b_base = reinterpret_cast<const unsigned char*>(Kc + (size_t)b * S_max * r) + (tid & 3) * 16;
     const size_t row_bytes = (size_t)r * ES;
-    auto b_dst = [&](int i) { return C::A_BYTES + swz((tid + i * NT) >> 3, tid & 7); };
+    auto b_dst = [&](int i) { return C::A_BYTES + swz64((tid + i * NT) >> 2, tid & 3); };
 
     f32x16 acc[4][NB];
 #pragma unroll
@@ -169,13 +175,13 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
 
-    const int nkc = r * ES / kLgChunk;
+    const int nkc = r * ES / kLgStep;
     struct Regs { u32x4 a[NA]; u32x4 b[NBP]; };
     auto g_load = [&](Regs& R, int kc) {
 #pragma unroll
         for (int i = 0; i < NA; ++i) R.a[i] = ld16(a_src(i, kc));
 #pragma unroll
-        for (int i = 0; i < NBP; ++i) R.b[i] = ld16(b_base + (size_t)b_row[i] * row_bytes + (size_t)kc * kLgChunk);
+        for (int i = 0; i < NBP; ++i) R.b[i] = ld16(b_base + (size_t)b_row[i] * row_bytes + (size_t)kc * kLgStep);
     };
     auto l_store = [&](const Regs& R, int buf) {
         unsigned char* base = lds + (size_t)buf * C::STAGE;
@@ -185,44 +191,27 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
         for (int i = 0; i < NBP; ++i) *reinterpret_cast<u32x4*>(base + b_dst(i)) = R.b[i];
     };
     auto compute = [&](int buf) {
-        const unsigned char* pa = lds + (size_t)buf * C::STAGE + hh * 128 * kLgChunk;
-        const unsigned char* pb = lds + (size_t)buf * C::STAGE + C::A_BYTES + tg * NB * 32 * kLgChunk;
+        const unsigned char* pa = lds + (size_t)buf * C::STAGE + hh * 128 * kLgStep;
+        const unsigned char* pb = lds + (size_t)buf * C::STAGE + C::A_BYTES + tg * NB * 32 * kLgStep;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
+        for (int ks = 0; ks < 2; ++ks) {
             u32x4 bf[NB];
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
-                bf[nb] = *reinterpret_cast<const u32x4*>(pb + swz(nb * 32 + l32, ks * 2 + hi));
+                bf[nb] = *reinterpret_cast<const u32x4*>(pb + swz64(nb * 32 + l32, ks * 2 + hi));
             u32x4 af[4];
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb)
-                af[mb] = *reinterpret_cast<const u32x4*>(pa + swz(mb * 32 + l32, ks * 2 + hi));
+                af[mb] = *reinterpret_cast<const u32x4*>(pa + swz64(mb * 32 + l32, ks * 2 + hi));
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) mma_op<T>::run(af[mb], bf[nb], acc[mb][nb]);
         }
     };
-    if constexpr (DEEP) {
-        // two register sets: global loads run two steps ahead of the MFMAs
-        Regs R0, R1;
-        auto step = [&](int kc, Regs& RL, const Regs& RS) {
-            if (kc + 2 < nkc) g_load(RL, kc + 2);
-            compute(kc & 1);
-            if (kc + 1 < nkc) l_store(RS, (kc + 1) & 1);
-            __syncthreads();
-        };
-        g_load(R0, 0);
-        if (nkc > 1) g_load(R1, 1);
-        rotate_query();
-        l_store(R0, 0);
-        __syncthreads();
-        for (int kc = 0; kc < nkc; kc += 2) {
-            step(kc, R0, R1);                      // R0 held step kc (already in LDS); R1 holds kc+1
-            if (kc + 1 < nkc) step(kc + 1, R1, R0);
-        }
-    } else {
-        // one register set: step kc+1 goes to LDS, then the loads of step kc+2 fly during the MFMAs
+
+    // one register set: step kc+1 goes to LDS, then the loads of step kc+2 fly during the MFMAs
+    {
         Regs R;
         g_load(R, 0);
         rotate_query();
@@ -236,66 +225,98 @@ __global__ __launch_bounds__(64 * HEADS * NTG) void attend_logits_kernel(
             __syncthreads();
         }
     }
-    // ---- epilogue: lane holds, for token l32 of each block, slots mb*32 + 8a + 4hi + c;
-    // slot < 64 is the first element of pair (slot), slot+64 its partner (mb+2)
-    float dl[kMaxGroup][NB];
+
+    // ---- epilogue.  A lane holds, for token l32 of each block, slots mb*32 + 8a + 4hi + c; slot < 64
+    // is the first element of pair (slot), slot+64 its partner (mb+2).  Pass ps = 2*ml + ah covers
+    // the pairs ml*32 + ah*16 .. +16: the tokens' 128-byte cos/sin pieces are staged in LDS, double
+    // buffered, with the loads of the next pass in flight. ------------------------------------------
+    float dot[kMaxGroup][NB];
+#pragma unroll
+    for (int m = 0; m < kMaxGroup; ++m)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) dot[m][nb] = 0.f;
+    {
+        const unsigned char* rope_b = reinterpret_cast<const unsigned char*>(rope) + (tid & 7) * 16;
+        size_t cs_off[NCS];  // byte offset of this thread's token rows in the table
+#pragma unroll
+        for (int i = 0; i < NCS; ++i) cs_off[i] = (size_t)sPos[(tid + i * NT) >> 3] * (kPairs * sizeof(float2));
+        u32x4 CR[NCS];
+        auto cs_load = [&](int ps) {
+#pragma unroll
+            for (int i = 0; i < NCS; ++i) CR[i] = ld16(rope_b + cs_off[i] + ps * kLgChunk);
+        };
+        auto cs_store = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < NCS; ++i)
+                *reinterpret_cast<u32x4*>(lds + (size_t)buf * C::CS_BYTES + swz((tid + i * NT) >> 3, tid & 7)) = CR[i];
+        };
+        cs_load(0);
+        cs_store(0);
+        cs_load(1);
+        __syncthreads();
+#pragma unroll
+        for (int ps = 0; ps < 4; ++ps) {
+            const int ml = ps >> 1, ah = ps & 1;
+            const unsigned char* cb = lds + (size_t)(ps & 1) * C::CS_BYTES;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int row = (tg * NB + nb) * 32 + l32;
+#pragma unroll
+                for (int al = 0; al < 2; ++al) {
+                    const int a = 2 * ah + al;
+                    const int p0 = ml * 32 + a * 8 + hi * 4;
+                    const f32x4 t0 = *reinterpret_cast<const f32x4*>(cb + swz(row, al * 4 + hi * 2));      // pairs p0, p0+1
+                    const f32x4 t1 = *reinterpret_cast<const f32x4*>(cb + swz(row, al * 4 + hi * 2 + 1));  // p0+2, p0+3
+                    const float cc[4] = {t0.x, t0.z, t1.x, t1.z}, ss[4] = {t0.y, t0.w, t1.y, t1.w};
+                    float k1[4], k2[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float x1 = acc[ml][nb][a * 4 + c], x2 = acc[ml + 2][nb][a * 4 + c];
+                        k1[c] = x1 * cc[c] - x2 * ss[c];
+                        k2[c] = x2 * cc[c] + x1 * ss[c];
+                    }
+#pragma unroll
+                    for (int m = 0; m < kMaxGroup; ++m) {
+                        if (m < G) {
+                            const f32x4 q1 = *reinterpret_cast<const f32x4*>(&sQ[hh][m][p0]);
+                            const f32x4 q2 = *reinterpret_cast<const f32x4*>(&sQ[hh][m][kPairs + p0]);
+                            dot[m][nb] += q1.x * k1[0] + q1.y * k1[1] + q1.z * k1[2] + q1.w * k1[3] +
+                                          q2.x * k2[0] + q2.y * k2[1] + q2.z * k2[2] + q2.w * k2[3];
+                        }
+                    }
+                }
+            }
+            if (ps + 1 < 4) cs_store((ps + 1) & 1);
+            if (ps + 2 < 4) cs_load(ps + 2);
+            __syncthreads();
+        }
+    }
+
     bool ok[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int slot = tok0 + (tg * NB + nb) * 32 + l32;
-        const bool valid = slot < n;
-        ok[nb] = valid;
-        float dot[kMaxGroup];
-#pragma unroll
-        for (int m = 0; m < kMaxGroup; ++m) dot[m] = 0.f;
-        const float2* csrow = rope + (size_t)pos_e[nb] * kPairs;  // cos/sin of the token's angles
-#pragma unroll
-        for (int ml = 0; ml < 2; ++ml) {
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const int p0 = ml * 32 + a * 8 + hi * 4;
-                f32x4 t0 = *reinterpret_cast<const f32x4*>(csrow + p0);      // (c,s) of pairs p0, p0+1
-                f32x4 t1 = *reinterpret_cast<const f32x4*>(csrow + p0 + 2);  // pairs p0+2, p0+3
-                float cc[4] = {t0.x, t0.z, t1.x, t1.z}, ss[4] = {t0.y, t0.w, t1.y, t1.w};
-                float k1[4], k2[4];
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    float x1 = acc[ml][nb][a * 4 + c], x2 = acc[ml + 2][nb][a * 4 + c];
-                    k1[c] = x1 * cc[c] - x2 * ss[c];
-                    k2[c] = x2 * cc[c] + x1 * ss[c];
-                }
-#pragma unroll
-                for (int m = 0; m < kMaxGroup; ++m) {
-                    if (m < G) {
-                        f32x4 q1 = *reinterpret_cast<const f32x4*>(&sQ[hh][m][p0]);
-                        f32x4 q2 = *reinterpret_cast<const f32x4*>(&sQ[hh][m][kPairs + p0]);
-                        dot[m] += q1.x * k1[0] + q1.y * k1[1] + q1.z * k1[2] + q1.w * k1[3] +
-                                  q2.x * k2[0] + q2.y * k2[1] + q2.z * k2[2] + q2.w * k2[3];
-                    }
-                }
-            }
-        }
+        ok[nb] = slot < n;
 #pragma unroll
         for (int m = 0; m < kMaxGroup; ++m) {
-            dl[m][nb] = 0.f;
             if (m < G) {
-                float d = dot[m] + __shfl_xor(dot[m], 32, kWave);
-                dl[m][nb] = d;
-                if (hi == 0 && slot < lk) logits[((size_t)b * H + g * G + m) * lk + slot] = valid ? d : -INFINITY;
+                dot[m][nb] += __shfl_xor(dot[m][nb], 32, kWave);
+                if (hi == 0 && slot < lk) logits[((size_t)b * H + g * G + m) * lk + slot] = ok[nb] ? dot[m][nb] : -INFINITY;
             }
         }
     }
+
     // softmax statistics of this tile, per head: the waves' (max, sum exp) merged in wave order
 #pragma unroll
     for (int m = 0; m < kMaxGroup; ++m) {
         if (m < G) {  // uniform
             float mx = -INFINITY;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) mx = ok[nb] ? fmaxf(mx, dl[m][nb]) : mx;
+            for (int nb = 0; nb < NB; ++nb) mx = ok[nb] ? fmaxf(mx, dot[m][nb]) : mx;
             mx = wave_max(mx);
             float se = 0.f;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) se += (ok[nb] && hi == 0) ? __expf(dl[m][nb] - mx) : 0.f;
+            for (int nb = 0; nb < NB; ++nb) se += (ok[nb] && hi == 0) ? __expf(dot[m][nb] - mx) : 0.f;
             se = wave_sum(se);
             if (lane == 0) sStat[hh][tg][m] = make_float2(mx, se);
         }

@@ -78,7 +78,10 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     const bool q_in_table = qpos >= 0 && qpos <= S_max;  // the table holds exactly the needed values
     float2 qcs = rope[(size_t)(q_in_table ? qpos : 0) * kPairs + qp];
 
-    const unsigned char* a_src = reinterpret_cast<const unsigned char*>(UkP + (size_t)g * kHeadDim * r) + tid * 16;
+    // the packed U_k panel is [64-byte block of the latent axis][128 slots][64 B]: a 128-byte step is two
+    // blocks 8 KB apart, and piece (slot, column c) lies in block c/4 at slot*64 + (c%4)*16
+    const unsigned char* a_src = reinterpret_cast<const unsigned char*>(UkP + (size_t)g * kHeadDim * r) +
+                                 (pcol >> 2) * (kHeadDim * 64) + prow * 64 + (pcol & 3) * 16;
     const int a_dst0 = swz(prow, pcol), a_dst1 = swz(64 + prow, pcol);
     const int b_dst = kHeadDim * kLgChunk + swz(prow, pcol);
     const int nkc = r * ES / kLgChunk;
@@ -107,7 +110,7 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     auto load_a = [&](int c0, int s) {
         const size_t ao = (size_t)(c0 + s) * (kHeadDim * kLgChunk);
         P[s][0] = ld16(a_src + ao);
-        P[s][1] = ld16(a_src + ao + 64 * kLgChunk);
+        P[s][1] = ld16(a_src + ao + 64 * 64);  // slot 64 + t/8
     };
     constexpr int EARLY = NST < 4 ? NST : 4;  // U_k steps requested before the row indices arrive
 #pragma unroll

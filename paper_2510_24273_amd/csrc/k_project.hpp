@@ -153,15 +153,15 @@ __global__ void bump_seq_len_kernel(int32_t* __restrict__ seq_len, int B, int S_
 // one-time weight repacking (model-load time; not on the decode path)
 // ---------------------------------------------------------------------------------
 // section 0: UkT [r, D]      section 1: UvT [r, D]
-// section 2: Uk in reconstruction order: [H_kv][r/KE][128 slots][KE] with the head dims
-//            in RoPE pair order (slot p < 64: first element of pair p; 64+p: its partner)
+// section 2: Uk in reconstruction order: [H_kv][r/KE][128 slots][KE] (KE = 64 bytes of the latent
+//            axis) with the head dims in RoPE pair order (slot p < 64: first element of pair p; 64+p: its partner)
 // section 3: Uv [D, r] unchanged
 template <typename T>
 __global__ __launch_bounds__(256) void pack_weights_kernel(const T* __restrict__ Uk, const T* __restrict__ Uv,
                                                            T* __restrict__ packed, size_t section_elems,
                                                            int D, int r, int style)
 {
-    constexpr int KE = 128 / (int)sizeof(T);
+    constexpr int KE = 64 / (int)sizeof(T);
     const int sec = blockIdx.y;
     T* dst = packed + (size_t)sec * section_elems;
     for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < section_elems; e += (size_t)gridDim.x * 256) {

@@ -252,10 +252,10 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
         const size_t a_bytes = (size_t)d.H_kv * kHeadDim * d.r, b_bytes = (size_t)d.B * k_tot * d.r;
         const int heads_fastest = a_bytes <= b_bytes ? 1 : 0;
         ProfScope ps(c, SALS_K_ATTEND_LOGITS, st);
-#define SALS_LOGITS(HEADS, NTG, NB, DEEP)                                                                        \
+#define SALS_LOGITS(HEADS, NTG, NB)                                                                              \
     do {                                                                                                     \
         typedef logits_cfg<HEADS, NTG, NB> LC;                                                               \
-        auto kern = attend_logits_kernel<T, HEADS, NTG, NB, DEEP>;                                           \
+        auto kern = attend_logits_kernel<T, HEADS, NTG, NB>;                                                 \
         if (LC::LDS > 48 * 1024 &&                                                                           \
             hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                 (int)LC::LDS) != hipSuccess)                                                 \
@@ -267,8 +267,8 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
                            d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk, n_parts, heads_fastest, d.rope_style,   \
                            1.0f / std::sqrt((float)d.d));                                                    \
     } while (0)
-        if (d.H_kv % 2 == 0 && n_wg(2, 256) >= 384) SALS_LOGITS(2, 4, 2, false);   // 2 heads x 256 tokens, 8 waves
-        else if (n_wg(1, 256) >= 200) SALS_LOGITS(1, 4, 2, false);                 // 1 head  x 256 tokens
+        if (d.H_kv % 2 == 0 && n_wg(2, 256) >= 384) SALS_LOGITS(2, 4, 2);   // 2 heads x 256 tokens, 8 waves
+        else if (n_wg(1, 256) >= 200) SALS_LOGITS(1, 4, 2);                 // 1 head  x 256 tokens
         else {  // few tiles: 1 head x 64 tokens with the whole latent axis loaded ahead
             const int nkc = d.r * (int)sizeof(T) / kLgChunk;
             int nst = kLsMaxChunk;  // steps loaded ahead: the largest divisor of the step count
