@@ -7,9 +7,8 @@
 // staged through LDS in 64-byte steps of the latent axis: the packed U_k panel (shared by
 // the waves of a head) and the gathered latent rows (shared by the heads), each loaded
 // with 16 contiguous bytes per lane and written to a swizzled layout that the MFMA
-// fragment reads hit without bank conflicts.  Global loads run a step ahead of the MFMAs
-// (one register set, two LDS buffers); with 64-byte steps the two buffers take 64 KB, so two
-// workgroups share a compute unit and fill each other's prologue, barrier and epilogue gaps.
+// fragment reads hit without bank conflicts.  Three LDS stages and two fragment register sets
+// form a software pipeline in which every wave overlaps its own LDS traffic with its MFMAs.
 //
 // The reconstructed keys stay in the accumulators.  The epilogue streams the tokens' cos/sin
 // rows through the same LDS buffers, 16 RoPE pairs per pass, rotates the accumulators and
@@ -46,7 +45,7 @@ template <int HEADS, int NTG, int NB> struct logits_cfg {
     static constexpr int NBP = B_BYTES / 16 / NT;
     static constexpr int CS_BYTES = TOK * kLgChunk;        // cos/sin of 16 pairs for every token
     static constexpr int NCS = CS_BYTES / 16 / NT;
-    static constexpr size_t LDS = 2 * (size_t)(STAGE > CS_BYTES ? STAGE : CS_BYTES);
+    static constexpr size_t LDS = 3 * (size_t)STAGE > 2 * (size_t)CS_BYTES ? 3 * (size_t)STAGE : 2 * (size_t)CS_BYTES;
 };
 
 template <typename T, int HEADS, int NTG, int NB>
@@ -95,7 +94,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG, 2) void attend_logits_kernel(
         return;
     }
 
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // [2][A | B], later [2][cos/sin]
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // [3][A | B], later [2][cos/sin]
     __shared__ __attribute__((aligned(16))) float sQ[HEADS][kMaxGroup][kHeadDim];
     __shared__ float2 sCS[kPairs];
     __shared__ float2 sStat[HEADS][NTG][kMaxGroup];
@@ -190,39 +189,54 @@ __global__ __launch_bounds__(64 * HEADS * NTG, 2) void attend_logits_kernel(
 #pragma unroll
         for (int i = 0; i < NBP; ++i) *reinterpret_cast<u32x4*>(base + b_dst(i)) = R.b[i];
     };
-    auto compute = [&](int buf) {
+    // MFMA fragments of one half step (32 latent bytes): NB token blocks, 4 head-dim blocks
+    struct Frags { u32x4 b[NB]; u32x4 a[4]; };
+    auto read_frags = [&](Frags& F, int buf, int ks) {
         const unsigned char* pa = lds + (size_t)buf * C::STAGE + hh * 128 * kLgStep;
         const unsigned char* pb = lds + (size_t)buf * C::STAGE + C::A_BYTES + tg * NB * 32 * kLgStep;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            u32x4 bf[NB];
+        for (int nb = 0; nb < NB; ++nb) F.b[nb] = *reinterpret_cast<const u32x4*>(pb + swz64(nb * 32 + l32, ks * 2 + hi));
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                bf[nb] = *reinterpret_cast<const u32x4*>(pb + swz64(nb * 32 + l32, ks * 2 + hi));
-            u32x4 af[4];
+        for (int mb = 0; mb < 4; ++mb) F.a[mb] = *reinterpret_cast<const u32x4*>(pa + swz64(mb * 32 + l32, ks * 2 + hi));
+    };
+    auto mma_frags = [&](const Frags& F) {
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
-                af[mb] = *reinterpret_cast<const u32x4*>(pa + swz64(mb * 32 + l32, ks * 2 + hi));
+        for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) mma_op<T>::run(af[mb], bf[nb], acc[mb][nb]);
-        }
+            for (int nb = 0; nb < NB; ++nb) mma_op<T>::run(F.a[mb], F.b[nb], acc[mb][nb]);
     };
 
-    // one register set: step kc+1 goes to LDS, then the loads of step kc+2 fly during the MFMAs
+    // Software pipeline over three LDS stages.  After the barrier every wave of the workgroup is
+    // in the same phase, so LDS traffic and MFMAs only overlap if each wave overlaps them itself:
+    // while the MFMAs of one half step run, the fragments of the next half step are being read
+    // (from this stage, then from the next one, which the previous barrier already published),
+    // and the step after that moves from registers to the third stage.  The scheduling fences
+    // keep the compiler from sinking the reads behind the MFMAs that are meant to cover them.
     {
         Regs R;
+        Frags F0, F1;
         g_load(R, 0);
         rotate_query();
         l_store(R, 0);
-        if (nkc > 1) g_load(R, 1);
+        g_load(R, min(1, nkc - 1));
+        l_store(R, 1);
+        g_load(R, min(2, nkc - 1));
         __syncthreads();
+        read_frags(F0, 0, 0);
+        int cur = 0, nxt = 1, third = 2;  // stage of step kc, kc+1, kc+2
         for (int kc = 0; kc < nkc; ++kc) {
-            if (kc + 1 < nkc) l_store(R, (kc + 1) & 1);
-            if (kc + 2 < nkc) g_load(R, kc + 2);
-            compute(kc & 1);
+            read_frags(F1, cur, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_frags(F0);
+            __builtin_amdgcn_sched_barrier(0);
+            l_store(R, third);                       // step kc+2 (a copy of the last step past the end)
+            g_load(R, min(kc + 3, nkc - 1));
+            read_frags(F0, nxt, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_frags(F1);
+            __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
+            const int t = cur; cur = nxt; nxt = third; third = t;
         }
     }
 
