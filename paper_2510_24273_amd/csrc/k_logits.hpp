@@ -29,11 +29,14 @@ constexpr int kLgChunk = 128;  // bytes per row of a [rows][128 B] swizzled LDS 
 constexpr int kLgStep = 64;    // bytes of the latent axis per pipeline step (= one packed U_k block)
 constexpr int kXcds = 8;       // accelerator dies, workgroups are dealt to them round-robin
 
-// byte offset of 16-byte piece `pc` of row `row` inside a [rows][128 B] swizzled LDS tile
+// LDS tiles are read and written 16 bytes per lane; such an access is conflict-free when each
+// group of 16 consecutive lanes covers all 16 bank groups (address / 16 mod 16).  A fragment read
+// takes one piece index from 16 consecutive rows, a staging write takes consecutive pieces, so
+// the piece index is XOR-ed with row bits.
+// byte offset of 16-byte piece `pc` of row `row` inside a [rows][128 B] tile
 __device__ __forceinline__ int swz(int row, int pc) { return row * kLgChunk + ((pc ^ ((row >> 1) & 7)) << 4); }
-// the same for a [rows][64 B] tile: eight consecutive rows reading one piece index cover
-// all eight 16-byte bank groups
-__device__ __forceinline__ int swz64(int row, int pc) { return row * kLgStep + ((pc ^ ((row >> 1) & 3)) << 4); }
+// the same for a [rows][64 B] tile
+__device__ __forceinline__ int swz64(int row, int pc) { return row * kLgStep + ((pc ^ ((row >> 2) & 3)) << 4); }
 
 template <int HEADS, int NTG, int NB> struct logits_cfg {
     static constexpr int NT = 64 * HEADS * NTG;            // threads
@@ -226,15 +229,32 @@ __global__ __launch_bounds__(64 * HEADS * NTG, 2) void attend_logits_kernel(
         int cur = 0, nxt = 1, third = 2;  // stage of step kc, kc+1, kc+2
         for (int kc = 0; kc < nkc; ++kc) {
             read_frags(F1, cur, 1);
-            __builtin_amdgcn_sched_barrier(0);
             mma_frags(F0);
-            __builtin_amdgcn_sched_barrier(0);
             l_store(R, third);                       // step kc+2 (a copy of the last step past the end)
             g_load(R, min(kc + 3, nkc - 1));
             read_frags(F0, nxt, 0);
-            __builtin_amdgcn_sched_barrier(0);
             mma_frags(F1);
-            __builtin_amdgcn_sched_barrier(0);
+            // issue order: LDS and global memory instructions between the MFMAs that cover them
+            if constexpr (NB == 2) {
+#pragma unroll
+                for (int i = 0; i < 6; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA (first half step)
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read (second half step)
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA (second half step)
+                    __builtin_amdgcn_sched_group_barrier(0x200, NA + NBP >= 4 ? (NA + NBP) / 4 : 1, 0);  // LDS writes (step + 2)
+                    __builtin_amdgcn_sched_group_barrier(0x020, NA + NBP >= 4 ? (NA + NBP) / 4 : 1, 0);  // global loads (step + 3)
+                }
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // LDS reads (next step, first half)
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            }
             __syncthreads();
             const int t = cur; cur = nxt; nxt = third; third = t;
         }
