@@ -17,6 +17,7 @@
 #include "k_project.hpp"
 #include "k_scores.hpp"
 #include "k_topk.hpp"
+#include "k_topk_multi.hpp"
 #include "k_value.hpp"
 
 using namespace sals;
@@ -28,11 +29,12 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Layout {  // byte offsets into the workspace
-    size_t qt, scores, idx, n_sel, logits, stats, rope, tpart, tfin, total;
+    size_t qt, scores, idx, n_sel, logits, stats, rope, tpart, tfin, tm_part, tm_hist, tm_meta, tm_base, tm_cand, total;
     int lk;                      // logits row stride (floats)
     int max_parts;               // token tiles per head of the logits kernel, at most
     int pv_tok_per_wg, pv_ntr;   // value-sum token ranges
     int proj_np;                 // D-axis slices of the query projection
+    int tm_chunks;               // chunks of the multi-workgroup selection (0: one workgroup per sequence)
     size_t w_section;            // elements per section of the packed weights
 };
 
@@ -134,6 +136,15 @@ Layout make_layout(const sals_desc& d)
     L.rope = take((size_t)(d.S_max + 1) * kPairs * 8);  // positions 0 .. S_max (the query after a full cache)
     L.tpart = take((size_t)L.pv_ntr * d.B * d.H_q * d.r * 4);
     L.tfin = take((size_t)d.B * d.H_q * d.r * 4);
+    // long sequences: selection spread over 8192-score chunks
+    L.tm_chunks = d.S_max > 32768 ? ceil_div(d.S_max, kTmChunk) : 0;
+    if (L.tm_chunks > 0) {
+        L.tm_part = take((size_t)d.B * L.tm_chunks * sizeof(uint2));
+        L.tm_hist = take((size_t)d.B * L.tm_chunks * kTmBins * 4);
+        L.tm_meta = take((size_t)d.B * sizeof(TopkMeta));
+        L.tm_base = take((size_t)d.B * L.tm_chunks * 2 * 4);
+        L.tm_cand = take((size_t)d.B * kTmCand * sizeof(uint2));
+    }
     L.total = o;
     return L;
 }
@@ -213,14 +224,33 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
     const sals_desc& d = c->d;
     dim3 grid(d.B), block(kTopkThreads);
     ProfScope ps(c, SALS_K_TOPK, st);
-#define SALS_TOPK(F4)                                                                                \
+#define SALS_TOPK(F4, RUN_IF)                                                                        \
     hipLaunchKernelGGL((topk_kernel<F4>), grid, block, 0, st, scores, seq_len, idx, n_sel, d.S_max, \
-                       d.top_k, d.n_sink, d.n_recent)
-    if (d.S_max <= 4096) SALS_TOPK(1);
-    else if (d.S_max <= 8192) SALS_TOPK(2);
-    else if (d.S_max <= 16384) SALS_TOPK(4);
-    else if (d.S_max <= 32768) SALS_TOPK(8);
-    else SALS_TOPK(0);
+                       d.top_k, d.n_sink, d.n_recent, RUN_IF, (int)(sizeof(TopkMeta) / 4))
+    if (c->L.tm_chunks > 0) {
+        const Layout& L = c->L;
+        TopkMultiWs ws{reinterpret_cast<uint2*>(c->ws + L.tm_part), reinterpret_cast<uint32_t*>(c->ws + L.tm_hist),
+                       reinterpret_cast<TopkMeta*>(c->ws + L.tm_meta), reinterpret_cast<uint32_t*>(c->ws + L.tm_base),
+                       reinterpret_cast<uint2*>(c->ws + L.tm_cand)};
+        const int nc = L.tm_chunks;
+        dim3 cgrid(nc, d.B);
+        hipLaunchKernelGGL(topk_range_kernel, cgrid, block, 0, st, scores, seq_len, ws, d.S_max, nc, d.n_sink, d.n_recent);
+        hipLaunchKernelGGL(topk_hist_kernel, cgrid, block, 0, st, scores, seq_len, ws, d.S_max, nc, d.n_sink, d.n_recent);
+        hipLaunchKernelGGL(topk_resolve_kernel, grid, block, 0, st, seq_len, ws, d.S_max, nc, d.top_k, d.n_sink,
+                           d.n_recent);
+        hipLaunchKernelGGL(topk_place_kernel, cgrid, block, 0, st, scores, seq_len, ws, idx, d.S_max, nc, d.top_k,
+                           d.n_sink, d.n_recent);
+        hipLaunchKernelGGL(topk_finish_kernel, grid, dim3(kTmCand), 0, st, seq_len, ws, idx, n_sel, d.S_max, d.top_k,
+                           d.n_sink, d.n_recent);
+        // whatever the chain flagged (short cache, degenerate range, crowded threshold bin)
+        SALS_TOPK(0, reinterpret_cast<const uint32_t*>(ws.meta));
+        return launch_status();
+    }
+    const uint32_t* always = nullptr;
+    if (d.S_max <= 4096) SALS_TOPK(1, always);
+    else if (d.S_max <= 8192) SALS_TOPK(2, always);
+    else if (d.S_max <= 16384) SALS_TOPK(4, always);
+    else SALS_TOPK(8, always);
 #undef SALS_TOPK
     return launch_status();
 }

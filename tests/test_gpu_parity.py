@@ -122,6 +122,47 @@ def test_exact_ties_resolve_to_smaller_index(oracle):
     ctx.close()
 
 
+@pytest.mark.parametrize("case", ["random", "ragged", "plateaus", "constant", "short", "nonfinite"])
+def test_long_sequence_selection(oracle, case):
+    """S_max above 32768 takes the multi-workgroup selection; its index set must equal the
+    oracle's on the same fp32 scores (the oracle's rule: larger score first, ties to the smaller
+    index).  "plateaus" crowds the threshold bin and "constant" has an empty score range: both go
+    through the single-workgroup kernel that the chain falls back to, as does "short" (a cache no
+    longer than the selection) and a row holding infinities."""
+    S, top_k, n_sink, n_recent = 40000, 300, 4, 16
+    w = synth.shrink(SMALL, B=2, S=S, top_k=top_k, n_sink=n_sink, n_recent=n_recent, plant=0)
+    rng = np.random.default_rng(11)
+    sc = rng.standard_normal((2, S)).astype(np.float32) * 3.0
+    seq = np.array([S, S], np.int32)
+    if case == "ragged":
+        seq = np.array([S - 7, 33001], np.int32)
+    elif case == "plateaus":
+        sc = np.round(sc)                      # a few dozen distinct values, thousands of ties each
+    elif case == "constant":
+        sc[:] = 1.25
+        sc[1, 5000] = -0.0
+        sc[1, :5000] = 0.0
+        sc[1, 5001:] = 0.0
+    elif case == "short":
+        seq = np.array([top_k + n_sink + n_recent, 17], np.int32)
+    elif case == "nonfinite":
+        sc[0, 123] = np.inf
+        sc[0, 456] = -np.inf
+    ctx = gu.make_ctx(w)
+    k_tot = top_k + n_sink + n_recent
+    idx = torch.full((2, k_tot), -7, dtype=torch.int32, device=gu.DEV)
+    n = torch.full((2,), -7, dtype=torch.int32, device=gu.DEV)
+    d_sc = torch.from_numpy(sc).to(gu.DEV)
+    ctx.topk_select(d_sc, torch.from_numpy(seq).to(gu.DEV), idx, n)
+    torch.cuda.synchronize()
+    for b in range(2):
+        want = oracle.topk(sc[b, :seq[b]].astype(np.float64), top_k, n_sink, n_recent)
+        got = idx[b, :int(n[b])].cpu().numpy()
+        assert int(n[b]) == len(want), (case, b)
+        assert np.array_equal(np.sort(got), np.sort(want)), (case, b)
+    ctx.close()
+
+
 def test_compress_append_then_decode(oracle):
     """Algorithm 1 in order: compress the new token, append, then attend with the query on
     the appended row (q_pos = seq_len - 1)."""
