@@ -71,21 +71,15 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, TopkShared& sh, 
     return r;
 }
 
+// Selection for sequence b by the calling workgroup (1024 threads, all of them must call).
 // F4 > 0: keys of F4 float4 groups per thread stay in registers.  F4 == 0: stream.
-// run_if: when not null, sequence b is only processed if run_if[b * run_stride] is non-zero.
 template <int F4>
-__global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restrict__ scores,
-                                                            const int32_t* __restrict__ seq_len,
-                                                            int32_t* __restrict__ idx,
-                                                            int32_t* __restrict__ n_sel, int S_max,
-                                                            int top_k, int n_sink, int n_recent,
-                                                            const uint32_t* __restrict__ run_if, int run_stride)
+__device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float* __restrict__ scores,
+                                                     const int32_t* __restrict__ seq_len,
+                                                     int32_t* __restrict__ idx, int32_t* __restrict__ n_sel,
+                                                     int b, int S_max, int top_k, int n_sink, int n_recent)
 {
-    __shared__ TopkShared sh;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    const int b = blockIdx.x;
-    // optional run condition (a flag per sequence left by the multi-workgroup selection)
-    if (run_if != nullptr && run_if[(size_t)b * run_stride] == 0u) return;
     const int k_tot = top_k + n_sink + n_recent;
     const float* s = scores + (size_t)b * S_max;
     int32_t* out = idx + (size_t)b * k_tot;
@@ -301,6 +295,21 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
         og += g;
         oe += e;
     });
+}
+
+// run_if: when not null, sequence b is only processed if run_if[b * run_stride] is non-zero.
+template <int F4>
+__global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restrict__ scores,
+                                                            const int32_t* __restrict__ seq_len,
+                                                            int32_t* __restrict__ idx,
+                                                            int32_t* __restrict__ n_sel, int S_max,
+                                                            int top_k, int n_sink, int n_recent,
+                                                            const uint32_t* __restrict__ run_if, int run_stride)
+{
+    __shared__ TopkShared sh;
+    const int b = blockIdx.x;
+    if (run_if != nullptr && run_if[(size_t)b * run_stride] == 0u) return;
+    topk_select_sequence<F4>(sh, scores, seq_len, idx, n_sel, b, S_max, top_k, n_sink, n_recent);
 }
 
 }  // namespace sals

@@ -7,17 +7,18 @@
 // kernels that exchange a few kilobytes:
 //   range    per chunk: minimum and maximum candidate key
 //   hist     per chunk: histogram over 2048 linear bins of the sequence's [min, max]
-//   resolve  per sequence: the bin holding the top_k-th score, how many of its members are
-//            selected, and where every chunk's output starts
-//   place    per chunk: indices of the scores in higher bins go to their final positions (chunk
-//            order, then token order); members of the threshold bin go to a candidate list
+//   place    per chunk: from all chunk histograms, the bin holding the top_k-th score, how many of
+//            its members are selected and where the chunk's output starts (every workgroup of the
+//            sequence derives the same numbers); then the indices of the scores in higher bins go
+//            to their final positions (chunk order, then token order) and the members of the
+//            threshold bin to a candidate list
 //   finish   per sequence: ranks the candidates (ties towards the smaller index), writes the
 //            selected ones in token order, the sink / recent entries and n_sel
 // The result is the same set as topk_kernel's, a deterministic function of the scores; only
 // the order inside the top_k block differs (bins above the threshold first).  Cases this chain
 // does not cover (a cache no longer than the selection, a degenerate or non-finite score range,
-// more than 512 members in the threshold bin) raise a flag, and topk_kernel, launched after the
-// chain with that flag as its run condition, handles them.
+// more than 512 members in the threshold bin) raise a flag, and the finish kernel's workgroup
+// then selects that sequence from scratch the way topk_kernel does.
 #pragma once
 #include "common.hpp"
 #include "k_topk.hpp"
@@ -30,7 +31,7 @@ constexpr int kTmBins = 2048;
 constexpr int kTmMaxChunks = 128;         // S_max <= 2^20
 constexpr int kTmCand = 512;              // candidates the finish kernel ranks
 
-struct TopkMeta {        // per sequence, written by resolve
+struct TopkMeta {        // per sequence, written by the place kernel
     uint32_t fallback;   // 1: topk_kernel must redo the sequence
     uint32_t t_slot;     // threshold bin (slot 0 = top of the range)
     uint32_t kk;         // members of the threshold bin that are selected
@@ -45,7 +46,6 @@ struct TopkMultiWs {
     uint2* part;         // [B][n_chunk] (min key, max key) of the chunk's candidates
     uint32_t* hist;      // [B][n_chunk][kTmBins]
     TopkMeta* meta;      // [B]
-    uint32_t* base;      // [B][n_chunk][2] first output position / first candidate slot of the chunk
     uint2* cand;         // [B][kTmCand] (key, token index)
 };
 
@@ -145,21 +145,21 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(const float* __
     for (int t = tid; t < kTmBins; t += kTopkThreads) out[t] = hist[t];
 }
 
-__global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(const int32_t* __restrict__ seq_len,
-                                                                    TopkMultiWs ws, int S_max, int n_chunk,
-                                                                    int top_k, int n_sink, int n_recent)
+// The sequence-level decisions, taken identically by every workgroup of the sequence from the
+// chunk histograms: threshold bin, selected members, and the first output position / candidate
+// slot of chunk `chunk`.  Returns the meta record (fallback set if the chain does not apply).
+__device__ __forceinline__ TopkMeta tm_resolve(TopkShared& sh, uint32_t* s_above, uint32_t* s_memb,
+                                               const TopkMultiWs& ws, int b, int chunk, int S, int n_chunk,
+                                               int top_k, int n_sink, int n_recent, uint32_t* base_above,
+                                               uint32_t* base_cand)
 {
-    __shared__ TopkShared sh;
-    __shared__ uint32_t s_above[kTmMaxChunks], s_memb[kTmMaxChunks];
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int S = min(seq_len[b], S_max);
-    TopkMeta* meta = ws.meta + b;
-    float flo = 0.f, scale = 0.f;
-    const bool ok = tm_range(ws.part + (size_t)b * n_chunk, n_chunk, &flo, &scale) &&
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    TopkMeta m{};
+    const bool ok = tm_range(ws.part + (size_t)b * n_chunk, n_chunk, &m.flo, &m.scale) &&
                     S > top_k + n_sink + n_recent && top_k > 0;
     if (!ok) {  // uniform
-        if (tid == 0) { meta->fallback = 1u; meta->flo = 0.f; meta->scale = 0.f; }
-        return;
+        m.fallback = 1u;
+        return m;
     }
     // this thread's two bins, summed over the chunks
     const uint32_t* hb = ws.hist + (size_t)b * n_chunk * kTmBins + 2 * tid;
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(const int32_
         sh.sel_prefix = 2 * tid + 1; sh.sel_kk = (uint32_t)top_k - above - c0; sh.n_cand = c1;
     }
     __syncthreads();
-    const uint32_t t_slot = sh.sel_prefix, kk = sh.sel_kk, members = sh.n_cand;
+    m.t_slot = sh.sel_prefix; m.kk = sh.sel_kk; m.members = sh.n_cand;
     // per chunk: scores in bins above the threshold, members of the threshold bin (a wave per chunk)
     for (int c = wave; c < n_chunk; c += kTopkWaves) {
         const uint32_t* hc = ws.hist + ((size_t)b * n_chunk + c) * kTmBins;
@@ -192,25 +192,24 @@ __global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(const int32_
 #pragma unroll
         for (int i = 0; i < kTmBins / (4 * kWave); ++i) {
             const uint32_t s0 = 4u * (lane + kWave * i);
-            sum += (s0 < t_slot ? v[i].x : 0u) + (s0 + 1 < t_slot ? v[i].y : 0u) + (s0 + 2 < t_slot ? v[i].z : 0u) +
-                   (s0 + 3 < t_slot ? v[i].w : 0u);
+            sum += (s0 < m.t_slot ? v[i].x : 0u) + (s0 + 1 < m.t_slot ? v[i].y : 0u) + (s0 + 2 < m.t_slot ? v[i].z : 0u) +
+                   (s0 + 3 < m.t_slot ? v[i].w : 0u);
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) sum += (uint32_t)__shfl_xor((int)sum, o, kWave);
-        if (lane == 0) { s_above[c] = sum; s_memb[c] = hc[t_slot]; }
+        if (lane == 0) { s_above[c] = sum; s_memb[c] = hc[m.t_slot]; }
     }
     __syncthreads();
-    if (tid == 0) {
-        uint32_t a = 0u, m = 0u;
-        uint32_t* base = ws.base + (size_t)b * n_chunk * 2;
-        for (int c = 0; c < n_chunk; ++c) {
-            base[2 * c] = a; base[2 * c + 1] = m;
-            a += s_above[c]; m += s_memb[c];
-        }
-        meta->fallback = members > (uint32_t)kTmCand ? 1u : 0u;
-        meta->t_slot = t_slot; meta->kk = kk; meta->n_above = a; meta->members = members;
-        meta->flo = flo; meta->scale = scale;
+    uint32_t a = 0u, mm = 0u, a_here = 0u, m_here = 0u;
+    for (int c = 0; c < n_chunk; ++c) {
+        if (c == chunk) { a_here = a; m_here = mm; }
+        a += s_above[c]; mm += s_memb[c];
     }
+    *base_above = a_here;
+    *base_cand = m_here;
+    m.n_above = a;
+    m.fallback = m.members > (uint32_t)kTmCand ? 1u : 0u;
+    return m;
 }
 
 __global__ __launch_bounds__(kTopkThreads) void topk_place_kernel(const float* __restrict__ scores,
@@ -220,12 +219,16 @@ __global__ __launch_bounds__(kTopkThreads) void topk_place_kernel(const float* _
                                                                   int n_recent)
 {
     __shared__ TopkShared sh;
+    __shared__ uint32_t s_above[kTmMaxChunks], s_memb[kTmMaxChunks];
     const int chunk = blockIdx.x, b = blockIdx.y;
-    const TopkMeta m = ws.meta[b];
-    if (m.fallback) return;
     const int S = min(seq_len[b], S_max);
     uint32_t keys[4 * kTmF4];
     tm_load_keys(scores + (size_t)b * S_max, S_max, chunk, n_sink, S - n_recent, keys);
+    uint32_t base_above = 0u, base_cand = 0u;
+    const TopkMeta m = tm_resolve(sh, s_above, s_memb, ws, b, chunk, S, n_chunk, top_k, n_sink, n_recent,
+                                  &base_above, &base_cand);
+    if (chunk == 0 && threadIdx.x == 0) ws.meta[b] = m;  // for the finish kernel
+    if (m.fallback) return;
     int slot[4 * kTmF4];
     uint32_t n_ab = 0u, n_eq = 0u;
 #pragma unroll
@@ -236,11 +239,11 @@ __global__ __launch_bounds__(kTopkThreads) void topk_place_kernel(const float* _
     }
     int phase = 0;
     uint32_t tot_ab, tot_eq;
+    __syncthreads();
     block_excl_scan2(n_ab, n_eq, sh, phase, &tot_ab, &tot_eq);
-    const uint32_t* base = ws.base + ((size_t)b * n_chunk + chunk) * 2;
     int32_t* out = idx + (size_t)b * (top_k + n_sink + n_recent) + n_sink;
     uint2* cand = ws.cand + (size_t)b * kTmCand;
-    uint32_t pa = base[0] + n_ab, pc = base[1] + n_eq;
+    uint32_t pa = base_above + n_ab, pc = base_cand + n_eq;
 #pragma unroll
     for (int i = 0; i < 4 * kTmF4; ++i) {
         const int j = tm_token(chunk, i);
@@ -249,25 +252,32 @@ __global__ __launch_bounds__(kTopkThreads) void topk_place_kernel(const float* _
     }
 }
 
-__global__ __launch_bounds__(kTmCand) void topk_finish_kernel(const int32_t* __restrict__ seq_len, TopkMultiWs ws,
-                                                             int32_t* __restrict__ idx, int32_t* __restrict__ n_sel,
-                                                             int S_max, int top_k, int n_sink, int n_recent)
+// finish: ranks the candidates; a flagged sequence is selected from scratch by this workgroup
+__global__ __launch_bounds__(kTopkThreads) void topk_finish_kernel(const float* __restrict__ scores,
+                                                                   const int32_t* __restrict__ seq_len,
+                                                                   TopkMultiWs ws, int32_t* __restrict__ idx,
+                                                                   int32_t* __restrict__ n_sel, int S_max, int top_k,
+                                                                   int n_sink, int n_recent)
 {
+    __shared__ TopkShared sh;
     __shared__ uint2 s_c[kTmCand];
     __shared__ uint32_t s_sel[kTmCand];
     const int b = blockIdx.x, tid = threadIdx.x;
     const TopkMeta m = ws.meta[b];
-    if (m.fallback) return;
+    if (m.fallback) {  // uniform
+        topk_select_sequence<0>(sh, scores, seq_len, idx, n_sel, b, S_max, top_k, n_sink, n_recent);
+        return;
+    }
     const int S = min(seq_len[b], S_max);
     const int k_tot = top_k + n_sink + n_recent;
     int32_t* out = idx + (size_t)b * k_tot;
-    for (int t = tid; t < n_sink; t += kTmCand) out[t] = t;
-    for (int t = tid; t < n_recent; t += kTmCand) out[n_sink + top_k + t] = S - n_recent + t;
+    for (int t = tid; t < n_sink; t += kTopkThreads) out[t] = t;
+    for (int t = tid; t < n_recent; t += kTopkThreads) out[n_sink + top_k + t] = S - n_recent + t;
     if (tid == 0) n_sel[b] = k_tot;
     const uint32_t nm = m.members;
     uint2 me = make_uint2(0u, 0u);
     if ((uint32_t)tid < nm) me = ws.cand[(size_t)b * kTmCand + tid];
-    s_c[tid] = me;
+    if (tid < kTmCand) s_c[tid] = me;
     __syncthreads();
     // rank among the members: larger key first, equal keys by smaller token index
     uint32_t before = 0u;
@@ -277,7 +287,7 @@ __global__ __launch_bounds__(kTmCand) void topk_finish_kernel(const int32_t* __r
             before += (o.x > me.x) || (o.x == me.x && o.y < me.y);
         }
     const uint32_t sel = ((uint32_t)tid < nm && before < m.kk) ? 1u : 0u;
-    s_sel[tid] = sel;
+    if (tid < kTmCand) s_sel[tid] = sel;
     __syncthreads();
     if (sel) {  // position in token order among the selected members
         uint32_t pos = 0u;

@@ -29,7 +29,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Layout {  // byte offsets into the workspace
-    size_t qt, scores, idx, n_sel, logits, stats, rope, tpart, tfin, tm_part, tm_hist, tm_meta, tm_base, tm_cand, total;
+    size_t qt, scores, idx, n_sel, logits, stats, rope, tpart, tfin, tm_part, tm_hist, tm_meta, tm_cand, total;
     int lk;                      // logits row stride (floats)
     int max_parts;               // token tiles per head of the logits kernel, at most
     int pv_tok_per_wg, pv_ntr;   // value-sum token ranges
@@ -142,7 +142,6 @@ Layout make_layout(const sals_desc& d)
         L.tm_part = take((size_t)d.B * L.tm_chunks * sizeof(uint2));
         L.tm_hist = take((size_t)d.B * L.tm_chunks * kTmBins * 4);
         L.tm_meta = take((size_t)d.B * sizeof(TopkMeta));
-        L.tm_base = take((size_t)d.B * L.tm_chunks * 2 * 4);
         L.tm_cand = take((size_t)d.B * kTmCand * sizeof(uint2));
     }
     L.total = o;
@@ -230,20 +229,15 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
     if (c->L.tm_chunks > 0) {
         const Layout& L = c->L;
         TopkMultiWs ws{reinterpret_cast<uint2*>(c->ws + L.tm_part), reinterpret_cast<uint32_t*>(c->ws + L.tm_hist),
-                       reinterpret_cast<TopkMeta*>(c->ws + L.tm_meta), reinterpret_cast<uint32_t*>(c->ws + L.tm_base),
-                       reinterpret_cast<uint2*>(c->ws + L.tm_cand)};
+                       reinterpret_cast<TopkMeta*>(c->ws + L.tm_meta), reinterpret_cast<uint2*>(c->ws + L.tm_cand)};
         const int nc = L.tm_chunks;
         dim3 cgrid(nc, d.B);
         hipLaunchKernelGGL(topk_range_kernel, cgrid, block, 0, st, scores, seq_len, ws, d.S_max, nc, d.n_sink, d.n_recent);
         hipLaunchKernelGGL(topk_hist_kernel, cgrid, block, 0, st, scores, seq_len, ws, d.S_max, nc, d.n_sink, d.n_recent);
-        hipLaunchKernelGGL(topk_resolve_kernel, grid, block, 0, st, seq_len, ws, d.S_max, nc, d.top_k, d.n_sink,
-                           d.n_recent);
         hipLaunchKernelGGL(topk_place_kernel, cgrid, block, 0, st, scores, seq_len, ws, idx, d.S_max, nc, d.top_k,
                            d.n_sink, d.n_recent);
-        hipLaunchKernelGGL(topk_finish_kernel, grid, dim3(kTmCand), 0, st, seq_len, ws, idx, n_sel, d.S_max, d.top_k,
+        hipLaunchKernelGGL(topk_finish_kernel, grid, block, 0, st, scores, seq_len, ws, idx, n_sel, d.S_max, d.top_k,
                            d.n_sink, d.n_recent);
-        // whatever the chain flagged (short cache, degenerate range, crowded threshold bin)
-        SALS_TOPK(0, reinterpret_cast<const uint32_t*>(ws.meta));
         return launch_status();
     }
     const uint32_t* always = nullptr;
