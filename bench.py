@@ -36,6 +36,9 @@ def parse():
                     help="other configurations reported under 'extra' (comma list, '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one device-to-device copy of this many MiB (a kernel of known HBM "
+                         "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -91,8 +94,14 @@ def timed(torch, fn, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
-def kernel_table(ls, steps, roofline):
-    """Per-kernel average duration (us) over `steps` profiled steps + roofline figures."""
+def kernel_table(ls, steps, roofline, wall_us_per_layer_step):
+    """Per-kernel average duration (us) over `steps` profiled steps + roofline figures.
+
+    The library brackets every stage with a pair of HIP events on the launch stream.  A bracket also
+    contains the gap between the previous kernel's end and this kernel's start, which back-to-back
+    launches otherwise overlap; that gap is estimated live as (sum of bracketed times - wall time of the
+    same un-profiled step) / brackets and taken off every stage ("us"; "us_events" is the raw reading).
+    """
     torch, w = ls.torch, ls.w
     ls.ctx.profile(True)
     for _ in range(steps):
@@ -109,20 +118,21 @@ def kernel_table(ls, steps, roofline):
         "attend_pv": ("hbm", w.B * w.k_tot * w.r * w.esize),
         "attend_out": ("hbm", w.r * w.D_kv * w.esize),
     }
+    raw = {name: ms * 1e3 / n for name, (ms, n) in prof.items() if n > 0}
+    gap = max(0.0, (sum(raw.values()) - wall_us_per_layer_step) / max(1, len(raw)))
     rows = {}
-    for name, (ms, n) in prof.items():
-        if n == 0:
-            continue
-        us = ms * 1e3 / n
+    for name, us_ev in raw.items():
+        us = max(us_ev - gap, 0.25 * us_ev)
         bound, work = model[name]
         if bound == "hbm":
             ach, peak, unit = work / (us * 1e-6) / 1e9, roofline.HBM_PEAK_GBPS, "GB/s"
         else:
             peak = roofline.MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else roofline.VALU_F32_PEAK_TFLOPS
             ach, unit = work / (us * 1e-6) / 1e12, "TFLOP/s"
-        rows[name] = {"us": round(us, 3), "launches": n, "bound": bound, "work": int(work),
-                      "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4)}
-    return rows
+        rows[name] = {"us": round(us, 3), "us_events": round(us_ev, 3), "launches": prof[name][1], "bound": bound,
+                      "work": int(work), "achieved": round(ach, 2), "peak": peak, "unit": unit,
+                      "frac": round(ach / peak, 4)}
+    return rows, gap
 
 
 def measure(ls, steps, warmup, use_graph, roofline):
@@ -154,7 +164,8 @@ def measure(ls, steps, warmup, use_graph, roofline):
     res["algorithmic_bytes"] = roofline.algorithmic_bytes(w)
     res["pipeline_GBps"] = res["algorithmic_bytes"] / (res["us_per_layer_step"] * 1e-6) / 1e9
     res["pipeline_hbm_frac"] = res["pipeline_GBps"] / roofline.HBM_PEAK_GBPS
-    res["kernels"] = kernel_table(ls, max(3, steps // 3), roofline)
+    res["kernels"], res["event_gap_us"] = kernel_table(ls, max(3, steps // 3), roofline,
+                                                       res["eager_ms_per_step"] * 1e3 / n_layers)
     return res
 
 
@@ -199,10 +210,16 @@ def main():
     ls = LayerSet(w, n_layers, torch, binding, synth)
     log(f"[bench] resident inputs: {ls.bytes_resident() / 1e6:.0f} MB; timing")
     res = measure(ls, a.steps, a.warmup, not a.no_graph, roofline)
+    if a.calib_copy_mib > 0:
+        src = torch.ones(a.calib_copy_mib * (1 << 20) // 4, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
     kern = res["kernels"]
     dom = max(kern, key=lambda k: kern[k]["us"])
     dk = kern[dom]
-    traffic = roofline.MEASURED_TRAFFIC.get((dom, a.workload))
+    traffic = roofline.MEASURED_TRAFFIC.get((a.workload, dom))
     out = {
         "metric": "sals_decode_attn_us_per_layer_step", "value": round(res["us_per_layer_step"], 3),
         "unit": "us", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -217,7 +234,8 @@ def main():
         "pipeline": {"algorithmic_bytes": res["algorithmic_bytes"], "achieved_GBps": round(res["pipeline_GBps"], 1),
                      "hbm_peak_GBps": roofline.HBM_PEAK_GBPS, "frac": round(res["pipeline_hbm_frac"], 4)},
         "roofline": {"kernel": dom, "bound": dk["bound"], "achieved": dk["achieved"], "peak": dk["peak"],
-                     "unit": dk["unit"], "frac": dk["frac"], "traffic": traffic, "avg_us": dk["us"]},
+                     "unit": dk["unit"], "frac": dk["frac"], "traffic": traffic, "avg_us": dk["us"],
+                     "avg_us_events": dk["us_events"], "event_gap_us": round(res["event_gap_us"], 3)},
         "kernels": kern,
     }
     if not a.no_cpu_baseline:

@@ -51,6 +51,16 @@ def stage_flops(w, seq_len=None) -> dict:
         "attention": 4 * w.B * n_sel * w.H * w.d,
     }
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
-# copy kernel of known size); filled from the summaries under profiles/.
-MEASURED_TRAFFIC: dict = {}
+# HBM bytes per launch (read + written) measured with rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE,
+# each scaled by the same counter's reading for a 64 MiB device-to-device copy in the same run
+# (FETCH_SIZE reads half of the copied bytes on this chip, WRITE_SIZE all of them).  Source: the
+# summaries profiles/hbm_traffic_<workload>.txt.  The scaling assumes full 128-byte requests, so
+# kernels that fetch 64-byte pieces are over-counted by up to 2x.
+MEASURED_TRAFFIC: dict = {
+    ("cfg2", "attend_logits"): 12_818_000, ("cfg2", "attend_out"): 6_739_000, ("cfg2", "scores"): 5_479_000,
+    ("cfg2", "project"): 5_454_000, ("cfg2", "attend_pv"): 2_352_000, ("cfg2", "topk"): 35_000,
+    ("cfg3a", "attend_logits"): 100_025_000, ("cfg3a", "scores"): 86_832_000, ("cfg3a", "attend_pv"): 31_308_000,
+    ("cfg3a", "attend_out"): 16_032_000, ("cfg3a", "project"): 6_746_000, ("cfg3a", "topk"): 430_000,
+    ("cfg4", "scores"): 169_029_000, ("cfg4", "attend_logits"): 100_032_000, ("cfg4", "attend_pv"): 31_308_000,
+    ("cfg4", "attend_out"): 15_936_000, ("cfg4", "project"): 5_714_000, ("cfg4", "topk"): 768_000,
+}
