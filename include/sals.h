@@ -176,9 +176,9 @@ sals_status sals_decode_step(sals_ctx* ctx, const void* q, const int32_t* q_pos,
                              float* scores, int32_t* idx, int32_t* n_sel, void* hip_stream);
 
 /* ---- measurement aid --------------------------------------------------------------
- * Per-kernel timing for roofline figures.  While enabled, every kernel a stage call
- * launches is bracketed by a pair of HIP events on the call's stream (host-side event
- * objects; no device memory).  sals_profile_collect waits for the recorded events, adds
+ * Per-stage timing for roofline figures.  While enabled, every stage below (one kernel;
+ * for the selection of sequences above 32768 tokens a chain of four) is bracketed by a
+ * pair of HIP events on the call's stream (host-side event objects; no device memory).  sals_profile_collect waits for the recorded events, adds
  * the elapsed milliseconds and launch counts per kernel into total_ms / launches (host
  * arrays of SALS_N_KERNELS entries, overwritten) and forgets the records.  Timing with
  * events serialises neighbouring launches slightly; leave it off in timed runs. */

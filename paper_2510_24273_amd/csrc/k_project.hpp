@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(ProjArgs a)
 #pragma unroll
     for (int nb = 0; nb < kProjMaxCols / 16; ++nb) acc[nb] = f32x4v{0.f, 0.f, 0.f, 0.f};
 
-    // this wave's steps: wave, wave+8, ... ; kProjBatch steps of loads per round
+    // this wave's steps: wave, wave+4, ... ; kProjBatch steps of loads per round
     for (int ks0 = wave; ks0 < nks; ks0 += kProjWaves * kProjBatch) {
         u32x4 af[kProjBatch];
 #pragma unroll
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(ProjArgs a)
         }
     }
 
-    // fold the 8 D-slices in wave order; acc[nb][v] is (coordinate 4*kg+v, column nb*16+l16)
+    // fold the four waves' sums in wave order; acc[nb][v] is (coordinate 4*kg+v, column nb*16+l16)
 #pragma unroll
     for (int nb = 0; nb < kProjMaxCols / 16; ++nb) {
         if (nb < n_nblk) {  // uniform
