@@ -103,11 +103,16 @@ def kernel_table(ls, steps, roofline, wall_us_per_layer_step):
     same un-profiled step) / brackets and taken off every stage ("us"; "us_events" is the raw reading).
     """
     torch, w = ls.torch, ls.w
+    # three profiled rounds, per stage the smallest average: one stray stall (another process, a page
+    # fault) would otherwise land in whichever bracket it hit and skew the gap estimate
     ls.ctx.profile(True)
-    for _ in range(steps):
-        ls.step()
-    torch.cuda.synchronize()
-    prof = ls.ctx.profile_collect()
+    prof = None
+    for _ in range(3):
+        for _ in range(steps):
+            ls.step()
+        torch.cuda.synchronize()
+        p1 = ls.ctx.profile_collect()
+        prof = p1 if prof is None else {k: (min(prof[k], p1[k], key=lambda mn: mn[0] / max(mn[1], 1))) for k in p1}
     ls.ctx.profile(False)
     sb, sf = roofline.stage_bytes(w), roofline.stage_flops(w)
     model = {

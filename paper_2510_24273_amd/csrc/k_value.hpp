@@ -2,14 +2,15 @@
 // y_h = ((p_h V~_C) U_v[g(h) block]^T) : the same sum as p_h (V~_C U_v^T) in another order,
 // so the selected values are never reconstructed.
 //
-//   attend_pv   per (sequence, token range, 32 latent columns):
+//   attend_pv   per (sequence, token range, 64 latent columns):
 //               T[h,:] = sum_j p_hj V~[C_j,:]  on the matrix cores, tokens being the
-//               contraction axis (split over the four waves).  The softmax weights are formed
+//               contraction axis (each 64-token step split over the four waves); the gathered
+//               rows are transposed through LDS on the way.  The softmax weights are formed
 //               on the fly, p = exp(logit - m_h) / Z_h, with m_h and Z_h merged in the prologue
-//               from the per-tile statistics the logits kernel left.  With one range T is
-//               written in matrix-core form; with several, each range writes an fp32 partial sum.
-//   attend_out  y[(b,h), c] = sum_i T[(b,h), i] U_v[g*128 + c, i]  on the matrix cores; adds the
-//               range partials in order first when there are several.
+//               from the per-tile statistics the logits kernel left.  Each token range writes an
+//               fp32 partial sum.
+//   attend_out  y[(b,h), c] = sum_i T[(b,h), i] U_v[g*128 + c, i]  on the matrix cores, after
+//               adding the range partials in range order.
 //
 // bf16 storage: the fp32 weights p and the fp32 T are split into a bf16 head and a bf16
 // remainder (two MFMAs each), which keeps about 16 mantissa bits.  fp32 storage: fp32 MFMAs.
@@ -20,23 +21,11 @@
 
 namespace sals {
 
-constexpr int kPvTJ = 64;          // tokens per wave step
-constexpr int kPvCols = 32;        // latent columns per workgroup
+constexpr int kPvTJ = 64;          // tokens per step
+constexpr int kPvCols = 64;        // latent columns per workgroup
 constexpr int kPvMaxHeads = 64;    // H_q limit of these kernels
 constexpr int kMaxRanges = 32;     // token ranges per sequence
-
-// split an fp32 value for storage type T: bf16 -> (head, remainder); fp32 -> itself
-template <typename T>
-__device__ __forceinline__ void store_split(T* hi_arr, T* lo_arr, size_t at, float v)
-{
-    if constexpr (sizeof(T) == 2) {
-        bf16_t h = f32_to_bf16(v);
-        hi_arr[at] = h;
-        lo_arr[at] = f32_to_bf16(v - bf16_to_f32(h));
-    } else {
-        hi_arr[at] = v;
-    }
-}
+constexpr int kPvMaxTok = 4096;    // tokens per workgroup, at most (their cache rows sit in LDS)
 
 template <typename T>
 __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__ Vc,
@@ -44,27 +33,41 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
                                                         const int32_t* __restrict__ n_sel,
                                                         const float* __restrict__ logits,
                                                         const float2* __restrict__ stats, int n_parts,
-                                                        float* __restrict__ Tpart, T* __restrict__ Tfin,
+                                                        float* __restrict__ Tpart,
                                                         int B, int S_max, int r, int H, int k_tot, int lk,
-                                                        int tok_per_wg, int n_tr)
+                                                        int tok_per_wg)
 {
-    constexpr int VEC = elem<T>::vec;        // tokens per lane per MFMA group
+    constexpr int ES = (int)sizeof(T);
+    constexpr int VEC = elem<T>::vec;        // tokens per lane per MFMA group = elements per 16 bytes
     constexpr int KG = 2 * VEC;              // tokens per MFMA group (both half-waves)
-    constexpr int NKG = kPvTJ / KG;
-    constexpr bool kSplit = sizeof(T) == 2;
+    constexpr int NKG = kPvTJ / KG;          // MFMA groups per step, dealt to the four waves
+    constexpr bool kSplit = ES == 2;
+    constexpr int PPR = kPvCols * ES / 16;   // 16-byte pieces per gathered row
+    constexpr int NPC = kPvTJ * PPR / 256;   // pieces per thread per step
+    constexpr int PITCH = kPvTJ * ES + 8;    // bytes per column of the transposed tile (8-byte reads stay aligned)
 
-    __shared__ __attribute__((aligned(16))) float red[3][64][33];
-    __shared__ float2 sMZ[kPvMaxHeads];  // per head: softmax maximum, 1 / normaliser
+    // V~ rows arrive as they lie in memory (16 bytes = VEC columns of one token per lane) and are
+    // written to LDS transposed, [column][token], so that an MFMA operand (one column, VEC consecutive
+    // tokens per lane) is two 8-byte reads.
+    constexpr int VT_BYTES = 2 * kPvCols * PITCH, RED_BYTES = 4 * 64 * 33 * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char sBuf[VT_BYTES > RED_BYTES ? VT_BYTES : RED_BYTES];
+    unsigned char (*sVt)[kPvCols * PITCH] = reinterpret_cast<unsigned char (*)[kPvCols * PITCH]>(sBuf);
+    float (*red)[64][33] = reinterpret_cast<float (*)[64][33]>(sBuf);  // cross-wave sums, after the loop
+    __shared__ int sRow[kPvMaxTok];          // cache row of every token of the range
+    __shared__ float2 sMZ[kPvMaxHeads];      // per head: softmax maximum, 1 / normaliser
 
     const int b = blockIdx.z, tr = blockIdx.y, cb = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
     const int n = n_sel[b];
     const int j_begin = min(n, tr * tok_per_wg), j_end = min(n, j_begin + tok_per_wg);
-    const int col = cb * kPvCols + l32;
+    const int ntok = j_end - j_begin;
+    const int col0 = cb * kPvCols;
     const int n_mb = (H + 31) >> 5;
     const float* lg = logits + (size_t)b * H * lk;
+    const int32_t* ib = idx + (size_t)b * k_tot;
 
+    for (int t = tid; t < ntok; t += 256) sRow[t] = min(max(ib[j_begin + t], 0), S_max - 1);
     // softmax maximum and normaliser of every head: four lanes share a head's tiles and merge
     // them in a fixed order
     {
@@ -82,49 +85,82 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
     float2 mz[2];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) mz[mb] = sMZ[mb * 32 + l32];
-    const T* vbase = Vc + (size_t)b * S_max * r + col;
-    const int32_t* ib = idx + (size_t)b * k_tot;
-    T* Thi_arr = Tfin;
-    T* Tlo_arr = Tfin + (size_t)B * H * r;
 
-    f32x16 acc[2];
+    f32x16 acc[2][2];  // [head block][column block]
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
 
-    // every wave takes every fourth 64-token step of the range; weights past the selected
-    // tokens are zero, so a ragged last step only has to read valid rows
-    const int n_steps = (j_end - j_begin + kPvTJ - 1) / kPvTJ;
-    for (int step = wave; step < n_steps; step += 4) {
-        const int j0 = j_begin + step * kPvTJ;  // multiple of 64
-        int rows[NKG][VEC];
+    const unsigned char* vbytes = reinterpret_cast<const unsigned char*>(Vc + (size_t)b * S_max * r + col0);
+    const size_t row_bytes = (size_t)r * ES;
+    constexpr int NKQ = (NKG + 3) / 4;       // MFMA groups per wave per step
+    u32x4 R[NPC];
+    f32x4 X[NKQ][2][VEC / 4];                // this lane's logits of the step, fetched a step ahead
+    auto g_load = [&](int step) {
 #pragma unroll
-        for (int ks = 0; ks < NKG; ++ks)
+        for (int i = 0; i < NPC; ++i) {
+            const int q = tid + 256 * i, jj = q / PPR, pc = q % PPR;
+            // tokens past the range re-read its last row; their weights are zero
+            const int row = sRow[min(step * kPvTJ + jj, ntok - 1)];
+            R[i] = ld16(vbytes + (size_t)row * row_bytes + pc * 16);
+        }
 #pragma unroll
-            for (int t = 0; t < VEC; ++t) {
-                int j = min(j0 + ks * KG + hi * VEC + t, n - 1);
-                rows[ks][t] = min(max(ib[j], 0), S_max - 1);
-            }
-        u32x4 ah[NKG][2], al[NKG][2];
-#pragma unroll
-        for (int ks = 0; ks < NKG; ++ks)
+        for (int kq = 0; kq < NKQ; ++kq) {
+            const int ks = kq * 4 + wave;
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb) {
                 const int h = mb * 32 + l32;
-                const size_t off = (size_t)h * lk + j0 + ks * KG + hi * VEC;
-                const bool ok = mb < n_mb && h < H;
+                const bool ok = ks < NKG && mb < n_mb && h < H;
+                const size_t off = (size_t)h * lk + j_begin + step * kPvTJ + ks * KG + hi * VEC;
+#pragma unroll
+                for (int v = 0; v < VEC / 4; ++v)
+                    X[kq][mb][v] = ok ? *reinterpret_cast<const f32x4*>(lg + off + 4 * v)
+                                      : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            }
+        }
+    };
+    auto l_store = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < NPC; ++i) {
+            const int q = tid + 256 * i, jj = q / PPR, pc = q % PPR;
+            unsigned char* dst = sVt[buf] + (size_t)(pc * VEC) * PITCH + jj * ES;
+            const uint32_t w[4] = {R[i].x, R[i].y, R[i].z, R[i].w};
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                if constexpr (kSplit)
+                    *reinterpret_cast<uint16_t*>(dst + (size_t)e * PITCH) = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+                else
+                    *reinterpret_cast<uint32_t*>(dst + (size_t)e * PITCH) = w[e];
+            }
+        }
+    };
+
+    const int n_steps = (ntok + kPvTJ - 1) / kPvTJ;
+    if (n_steps > 0) g_load(0);
+    for (int step = 0; step < n_steps; ++step) {
+        const int buf = step & 1;
+        l_store(buf);
+        // softmax weights of this step from the logits fetched a step ahead
+        const int j0 = j_begin + step * kPvTJ;
+        u32x4 ah[NKQ][2], al[NKQ][2];
+#pragma unroll
+        for (int kq = 0; kq < NKQ; ++kq) {
+            const int tok = (kq * 4 + wave) * KG + hi * VEC;  // first of this lane's VEC tokens within the step
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) {
                 float pj[VEC];
 #pragma unroll
                 for (int v = 0; v < VEC; v += 4) {
-                    const f32x4 x = ok ? *reinterpret_cast<const f32x4*>(lg + off + v)
-                                       : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-                    // slots past the selected tokens carry no weight (their logits may be unwritten)
-                    const int jt = j0 + ks * KG + hi * VEC + v;
-                    pj[v] = jt < n ? __expf(x.x - mz[mb].x) * mz[mb].y : 0.f;
-                    pj[v + 1] = jt + 1 < n ? __expf(x.y - mz[mb].x) * mz[mb].y : 0.f;
-                    pj[v + 2] = jt + 2 < n ? __expf(x.z - mz[mb].x) * mz[mb].y : 0.f;
-                    pj[v + 3] = jt + 3 < n ? __expf(x.w - mz[mb].x) * mz[mb].y : 0.f;
+                    const f32x4 x = X[kq][mb][v / 4];
+                    // slots past the range carry no weight (their logits may be unwritten)
+                    const int jt = j0 + tok + v;
+                    pj[v] = jt < j_end ? __expf(x.x - mz[mb].x) * mz[mb].y : 0.f;
+                    pj[v + 1] = jt + 1 < j_end ? __expf(x.y - mz[mb].x) * mz[mb].y : 0.f;
+                    pj[v + 2] = jt + 2 < j_end ? __expf(x.z - mz[mb].x) * mz[mb].y : 0.f;
+                    pj[v + 3] = jt + 3 < j_end ? __expf(x.w - mz[mb].x) * mz[mb].y : 0.f;
                 }
                 if constexpr (kSplit) {
                     uint32_t ph[VEC], pl[VEC];
@@ -134,63 +170,62 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
                         ph[v] = hb;
                         pl[v] = f32_to_bf16(pj[v] - bf16_to_f32(hb));
                     }
-                    ah[ks][mb] = u32x4{ph[0] | (ph[1] << 16), ph[2] | (ph[3] << 16), ph[4] | (ph[5] << 16),
+                    ah[kq][mb] = u32x4{ph[0] | (ph[1] << 16), ph[2] | (ph[3] << 16), ph[4] | (ph[5] << 16),
                                        ph[6] | (ph[7] << 16)};
-                    al[ks][mb] = u32x4{pl[0] | (pl[1] << 16), pl[2] | (pl[3] << 16), pl[4] | (pl[5] << 16),
+                    al[kq][mb] = u32x4{pl[0] | (pl[1] << 16), pl[2] | (pl[3] << 16), pl[4] | (pl[5] << 16),
                                        pl[6] | (pl[7] << 16)};
                 } else {
-                    ah[ks][mb] = u32x4{__float_as_uint(pj[0]), __float_as_uint(pj[1]), __float_as_uint(pj[2]),
+                    ah[kq][mb] = u32x4{__float_as_uint(pj[0]), __float_as_uint(pj[1]), __float_as_uint(pj[2]),
                                        __float_as_uint(pj[3])};
                 }
             }
-        u32x4 vfrag[NKG];
+        }
+        if (step + 1 < n_steps) g_load(step + 1);
+        __syncthreads();  // tile `buf` complete; the other tile was last read a barrier ago
 #pragma unroll
-        for (int ks = 0; ks < NKG; ++ks) {
-            if constexpr (kSplit) {
-                uint32_t e[8];
+        for (int kq = 0; kq < NKQ; ++kq) {
+            const int ks = kq * 4 + wave;
+            if (ks < NKG) {  // uniform
+                const int tok = ks * KG + hi * VEC;
 #pragma unroll
-                for (int t = 0; t < 8; ++t) e[t] = vbase[(size_t)rows[ks][t] * r];
-                vfrag[ks] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16),
-                                  e[6] | (e[7] << 16)};
-            } else {
-                float e[4];
+                for (int nb = 0; nb < 2; ++nb) {
+                    const unsigned char* src = sVt[buf] + (size_t)(nb * 32 + l32) * PITCH + tok * ES;
+                    const uint2 lo8 = *reinterpret_cast<const uint2*>(src);
+                    const uint2 hi8 = *reinterpret_cast<const uint2*>(src + 8);
+                    const u32x4 vf = u32x4{lo8.x, lo8.y, hi8.x, hi8.y};
 #pragma unroll
-                for (int t = 0; t < 4; ++t) e[t] = vbase[(size_t)rows[ks][t] * r];
-                vfrag[ks] = u32x4{__float_as_uint(e[0]), __float_as_uint(e[1]), __float_as_uint(e[2]),
-                                  __float_as_uint(e[3])};
+                    for (int mb = 0; mb < 2; ++mb) {
+                        if (mb < n_mb) {
+                            mma_op<T>::run(ah[kq][mb], vf, acc[mb][nb]);
+                            if constexpr (kSplit) mma_op<T>::run(al[kq][mb], vf, acc[mb][nb]);
+                        }
+                    }
+                }
             }
         }
-#pragma unroll
-        for (int ks = 0; ks < NKG; ++ks)
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
-                if (mb < n_mb) {
-                    mma_op<T>::run(ah[ks][mb], vfrag[ks], acc[mb]);
-                    if constexpr (kSplit) mma_op<T>::run(al[ks][mb], vfrag[ks], acc[mb]);
-                }
-            }
     }
 
-    // add the four waves' sums in wave order; acc[mb][4a+c] is head mb*32+8a+4hi+c, column l32
-    if (wave > 0) {
+    // add the four waves' sums in wave order, one column block at a time; every wave finishes a
+    // quarter of the heads.  acc[mb][nb][4a+c] is head mb*32+8a+4hi+c, column nb*32+l32
+    float* out_t = Tpart + (((size_t)tr * B + b) * H) * r;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        __syncthreads();
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) red[wave - 1][lane][mb * 16 + v] = acc[mb][v];
-    }
-    __syncthreads();
-    if (wave == 0) {
+            for (int v = 0; v < 16; ++v) red[wave][lane][mb * 16 + v] = acc[mb][nb][v];
+        __syncthreads();
+        const int col = col0 + nb * 32 + l32;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int h = mb * 32 + (v >> 2) * 8 + hi * 4 + (v & 3);
-                if (h < H) {
-                    float t = acc[mb][v] + red[0][lane][mb * 16 + v] + red[1][lane][mb * 16 + v] +
-                              red[2][lane][mb * 16 + v];
-                    if (n_tr == 1) store_split<T>(Thi_arr, Tlo_arr, ((size_t)b * H + h) * r + col, t);
-                    else Tpart[(((size_t)tr * B + b) * H + h) * r + col] = t;
-                }
+            for (int c = 0; c < 4; ++c) {
+                const int v = wave * 4 + c;  // a = wave
+                const int h = mb * 32 + wave * 8 + hi * 4 + c;
+                if (h < H)
+                    out_t[(size_t)h * r + col] = ((red[0][lane][mb * 16 + v] + red[1][lane][mb * 16 + v]) +
+                                                  red[2][lane][mb * 16 + v]) + red[3][lane][mb * 16 + v];
             }
     }
 }
@@ -198,16 +233,16 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
 // ---------------------------------------------------------------------------------
 // output projection: y[(b,h), c] = sum_i T[(b,h), i] U_v[g*128 + c, i]
 //
-// One workgroup per (KV head, 16 output channels): 8 x H_kv workgroups, so that the single
-// pass over U_v is spread over the whole chip.  16x16 MFMA tiles: rows are the (sequence,
+// One workgroup per (KV head, 16 output channels, tile of 16 rows): 8 x H_kv x ceil(B*G/16)
+// workgroups, so that the pass over U_v is spread over the whole chip.  16x16 MFMA tiles: rows are the (sequence,
 // head of the group) pairs, columns the channels; the latent axis is split over the four
 // waves, every wave issuing all of its loads as one batch.
 // ---------------------------------------------------------------------------------
 constexpr int kOutBatch = 8;  // latent steps of loads kept in flight per round
 
 template <typename T>
-__global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ Uv, const T* __restrict__ Tfin,
-                                                         const float* __restrict__ Tpart, T* __restrict__ out,
+__global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ Uv, const float* __restrict__ Tpart,
+                                                         T* __restrict__ out,
                                                          int B, int r, int H, int H_kv, int n_tr)
 {
     constexpr int VEC = elem<T>::vec;
@@ -222,11 +257,10 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
     const int n_rows = B * G;  // (sequence, head of this group) pairs
     const int nks = r / KS;
     const T* urow = Uv + ((size_t)g * kHeadDim + cb * 16 + l16) * r + kg * VEC;
-    const T* Thi_arr = Tfin;
-    const T* Tlo_arr = Tfin + (size_t)B * H * r;
     const size_t tstride = (size_t)B * H * r;
 
-    for (int row0 = 0; row0 < n_rows; row0 += 16) {
+    {
+        const int row0 = blockIdx.z * 16;  // this workgroup's tile of 16 rows
         const int row = row0 + l16;
         const bool row_ok = row < n_rows;
         const int bb = row_ok ? row / G : 0, h = row_ok ? g * G + row % G : 0;
@@ -234,58 +268,56 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
         f32x4v acc = {0.f, 0.f, 0.f, 0.f};
         for (int ks0 = wave; ks0 < nks; ks0 += 4 * kOutBatch) {  // this wave: ks0, ks0+4, ...
             u32x4 bf[kOutBatch], ah[kOutBatch], al[kOutBatch];
+            float tm[kOutBatch][VEC];  // T of this lane's row: the token ranges' partial sums, added in range order
 #pragma unroll
             for (int u = 0; u < kOutBatch; ++u) {
                 const int ks = ks0 + 4 * u;
-                const bool ok = ks < nks;
-                const int i0 = ks * KS;
-                bf[u] = ok ? ld16(urow + i0) : u32x4{0, 0, 0, 0};
-                ah[u] = u32x4{0, 0, 0, 0};
-                al[u] = u32x4{0, 0, 0, 0};
-                if (ok && row_ok) {
-                    if (n_tr == 1) {
-                        ah[u] = ld16(Thi_arr + trow + i0);
-                        if constexpr (kSplit) al[u] = ld16(Tlo_arr + trow + i0);
-                    } else {
-                        // several token ranges: add their fp32 partial sums in range order, then split
-                        float tm[VEC];
+                bf[u] = ks < nks ? ld16(urow + ks * KS) : u32x4{0, 0, 0, 0};
 #pragma unroll
-                        for (int v = 0; v < VEC; ++v) tm[v] = 0.f;
-                        for (int t0 = 0; t0 < n_tr; t0 += 4) {
-                            f32x4 x[4][VEC / 4];
+                for (int v = 0; v < VEC; ++v) tm[u][v] = 0.f;
+            }
+            // two ranges per round, the loads of all kOutBatch steps in flight together
+            for (int t0 = 0; t0 < n_tr; t0 += 2) {
+                f32x4 x[kOutBatch][2][VEC / 4];
 #pragma unroll
-                            for (int w = 0; w < 4; ++w)
+                for (int u = 0; u < kOutBatch; ++u) {
+                    const int ks = ks0 + 4 * u;
 #pragma unroll
-                                for (int v = 0; v < VEC / 4; ++v)
-                                    x[w][v] = t0 + w < n_tr
-                                                  ? *reinterpret_cast<const f32x4*>(Tpart + (size_t)(t0 + w) * tstride +
-                                                                                    trow + i0 + 4 * v)
-                                                  : f32x4{0.f, 0.f, 0.f, 0.f};
+                    for (int w = 0; w < 2; ++w)
 #pragma unroll
-                            for (int w = 0; w < 4; ++w)
+                        for (int v = 0; v < VEC / 4; ++v)
+                            x[u][w][v] = (ks < nks && row_ok && t0 + w < n_tr)
+                                             ? *reinterpret_cast<const f32x4*>(Tpart + (size_t)(t0 + w) * tstride + trow +
+                                                                               ks * KS + 4 * v)
+                                             : f32x4{0.f, 0.f, 0.f, 0.f};
+                }
 #pragma unroll
-                                for (int v = 0; v < VEC / 4; ++v) {
-                                    tm[4 * v] += x[w][v].x; tm[4 * v + 1] += x[w][v].y;
-                                    tm[4 * v + 2] += x[w][v].z; tm[4 * v + 3] += x[w][v].w;
-                                }
+                for (int u = 0; u < kOutBatch; ++u)
+#pragma unroll
+                    for (int w = 0; w < 2; ++w)
+#pragma unroll
+                        for (int v = 0; v < VEC / 4; ++v) {
+                            tm[u][4 * v] += x[u][w][v].x; tm[u][4 * v + 1] += x[u][w][v].y;
+                            tm[u][4 * v + 2] += x[u][w][v].z; tm[u][4 * v + 3] += x[u][w][v].w;
                         }
-                        if constexpr (kSplit) {
-                            uint32_t hw[8], lw[8];
+            }
 #pragma unroll
-                            for (int v = 0; v < 8; ++v) {
-                                bf16_t ph = f32_to_bf16(tm[v]);
-                                hw[v] = ph;
-                                lw[v] = f32_to_bf16(tm[v] - bf16_to_f32(ph));
-                            }
-                            ah[u] = u32x4{hw[0] | (hw[1] << 16), hw[2] | (hw[3] << 16), hw[4] | (hw[5] << 16),
-                                          hw[6] | (hw[7] << 16)};
-                            al[u] = u32x4{lw[0] | (lw[1] << 16), lw[2] | (lw[3] << 16), lw[4] | (lw[5] << 16),
-                                          lw[6] | (lw[7] << 16)};
-                        } else {
-                            ah[u] = u32x4{__float_as_uint(tm[0]), __float_as_uint(tm[1]), __float_as_uint(tm[2]),
-                                          __float_as_uint(tm[3])};
-                        }
+            for (int u = 0; u < kOutBatch; ++u) {
+                if constexpr (kSplit) {
+                    uint32_t hw[8], lw[8];
+#pragma unroll
+                    for (int v = 0; v < 8; ++v) {
+                        bf16_t ph = f32_to_bf16(tm[u][v]);
+                        hw[v] = ph;
+                        lw[v] = f32_to_bf16(tm[u][v] - bf16_to_f32(ph));
                     }
+                    ah[u] = u32x4{hw[0] | (hw[1] << 16), hw[2] | (hw[3] << 16), hw[4] | (hw[5] << 16),
+                                  hw[6] | (hw[7] << 16)};
+                    al[u] = u32x4{lw[0] | (lw[1] << 16), lw[2] | (lw[3] << 16), lw[4] | (lw[5] << 16),
+                                  lw[6] | (lw[7] << 16)};
+                } else {
+                    ah[u] = u32x4{__float_as_uint(tm[u][0]), __float_as_uint(tm[u][1]), __float_as_uint(tm[u][2]),
+                                  __float_as_uint(tm[u][3])};
                 }
             }
 #pragma unroll

@@ -29,7 +29,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Layout {  // byte offsets into the workspace
-    size_t qt, scores, idx, n_sel, logits, stats, rope, tpart, tfin, tm_part, tm_hist, tm_meta, tm_cand, total;
+    size_t qt, scores, idx, n_sel, logits, stats, rope, tpart, tm_part, tm_hist, tm_meta, tm_cand, total;
     int lk;                      // logits row stride (floats)
     int max_parts;               // token tiles per head of the logits kernel, at most
     int pv_tok_per_wg, pv_ntr;   // value-sum token ranges
@@ -114,13 +114,14 @@ Layout make_layout(const sals_desc& d)
         while (np < 8 && (d.r / 16) * np < 256 && nks % (np * 2) == 0 && nks / (np * 2) >= 4) np *= 2;
         L.proj_np = np;
     }
-    // value sum: split the selected tokens into ranges until about 256 workgroups exist
+    // value sum: split the selected tokens into ranges of whole 64-token steps (at least four steps, at
+    // most kPvMaxTok tokens) until about 256 workgroups exist
     {
         int blocks = d.r / kPvCols;
         int want = ceil_div(256, blocks * d.B);
         int n_tr = std::max(1, std::min(std::min(want, kMaxRanges), ceil_div(k_tot, 4 * kPvTJ)));
+        n_tr = std::max(n_tr, ceil_div(k_tot, kPvMaxTok));
         int tok = ceil_div(ceil_div(k_tot, n_tr), kPvTJ) * kPvTJ;
-        tok = std::max(tok, ceil_div(ceil_div(k_tot, kMaxRanges), kPvTJ) * kPvTJ);
         L.pv_tok_per_wg = tok;
         L.pv_ntr = ceil_div(k_tot, tok);
     }
@@ -135,7 +136,6 @@ Layout make_layout(const sals_desc& d)
     L.stats = take((size_t)d.B * d.H_q * L.max_parts * 8);
     L.rope = take((size_t)(d.S_max + 1) * kPairs * 8);  // positions 0 .. S_max (the query after a full cache)
     L.tpart = take((size_t)L.pv_ntr * d.B * d.H_q * d.r * 4);
-    L.tfin = take((size_t)d.B * d.H_q * d.r * 4);
     // long sequences: selection spread over 8192-score chunks
     L.tm_chunks = d.S_max > 32768 ? ceil_div(d.S_max, kTmChunk) : 0;
     if (L.tm_chunks > 0) {
@@ -261,7 +261,6 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     float2* stats = reinterpret_cast<float2*>(c->ws + L.stats);
     const float2* rope = reinterpret_cast<const float2*>(c->ws + L.rope);
     float* tpart = reinterpret_cast<float*>(c->ws + L.tpart);
-    T* tfin = reinterpret_cast<T*>(c->ws + L.tfin);
     int n_parts = 0;
     if (!c->rope_ready) {  // first use of the context: cos/sin of every cache position, ahead of the logits
         const size_t n = (size_t)(d.S_max + 1) * kPairs;
@@ -327,14 +326,15 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     {
         ProfScope ps(c, SALS_K_ATTEND_PV, st);
         hipLaunchKernelGGL((attend_pv_kernel<T>), dim3(d.r / kPvCols, L.pv_ntr, d.B), dim3(256), 0, st,
-                           static_cast<const T*>(Vc), idx, n_sel, logits, stats, n_parts, tpart, tfin, d.B, d.S_max,
-                           d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr);
+                           static_cast<const T*>(Vc), idx, n_sel, logits, stats, n_parts, tpart, d.B, d.S_max,
+                           d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg);
     }
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     {
         ProfScope ps(c, SALS_K_ATTEND_OUT, st);
-        hipLaunchKernelGGL((attend_out_kernel<T>), dim3(kHeadDim / 16, d.H_kv), dim3(256), 0, st,
-                           w_section<T>(c, W, 3), tfin, tpart, static_cast<T*>(out), d.B, d.r, d.H_q, d.H_kv,
+        hipLaunchKernelGGL((attend_out_kernel<T>), dim3(kHeadDim / 16, d.H_kv, ceil_div(d.B * (d.H_q / d.H_kv), 16)),
+                           dim3(256), 0, st,
+                           w_section<T>(c, W, 3), tpart, static_cast<T*>(out), d.B, d.r, d.H_q, d.H_kv,
                            L.pv_ntr);
     }
     return launch_status();
