@@ -24,7 +24,7 @@ namespace sals {
 constexpr int kPvTJ = 64;          // tokens per step
 constexpr int kPvCols = 64;        // latent columns per workgroup
 constexpr int kPvMaxHeads = 64;    // H_q limit of these kernels
-constexpr int kMaxRanges = 32;     // token ranges per sequence
+constexpr int kMaxRanges = 8;      // token ranges per sequence (the output projection adds them up)
 constexpr int kPvMaxTok = 4096;    // tokens per workgroup, at most (their cache rows sit in LDS)
 
 template <typename T>
@@ -75,7 +75,14 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
         float2 st = make_float2(-INFINITY, 0.f);
         if (h < H) {
             const float2* sp = stats + ((size_t)b * H + h) * n_parts;
-            for (int t = sub; t < n_parts; t += 4) st = stat_merge(st, sp[t]);
+            for (int t0 = sub; t0 < n_parts; t0 += 32) {  // eight loads in flight per round
+                float2 e[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    e[u] = t0 + 4 * u < n_parts ? sp[t0 + 4 * u] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) st = stat_merge(st, e[u]);
+            }
         }
         st = stat_merge(st, make_float2(__shfl_xor(st.x, 1, kWave), __shfl_xor(st.y, 1, kWave)));
         st = stat_merge(st, make_float2(__shfl_xor(st.x, 2, kWave), __shfl_xor(st.y, 2, kWave)));
@@ -97,15 +104,16 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
     const unsigned char* vbytes = reinterpret_cast<const unsigned char*>(Vc + (size_t)b * S_max * r + col0);
     const size_t row_bytes = (size_t)r * ES;
     constexpr int NKQ = (NKG + 3) / 4;       // MFMA groups per wave per step
-    u32x4 R[NPC];
-    f32x4 X[NKQ][2][VEC / 4];                // this lane's logits of the step, fetched a step ahead
-    auto g_load = [&](int step) {
+    // what a step needs from global memory: the gathered row pieces and this lane's logits; two
+    // such sets alternate, so the loads run two steps ahead
+    struct Stage { u32x4 R[NPC]; f32x4 X[NKQ][2][VEC / 4]; };
+    auto g_load = [&](Stage& S, int step) {
 #pragma unroll
         for (int i = 0; i < NPC; ++i) {
             const int q = tid + 256 * i, jj = q / PPR, pc = q % PPR;
             // tokens past the range re-read its last row; their weights are zero
             const int row = sRow[min(step * kPvTJ + jj, ntok - 1)];
-            R[i] = ld16(vbytes + (size_t)row * row_bytes + pc * 16);
+            S.R[i] = ld16(vbytes + (size_t)row * row_bytes + pc * 16);
         }
 #pragma unroll
         for (int kq = 0; kq < NKQ; ++kq) {
@@ -117,17 +125,17 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
                 const size_t off = (size_t)h * lk + j_begin + step * kPvTJ + ks * KG + hi * VEC;
 #pragma unroll
                 for (int v = 0; v < VEC / 4; ++v)
-                    X[kq][mb][v] = ok ? *reinterpret_cast<const f32x4*>(lg + off + 4 * v)
+                    S.X[kq][mb][v] = ok ? *reinterpret_cast<const f32x4*>(lg + off + 4 * v)
                                       : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
             }
         }
     };
-    auto l_store = [&](int buf) {
+    auto l_store = [&](const Stage& S, int buf) {
 #pragma unroll
         for (int i = 0; i < NPC; ++i) {
             const int q = tid + 256 * i, jj = q / PPR, pc = q % PPR;
             unsigned char* dst = sVt[buf] + (size_t)(pc * VEC) * PITCH + jj * ES;
-            const uint32_t w[4] = {R[i].x, R[i].y, R[i].z, R[i].w};
+            const uint32_t w[4] = {S.R[i].x, S.R[i].y, S.R[i].z, S.R[i].w};
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
                 if constexpr (kSplit)
@@ -139,10 +147,9 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
     };
 
     const int n_steps = (ntok + kPvTJ - 1) / kPvTJ;
-    if (n_steps > 0) g_load(0);
-    for (int step = 0; step < n_steps; ++step) {
+    auto do_step = [&](Stage& S, int step) {
         const int buf = step & 1;
-        l_store(buf);
+        l_store(S, buf);
         // softmax weights of this step from the logits fetched a step ahead
         const int j0 = j_begin + step * kPvTJ;
         u32x4 ah[NKQ][2], al[NKQ][2];
@@ -154,7 +161,7 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
                 float pj[VEC];
 #pragma unroll
                 for (int v = 0; v < VEC; v += 4) {
-                    const f32x4 x = X[kq][mb][v / 4];
+                    const f32x4 x = S.X[kq][mb][v / 4];
                     // slots past the range carry no weight (their logits may be unwritten)
                     const int jt = j0 + tok + v;
                     pj[v] = jt < j_end ? __expf(x.x - mz[mb].x) * mz[mb].y : 0.f;
@@ -180,7 +187,7 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
                 }
             }
         }
-        if (step + 1 < n_steps) g_load(step + 1);
+        if (step + 2 < n_steps) g_load(S, step + 2);
         __syncthreads();  // tile `buf` complete; the other tile was last read a barrier ago
 #pragma unroll
         for (int kq = 0; kq < NKQ; ++kq) {
@@ -203,6 +210,13 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
                 }
             }
         }
+    };
+    Stage S0, S1;
+    if (n_steps > 0) g_load(S0, 0);
+    if (n_steps > 1) g_load(S1, 1);
+    for (int step = 0; step < n_steps; step += 2) {
+        do_step(S0, step);
+        if (step + 1 < n_steps) do_step(S1, step + 1);
     }
 
     // add the four waves' sums in wave order, one column block at a time; every wave finishes a

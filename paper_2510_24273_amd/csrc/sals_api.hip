@@ -114,12 +114,12 @@ Layout make_layout(const sals_desc& d)
         while (np < 8 && (d.r / 16) * np < 256 && nks % (np * 2) == 0 && nks / (np * 2) >= 4) np *= 2;
         L.proj_np = np;
     }
-    // value sum: split the selected tokens into ranges of whole 64-token steps (at least four steps, at
+    // value sum: split the selected tokens into ranges of whole 64-token steps (at least two steps, at
     // most kPvMaxTok tokens) until about 256 workgroups exist
     {
         int blocks = d.r / kPvCols;
         int want = ceil_div(256, blocks * d.B);
-        int n_tr = std::max(1, std::min(std::min(want, kMaxRanges), ceil_div(k_tot, 4 * kPvTJ)));
+        int n_tr = std::max(1, std::min(std::min(want, kMaxRanges), ceil_div(k_tot, 2 * kPvTJ)));
         n_tr = std::max(n_tr, ceil_div(k_tot, kPvMaxTok));
         int tok = ceil_div(ceil_div(k_tot, n_tr), kPvTJ) * kPvTJ;
         L.pv_tok_per_wg = tok;
