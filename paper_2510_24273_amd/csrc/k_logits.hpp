@@ -52,7 +52,7 @@ template <int HEADS, int NTG, int NB> struct logits_cfg {
 };
 
 template <typename T, int HEADS, int NTG, int NB>
-__global__ __launch_bounds__(64 * HEADS * NTG, 2) void attend_logits_kernel(
+__global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void attend_logits_kernel(
     const T* __restrict__ Kc, const T* __restrict__ UkP, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ n_sel, const T* __restrict__ q, const int32_t* __restrict__ q_pos,
     const float2* __restrict__ rope, InvFreq inv,
@@ -192,6 +192,20 @@ __global__ __launch_bounds__(64 * HEADS * NTG, 2) void attend_logits_kernel(
 #pragma unroll
         for (int i = 0; i < NBP; ++i) *reinterpret_cast<u32x4*>(base + b_dst(i)) = R.b[i];
     };
+    // cos/sin rows of the tile's tokens for the epilogue, 128 bytes (16 pairs) per token and pass
+    const unsigned char* rope_b = reinterpret_cast<const unsigned char*>(rope) + (tid & 7) * 16;
+    size_t cs_off[NCS];  // byte offset of this thread's token rows in the table
+    u32x4 CR[NCS];
+    auto cs_load = [&](int ps) {
+#pragma unroll
+        for (int i = 0; i < NCS; ++i) CR[i] = ld16(rope_b + cs_off[i] + ps * kLgChunk);
+    };
+    auto cs_store = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < NCS; ++i)
+            *reinterpret_cast<u32x4*>(lds + (size_t)buf * C::CS_BYTES + swz((tid + i * NT) >> 3, tid & 7)) = CR[i];
+    };
+
     // MFMA fragments of one half step (32 latent bytes): NB token blocks, 4 head-dim blocks
     struct Frags { u32x4 b[NB]; u32x4 a[4]; };
     auto read_frags = [&](Frags& F, int buf, int ks) {
@@ -218,11 +232,17 @@ __global__ __launch_bounds__(64 * HEADS * NTG, 2) void attend_logits_kernel(
     {
         Regs R;
         Frags F0, F1;
-        g_load(R, 0);
-        rotate_query();
-        l_store(R, 0);
-        g_load(R, min(1, nkc - 1));
-        l_store(R, 1);
+        {
+            Regs R1;  // second set for the fill only: the first two steps are requested together
+            g_load(R, 0);
+            g_load(R1, min(1, nkc - 1));
+            rotate_query();  // (its barrier also publishes sPos)
+#pragma unroll
+            for (int i = 0; i < NCS; ++i) cs_off[i] = (size_t)sPos[(tid + i * NT) >> 3] * (kPairs * sizeof(float2));
+            cs_load(0);      // cos/sin of the first epilogue pass: in flight during the whole main loop
+            l_store(R, 0);
+            l_store(R1, 1);
+        }
         g_load(R, min(2, nkc - 1));
         __syncthreads();
         read_frags(F0, 0, 0);
@@ -270,21 +290,6 @@ __global__ __launch_bounds__(64 * HEADS * NTG, 2) void attend_logits_kernel(
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) dot[m][nb] = 0.f;
     {
-        const unsigned char* rope_b = reinterpret_cast<const unsigned char*>(rope) + (tid & 7) * 16;
-        size_t cs_off[NCS];  // byte offset of this thread's token rows in the table
-#pragma unroll
-        for (int i = 0; i < NCS; ++i) cs_off[i] = (size_t)sPos[(tid + i * NT) >> 3] * (kPairs * sizeof(float2));
-        u32x4 CR[NCS];
-        auto cs_load = [&](int ps) {
-#pragma unroll
-            for (int i = 0; i < NCS; ++i) CR[i] = ld16(rope_b + cs_off[i] + ps * kLgChunk);
-        };
-        auto cs_store = [&](int buf) {
-#pragma unroll
-            for (int i = 0; i < NCS; ++i)
-                *reinterpret_cast<u32x4*>(lds + (size_t)buf * C::CS_BYTES + swz((tid + i * NT) >> 3, tid & 7)) = CR[i];
-        };
-        cs_load(0);
         cs_store(0);
         cs_load(1);
         __syncthreads();
