@@ -255,25 +255,29 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
             read_frags(F0, nxt, 0);
             mma_frags(F1);
             // issue order: LDS and global memory instructions between the MFMAs that cover them
-            if constexpr (NB == 2) {
+            {
+                constexpr int NM = 4 * NB;            // MFMAs per half step
+                constexpr int NR = 4 + NB;            // fragment reads per half step
+                constexpr int NW = NA + NBP;          // staging writes = global loads per step
+                static_assert(NR <= NM && NW < NM, "not enough MFMAs to cover the memory instructions");
 #pragma unroll
-                for (int i = 0; i < 6; ++i) {
+                for (int i = 0; i < NR; ++i) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA (first half step)
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read (second half step)
                 }
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                if constexpr (NM > NR) __builtin_amdgcn_sched_group_barrier(0x008, NM - NR, 0);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
+                for (int i = 0; i < NW; ++i) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA (second half step)
-                    __builtin_amdgcn_sched_group_barrier(0x200, NA + NBP >= 4 ? (NA + NBP) / 4 : 1, 0);  // LDS writes (step + 2)
-                    __builtin_amdgcn_sched_group_barrier(0x020, NA + NBP >= 4 ? (NA + NBP) / 4 : 1, 0);  // global loads (step + 3)
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS write (step + 2)
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load (step + 3)
                 }
+                constexpr int REM = NM - NW, RPM = (NR + REM - 1) / REM;
 #pragma unroll
-                for (int i = 0; i < 3; ++i) {
+                for (int i = 0; i < REM; ++i) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // LDS reads (next step, first half)
+                    __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);  // LDS reads (next step, first half)
                 }
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             }
             __syncthreads();
             const int t = cur; cur = nxt; nxt = third; third = t;
