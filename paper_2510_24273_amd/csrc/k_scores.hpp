@@ -37,7 +37,9 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restri
 
     auto load_row = [&](int j0, u32x4* piece) {
         const int j = j0 + wave * 4 + quad;
-        const bool live = j < S;
+        // every row below S_max is readable, so the loads do not wait for the sequence length;
+        // rows past it are overwritten with -inf when the score is stored
+        const bool live = j < S_max;
 #pragma unroll
         for (int n = 0; n < NCH; ++n) {
             int p = li + 16 * n;

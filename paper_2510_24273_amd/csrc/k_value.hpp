@@ -67,7 +67,12 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
     const float* lg = logits + (size_t)b * H * lk;
     const int32_t* ib = idx + (size_t)b * k_tot;
 
-    for (int t = tid; t < ntok; t += 256) sRow[t] = min(max(ib[j_begin + t], 0), S_max - 1);
+    // (the index loads only depend on the nominal range, so they are in flight together with n)
+    for (int t = tid; t < tok_per_wg; t += 256) {
+        const int j = tr * tok_per_wg + t;
+        const int v = j < k_tot ? ib[j] : 0;
+        if (t < ntok) sRow[t] = min(max(v, 0), S_max - 1);
+    }
     // softmax maximum and normaliser of every head: four lanes share a head's tiles and merge
     // them in a fixed order
     {
