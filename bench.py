@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer buffer sets (0 = workload default)")
-    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5",
+    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg2_rhalf,cfg4_rhalf",
                     help="other configurations reported under 'extra' (comma list, '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
@@ -206,7 +206,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
-    w = synth.CONFIGS[a.workload]
+    w = synth.lookup(a.workload)
     n_layers = a.layers or w.n_layers
     if n_layers == 1:   # single-layer configs: rotate enough distinct sets to defeat the 256 MB LLC
         per = roofline.algorithmic_bytes(w) + w.r * w.D_kv * w.esize
@@ -251,7 +251,7 @@ def main():
     torch.cuda.empty_cache()
     extra = {}
     for name in [x for x in a.extras.split(",") if x and x != a.workload]:
-        we = synth.CONFIGS[name]
+        we = synth.lookup(name)
         per = roofline.algorithmic_bytes(we) + we.r * we.D_kv * we.esize
         nl = max(2, min(8, int(600e6 // per) + 1))
         log(f"[bench] extra {we.name}: {nl} layer sets")

@@ -5,6 +5,8 @@
 
 namespace sals {
 
+constexpr int kXcds = 8;       // accelerator dies, workgroups are dealt to them round-robin
+
 constexpr int kWave = 64;
 constexpr int kHeadDim = 128;        // head width the kernels are written for
 constexpr int kPairs = kHeadDim / 2; // RoPE pairs per head

@@ -27,7 +27,6 @@ namespace sals {
 
 constexpr int kLgChunk = 128;  // bytes per row of a [rows][128 B] swizzled LDS tile
 constexpr int kLgStep = 64;    // bytes of the latent axis per pipeline step (= one packed U_k block)
-constexpr int kXcds = 8;       // accelerator dies, workgroups are dealt to them round-robin
 
 // LDS tiles are read and written 16 bytes per lane; such an access is conflict-free when each
 // group of 16 consecutive lanes covers all 16 bank groups (address / 16 mod 16).  A fragment read

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
                                                         const float2* __restrict__ stats, int n_parts,
                                                         float* __restrict__ Tpart,
                                                         int B, int S_max, int r, int H, int k_tot, int lk,
-                                                        int tok_per_wg)
+                                                        int tok_per_wg, int n_tr)
 {
     constexpr int ES = (int)sizeof(T);
     constexpr int VEC = elem<T>::vec;        // tokens per lane per MFMA group = elements per 16 bytes
@@ -56,7 +56,15 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
     __shared__ int sRow[kPvMaxTok];          // cache row of every token of the range
     __shared__ float2 sMZ[kPvMaxHeads];      // per head: softmax maximum, 1 / normaliser
 
-    const int b = blockIdx.z, tr = blockIdx.y, cb = blockIdx.x;
+    // Work items are ordered (sequence, token range, column block) with the column block fastest.
+    // Workgroup ids are dealt round-robin to the XCDs; the map below gives each XCD a contiguous run of
+    // the list, so the column blocks of one token range (same indices, logits and statistics, adjacent
+    // 128-byte pieces of the same cache rows) meet in one L2.
+    const int n_cb = r / kPvCols;
+    const int total = n_cb * n_tr * B;  // = gridDim.x
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds, qn = total / kXcds, rem = total % kXcds;
+    const int item = (xcd < rem ? xcd * (qn + 1) : rem * (qn + 1) + (xcd - rem) * qn) + slot;
+    const int cb = item % n_cb, tr = (item / n_cb) % n_tr, b = item / (n_cb * n_tr);
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
     const int n = n_sel[b];
@@ -269,7 +277,9 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
     constexpr bool kSplit = sizeof(T) == 2;
     __shared__ __attribute__((aligned(16))) float red[3][64][5];
 
-    const int g = blockIdx.y, cb = blockIdx.x;
+    // KV head fastest: workgroup ids are dealt round-robin to the XCDs, so the eight channel blocks of
+    // a head (which read the same value sums) share one XCD's L2 whenever H_kv is a multiple of 8
+    const int g = blockIdx.x, cb = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, kg = lane >> 4;
     const int G = H / H_kv;

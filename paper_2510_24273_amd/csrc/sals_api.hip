@@ -325,14 +325,15 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     }
     {
         ProfScope ps(c, SALS_K_ATTEND_PV, st);
-        hipLaunchKernelGGL((attend_pv_kernel<T>), dim3(d.r / kPvCols, L.pv_ntr, d.B), dim3(256), 0, st,
+        const int n_items = (d.r / kPvCols) * L.pv_ntr * d.B;
+        hipLaunchKernelGGL((attend_pv_kernel<T>), dim3(n_items), dim3(256), 0, st,
                            static_cast<const T*>(Vc), idx, n_sel, logits, stats, n_parts, tpart, d.B, d.S_max,
-                           d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg);
+                           d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr);
     }
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     {
         ProfScope ps(c, SALS_K_ATTEND_OUT, st);
-        hipLaunchKernelGGL((attend_out_kernel<T>), dim3(kHeadDim / 16, d.H_kv, ceil_div(d.B * (d.H_q / d.H_kv), 16)),
+        hipLaunchKernelGGL((attend_out_kernel<T>), dim3(d.H_kv, kHeadDim / 16, ceil_div(d.B * (d.H_q / d.H_kv), 16)),
                            dim3(256), 0, st,
                            w_section<T>(c, W, 3), tpart, static_cast<T*>(out), d.B, d.r, d.H_q, d.H_kv,
                            L.pv_ntr);

@@ -80,6 +80,19 @@ def shrink(w: Workload, **kw) -> Workload:
     return replace(w, **kw)
 
 
+# The paper's own scoring rank r* = r/2 (Sec. 4.3, Sec. 5.1) on the measured shapes: same inputs,
+# scores taken over the leading half of the latent coordinates only.
+VARIANTS = {
+    name + "_rhalf": replace(w, name=w.name + "_rscore" + str(w.r // 2), r_score=w.r // 2)
+    for name, w in CONFIGS.items() if name in ("cfg2", "cfg3a", "cfg4")
+}
+
+
+def lookup(name: str) -> Workload:
+    """A measured configuration or one of its variants, by short name."""
+    return CONFIGS[name] if name in CONFIGS else VARIANTS[name]
+
+
 # ---- storage rounding ------------------------------------------------------
 
 def to_bf16_bits(x: np.ndarray) -> np.ndarray:
