@@ -5,7 +5,10 @@ Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 
 Every function takes and returns float64 numpy arrays (int32 for indices) and
 forwards to the plain C implementation in ``sals_oracle.c``, one call per step
-of Algorithm 1 of the paper (arXiv 2510.24273).
+of Algorithm 1 of the paper (arXiv 2510.24273).  The quantised value cache of
+Sec. 5.1 (quantise, de-quantise, byte packing, attention over it) is plain
+numpy at the end of this file; its pins are in ``tests/test_oracle_qv_pins.py``,
+those of everything else in ``tests/test_oracle_pins.py``.
 """
 from __future__ import annotations
 
@@ -183,3 +186,92 @@ def decode_step(q, q_pos, Kc, Vc, Uk, Uv, H_kv, top_k, theta, r_score=None, n_si
                                     s.ctypes.data_as(_f64p), idx.ctypes.data_as(_i32p),
                                     ctypes.byref(n_sel))
     return {"y": y, "qt": qt, "s": s[:S], "idx": idx[: n_sel.value].copy()}
+
+
+# ---------------------------------------------------------------------------
+# Quantised full-rank value cache (Sec. 5.1: values are not projected; they are
+# stored with channel-wise group quantisation, 4 bit at the 25 % setting and
+# 2 bit at 12.5 %, following KIVI's asymmetric uniform scheme; Algorithm 1's
+# V-hat).  Plain numpy.  Reading taken where the paper is silent: a token's
+# D_kv channels are cut into groups of 32 consecutive channels; a group stores
+# its minimum (zero point) and step (scale) in the storage type and one
+# unsigned code per channel:
+#     scale = (max - min) / (2^bits - 1),  code = round((v - min) / scale),
+#     v^    = min + scale * code.
+# The code is an integer decided by floating point, so it is decided in the
+# precision the kernels use: float32, IEEE subtraction and division, ties to
+# even, with the *stored* (rounded) scale.  Everything downstream is float64.
+# ---------------------------------------------------------------------------
+QV_GROUP = 32
+
+
+def _round_to_storage(x32, dtype):
+    """float32 array -> nearest value of the storage type, returned as float32."""
+    x32 = np.ascontiguousarray(x32, dtype=np.float32)
+    if dtype == "f32":
+        return x32
+    assert dtype == "bf16"
+    u = x32.view(np.uint32)
+    u = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+    return u.view(np.float32)
+
+
+def quantize_values(v, bits, dtype):
+    """v [n, D] (values exact in the storage type `dtype`) -> (codes uint8 [n, D],
+    scale float64 [n, D/32], zero float64 [n, D/32]); scale and zero are exact in `dtype`."""
+    v32 = np.ascontiguousarray(v, dtype=np.float32)
+    n, D = v32.shape
+    assert D % QV_GROUP == 0 and bits in (2, 4)
+    levels = np.float32((1 << bits) - 1)
+    g = v32.reshape(n, D // QV_GROUP, QV_GROUP)
+    mn, mx = g.min(axis=-1), g.max(axis=-1)
+    scale = _round_to_storage((mx - mn) / levels, dtype)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        t = np.rint((g - mn[..., None]) / scale[..., None])
+    t = np.where(scale[..., None] > 0, t, np.float32(0))
+    codes = np.clip(t, 0, levels).astype(np.uint8).reshape(n, D)
+    return codes, scale.astype(np.float64), mn.astype(np.float64)
+
+
+def dequantize_values(codes, scale, zero):
+    """codes [n, D], scale / zero [n, D/32] -> v^ [n, D] = zero + scale * code (float64)."""
+    codes = np.asarray(codes)
+    n, D = codes.shape
+    c = codes.astype(np.float64).reshape(n, D // QV_GROUP, QV_GROUP)
+    return (np.asarray(zero, dtype=np.float64)[..., None]
+            + np.asarray(scale, dtype=np.float64)[..., None] * c).reshape(n, D)
+
+
+def pack_codes(codes, bits):
+    """codes [n, D] -> bytes [n, D*bits/8]: channel c sits in byte c*bits/8 at bit (c*bits) % 8."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    per = 8 // bits
+    n, D = codes.shape
+    c = codes.reshape(n, D // per, per).astype(np.uint32)
+    out = np.zeros((n, D // per), dtype=np.uint32)
+    for i in range(per):
+        out |= c[:, :, i] << np.uint32(i * bits)
+    return out.astype(np.uint8)
+
+
+def unpack_codes(packed, bits):
+    packed = np.asarray(packed, dtype=np.uint8)
+    per = 8 // bits
+    parts = [(packed >> np.uint8(i * bits)) & np.uint8((1 << bits) - 1) for i in range(per)]
+    return np.stack(parts, axis=-1).reshape(packed.shape[0], -1)
+
+
+def sparse_attend_qv(q, q_pos, Kc, Uk, codes, scale, zero, idx, H_kv, theta, rope_style=0):
+    """Algorithm 1 from the reconstruction step on, with the paper's value path: keys are
+    reconstructed from the latent cache and rotated; values are the de-quantised rows of the
+    quantised full-rank cache (codes [S, D_kv], scale / zero [S, D_kv/32])."""
+    q = np.asarray(q, dtype=np.float64)
+    H, d = q.shape
+    idx = np.asarray(idx, dtype=np.int32)
+    n = idx.shape[0]
+    K_C = reconstruct(Kc, idx, Uk).reshape(n, H_kv, d)
+    KR = rope(K_C, idx, theta, rope_style) if n else K_C
+    qR = rope(q.reshape(1, H, d), [q_pos], theta, rope_style).reshape(H, d)
+    V_C = dequantize_values(np.asarray(codes)[idx], np.asarray(scale)[idx],
+                            np.asarray(zero)[idx]).reshape(n, H_kv, d)
+    return attend(qR, KR, V_C)
