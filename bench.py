@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer buffer sets (0 = workload default)")
-    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg2_rhalf,cfg4_rhalf",
+    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg2_rhalf,cfg4_rhalf,cfg2_qv4,cfg4_qv4",
                     help="other configurations reported under 'extra' (comma list, '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
@@ -67,6 +67,10 @@ class LayerSet:
                 self.host0 = L
             G = {k: up(v) for k, v in L.items() if hasattr(v, "dtype")}
             G["W"] = self.ctx.pack_weights(G.pop("Uk"), G.pop("Uv"))   # one-time repack, as at model load
+            if w.qv_bits:   # quantised full-rank value cache in place of the latent one
+                del G["Vc"]
+                codes, meta = synth.make_qv_cache(w, l, w.qv_bits)
+                G["Vq"], G["Vmeta"] = torch.from_numpy(codes).to(dev), up(meta)
             self.layers.append(G)
             if l % 8 == 7 or n_layers <= 4:
                 log(f"  [{w.name}] layer {l + 1}/{n_layers} generated")
@@ -75,6 +79,11 @@ class LayerSet:
         self.out = [torch.empty((w.B, w.H, w.d), dtype=odt, device=dev) for _ in range(n_layers)]
 
     def step(self):
+        if self.w.qv_bits:
+            for G, o in zip(self.layers, self.out):
+                self.ctx.decode_step_qv(G["q"], G["q_pos"], G["Kc"], G["Vq"], G["Vmeta"], self.w.qv_bits, G["W"],
+                                        G["seq_len"], o)
+            return
         for G, o in zip(self.layers, self.out):
             self.ctx.decode_step(G["q"], G["q_pos"], G["Kc"], G["Vc"], G["W"], G["seq_len"], o)
 
@@ -122,6 +131,7 @@ def kernel_table(ls, steps, roofline, wall_us_per_layer_step):
         "attend_logits": ("mfma", sf["reconstruct_k"]),
         "attend_pv": ("hbm", w.B * w.k_tot * w.r * w.esize),
         "attend_out": ("hbm", w.r * w.D_kv * w.esize),
+        "attend_qv": ("hbm", w.B * w.k_tot * (w.D_kv * max(w.qv_bits, 1) // 8 + w.D_kv // 32 * 2 * w.esize)),
     }
     raw = {name: ms * 1e3 / n for name, (ms, n) in prof.items() if n > 0}
     gap = max(0.0, (sum(raw.values()) - wall_us_per_layer_step) / max(1, len(raw)))

@@ -175,6 +175,49 @@ sals_status sals_decode_step(sals_ctx* ctx, const void* q, const int32_t* q_pos,
                              const void* Vc, const void* W, const int32_t* seq_len, void* out,
                              float* scores, int32_t* idx, int32_t* n_sel, void* hip_stream);
 
+/* ---- quantised full-rank value cache -----------------------------------------------
+ * The paper's own value path (Sec. 5.1; the quantised cache V-hat that Algorithm 1 appends
+ * to and reads in its last step): values are not projected; each token's D_kv value channels
+ * are stored with channel-wise group quantisation, `bits` = 4 (the 25 % setting) or 2
+ * (12.5 %), asymmetric and uniform as in KIVI.  Where the paper gives no detail the layout is:
+ * groups of SALS_QV_GROUP = 32 consecutive channels; per group  zero = min,
+ * scale = T((max - min) / (2^bits - 1));  per channel
+ * code = clamp(rint((v - zero) / scale), 0, 2^bits - 1)  evaluated in fp32 (IEEE division,
+ * ties to even; code 0 when scale == 0);  de-quantised value  v^ = zero + scale * code.
+ *   Vq    [B, S_max, D_kv*bits/8] bytes: channel c of a token in byte c*bits/8 at bit (c*bits) % 8
+ *   Vmeta [B, S_max, D_kv/32, 2] T     : (scale, zero) of each group
+ * The three calls mirror sals_compress_append / sals_sparse_attend / sals_decode_step with this
+ * cache in place of the latent value cache; keys, scores and selection are unchanged, and the
+ * U_v sections of `W` are not read (any [D_kv, r] array may be packed in their place). */
+enum { SALS_QV_GROUP = 32 };
+
+/* Bytes per token of the code array and of the (scale, zero) array.  Host-only. */
+sals_status sals_qv_row_bytes(const sals_desc* desc, int bits, size_t* code_bytes,
+                              size_t* meta_bytes);
+
+/* Algorithm 1, projection and append steps:  k~ = Uk^T k_new to row seq_len[b] of Kc[b]; the
+ * quantised v_new to row seq_len[b] of Vq[b] / Vmeta[b]; then seq_len[b] += 1.  A sequence
+ * whose cache is full is left untouched.
+ *   k_new, v_new [B, D_kv] T;  Kc [B,S_max,r] T in/out;  Vq, Vmeta in/out;  seq_len [B] in/out */
+sals_status sals_compress_append_qv(sals_ctx* ctx, const void* k_new, const void* v_new,
+                                    const void* W, void* Kc, void* Vq, void* Vmeta, int bits,
+                                    int32_t* seq_len, void* hip_stream);
+
+/* Algorithm 1, reconstruction to output steps, with
+ *   out[b, h] = sum_j softmax_j( RoPE(q[b,h]) . K_C[j, g(h)] / sqrt(d) ) v^[b, idx[b,j], g(h)]
+ * (fp32 accumulation, one rounding to T).  Everything else as sals_sparse_attend. */
+sals_status sals_sparse_attend_qv(sals_ctx* ctx, const void* q, const int32_t* q_pos,
+                                  const void* Kc, const void* Vq, const void* Vmeta, int bits,
+                                  const void* W, const int32_t* idx, const int32_t* n_sel,
+                                  void* out, void* hip_stream);
+
+/* sals_latent_scores, sals_topk_select, sals_sparse_attend_qv on one stream; `scores`, `idx`,
+ * `n_sel` may each be NULL (then they live in the workspace). */
+sals_status sals_decode_step_qv(sals_ctx* ctx, const void* q, const int32_t* q_pos,
+                                const void* Kc, const void* Vq, const void* Vmeta, int bits,
+                                const void* W, const int32_t* seq_len, void* out, float* scores,
+                                int32_t* idx, int32_t* n_sel, void* hip_stream);
+
 /* ---- measurement aid --------------------------------------------------------------
  * Per-stage timing for roofline figures.  While enabled, every stage below (one kernel;
  * for the selection of sequences above 32768 tokens a chain of four) is bracketed by a
@@ -189,7 +232,8 @@ enum {
     SALS_K_ATTEND_LOGITS = 3,  /* MFMA key reconstruction + RoPE + q.K         */
     SALS_K_ATTEND_PV = 4,      /* softmax + latent-space value sum             */
     SALS_K_ATTEND_OUT = 5,     /* output projection through U_v                */
-    SALS_N_KERNELS = 6
+    SALS_K_ATTEND_QV = 6,      /* softmax + sum over the quantised value cache */
+    SALS_N_KERNELS = 7
 };
 const char* sals_kernel_name(int kernel);
 sals_status sals_profile_enable(sals_ctx* ctx, int on);

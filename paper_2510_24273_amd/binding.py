@@ -27,8 +27,9 @@ EXPORTS = (
     "sals_compress_append", "sals_latent_scores", "sals_topk_select", "sals_sparse_attend",
     "sals_decode_step", "sals_kernel_name", "sals_profile_enable", "sals_profile_collect",
     "sals_packed_weight_bytes", "sals_pack_weights",
+    "sals_qv_row_bytes", "sals_compress_append_qv", "sals_sparse_attend_qv", "sals_decode_step_qv",
 )
-N_KERNELS = 6
+N_KERNELS = 7
 
 
 class SalsDesc(ctypes.Structure):
@@ -63,6 +64,11 @@ def load_library() -> ctypes.CDLL:
     lib.sals_topk_select.argtypes = [vp, f32p, i32p, i32p, i32p, vp]
     lib.sals_sparse_attend.argtypes = [vp, vp, i32p, vp, vp, vp, i32p, i32p, vp, vp]
     lib.sals_decode_step.argtypes = [vp, vp, i32p, vp, vp, vp, i32p, vp, f32p, i32p, i32p, vp]
+    lib.sals_qv_row_bytes.argtypes = [ctypes.POINTER(SalsDesc), ctypes.c_int, ctypes.POINTER(ctypes.c_size_t),
+                                      ctypes.POINTER(ctypes.c_size_t)]
+    lib.sals_compress_append_qv.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, i32p, vp]
+    lib.sals_sparse_attend_qv.argtypes = [vp, vp, i32p, vp, vp, vp, ctypes.c_int, vp, i32p, i32p, vp, vp]
+    lib.sals_decode_step_qv.argtypes = [vp, vp, i32p, vp, vp, vp, ctypes.c_int, vp, i32p, vp, f32p, i32p, i32p, vp]
     lib.sals_kernel_name.restype = ctypes.c_char_p
     lib.sals_kernel_name.argtypes = [ctypes.c_int]
     lib.sals_profile_enable.argtypes = [vp, ctypes.c_int]
@@ -101,6 +107,15 @@ def packed_weight_bytes(desc: SalsDesc) -> int:
     if st != SALS_OK:
         raise SalsError(st, "sals_packed_weight_bytes")
     return int(n.value)
+
+
+def qv_row_bytes(desc: SalsDesc, bits: int):
+    """(code bytes, meta bytes) per token of the quantised value cache."""
+    c, m = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    st = _lib.sals_qv_row_bytes(ctypes.byref(desc), int(bits), ctypes.byref(c), ctypes.byref(m))
+    if st != SALS_OK:
+        raise SalsError(st, "sals_qv_row_bytes")
+    return int(c.value), int(m.value)
 
 
 def _p(t):
@@ -176,3 +191,18 @@ class Sals:
         self._check(_lib.sals_decode_step(self._h, _p(q), _p(q_pos), _p(Kc), _p(Vc), _p(W), _p(seq_len),
                                           _p(out), _p(scores), _p(idx), _p(n_sel), _stream()),
                     "sals_decode_step")
+
+    # ---- quantised full-rank value cache (codes Vq, per-group (scale, zero) Vmeta) ----
+    def compress_append_qv(self, k_new, v_new, W, Kc, Vq, Vmeta, bits, seq_len):
+        self._check(_lib.sals_compress_append_qv(self._h, _p(k_new), _p(v_new), _p(W), _p(Kc), _p(Vq), _p(Vmeta),
+                                                 int(bits), _p(seq_len), _stream()), "sals_compress_append_qv")
+
+    def sparse_attend_qv(self, q, q_pos, Kc, Vq, Vmeta, bits, W, idx, n_sel, out):
+        self._check(_lib.sals_sparse_attend_qv(self._h, _p(q), _p(q_pos), _p(Kc), _p(Vq), _p(Vmeta), int(bits),
+                                               _p(W), _p(idx), _p(n_sel), _p(out), _stream()),
+                    "sals_sparse_attend_qv")
+
+    def decode_step_qv(self, q, q_pos, Kc, Vq, Vmeta, bits, W, seq_len, out, scores=None, idx=None, n_sel=None):
+        self._check(_lib.sals_decode_step_qv(self._h, _p(q), _p(q_pos), _p(Kc), _p(Vq), _p(Vmeta), int(bits), _p(W),
+                                             _p(seq_len), _p(out), _p(scores), _p(idx), _p(n_sel), _stream()),
+                    "sals_decode_step_qv")

@@ -1,0 +1,261 @@
+// Quantised full-rank value cache (Sec. 5.1; the V-hat of Algorithm 1).
+//
+// The paper keeps values at full rank and stores them with channel-wise group quantisation
+// (4 bit at its 25 % setting, 2 bit at 12.5 %), following KIVI's asymmetric uniform scheme.
+// Layout used here: a token's D_kv channels form groups of 32 consecutive channels; per group
+// the cache holds (scale, zero) as two elements of the storage type T, and per channel an
+// unsigned code of BITS bits, channel c in byte c*BITS/8 at bit (c*BITS) % 8:
+//     scale = T((max - min) / (2^BITS - 1)),  zero = min,
+//     code  = clamp(rint((v - zero) / scale), 0, 2^BITS - 1)   (fp32, IEEE division, ties to even),
+//     v^    = zero + scale * code.
+//
+//   Vq    [B, S_max, D_kv*BITS/8] bytes      Vmeta [B, S_max, D_kv/32, 2] T
+//
+// qv_quantize_kernel writes the new token's row.  attend_qv_kernel evaluates the last step of
+// Algorithm 1, y[h] = sum_j p[h,j] v^[C_j, g(h)], from the logits and tile statistics the logits
+// kernel left behind: a gather of k rows of D_kv*BITS/8 bytes, no matrix product.  A thread owns
+// 16 channels of one KV head for the whole token range, so the sum over tokens never leaves its
+// registers; with  p*v^ = (p*zero) + (p*scale)*code  a token costs one multiply per head and one
+// fused multiply-add per (head, channel).
+#pragma once
+#include "common.hpp"
+#include "k_attend.hpp"
+
+namespace sals {
+
+constexpr int kQvGroup = 32;        // channels per quantisation group
+constexpr int kQvCh = 16;           // channels per thread of the attention kernel
+constexpr int kQvMaxRanges = 32;    // token ranges a sequence's selection is split into at most
+constexpr int kQvMaxTok = 4096;     // tokens per range at most
+constexpr int kQvMaxHeads = 64;     // query heads a workgroup serves at most (HB * group size)
+
+template <typename T> struct qv_meta;
+template <> struct qv_meta<float> {
+    static __device__ __forceinline__ float2 load(const float* p) { return *reinterpret_cast<const float2*>(p); }
+    static __device__ __forceinline__ float round(float s) { return s; }
+    static __device__ __forceinline__ void store(float* p, float s, float z) { *reinterpret_cast<float2*>(p) = make_float2(s, z); }
+};
+template <> struct qv_meta<bf16_t> {
+    static __device__ __forceinline__ float2 load(const bf16_t* p)
+    {
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(p);
+        return make_float2(bf16lo(w), bf16hi(w));
+    }
+    static __device__ __forceinline__ float round(float s) { return bf16_to_f32(f32_to_bf16(s)); }
+    static __device__ __forceinline__ void store(bf16_t* p, float s, float z)
+    {
+        *reinterpret_cast<uint32_t*>(p) = (uint32_t)f32_to_bf16(s) | ((uint32_t)f32_to_bf16(z) << 16);
+    }
+};
+
+// One group per 32 lanes: row seq_len[b] of the quantised cache from the new token's value.
+// A sequence whose cache is full is left untouched.  grid (D/32/8, B), 256 threads.
+template <typename T, int BITS>
+__global__ __launch_bounds__(256) void qv_quantize_kernel(const T* __restrict__ v_new, unsigned char* __restrict__ Vq,
+                                                          T* __restrict__ Vmeta, const int32_t* __restrict__ seq_len,
+                                                          int D, int S_max)
+{
+    constexpr float kLevels = (float)((1 << BITS) - 1);
+    constexpr int PER = 32 / BITS;  // codes per 32-bit word
+    const int b = blockIdx.y;
+    const int gi = blockIdx.x * 8 + (threadIdx.x >> 5), l = threadIdx.x & 31;
+    const int n_groups = D / kQvGroup;
+    const int row = seq_len[b];
+    if (gi >= n_groups || row < 0 || row >= S_max) return;
+    const float v = elem<T>::load(v_new + (size_t)b * D + gi * kQvGroup + l);
+    float mn = v, mx = v;
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, o, 32));
+        mx = fmaxf(mx, __shfl_xor(mx, o, 32));
+    }
+    const float scale = qv_meta<T>::round((mx - mn) / kLevels);
+    float t = scale > 0.f ? rintf((v - mn) / scale) : 0.f;
+    t = fminf(fmaxf(t, 0.f), kLevels);
+    uint32_t w = (uint32_t)t << ((l % PER) * BITS);
+#pragma unroll
+    for (int o = 1; o < PER; o <<= 1) w |= (uint32_t)__shfl_xor((int)w, o, 32);
+    const size_t tok = (size_t)b * S_max + row;
+    if (l % PER == 0)
+        *reinterpret_cast<uint32_t*>(Vq + tok * ((size_t)D * BITS / 8) + (size_t)(gi * kQvGroup + l) * BITS / 8) = w;
+    if (l == 0) qv_meta<T>::store(Vmeta + (tok * n_groups + gi) * 2, scale, mn);
+}
+
+struct QvArgs {
+    const unsigned char* Vq;
+    const void* Vmeta;
+    const int32_t* idx;
+    const int32_t* n_sel;
+    const float* logits;
+    const float2* stats;
+    float* part;   // [n_tr, B, H, 128] fp32 partial outputs; unused when n_tr == 1
+    void* out;     // [B, H, 128] T
+    int n_parts, B, S_max, H, H_kv, k_tot, lk, tok_per_wg, n_tr, HB;
+};
+
+// grid (n_tr, H_kv / HB, B), 256 threads.  HB KV heads per workgroup (a power of two <= 32):
+// HB*8 threads cover a token's channels, 256 / (HB*8) tokens are in progress side by side
+// ("slots") and are added up through LDS at the end, in slot order.
+template <typename T, int BITS, int GMAX>
+__global__ __launch_bounds__(256) void attend_qv_kernel(QvArgs a)
+{
+    constexpr int CB = kQvCh * BITS / 8;  // code bytes per thread and token: 8 or 4
+    constexpr int NW = CB / 4;
+    constexpr int UN = GMAX > 4 ? 4 : 8;  // tokens whose loads are in flight together, per thread
+    __shared__ int sRow[kQvMaxTok];
+    __shared__ float2 sMZ[kQvMaxHeads];
+    __shared__ __attribute__((aligned(16))) float red[256][kQvCh + 1];
+
+    const int tr = blockIdx.x, hb = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x;
+    const int H = a.H, G = H / a.H_kv, HB = a.HB;
+    const int TPT = HB * (kHeadDim / kQvCh), TS = 256 / TPT;
+    const int slot = tid / TPT, u = tid % TPT;
+    const int kvh = hb * HB + u / (kHeadDim / kQvCh), c0 = (u % (kHeadDim / kQvCh)) * kQvCh;
+    const int n = a.n_sel[b];
+    const int j_begin = min(n, tr * a.tok_per_wg), j_end = min(n, j_begin + a.tok_per_wg);
+    const int ntok = j_end - j_begin;
+    const int32_t* ib = a.idx + (size_t)b * a.k_tot;
+
+    for (int t = tid; t < a.tok_per_wg; t += 256) {  // (independent of n: in flight together with it)
+        const int j = tr * a.tok_per_wg + t;
+        const int v = j < a.k_tot ? ib[j] : 0;
+        if (t < ntok) sRow[t] = min(max(v, 0), a.S_max - 1);
+    }
+    {   // softmax maximum and normaliser of this workgroup's heads: four lanes per head merge the
+        // tile statistics in a fixed order
+        const int hl = tid >> 2, sub = tid & 3;
+        float2 st = make_float2(-INFINITY, 0.f);
+        if (hl < HB * G) {
+            const float2* sp = a.stats + ((size_t)b * H + hb * HB * G + hl) * a.n_parts;
+            for (int t0 = sub; t0 < a.n_parts; t0 += 32) {
+                float2 e[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) e[i] = t0 + 4 * i < a.n_parts ? sp[t0 + 4 * i] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) st = stat_merge(st, e[i]);
+            }
+        }
+        st = stat_merge(st, make_float2(__shfl_xor(st.x, 1, kWave), __shfl_xor(st.y, 1, kWave)));
+        st = stat_merge(st, make_float2(__shfl_xor(st.x, 2, kWave), __shfl_xor(st.y, 2, kWave)));
+        if (sub == 0 && hl < HB * G) sMZ[hl] = make_float2(st.x > -INFINITY ? st.x : 0.f, st.y > 0.f ? 1.f / st.y : 0.f);
+    }
+    __syncthreads();
+    float2 mz[GMAX];
+#pragma unroll
+    for (int m = 0; m < GMAX; ++m) mz[m] = m < G ? sMZ[(kvh - hb * HB) * G + m] : make_float2(0.f, 0.f);
+
+    float acc[GMAX][kQvCh], bias[GMAX];
+#pragma unroll
+    for (int m = 0; m < GMAX; ++m) {
+        bias[m] = 0.f;
+#pragma unroll
+        for (int c = 0; c < kQvCh; ++c) acc[m][c] = 0.f;
+    }
+
+    const int n_groups = a.H_kv * (kHeadDim / kQvGroup);
+    const size_t row_bytes = (size_t)a.H_kv * kHeadDim * BITS / 8;
+    const unsigned char* vq = a.Vq + (size_t)b * a.S_max * row_bytes + (size_t)(kvh * kHeadDim + c0) * BITS / 8;
+    const T* vm = static_cast<const T*>(a.Vmeta) + ((size_t)b * a.S_max * n_groups + kvh * (kHeadDim / kQvGroup) + c0 / kQvGroup) * 2;
+    const float* lg = a.logits + ((size_t)b * H + (size_t)kvh * G) * a.lk + j_begin;
+
+    for (int t0 = slot; t0 < ntok; t0 += TS * UN) {
+        uint32_t cw[UN][NW];
+        float2 sz[UN];
+        float x[UN][GMAX];
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            const int t = t0 + i * TS;
+            const int tc = min(t, ntok - 1);  // a token past the range re-reads the last row with weight zero
+            const size_t row = (size_t)sRow[tc];
+            if (NW == 2) {
+                const uint2 w2 = *reinterpret_cast<const uint2*>(vq + row * row_bytes);
+                cw[i][0] = w2.x; cw[i][NW - 1] = w2.y;
+            } else {
+                cw[i][0] = *reinterpret_cast<const uint32_t*>(vq + row * row_bytes);
+            }
+            sz[i] = qv_meta<T>::load(vm + row * n_groups * 2);
+#pragma unroll
+            for (int m = 0; m < GMAX; ++m) x[i][m] = (m < G && t < ntok) ? lg[(size_t)m * a.lk + tc] : -INFINITY;
+        }
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            float cf[kQvCh];
+#pragma unroll
+            for (int c = 0; c < kQvCh; ++c)
+                cf[c] = (float)((cw[i][(c * BITS) / 32] >> ((c * BITS) % 32)) & ((1u << BITS) - 1u));
+#pragma unroll
+            for (int m = 0; m < GMAX; ++m) {
+                if (m < G) {  // uniform
+                    const float p = __expf(x[i][m] - mz[m].x) * mz[m].y;  // exp(-inf) = 0 masks the padding
+                    const float ps = p * sz[i].x;
+                    bias[m] = fmaf(p, sz[i].y, bias[m]);
+#pragma unroll
+                    for (int c = 0; c < kQvCh; ++c) acc[m][c] = fmaf(ps, cf[c], acc[m][c]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < GMAX; ++m)
+#pragma unroll
+        for (int c = 0; c < kQvCh; ++c) acc[m][c] += bias[m];
+
+    // the token slots' sums, added in slot order by the threads of slot 0
+    if (TS > 1) {  // uniform
+#pragma unroll
+        for (int m = 0; m < GMAX; ++m) {
+            if (m < G) {  // uniform
+                __syncthreads();
+#pragma unroll
+                for (int c = 0; c < kQvCh; ++c) red[tid][c] = acc[m][c];
+                __syncthreads();
+                if (slot == 0) {
+                    for (int s = 1; s < TS; ++s)
+#pragma unroll
+                        for (int c = 0; c < kQvCh; ++c) acc[m][c] += red[s * TPT + u][c];
+                }
+            }
+        }
+    }
+    if (slot != 0) return;
+#pragma unroll
+    for (int m = 0; m < GMAX; ++m) {
+        if (m < G) {  // uniform
+            const int h = kvh * G + m;
+            if (a.n_tr > 1) {
+                float* dst = a.part + (((size_t)tr * a.B + b) * H + h) * kHeadDim + c0;
+#pragma unroll
+                for (int c = 0; c < kQvCh; c += 4)
+                    *reinterpret_cast<f32x4*>(dst + c) = f32x4{acc[m][c], acc[m][c + 1], acc[m][c + 2], acc[m][c + 3]};
+            } else {
+                T* dst = static_cast<T*>(a.out) + ((size_t)b * H + h) * kHeadDim + c0;
+#pragma unroll
+                for (int c = 0; c < kQvCh; ++c) elem<T>::store(dst + c, acc[m][c]);
+            }
+        }
+    }
+}
+
+// out = sum over the token ranges' partial outputs, in range order, rounded once to T.
+// One thread per 4 output elements.
+template <typename T>
+__global__ __launch_bounds__(256) void qv_merge_kernel(const float* __restrict__ part, T* __restrict__ out, int n_tr,
+                                                       size_t n4)
+{
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n4) return;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int t0 = 0; t0 < n_tr; t0 += 8) {
+        f32x4 x[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            x[i] = t0 + i < n_tr ? *reinterpret_cast<const f32x4*>(part + ((size_t)(t0 + i) * n4 + e) * 4) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { s.x += x[i].x; s.y += x[i].y; s.z += x[i].z; s.w += x[i].w; }
+    }
+    T* dst = out + e * 4;
+    elem<T>::store(dst, s.x); elem<T>::store(dst + 1, s.y); elem<T>::store(dst + 2, s.z); elem<T>::store(dst + 3, s.w);
+}
+
+}  // namespace sals

@@ -18,6 +18,7 @@
 #include "k_scores.hpp"
 #include "k_topk.hpp"
 #include "k_topk_multi.hpp"
+#include "k_qvalue.hpp"
 #include "k_value.hpp"
 
 using namespace sals;
@@ -29,10 +30,11 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Layout {  // byte offsets into the workspace
-    size_t qt, scores, idx, n_sel, logits, stats, rope, tpart, tm_part, tm_hist, tm_meta, tm_cand, total;
+    size_t qt, scores, idx, n_sel, logits, stats, rope, tpart, qv_part, tm_part, tm_hist, tm_meta, tm_cand, total;
     int lk;                      // logits row stride (floats)
     int max_parts;               // token tiles per head of the logits kernel, at most
     int pv_tok_per_wg, pv_ntr;   // value-sum token ranges
+    int qv_hb, qv_tok_per_wg, qv_ntr;  // quantised-value attention: KV heads per workgroup, token ranges
     int proj_np;                 // D-axis slices of the query projection
     int tm_chunks;               // chunks of the multi-workgroup selection (0: one workgroup per sequence)
     size_t w_section;            // elements per section of the packed weights
@@ -57,7 +59,7 @@ struct sals_ctx {
 namespace {
 
 const char* const kKernelNames[SALS_N_KERNELS] = {
-    "project", "scores", "topk", "attend_logits", "attend_pv", "attend_out"};
+    "project", "scores", "topk", "attend_logits", "attend_pv", "attend_out", "attend_qv"};
 
 // Brackets one kernel launch with a pair of events while profiling is on.
 struct ProfScope {
@@ -136,6 +138,19 @@ Layout make_layout(const sals_desc& d)
     L.stats = take((size_t)d.B * d.H_q * L.max_parts * 8);
     L.rope = take((size_t)(d.S_max + 1) * kPairs * 8);  // positions 0 .. S_max (the query after a full cache)
     L.tpart = take((size_t)L.pv_ntr * d.B * d.H_q * d.r * 4);
+    {   // quantised-value attention: KV heads per workgroup = the largest power of two <= 32 dividing
+        // H_kv; token ranges until about 512 workgroups exist, at least 8 tokens per slot and range
+        int hb = 1;
+        while (hb < 32 && d.H_kv % (hb * 2) == 0) hb *= 2;
+        const int slots = 256 / (hb * (kHeadDim / kQvCh));
+        int n_tr = std::min(kQvMaxRanges, ceil_div(512, d.B * (d.H_kv / hb)));
+        n_tr = std::max(1, std::min(n_tr, k_tot / (8 * slots)));
+        n_tr = std::max(n_tr, ceil_div(k_tot, kQvMaxTok));
+        L.qv_hb = hb;
+        L.qv_tok_per_wg = ceil_div(k_tot, n_tr);
+        L.qv_ntr = ceil_div(k_tot, L.qv_tok_per_wg);
+        L.qv_part = take((size_t)L.qv_ntr * d.B * d.H_q * kHeadDim * 4);
+    }
     // long sequences: selection spread over 8192-score chunks
     L.tm_chunks = d.S_max > 32768 ? ceil_div(d.S_max, kTmChunk) : 0;
     if (L.tm_chunks > 0) {
@@ -161,9 +176,11 @@ template <typename T> inline const T* w_section(const sals_ctx* c, const void* W
     return static_cast<const T*>(W) + (size_t)sec * c->L.w_section;
 }
 
+// QUERY: x0 = q.  Otherwise x0 / x1 = new key / value rows (x1 may be null: keys only); `bump` advances
+// the sequence lengths afterwards.
 template <typename T, bool QUERY>
 sals_status launch_project(const sals_ctx* c, const void* W, const void* x0, const void* x1, void* cache0,
-                           void* cache1, int32_t* seq_len, hipStream_t st)
+                           void* cache1, int32_t* seq_len, hipStream_t st, bool bump = true)
 {
     const sals_desc& d = c->d;
     ProjArgs a{};
@@ -174,13 +191,13 @@ sals_status launch_project(const sals_ctx* c, const void* W, const void* x0, con
     a.out_f32 = reinterpret_cast<float*>(c->ws + c->L.qt);
     a.seq_len = seq_len;
     a.B = d.B; a.D = d.H_kv * d.d; a.r = d.r; a.H = d.H_q; a.H_kv = d.H_kv; a.d = d.d;
-    a.S_max = d.S_max; a.nproj = QUERY ? 1 : 2; a.np = QUERY ? c->L.proj_np : 1;
+    a.S_max = d.S_max; a.nproj = (QUERY || x1 == nullptr) ? 1 : 2; a.np = QUERY ? c->L.proj_np : 1;
     {
         ProfScope ps(c, SALS_K_PROJECT, st);
         hipLaunchKernelGGL((project_kernel<T, QUERY>), dim3(d.r / 16, a.np, a.nproj), dim3(kProjThreads), 0, st, a);
     }
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
-    if (!QUERY)
+    if (!QUERY && bump)
         hipLaunchKernelGGL(bump_seq_len_kernel, dim3(ceil_div(d.B, 128)), dim3(128), 0, st, seq_len, d.B, d.S_max);
     return launch_status();
 }
@@ -249,10 +266,14 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
     return launch_status();
 }
 
+struct QvCache { const void* codes; const void* meta; int bits; };  // quantised full-rank value cache
+
+// qv == nullptr: latent value cache Vc, value sum in latent space and output projection through U_v.
+// Otherwise: values are the de-quantised rows of the quantised cache (Vc unused).
 template <typename T>
 sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos, const void* Kc,
                           const void* Vc, const void* W, const int32_t* idx, const int32_t* n_sel, void* out,
-                          hipStream_t st)
+                          hipStream_t st, const QvCache* qv = nullptr)
 {
     const sals_desc& d = c->d;
     const Layout& L = c->L;
@@ -322,6 +343,30 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
         }
 #undef SALS_LOGITS
         if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+    }
+    if (qv != nullptr) {
+        ProfScope ps(c, SALS_K_ATTEND_QV, st);
+        QvArgs a{static_cast<const unsigned char*>(qv->codes), qv->meta, idx, n_sel, logits, stats,
+                 reinterpret_cast<float*>(c->ws + L.qv_part), out, n_parts, d.B, d.S_max, d.H_q, d.H_kv, k_tot, L.lk,
+                 L.qv_tok_per_wg, L.qv_ntr, L.qv_hb};
+        const dim3 grid(L.qv_ntr, d.H_kv / L.qv_hb, d.B);
+        const int G = d.H_q / d.H_kv;
+#define SALS_QV(BITS, GMAX) hipLaunchKernelGGL((attend_qv_kernel<T, BITS, GMAX>), grid, dim3(256), 0, st, a)
+#define SALS_QV_G(BITS)                                                                                 \
+    do {                                                                                                \
+        if (G <= 1) SALS_QV(BITS, 1); else if (G <= 2) SALS_QV(BITS, 2);                                \
+        else if (G <= 4) SALS_QV(BITS, 4); else SALS_QV(BITS, 8);                                       \
+    } while (0)
+        if (qv->bits == 4) SALS_QV_G(4); else SALS_QV_G(2);
+#undef SALS_QV_G
+#undef SALS_QV
+        if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+        if (L.qv_ntr > 1) {
+            const size_t n4 = (size_t)d.B * d.H_q * kHeadDim / 4;
+            hipLaunchKernelGGL((qv_merge_kernel<T>), dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, a.part,
+                               static_cast<T*>(out), L.qv_ntr, n4);
+        }
+        return launch_status();
     }
     {
         ProfScope ps(c, SALS_K_ATTEND_PV, st);
@@ -508,6 +553,75 @@ sals_status sals_decode_step(sals_ctx* ctx, const void* q, const int32_t* q_pos,
     s = sals_topk_select(ctx, scores, seq_len, idx, n_sel, hip_stream);
     if (s != SALS_OK) return s;
     return sals_sparse_attend(ctx, q, q_pos, Kc, Vc, W, idx, n_sel, out, hip_stream);
+}
+
+sals_status sals_qv_row_bytes(const sals_desc* desc, int bits, size_t* code_bytes, size_t* meta_bytes)
+{
+    if (!code_bytes || !meta_bytes) return SALS_ERR_INVALID_ARG;
+    sals_status s = validate(desc);
+    if (s != SALS_OK) return s;
+    if (bits != 2 && bits != 4) return SALS_ERR_UNSUPPORTED;
+    const size_t D = (size_t)desc->H_kv * desc->d;
+    *code_bytes = D * bits / 8;
+    *meta_bytes = D / kQvGroup * 2 * (desc->dtype == SALS_BF16 ? 2 : 4);
+    return SALS_OK;
+}
+
+sals_status sals_compress_append_qv(sals_ctx* ctx, const void* k_new, const void* v_new, const void* W, void* Kc,
+                                    void* Vq, void* Vmeta, int bits, int32_t* seq_len, void* hip_stream)
+{
+    if (!ctx || bad(k_new) || bad(v_new) || bad(W) || bad(Kc) || bad(Vq) || bad(Vmeta) || !seq_len)
+        return SALS_ERR_INVALID_ARG;
+    if (bits != 2 && bits != 4) return SALS_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const sals_desc& d = ctx->d;
+    const bool bf = d.dtype == SALS_BF16;
+    sals_status s = bf ? launch_project<bf16_t, false>(ctx, W, k_new, nullptr, Kc, nullptr, seq_len, st, false)
+                       : launch_project<float, false>(ctx, W, k_new, nullptr, Kc, nullptr, seq_len, st, false);
+    if (s != SALS_OK) return s;
+    const int D = d.H_kv * d.d;
+    const dim3 grid(ceil_div(D / kQvGroup, 8), d.B);
+    unsigned char* codes = static_cast<unsigned char*>(Vq);
+#define SALS_QUANT(T, BITS)                                                                                   \
+    hipLaunchKernelGGL((qv_quantize_kernel<T, BITS>), grid, dim3(256), 0, st, static_cast<const T*>(v_new), codes, \
+                       static_cast<T*>(Vmeta), seq_len, D, d.S_max)
+    if (bf) { if (bits == 4) SALS_QUANT(bf16_t, 4); else SALS_QUANT(bf16_t, 2); }
+    else    { if (bits == 4) SALS_QUANT(float, 4); else SALS_QUANT(float, 2); }
+#undef SALS_QUANT
+    if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+    hipLaunchKernelGGL(bump_seq_len_kernel, dim3(ceil_div(d.B, 128)), dim3(128), 0, st, seq_len, d.B, d.S_max);
+    return launch_status();
+}
+
+sals_status sals_sparse_attend_qv(sals_ctx* ctx, const void* q, const int32_t* q_pos, const void* Kc,
+                                  const void* Vq, const void* Vmeta, int bits, const void* W, const int32_t* idx,
+                                  const int32_t* n_sel, void* out, void* hip_stream)
+{
+    if (!ctx || bad(q) || !q_pos || bad(Kc) || bad(Vq) || bad(Vmeta) || bad(W) || !idx || !n_sel || bad(out))
+        return SALS_ERR_INVALID_ARG;
+    if (bits != 2 && bits != 4) return SALS_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const QvCache qv{Vq, Vmeta, bits};
+    return ctx->d.dtype == SALS_BF16 ? launch_attend<bf16_t>(ctx, q, q_pos, Kc, nullptr, W, idx, n_sel, out, st, &qv)
+                                     : launch_attend<float>(ctx, q, q_pos, Kc, nullptr, W, idx, n_sel, out, st, &qv);
+}
+
+sals_status sals_decode_step_qv(sals_ctx* ctx, const void* q, const int32_t* q_pos, const void* Kc,
+                                const void* Vq, const void* Vmeta, int bits, const void* W, const int32_t* seq_len,
+                                void* out, float* scores, int32_t* idx, int32_t* n_sel, void* hip_stream)
+{
+    if (!ctx || bad(q) || !q_pos || bad(Kc) || bad(Vq) || bad(Vmeta) || bad(W) || !seq_len || bad(out))
+        return SALS_ERR_INVALID_ARG;
+    if (bits != 2 && bits != 4) return SALS_ERR_UNSUPPORTED;
+    if (scores && !aligned16(scores)) return SALS_ERR_INVALID_ARG;
+    if (!scores) scores = reinterpret_cast<float*>(ctx->ws + ctx->L.scores);
+    if (!idx) idx = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.idx);
+    if (!n_sel) n_sel = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_sel);
+    sals_status s = sals_latent_scores(ctx, q, W, Kc, seq_len, scores, hip_stream);
+    if (s != SALS_OK) return s;
+    s = sals_topk_select(ctx, scores, seq_len, idx, n_sel, hip_stream);
+    if (s != SALS_OK) return s;
+    return sals_sparse_attend_qv(ctx, q, q_pos, Kc, Vq, Vmeta, bits, W, idx, n_sel, out, hip_stream);
 }
 
 }  // extern "C"

@@ -28,7 +28,9 @@ def stage_bytes(w, seq_len=None) -> dict:
         "scores": w.B * (S * w.rs * e + 4 * S),          # K~ stream + score write
         "select": w.B * 4 * S,                            # score read
         "attend_k": w.B * n_sel * w.r * e + w.r * w.D_kv * e,   # gathered K~ rows + U_k
-        "attend_v": w.B * n_sel * w.r * e + w.r * w.D_kv * e,   # gathered V~ rows + U_v
+        # gathered V~ rows + U_v, or (quantised value cache) gathered code rows + per-group (scale, zero)
+        "attend_v": (w.B * n_sel * w.r * e + w.r * w.D_kv * e) if not getattr(w, "qv_bits", 0)
+        else w.B * n_sel * (w.D_kv * w.qv_bits // 8 + w.D_kv // 32 * 2 * e),
         "small": small,
     }
 

@@ -41,6 +41,7 @@ class Workload:
     corr_frac: float = 0.0       # fraction of rows correlated with the query
     corr_rho: float = 0.3
     scale: float = 1.0           # extra cache scale (stress cases only)
+    qv_bits: int = 0             # > 0: values live in the quantised full-rank cache (2 | 4 bits)
 
     @property
     def D_kv(self):
@@ -86,6 +87,11 @@ VARIANTS = {
     name + "_rhalf": replace(w, name=w.name + "_rscore" + str(w.r // 2), r_score=w.r // 2)
     for name, w in CONFIGS.items() if name in ("cfg2", "cfg3a", "cfg4")
 }
+# The paper's own value path (Sec. 5.1): quantised full-rank value cache, 4 bit (25 % setting) / 2 bit.
+VARIANTS.update({
+    f"{name}_qv{bits}": replace(w, name=f"{w.name}_qvalue{bits}bit", qv_bits=bits)
+    for name, w in CONFIGS.items() if name in ("cfg2", "cfg3a", "cfg3b", "cfg4") for bits in (4, 2)
+})
 
 
 def lookup(name: str) -> Workload:
@@ -203,3 +209,34 @@ def make_layer(w: Workload, layer: int = 0, seq_lens=None):
     sl = np.asarray(seq_lens, dtype=np.int32)
     return {"q": q, "Kc": Kc, "Vc": Vc, "Uk": Uk, "Uv": Uv, "seq_len": sl,
             "q_pos": sl.copy(), "planted": planted}
+
+
+# ---- quantised full-rank value cache (the paper's value path, Sec. 5.1) ----------------
+
+QV_GROUP = 32   # channels per quantisation group (layout constant of the cache format)
+
+
+def make_values(w: Workload, layer: int = 0, n_rows: int | None = None) -> np.ndarray:
+    """Full-rank value rows [B, n_rows, D_kv], storage-rounded: N(0,1) times a per-channel
+    magnitude drawn once per layer (log-normal, sigma 0.5), as value activations have
+    channel-dependent ranges.  Input of the quantiser under test."""
+    n_rows = w.S if n_rows is None else n_rows
+    rng = np.random.default_rng(seed_of(w, layer, 77))
+    mag = np.exp(0.5 * rng.standard_normal(w.D_kv))
+    v = rng.standard_normal((w.B, n_rows, w.D_kv), dtype=np.float32).astype(np.float64) * mag
+    return store(v, w.dtype)
+
+
+def make_qv_cache(w: Workload, layer: int, bits: int):
+    """A quantised value cache made directly in its stored form (no quantiser involved):
+    code bytes [B, S, D_kv*bits/8] uniformly random (every code value equally likely) and
+    per-group (scale, zero) [B, S, D_kv/32, 2] in the storage type, with
+    scale = |N(0,1)| * 4/(2^bits - 1) + a small floor and zero = -2 + 0.5 N(0,1): the
+    ranges a unit-variance group of 32 channels produces."""
+    rng = np.random.default_rng(seed_of(w, layer, 78) + bits)
+    codes = rng.integers(0, 256, size=(w.B, w.S, w.D_kv * bits // 8), dtype=np.uint8)
+    ng = w.D_kv // QV_GROUP
+    scale = (np.abs(rng.standard_normal((w.B, w.S, ng), dtype=np.float32)) + 0.05) * (4.0 / ((1 << bits) - 1))
+    zero = -2.0 + 0.5 * rng.standard_normal((w.B, w.S, ng), dtype=np.float32)
+    meta = store(np.stack([scale, zero], axis=-1), w.dtype)
+    return codes, meta
