@@ -27,7 +27,6 @@ constexpr int kQvGroup = 32;        // channels per quantisation group
 constexpr int kQvCh = 16;           // channels per thread of the attention kernel
 constexpr int kQvMaxRanges = 32;    // token ranges a sequence's selection is split into at most
 constexpr int kQvMaxTok = 4096;     // tokens per range at most
-constexpr int kQvMaxHeads = 64;     // query heads a workgroup serves at most (HB * group size)
 
 template <typename T> struct qv_meta;
 template <> struct qv_meta<float> {
@@ -90,12 +89,17 @@ struct QvArgs {
     const float2* stats;
     float* part;   // [n_tr, B, H, 128] fp32 partial outputs; unused when n_tr == 1
     void* out;     // [B, H, 128] T
-    int n_parts, B, S_max, H, H_kv, k_tot, lk, tok_per_wg, n_tr, HB;
+    int n_parts, B, S_max, H, H_kv, k_tot, lk, tok_per_wg, n_tr;
 };
 
-// grid (n_tr, H_kv / HB, B), 256 threads.  HB KV heads per workgroup (a power of two <= 32):
-// HB*8 threads cover a token's channels, 256 / (HB*8) tokens are in progress side by side
-// ("slots") and are added up through LDS at the end, in slot order.
+constexpr int kQvTpt = kHeadDim / kQvCh;  // threads per token: 8
+constexpr int kQvSlots = 256 / kQvTpt;    // tokens in progress side by side: 32
+
+// One workgroup per (sequence, token range, KV head): 8 threads cover the head's 128 channels of a
+// token, 32 tokens ("slots") are in progress side by side and are added up through LDS at the end,
+// in slot order.  1-D grid of B * n_tr * H_kv workgroups; ids are dealt round-robin to the XCDs and
+// mapped so that each XCD gets a contiguous run of the work list (KV head fastest): the heads of a
+// token range read neighbouring pieces of the same cache rows and meet in one L2.
 template <typename T, int BITS, int GMAX>
 __global__ __launch_bounds__(256) void attend_qv_kernel(QvArgs a)
 {
@@ -103,47 +107,59 @@ __global__ __launch_bounds__(256) void attend_qv_kernel(QvArgs a)
     constexpr int NW = CB / 4;
     constexpr int UN = GMAX > 4 ? 4 : 8;  // tokens whose loads are in flight together, per thread
     __shared__ int sRow[kQvMaxTok];
-    __shared__ float2 sMZ[kQvMaxHeads];
+    __shared__ float2 sMZ[kMaxGroup];
     __shared__ __attribute__((aligned(16))) float red[256][kQvCh + 1];
 
-    const int tr = blockIdx.x, hb = blockIdx.y, b = blockIdx.z;
+    int tr, kvh, b;
+    {
+        const int total = a.B * a.n_tr * a.H_kv;  // = gridDim.x
+        const int xcd = blockIdx.x % kXcds, sl = blockIdx.x / kXcds, qn = total / kXcds, rem = total % kXcds;
+        const int item = (xcd < rem ? xcd * (qn + 1) : rem * (qn + 1) + (xcd - rem) * qn) + sl;
+        kvh = item % a.H_kv; tr = (item / a.H_kv) % a.n_tr; b = item / (a.H_kv * a.n_tr);
+    }
     const int tid = threadIdx.x;
-    const int H = a.H, G = H / a.H_kv, HB = a.HB;
-    const int TPT = HB * (kHeadDim / kQvCh), TS = 256 / TPT;
-    const int slot = tid / TPT, u = tid % TPT;
-    const int kvh = hb * HB + u / (kHeadDim / kQvCh), c0 = (u % (kHeadDim / kQvCh)) * kQvCh;
-    const int n = a.n_sel[b];
-    const int j_begin = min(n, tr * a.tok_per_wg), j_end = min(n, j_begin + a.tok_per_wg);
-    const int ntok = j_end - j_begin;
+    const int H = a.H, G = H / a.H_kv;
+    const int slot = tid / kQvTpt, u = tid % kQvTpt, c0 = u * kQvCh;
     const int32_t* ib = a.idx + (size_t)b * a.k_tot;
 
-    for (int t = tid; t < a.tok_per_wg; t += 256) {  // (independent of n: in flight together with it)
-        const int j = tr * a.tok_per_wg + t;
-        const int v = j < a.k_tot ? ib[j] : 0;
-        if (t < ntok) sRow[t] = min(max(v, 0), a.S_max - 1);
+    // Everything the prologue needs from memory is requested before anything is waited for: the
+    // first tile statistics of this KV head's query heads (32 lanes per head), the selection count
+    // and up to four token indices per thread.  (Whole 8-byte loads: a float2 load would be split and
+    // its second half sunk behind the merge's early exit.)
+    const int sm = tid >> 5, sub = tid & 31;
+    const float2* sp = a.stats + ((size_t)b * H + kvh * G + min(sm, G - 1)) * a.n_parts;
+    constexpr unsigned long long kNeutral = 0x00000000ff800000ull;  // (-inf, 0)
+    const unsigned long long st0 = (sm < G && sub < a.n_parts) ? *reinterpret_cast<const unsigned long long*>(sp + sub) : kNeutral;
+    const int n = a.n_sel[b];
+    int iv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = tid + 256 * i, j = tr * a.tok_per_wg + t;
+        iv[i] = (t < a.tok_per_wg && j < a.k_tot) ? ib[j] : 0;
     }
-    {   // softmax maximum and normaliser of this workgroup's heads: four lanes per head merge the
-        // tile statistics in a fixed order
-        const int hl = tid >> 2, sub = tid & 3;
-        float2 st = make_float2(-INFINITY, 0.f);
-        if (hl < HB * G) {
-            const float2* sp = a.stats + ((size_t)b * H + hb * HB * G + hl) * a.n_parts;
-            for (int t0 = sub; t0 < a.n_parts; t0 += 32) {
-                float2 e[8];
+    asm volatile("" ::: "memory");
+    const int j_begin = min(n, tr * a.tok_per_wg), j_end = min(n, j_begin + a.tok_per_wg);
+    const int ntok = j_end - j_begin;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) e[i] = t0 + 4 * i < a.n_parts ? sp[t0 + 4 * i] : make_float2(-INFINITY, 0.f);
+    for (int i = 0; i < 4; ++i) {
+        const int t = tid + 256 * i;
+        if (t < ntok) sRow[t] = min(max(iv[i], 0), a.S_max - 1);
+    }
+    for (int t = tid + 1024; t < ntok; t += 256)  // long ranges: the rest, one load per round
+        sRow[t] = min(max(ib[tr * a.tok_per_wg + t], 0), a.S_max - 1);
+    {   // softmax maximum and normaliser per query head: the head's tile statistics merged in a fixed order
+        float2 st = make_float2(__uint_as_float((uint32_t)st0), __uint_as_float((uint32_t)(st0 >> 32)));
+        if (sm < G)
+            for (int t0 = sub + 32; t0 < a.n_parts; t0 += 32) st = stat_merge(st, sp[t0]);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) st = stat_merge(st, e[i]);
-            }
-        }
-        st = stat_merge(st, make_float2(__shfl_xor(st.x, 1, kWave), __shfl_xor(st.y, 1, kWave)));
-        st = stat_merge(st, make_float2(__shfl_xor(st.x, 2, kWave), __shfl_xor(st.y, 2, kWave)));
-        if (sub == 0 && hl < HB * G) sMZ[hl] = make_float2(st.x > -INFINITY ? st.x : 0.f, st.y > 0.f ? 1.f / st.y : 0.f);
+        for (int o = 1; o < 32; o <<= 1)
+            st = stat_merge(st, make_float2(__shfl_xor(st.x, o, kWave), __shfl_xor(st.y, o, kWave)));
+        if (sub == 0 && sm < G) sMZ[sm] = make_float2(st.x > -INFINITY ? st.x : 0.f, st.y > 0.f ? 1.f / st.y : 0.f);
     }
     __syncthreads();
     float2 mz[GMAX];
 #pragma unroll
-    for (int m = 0; m < GMAX; ++m) mz[m] = m < G ? sMZ[(kvh - hb * HB) * G + m] : make_float2(0.f, 0.f);
+    for (int m = 0; m < GMAX; ++m) mz[m] = m < G ? sMZ[m] : make_float2(0.f, 0.f);
 
     float acc[GMAX][kQvCh], bias[GMAX];
 #pragma unroll
@@ -159,13 +175,13 @@ __global__ __launch_bounds__(256) void attend_qv_kernel(QvArgs a)
     const T* vm = static_cast<const T*>(a.Vmeta) + ((size_t)b * a.S_max * n_groups + kvh * (kHeadDim / kQvGroup) + c0 / kQvGroup) * 2;
     const float* lg = a.logits + ((size_t)b * H + (size_t)kvh * G) * a.lk + j_begin;
 
-    for (int t0 = slot; t0 < ntok; t0 += TS * UN) {
+    for (int t0 = slot; t0 < ntok; t0 += kQvSlots * UN) {
         uint32_t cw[UN][NW];
         float2 sz[UN];
         float x[UN][GMAX];
 #pragma unroll
         for (int i = 0; i < UN; ++i) {
-            const int t = t0 + i * TS;
+            const int t = t0 + i * kQvSlots;
             const int tc = min(t, ntok - 1);  // a token past the range re-reads the last row with weight zero
             const size_t row = (size_t)sRow[tc];
             if (NW == 2) {
@@ -201,37 +217,22 @@ __global__ __launch_bounds__(256) void attend_qv_kernel(QvArgs a)
 #pragma unroll
         for (int c = 0; c < kQvCh; ++c) acc[m][c] += bias[m];
 
-    // the token slots' sums, added in slot order by the threads of slot 0
-    if (TS > 1) {  // uniform
-#pragma unroll
-        for (int m = 0; m < GMAX; ++m) {
-            if (m < G) {  // uniform
-                __syncthreads();
-#pragma unroll
-                for (int c = 0; c < kQvCh; ++c) red[tid][c] = acc[m][c];
-                __syncthreads();
-                if (slot == 0) {
-                    for (int s = 1; s < TS; ++s)
-#pragma unroll
-                        for (int c = 0; c < kQvCh; ++c) acc[m][c] += red[s * TPT + u][c];
-                }
-            }
-        }
-    }
-    if (slot != 0) return;
+    // the 32 token slots' sums: thread e < 128 adds channel e of the head over the slots, in slot order
 #pragma unroll
     for (int m = 0; m < GMAX; ++m) {
         if (m < G) {  // uniform
-            const int h = kvh * G + m;
-            if (a.n_tr > 1) {
-                float* dst = a.part + (((size_t)tr * a.B + b) * H + h) * kHeadDim + c0;
+            __syncthreads();
 #pragma unroll
-                for (int c = 0; c < kQvCh; c += 4)
-                    *reinterpret_cast<f32x4*>(dst + c) = f32x4{acc[m][c], acc[m][c + 1], acc[m][c + 2], acc[m][c + 3]};
-            } else {
-                T* dst = static_cast<T*>(a.out) + ((size_t)b * H + h) * kHeadDim + c0;
-#pragma unroll
-                for (int c = 0; c < kQvCh; ++c) elem<T>::store(dst + c, acc[m][c]);
+            for (int c = 0; c < kQvCh; ++c) red[tid][c] = acc[m][c];
+            __syncthreads();
+            if (tid < kHeadDim) {
+                const int uu = tid / kQvCh, cc = tid % kQvCh;
+                float s = 0.f;
+#pragma unroll 8
+                for (int sl = 0; sl < kQvSlots; ++sl) s += red[sl * kQvTpt + uu][cc];
+                const int h = kvh * G + m;
+                if (a.n_tr > 1) a.part[(((size_t)tr * a.B + b) * H + h) * kHeadDim + tid] = s;
+                else elem<T>::store(static_cast<T*>(a.out) + ((size_t)b * H + h) * kHeadDim + tid, s);
             }
         }
     }

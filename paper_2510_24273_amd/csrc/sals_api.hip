@@ -34,7 +34,7 @@ struct Layout {  // byte offsets into the workspace
     int lk;                      // logits row stride (floats)
     int max_parts;               // token tiles per head of the logits kernel, at most
     int pv_tok_per_wg, pv_ntr;   // value-sum token ranges
-    int qv_hb, qv_tok_per_wg, qv_ntr;  // quantised-value attention: KV heads per workgroup, token ranges
+    int qv_tok_per_wg, qv_ntr;   // quantised-value attention: token ranges
     int proj_np;                 // D-axis slices of the query projection
     int tm_chunks;               // chunks of the multi-workgroup selection (0: one workgroup per sequence)
     size_t w_section;            // elements per section of the packed weights
@@ -138,15 +138,10 @@ Layout make_layout(const sals_desc& d)
     L.stats = take((size_t)d.B * d.H_q * L.max_parts * 8);
     L.rope = take((size_t)(d.S_max + 1) * kPairs * 8);  // positions 0 .. S_max (the query after a full cache)
     L.tpart = take((size_t)L.pv_ntr * d.B * d.H_q * d.r * 4);
-    {   // quantised-value attention: KV heads per workgroup = the largest power of two <= 32 dividing
-        // H_kv; token ranges until about 512 workgroups exist, at least 8 tokens per slot and range
-        int hb = 1;
-        while (hb < 32 && d.H_kv % (hb * 2) == 0) hb *= 2;
-        const int slots = 256 / (hb * (kHeadDim / kQvCh));
-        int n_tr = std::min(kQvMaxRanges, ceil_div(512, d.B * (d.H_kv / hb)));
-        n_tr = std::max(1, std::min(n_tr, k_tot / (8 * slots)));
+    {   // quantised-value attention: one workgroup per (sequence, token range, KV head), 32 tokens side
+        // by side; a second range (and with it the merge launch) only pays above ~32 tokens per slot
+        int n_tr = k_tot <= 32 * kQvSlots ? 1 : std::min(kQvMaxRanges, ceil_div(k_tot, 16 * kQvSlots));
         n_tr = std::max(n_tr, ceil_div(k_tot, kQvMaxTok));
-        L.qv_hb = hb;
         L.qv_tok_per_wg = ceil_div(k_tot, n_tr);
         L.qv_ntr = ceil_div(k_tot, L.qv_tok_per_wg);
         L.qv_part = take((size_t)L.qv_ntr * d.B * d.H_q * kHeadDim * 4);
@@ -348,8 +343,8 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
         ProfScope ps(c, SALS_K_ATTEND_QV, st);
         QvArgs a{static_cast<const unsigned char*>(qv->codes), qv->meta, idx, n_sel, logits, stats,
                  reinterpret_cast<float*>(c->ws + L.qv_part), out, n_parts, d.B, d.S_max, d.H_q, d.H_kv, k_tot, L.lk,
-                 L.qv_tok_per_wg, L.qv_ntr, L.qv_hb};
-        const dim3 grid(L.qv_ntr, d.H_kv / L.qv_hb, d.B);
+                 L.qv_tok_per_wg, L.qv_ntr};
+        const dim3 grid(L.qv_ntr * d.H_kv * d.B);
         const int G = d.H_q / d.H_kv;
 #define SALS_QV(BITS, GMAX) hipLaunchKernelGGL((attend_qv_kernel<T, BITS, GMAX>), grid, dim3(256), 0, st, a)
 #define SALS_QV_G(BITS)                                                                                 \
