@@ -95,5 +95,21 @@ def test_create_checks_workspace_and_calls_check_pointers(sb):
     assert lib.sals_pack_weights(h, ok, ok, None, None) == sb.SALS_ERR_INVALID_ARG
     assert lib.sals_pack_weights(h, ok, ok, ok + 16, None) == sb.SALS_ERR_INVALID_ARG   # W not 256-aligned
     assert sb.packed_weight_bytes(d) == 4 * 8 * 128 * 512 * 2
+    # quantised value cache: sizes, and argument checks ahead of any launch
+    assert sb.qv_row_bytes(d, 4) == (8 * 128 // 2, 8 * 128 // 32 * 2 * 2)
+    assert sb.qv_row_bytes(d, 2) == (8 * 128 // 4, 8 * 128 // 32 * 2 * 2)
+    assert sb.qv_row_bytes(_desc(sb, dtype="f32"), 4)[1] == 8 * 128 // 32 * 2 * 4
+    with pytest.raises(sb.SalsError) as e:
+        sb.qv_row_bytes(d, 3)
+    assert e.value.code == sb.SALS_ERR_UNSUPPORTED
+    assert lib.sals_compress_append_qv(h, ok, ok, ok, ok, ok, ok, 8, ok, None) == sb.SALS_ERR_UNSUPPORTED
+    assert lib.sals_compress_append_qv(h, ok, ok, ok, ok, None, ok, 4, ok, None) == sb.SALS_ERR_INVALID_ARG
+    assert lib.sals_compress_append_qv(h, ok, ok, ok, ok, ok, ok, 4, None, None) == sb.SALS_ERR_INVALID_ARG
+    assert lib.sals_sparse_attend_qv(h, ok, ok, ok, ok, ok, 1, ok, ok, ok, ok, None) == sb.SALS_ERR_UNSUPPORTED
+    assert lib.sals_sparse_attend_qv(h, ok, ok, ok, ok + 8, ok, 4, ok, ok, ok, ok, None) == sb.SALS_ERR_INVALID_ARG
+    assert lib.sals_decode_step_qv(h, ok, ok, ok, ok, None, 2, ok, ok, ok, None, None, None, None) \
+        == sb.SALS_ERR_INVALID_ARG
+    assert lib.sals_decode_step_qv(h, ok, ok, ok, ok, ok, 16, ok, ok, ok, None, None, None, None) \
+        == sb.SALS_ERR_UNSUPPORTED
     lib.sals_destroy(h)
     lib.sals_destroy(None)
