@@ -275,3 +275,20 @@ def sparse_attend_qv(q, q_pos, Kc, Uk, codes, scale, zero, idx, H_kv, theta, rop
     V_C = dequantize_values(np.asarray(codes)[idx], np.asarray(scale)[idx],
                             np.asarray(zero)[idx]).reshape(n, H_kv, d)
     return attend(qR, KR, V_C)
+
+
+# ---------------------------------------------------------------------------
+# Dense decode attention, the baseline the paper measures against (Sec. 5.3,
+# Table 6: attention over the whole full-rank cache).  K is the cache as a
+# dense model keeps it, keys already rotated at their positions.
+# ---------------------------------------------------------------------------
+
+def dense_decode(q, q_pos, KR, V, theta, rope_style=0):
+    """q [H,d] pre-RoPE, KR [S,H_kv,d] rotated keys, V [S,H_kv,d] -> y [H,d]:
+    softmax(RoPE(q, q_pos) . KR^T / sqrt(d)) V over all S tokens (Eq. 5 with C = everything)."""
+    q = np.asarray(q, dtype=np.float64)
+    H, d = q.shape
+    if np.asarray(KR).shape[0] == 0:
+        return np.zeros((H, d))
+    qR = rope(q.reshape(1, H, d), [q_pos], theta, rope_style).reshape(H, d)
+    return attend(qR, KR, V)

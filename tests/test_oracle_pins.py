@@ -377,6 +377,20 @@ def test_planted_tokens_are_selected(oracle):
     assert set(np.argsort(-out["s"])[:3].tolist()) == set(L["planted"][0].tolist())
 
 
+def test_dense_decode_matches_brute_force(oracle):
+    """The dense baseline over a cache of rotated keys equals dense RoPE attention written with
+    complex rotations on the pre-RoPE keys (GQA, odd length)."""
+    rng = np.random.default_rng(33)
+    H, H_kv, d, S, theta = 6, 2, 16, 23, 1e4
+    q = rng.standard_normal((H, d))
+    K = rng.standard_normal((S, H_kv, d))
+    V = rng.standard_normal((S, H_kv, d))
+    KR = np.stack([_rope_complex(K[t], t, theta) for t in range(S)])
+    y = oracle.dense_decode(q, S + 3, KR, V, theta)
+    np.testing.assert_allclose(y, dense_rope_attention(q, K, V, S + 3, theta), rtol=0, atol=1e-12)
+    assert not oracle.dense_decode(q, 0, KR[:0], V[:0], theta).any()
+
+
 def test_traffic_model_fixture():
     """Sec. 4.5: full attention moves 2sd, SALS s r* + 2kr; the printed speed-up range
     7.69x..14.28x is the reciprocal of Table 2's memory-access column 0.13 / 0.07."""
