@@ -36,6 +36,8 @@ def parse():
                     help="other configurations reported under 'extra' (comma list, '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-dense", action="store_true",
+                    help="skip the dense-attention baseline (full-rank cache of the same shape) timed beside each workload")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB (a kernel of known HBM "
                          "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -89,6 +91,60 @@ class LayerSet:
 
     def bytes_resident(self):
         return sum(t.numel() * t.element_size() for G in self.layers for t in G.values())
+
+
+class DenseSet:
+    """Device-resident full-rank caches (keys as a dense model keeps them: already rotated) for the dense
+    baseline at a workload's shape, generated on the device (seeded), + one context."""
+
+    def __init__(self, w, n_layers, torch, binding):
+        self.w, self.torch = w, torch
+        dev = "cuda:0"
+        desc = binding.make_desc(w.B, w.S, w.H, w.H_kv, w.d, w.r, w.top_k, w.dtype, rope_theta=w.theta,
+                                 rope_style=w.rope_style)
+        self.ctx = binding.Sals(desc, dev)
+        dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(10_000 * w.cfg_id + 79)
+        self.layers = []
+        for _ in range(n_layers):
+            self.layers.append({
+                "q": torch.randn((w.B, w.H, w.d), generator=gen, device=dev, dtype=torch.float32).to(dt),
+                "K": torch.randn((w.B, w.S, w.H_kv, w.d), generator=gen, device=dev, dtype=dt),
+                "V": torch.randn((w.B, w.S, w.H_kv, w.d), generator=gen, device=dev, dtype=dt),
+            })
+        self.seq_len = torch.full((w.B,), w.S, dtype=torch.int32, device=dev)
+        self.out = [torch.empty((w.B, w.H, w.d), dtype=dt, device=dev) for _ in range(n_layers)]
+        torch.cuda.synchronize()
+
+    def step(self):
+        for G, o in zip(self.layers, self.out):
+            self.ctx.dense_attend(G["q"], self.seq_len, G["K"], G["V"], self.seq_len, o)
+
+
+def measure_dense(w, steps, warmup, use_graph, torch, binding):
+    """us per layer-step of the dense baseline at w's shape (best of eager and graph replay) and its
+    achieved HBM rate over the 2*B*S*D_kv cache elements it has to read."""
+    per = 2 * w.B * w.S * w.D_kv * w.esize
+    nl = max(2, min(8, int(600e6 // per) + 1))
+    ds = DenseSet(w, nl, torch, binding)
+    ms = timed(torch, ds.step, steps, warmup)
+    if use_graph:
+        g = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            ds.step()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(g, stream=s):
+                ds.step()
+        torch.cuda.synchronize()
+        ms = min(ms, timed(torch, g.replay, steps, warmup))
+    us = ms * 1e3 / nl
+    del ds
+    torch.cuda.empty_cache()
+    return {"us_per_layer_step": round(us, 2), "cache_bytes": per, "achieved_GBps": round(per / (us * 1e-6) / 1e9, 1),
+            "hbm_frac": round(per / (us * 1e-6) / 1e9 / 8000.0, 4)}
 
 
 def timed(torch, fn, steps, warmup):
@@ -253,6 +309,12 @@ def main():
                      "avg_us_events": dk["us_events"], "event_gap_us": round(res["event_gap_us"], 3)},
         "kernels": kern,
     }
+    dense_done = {}
+    if not a.no_dense:
+        log("[bench] dense baseline at the same shape")
+        out["dense_baseline"] = measure_dense(w, max(5, a.steps // 2), 2, not a.no_graph, torch, binding)
+        out["dense_baseline"]["speedup_of_sals"] = round(out["dense_baseline"]["us_per_layer_step"] / out["value"], 3)
+        dense_done[(w.B, w.S, w.H, w.H_kv, w.dtype)] = out["dense_baseline"]
     if not a.no_cpu_baseline:
         log("[bench] timing the CPU oracle")
         host = [ls.host0] + [synth.make_layer(w, l) for l in range(1, min(3, n_layers))] if w.B == 1 else [ls.host0]
@@ -274,6 +336,13 @@ def main():
                        "kernels_frac": {k: v["frac"] for k, v in r["kernels"].items()}}
         del lse
         torch.cuda.empty_cache()
+        if not a.no_dense:
+            key = (we.B, we.S, we.H, we.H_kv, we.dtype)
+            if key not in dense_done:
+                dense_done[key] = measure_dense(we, max(5, a.steps // 3), 2, not a.no_graph, torch, binding)
+            extra[name]["dense_us_per_layer_step"] = dense_done[key]["us_per_layer_step"]
+            extra[name]["dense_hbm_frac"] = dense_done[key]["hbm_frac"]
+            extra[name]["speedup_vs_dense"] = round(dense_done[key]["us_per_layer_step"] / r["us_per_layer_step"], 3)
     if extra:
         out["extra"] = extra
     print(json.dumps(out), flush=True)

@@ -218,6 +218,18 @@ sals_status sals_decode_step_qv(sals_ctx* ctx, const void* q, const int32_t* q_p
                                 const void* W, const int32_t* seq_len, void* out, float* scores,
                                 int32_t* idx, int32_t* n_sel, void* hip_stream);
 
+/* ---- dense baseline -----------------------------------------------------------------
+ * Dense decode attention over a full-rank KV cache, the baseline the paper quotes its
+ * speed-ups against (Sec. 5.3, Table 6), for comparisons on the same hardware:
+ *   out[b,h] = softmax_j( RoPE(q[b,h], q_pos[b]) . K[b,j,g(h)] / sqrt(d) ) V[b,j,g(h)],  j < seq_len[b]
+ * with every cached token attended (Eq. 5 with the selected set = everything).  K holds the
+ * keys as a dense model caches them, already rotated at their positions; fp32 online softmax,
+ * one rounding to T.  out[b] is zero when seq_len[b] == 0.
+ *   q [B,H_q,d] T pre-RoPE;  q_pos [B] int32;  K, V [B,S_max,H_kv,d] T;  seq_len [B] int32;
+ *   out [B,H_q,d] T */
+sals_status sals_dense_attend(sals_ctx* ctx, const void* q, const int32_t* q_pos, const void* K,
+                              const void* V, const int32_t* seq_len, void* out, void* hip_stream);
+
 /* ---- measurement aid --------------------------------------------------------------
  * Per-stage timing for roofline figures.  While enabled, every stage below (one kernel;
  * for the selection of sequences above 32768 tokens a chain of four) is bracketed by a
@@ -233,7 +245,8 @@ enum {
     SALS_K_ATTEND_PV = 4,      /* softmax + latent-space value sum             */
     SALS_K_ATTEND_OUT = 5,     /* output projection through U_v                */
     SALS_K_ATTEND_QV = 6,      /* softmax + sum over the quantised value cache */
-    SALS_N_KERNELS = 7
+    SALS_K_DENSE = 7,          /* dense baseline attention (+ its chunk merge)  */
+    SALS_N_KERNELS = 8
 };
 const char* sals_kernel_name(int kernel);
 sals_status sals_profile_enable(sals_ctx* ctx, int on);

@@ -28,8 +28,9 @@ EXPORTS = (
     "sals_decode_step", "sals_kernel_name", "sals_profile_enable", "sals_profile_collect",
     "sals_packed_weight_bytes", "sals_pack_weights",
     "sals_qv_row_bytes", "sals_compress_append_qv", "sals_sparse_attend_qv", "sals_decode_step_qv",
+    "sals_dense_attend",
 )
-N_KERNELS = 7
+N_KERNELS = 8
 
 
 class SalsDesc(ctypes.Structure):
@@ -69,6 +70,7 @@ def load_library() -> ctypes.CDLL:
     lib.sals_compress_append_qv.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, i32p, vp]
     lib.sals_sparse_attend_qv.argtypes = [vp, vp, i32p, vp, vp, vp, ctypes.c_int, vp, i32p, i32p, vp, vp]
     lib.sals_decode_step_qv.argtypes = [vp, vp, i32p, vp, vp, vp, ctypes.c_int, vp, i32p, vp, f32p, i32p, i32p, vp]
+    lib.sals_dense_attend.argtypes = [vp, vp, i32p, vp, vp, i32p, vp, vp]
     lib.sals_kernel_name.restype = ctypes.c_char_p
     lib.sals_kernel_name.argtypes = [ctypes.c_int]
     lib.sals_profile_enable.argtypes = [vp, ctypes.c_int]
@@ -206,3 +208,8 @@ class Sals:
         self._check(_lib.sals_decode_step_qv(self._h, _p(q), _p(q_pos), _p(Kc), _p(Vq), _p(Vmeta), int(bits), _p(W),
                                              _p(seq_len), _p(out), _p(scores), _p(idx), _p(n_sel), _stream()),
                     "sals_decode_step_qv")
+
+    # ---- dense baseline over a full-rank cache of rotated keys ----
+    def dense_attend(self, q, q_pos, K, V, seq_len, out):
+        self._check(_lib.sals_dense_attend(self._h, _p(q), _p(q_pos), _p(K), _p(V), _p(seq_len), _p(out),
+                                           _stream()), "sals_dense_attend")

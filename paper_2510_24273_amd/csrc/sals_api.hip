@@ -12,6 +12,7 @@
 
 #include "common.hpp"
 #include "k_attend.hpp"
+#include "k_dense.hpp"
 #include "k_logits.hpp"
 #include "k_logits_small.hpp"
 #include "k_project.hpp"
@@ -30,11 +31,12 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Layout {  // byte offsets into the workspace
-    size_t qt, scores, idx, n_sel, logits, stats, rope, tpart, qv_part, tm_part, tm_hist, tm_meta, tm_cand, total;
+    size_t qt, scores, idx, n_sel, logits, stats, rope, tpart, qv_part, dn_part, tm_part, tm_hist, tm_meta, tm_cand, total;
     int lk;                      // logits row stride (floats)
     int max_parts;               // token tiles per head of the logits kernel, at most
     int pv_tok_per_wg, pv_ntr;   // value-sum token ranges
     int qv_tok_per_wg, qv_ntr;   // quantised-value attention: token ranges
+    int dn_chunks, dn_tok;       // dense baseline: token chunks per sequence, tokens per chunk
     int proj_np;                 // D-axis slices of the query projection
     int tm_chunks;               // chunks of the multi-workgroup selection (0: one workgroup per sequence)
     size_t w_section;            // elements per section of the packed weights
@@ -59,7 +61,7 @@ struct sals_ctx {
 namespace {
 
 const char* const kKernelNames[SALS_N_KERNELS] = {
-    "project", "scores", "topk", "attend_logits", "attend_pv", "attend_out", "attend_qv"};
+    "project", "scores", "topk", "attend_logits", "attend_pv", "attend_out", "attend_qv", "dense_attend"};
 
 // Brackets one kernel launch with a pair of events while profiling is on.
 struct ProfScope {
@@ -145,6 +147,13 @@ Layout make_layout(const sals_desc& d)
         L.qv_tok_per_wg = ceil_div(k_tot, n_tr);
         L.qv_ntr = ceil_div(k_tot, L.qv_tok_per_wg);
         L.qv_part = take((size_t)L.qv_ntr * d.B * d.H_q * kHeadDim * 4);
+    }
+    {   // dense baseline: token chunks until about 2048 workgroups stream the cache, 256 tokens at least
+        int n = std::min(kDnMaxChunks, std::max(1, ceil_div(2048, d.B * d.H_kv)));
+        n = std::max(1, std::min(n, d.S_max / 256));
+        L.dn_tok = ceil_div(ceil_div(d.S_max, n), 16) * 16;
+        L.dn_chunks = ceil_div(d.S_max, L.dn_tok);
+        L.dn_part = take((size_t)d.B * d.H_q * L.dn_chunks * kDnRec * 4);
     }
     // long sequences: selection spread over 8192-score chunks
     L.tm_chunks = d.S_max > 32768 ? ceil_div(d.S_max, kTmChunk) : 0;
@@ -261,6 +270,42 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
     return launch_status();
 }
 
+// first use of a context: cos/sin of every cache position 0 .. S_max, ahead of the kernels that read it
+sals_status ensure_rope_table(const sals_ctx* c, hipStream_t st)
+{
+    if (c->rope_ready) return SALS_OK;
+    const size_t n = (size_t)(c->d.S_max + 1) * kPairs;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                       reinterpret_cast<float2*>(c->ws + c->L.rope), c->inv, c->d.S_max + 1);
+    if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+    const_cast<sals_ctx*>(c)->rope_ready = true;
+    return SALS_OK;
+}
+
+template <typename T>
+sals_status launch_dense(const sals_ctx* c, const void* q, const int32_t* q_pos, const void* K, const void* V,
+                         const int32_t* seq_len, void* out, hipStream_t st)
+{
+    const sals_desc& d = c->d;
+    const Layout& L = c->L;
+    if (ensure_rope_table(c, st) != SALS_OK) return SALS_ERR_HIP;
+    float* part = reinterpret_cast<float*>(c->ws + L.dn_part);
+    const float2* rope = reinterpret_cast<const float2*>(c->ws + L.rope);
+    const int G = d.H_q / d.H_kv;
+    const dim3 grid(L.dn_chunks, d.H_kv, d.B);
+    ProfScope ps(c, SALS_K_DENSE, st);
+#define SALS_DENSE(GMAX)                                                                                   \
+    hipLaunchKernelGGL((dense_attend_kernel<T, GMAX>), grid, dim3(256), 0, st, static_cast<const T*>(q), q_pos, \
+                       static_cast<const T*>(K), static_cast<const T*>(V), seq_len, rope, c->inv, part, d.S_max, \
+                       d.H_q, d.H_kv, L.dn_chunks, L.dn_tok, d.rope_style, 1.0f / std::sqrt((float)d.d))
+    if (G <= 1) SALS_DENSE(1); else if (G <= 2) SALS_DENSE(2); else if (G <= 4) SALS_DENSE(4); else SALS_DENSE(8);
+#undef SALS_DENSE
+    if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+    hipLaunchKernelGGL((dense_merge_kernel<T>), dim3(d.B * d.H_q), dim3(128), 0, st, part, static_cast<T*>(out),
+                       L.dn_chunks);
+    return launch_status();
+}
+
 struct QvCache { const void* codes; const void* meta; int bits; };  // quantised full-rank value cache
 
 // qv == nullptr: latent value cache Vc, value sum in latent space and output projection through U_v.
@@ -278,13 +323,7 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     const float2* rope = reinterpret_cast<const float2*>(c->ws + L.rope);
     float* tpart = reinterpret_cast<float*>(c->ws + L.tpart);
     int n_parts = 0;
-    if (!c->rope_ready) {  // first use of the context: cos/sin of every cache position, ahead of the logits
-        const size_t n = (size_t)(d.S_max + 1) * kPairs;
-        hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                           reinterpret_cast<float2*>(c->ws + L.rope), c->inv, d.S_max + 1);
-        if (launch_status() != SALS_OK) return SALS_ERR_HIP;
-        const_cast<sals_ctx*>(c)->rope_ready = true;
-    }
+    if (ensure_rope_table(c, st) != SALS_OK) return SALS_ERR_HIP;
     {   // logits: the largest tile (most operand reuse) that still gives the chip enough workgroups
         auto n_wg = [&](int heads, int tok) { return (long long)ceil_div(k_tot, tok) * (d.H_kv / heads) * d.B; };
         // replicate the smaller operand across the XCDs' L2s: all of U_k, or the gathered rows
@@ -617,6 +656,15 @@ sals_status sals_decode_step_qv(sals_ctx* ctx, const void* q, const int32_t* q_p
     s = sals_topk_select(ctx, scores, seq_len, idx, n_sel, hip_stream);
     if (s != SALS_OK) return s;
     return sals_sparse_attend_qv(ctx, q, q_pos, Kc, Vq, Vmeta, bits, W, idx, n_sel, out, hip_stream);
+}
+
+sals_status sals_dense_attend(sals_ctx* ctx, const void* q, const int32_t* q_pos, const void* K, const void* V,
+                              const int32_t* seq_len, void* out, void* hip_stream)
+{
+    if (!ctx || bad(q) || !q_pos || bad(K) || bad(V) || !seq_len || bad(out)) return SALS_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    return ctx->d.dtype == SALS_BF16 ? launch_dense<bf16_t>(ctx, q, q_pos, K, V, seq_len, out, st)
+                                     : launch_dense<float>(ctx, q, q_pos, K, V, seq_len, out, st);
 }
 
 }  // extern "C"

@@ -240,3 +240,16 @@ def make_qv_cache(w: Workload, layer: int, bits: int):
     zero = -2.0 + 0.5 * rng.standard_normal((w.B, w.S, ng), dtype=np.float32)
     meta = store(np.stack([scale, zero], axis=-1), w.dtype)
     return codes, meta
+
+
+# ---- dense baseline: a full-rank cache as a dense model keeps it ------------------------
+
+def make_dense_cache(w: Workload, layer: int = 0):
+    """q [B,H,d] and a full-rank cache K, V [B,S,H_kv,d], storage-rounded.  K stands for keys
+    already rotated at their positions (a rotation leaves the N(0,1) entries N(0,1)); with q
+    also N(0,1) the logits have unit variance after the 1/sqrt(d)."""
+    rng = np.random.default_rng(seed_of(w, layer, 79))
+    q = rng.standard_normal((w.B, w.H, w.d))
+    K = rng.standard_normal((w.B, w.S, w.H_kv, w.d), dtype=np.float32)
+    V = rng.standard_normal((w.B, w.S, w.H_kv, w.d), dtype=np.float32)
+    return {"q": store(q, w.dtype), "K": store(K, w.dtype), "V": store(V, w.dtype)}

@@ -111,5 +111,7 @@ def test_create_checks_workspace_and_calls_check_pointers(sb):
         == sb.SALS_ERR_INVALID_ARG
     assert lib.sals_decode_step_qv(h, ok, ok, ok, ok, ok, 16, ok, ok, ok, None, None, None, None) \
         == sb.SALS_ERR_UNSUPPORTED
+    assert lib.sals_dense_attend(h, ok, ok, ok, None, ok, ok, None) == sb.SALS_ERR_INVALID_ARG
+    assert lib.sals_dense_attend(h, ok, None, ok, ok, ok, ok, None) == sb.SALS_ERR_INVALID_ARG
     lib.sals_destroy(h)
     lib.sals_destroy(None)
