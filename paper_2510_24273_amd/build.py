@@ -39,7 +39,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if not force and not is_stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB] + sources()
+    cmd = [hipcc] + HIPCC_FLAGS + os.environ.get("SALS_EXTRA_FLAGS", "").split() + ["-o", LIB] + sources()
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
