@@ -59,10 +59,10 @@ def stage_flops(w, seq_len=None) -> dict:
 # summaries profiles/hbm_traffic_<workload>.txt.  The scaling assumes full 128-byte requests, so
 # kernels that fetch 64-byte pieces are over-counted by up to 2x.
 MEASURED_TRAFFIC: dict = {
-    ("cfg2", "attend_logits"): 12_818_000, ("cfg2", "attend_out"): 6_739_000, ("cfg2", "scores"): 5_479_000,
-    ("cfg2", "project"): 5_454_000, ("cfg2", "attend_pv"): 2_352_000, ("cfg2", "topk"): 35_000,
-    ("cfg3a", "attend_logits"): 100_025_000, ("cfg3a", "scores"): 86_832_000, ("cfg3a", "attend_pv"): 31_308_000,
-    ("cfg3a", "attend_out"): 16_032_000, ("cfg3a", "project"): 6_746_000, ("cfg3a", "topk"): 430_000,
-    ("cfg4", "scores"): 169_029_000, ("cfg4", "attend_logits"): 100_032_000, ("cfg4", "attend_pv"): 31_308_000,
-    ("cfg4", "attend_out"): 15_936_000, ("cfg4", "project"): 5_714_000, ("cfg4", "topk"): 768_000,
+    ("cfg2", "attend_logits"): 12_828_000, ("cfg2", "attend_out"): 5_709_000, ("cfg2", "scores"): 5_480_000,
+    ("cfg2", "project"): 5_454_000, ("cfg2", "attend_pv"): 1_310_000, ("cfg2", "topk"): 35_000,
+    ("cfg3a", "attend_logits"): 100_014_000, ("cfg3a", "scores"): 86_831_000, ("cfg3a", "attend_pv"): 14_366_000,
+    ("cfg3a", "attend_out"): 8_125_000, ("cfg3a", "project"): 6_745_000, ("cfg3a", "topk"): 428_000,
+    ("cfg4", "scores"): 169_028_000, ("cfg4", "attend_logits"): 100_022_000, ("cfg4", "attend_pv"): 14_217_000,
+    ("cfg4", "attend_out"): 7_699_000, ("cfg4", "project"): 5_713_000, ("cfg4", "topk"): 763_000,
 }
