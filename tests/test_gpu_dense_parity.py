@@ -70,6 +70,11 @@ def test_interleaved_rope_and_query_beyond_the_table(oracle):
     _case(oracle, w, q_pos=[w.S + 1, 1_000_003])
 
 
+def test_maximum_cache_length(oracle):
+    """2^20 cached tokens (64 chunks of 16384)."""
+    _case(oracle, synth.shrink(SMALL, B=1, S=1 << 20, H=8, H_kv=1, r=64))
+
+
 def test_cfg2_shape_full(oracle):
     _case(oracle, C["cfg2"])
 

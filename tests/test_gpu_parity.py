@@ -163,6 +163,21 @@ def test_long_sequence_selection(oracle, case):
     ctx.close()
 
 
+def test_maximum_sizes(oracle):
+    """The descriptor's upper limits in one case: a 2^20-row cache (128 selection chunks, the largest
+    cos/sin table), 65536 selected tokens with sinks and a recent window, at the smallest rank."""
+    w = synth.shrink(SMALL, B=1, S=1 << 20, H=8, H_kv=1, r=64, top_k=65536 - 16 - 64, n_sink=16, n_recent=64,
+                     plant=0)
+    _run(oracle, w, label="max S_max and k_tot")
+
+
+def test_maximum_rank_and_batch_columns(oracle):
+    """r = r_score = 1024 (the largest rank), and B * (H_q / H_kv) = 128 (the widest projection)."""
+    _run(oracle, synth.shrink(SMALL, B=2, S=700, r=1024, plant=0), seq_lens=[700, 257], label="r=1024")
+    _run(oracle, synth.shrink(SMALL, B=16, S=300, H=8, H_kv=1, r=128, top_k=40, plant=0), seqs=[0, 15],
+         label="B*G=128")
+
+
 def test_compress_append_then_decode(oracle):
     """Algorithm 1 in order: compress the new token, append, then attend with the query on
     the appended row (q_pos = seq_len - 1)."""

@@ -87,6 +87,12 @@ def test_many_token_ranges_and_window(oracle):
     _attend_case(oracle, w, 2)
 
 
+def test_maximum_sizes(oracle):
+    """2^20 cache rows and 65536 selected tokens (32 token ranges of 2048)."""
+    w = synth.shrink(SMALL, B=1, S=1 << 20, H=8, H_kv=1, r=64, top_k=65536 - 16 - 64, n_sink=16, n_recent=64)
+    _attend_case(oracle, w, 4)
+
+
 def test_cfg2_full(oracle):
     _attend_case(oracle, C["cfg2"], 4)
 
