@@ -119,11 +119,13 @@ Layout make_layout(const sals_desc& d)
         L.proj_np = np;
     }
     // value sum: split the selected tokens into ranges of whole 64-token steps (at least two steps, at
-    // most kPvMaxTok tokens) until about 256 workgroups exist
+    // most kPvMaxTok tokens) as long as every workgroup still gets a CU of its own (measured: a few CUs
+    // with two workgroups set the kernel's duration)
     {
         int blocks = d.r / kPvCols;
-        int want = ceil_div(256, blocks * d.B);
+        int want = std::max(1, 256 / (blocks * d.B));
         int n_tr = std::max(1, std::min(std::min(want, kMaxRanges), ceil_div(k_tot, 2 * kPvTJ)));
+        if (const char* e = std::getenv("SALS_TUNE_PV_RANGES")) n_tr = std::max(1, std::atoi(e));  // tuning aid
         n_tr = std::max(n_tr, ceil_div(k_tot, kPvMaxTok));
         int tok = ceil_div(ceil_div(k_tot, n_tr), kPvTJ) * kPvTJ;
         L.pv_tok_per_wg = tok;
