@@ -347,8 +347,15 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
                            d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk, n_parts, heads_fastest, d.rope_style,   \
                            1.0f / std::sqrt((float)d.d));                                                    \
     } while (0)
-        if (d.H_kv % 2 == 0 && n_wg(2, 256) >= 384) SALS_LOGITS(2, 4, 2);   // 2 heads x 256 tokens, 8 waves
-        else if (n_wg(1, 256) >= 200) SALS_LOGITS(1, 4, 2);                 // 1 head  x 256 tokens
+        // the 64-token kernel while its workgroups fit the chip in one round (or too few large tiles exist)
+        int pick = (d.H_kv % 2 == 0 && n_wg(2, 256) >= 384) ? 1 : ((n_wg(1, 64) > 256 && n_wg(1, 256) >= 96) ? 2 : 3);
+        if (const char* e = std::getenv("SALS_TUNE_LOGITS")) {  // tuning aid: 1 | 2 | 3
+            const int v = std::atoi(e);
+            if (v == 1 && d.H_kv % 2 == 0) pick = 1;
+            if (v == 2 || v == 3) pick = v;
+        }
+        if (pick == 1) SALS_LOGITS(2, 4, 2);        // 2 heads x 256 tokens, 8 waves
+        else if (pick == 2) SALS_LOGITS(1, 4, 2);   // 1 head  x 256 tokens
         else {  // few tiles: 1 head x 64 tokens with the whole latent axis loaded ahead
             const int nkc = d.r * (int)sizeof(T) / kLgChunk;
             int nst = kLsMaxChunk;  // steps loaded ahead: the largest divisor of the step count
