@@ -125,7 +125,7 @@ Layout make_layout(const sals_desc& d)
         int blocks = d.r / kPvCols;
         int want = std::max(1, 256 / (blocks * d.B));
         int n_tr = std::max(1, std::min(std::min(want, kMaxRanges), ceil_div(k_tot, 2 * kPvTJ)));
-        if (const char* e = std::getenv("SALS_TUNE_PV_RANGES")) n_tr = std::max(1, std::atoi(e));  // tuning aid
+        if (const char* e = std::getenv("SALS_TUNE_PV_RANGES")) n_tr = std::max(1, std::min(64, std::atoi(e)));  // tuning aid
         n_tr = std::max(n_tr, ceil_div(k_tot, kPvMaxTok));
         int tok = ceil_div(ceil_div(k_tot, n_tr), kPvTJ) * kPvTJ;
         L.pv_tok_per_wg = tok;
@@ -218,7 +218,7 @@ sals_status launch_scores(const sals_ctx* c, const void* Kc, const int32_t* seq_
     // rows per workgroup: a multiple of 16 giving roughly 1024 workgroups, 16..128 rows (measured optimum)
     long long total_rows = (long long)d.B * d.S_max;
     int rows = (int)std::min<long long>(128, std::max<long long>(16, total_rows / 1024));
-    if (const char* e = std::getenv("SALS_TUNE_SCORE_ROWS")) rows = std::atoi(e);  // tuning aid
+    if (const char* e = std::getenv("SALS_TUNE_SCORE_ROWS")) rows = std::max(16, std::min(1 << 16, std::atoi(e)));  // tuning aid
     rows = ceil_div(rows, kScoreRowsPerIter) * kScoreRowsPerIter;
     dim3 grid(ceil_div(d.S_max, rows), d.B);
     const float* qt = reinterpret_cast<const float*>(c->ws + c->L.qt);
