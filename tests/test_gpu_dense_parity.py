@@ -60,7 +60,7 @@ def test_empty_and_single_token_sequences(oracle):
     _case(oracle, synth.shrink(SMALL, B=4), seq_lens=[0, 1, 16, 17])
 
 
-@pytest.mark.parametrize("H_kv,H", [(8, 32), (4, 32), (2, 4), (1, 8), (3, 6)])
+@pytest.mark.parametrize("H_kv,H", [(8, 32), (4, 32), (2, 4), (1, 8), (3, 6), (64, 64), (8, 64)])
 def test_gqa_groups(oracle, H_kv, H):
     _case(oracle, synth.shrink(SMALL, B=2, S=600, H=H, H_kv=H_kv), seq_lens=[600, 333])
 

@@ -74,6 +74,13 @@ def test_gqa_groups(oracle):
         _run(oracle, w, seq_lens=[600, 333], label=f"gqa H={H} H_kv={H_kv}")
 
 
+def test_sixty_four_query_heads(oracle):
+    """H_q = 64, the most the kernels take: as 64 KV heads, and as 8 groups of 8."""
+    for H_kv in (64, 8):
+        w = synth.shrink(SMALL, H=64, H_kv=H_kv, B=2, S=500, plant=0)
+        _run(oracle, w, seq_lens=[500, 129], label=f"H=64 H_kv={H_kv}")
+
+
 def test_truncated_scoring_rank(oracle):
     w = synth.shrink(SMALL, r=256, r_score=128, B=2)
     _run(oracle, w, seq_lens=[1000, 500])
