@@ -74,6 +74,16 @@ def test_gqa_groups(oracle):
         _run(oracle, w, seq_lens=[600, 333], label=f"gqa H={H} H_kv={H_kv}")
 
 
+def test_odd_sizes(oracle):
+    """A cache capacity that is not a multiple of 4 (score rows of later sequences start unaligned), an odd
+    selection budget, an odd multiple of 8 as scoring rank."""
+    w = synth.shrink(SMALL, B=3, S=997, top_k=97, n_sink=3, n_recent=5, r=192, r_score=72, plant=0)
+    _run(oracle, w, seq_lens=[997, 501, 106], label="S_max=997")
+    for dtype in ("bf16", "f32"):
+        wq = synth.shrink(w, dtype=dtype)
+        _run(oracle, wq, seq_lens=[997, 104, 105], label=f"S_max=997 {dtype}, cache barely longer than the selection")
+
+
 def test_sixty_four_query_heads(oracle):
     """H_q = 64, the most the kernels take: as 64 KV heads, and as 8 groups of 8."""
     for H_kv in (64, 8):
