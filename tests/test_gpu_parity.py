@@ -180,6 +180,63 @@ def test_long_sequence_selection(oracle, case):
     ctx.close()
 
 
+def test_selection_random_shapes(oracle):
+    """Seeded sweep over cache capacities up to 70000 (all four per-thread key counts of the single-workgroup
+    kernel and the multi-workgroup chain), budgets, windows, ragged lengths and tie densities: the selected
+    set must equal the oracle's on the same fp32 scores, bit for bit."""
+    rng = np.random.default_rng(2024)
+    caps = [5, 64, 1000, 4096, 4100, 8192, 9000, 16384, 20000, 32768, 33000, 70000]
+    for case, S_max in enumerate(caps * 2):
+        B = int(rng.integers(1, 4))
+        top_k = int(rng.integers(1, max(2, min(S_max, 3000))))
+        n_sink = int(rng.integers(0, 5))
+        n_recent = int(rng.integers(0, 70)) if S_max > 200 else 0
+        w = synth.shrink(SMALL, B=B, S=S_max, top_k=top_k, n_sink=n_sink, n_recent=n_recent, plant=0)
+        sc = rng.standard_normal((B, S_max)).astype(np.float32)
+        mode = case % 3
+        if mode == 1:
+            sc = np.round(sc * 4) / 4                      # dense ties
+        elif mode == 2:
+            sc = sc * np.float32(1e-3) + np.float32(7.0)   # narrow range far from zero
+        seq = rng.integers(0, S_max + 1, size=B).astype(np.int32)
+        seq[0] = S_max
+        print(f"[case] selection S_max={S_max} B={B} top_k={top_k} sink={n_sink} recent={n_recent} mode={mode} "
+              f"seq={seq.tolist()}", flush=True)
+        ctx = gu.make_ctx(w)
+        idx = torch.full((B, w.k_tot), -7, dtype=torch.int32, device=gu.DEV)
+        n = torch.full((B,), -7, dtype=torch.int32, device=gu.DEV)
+        ctx.topk_select(torch.from_numpy(sc).to(gu.DEV), torch.from_numpy(seq).to(gu.DEV), idx, n)
+        torch.cuda.synchronize()
+        for b in range(B):
+            want = oracle.topk(sc[b, :seq[b]].astype(np.float64), top_k, n_sink, n_recent)
+            got = idx[b, :int(n[b])].cpu().numpy()
+            assert int(n[b]) == len(want), (S_max, b)
+            assert np.array_equal(np.sort(got), np.sort(want)), (S_max, b)
+            assert np.all(idx[b, int(n[b]):].cpu().numpy() == 0)
+        ctx.close()
+
+
+def test_decode_random_shapes(oracle):
+    """Seeded sweep over descriptors: ranks, head layouts, batch sizes, budgets, windows, both storage types
+    and both RoPE pairings; every stage of every sequence against the oracle."""
+    rng = np.random.default_rng(77)
+    for case in range(14):
+        H_kv = int(rng.choice([1, 2, 3, 4, 8, 16, 32]))
+        G = int(rng.choice([g for g in (1, 2, 3, 4, 8) if g * H_kv <= 64]))
+        B = int(rng.integers(1, 5))
+        r = 64 * int(rng.integers(1, 9))
+        S = int(rng.integers(40, 2500))
+        top_k = int(rng.integers(1, min(S, 700)))
+        w = synth.shrink(SMALL, B=B, S=S, H=H_kv * G, H_kv=H_kv, r=r, r_score=8 * int(rng.integers(1, r // 8 + 1)),
+                         top_k=top_k, n_sink=int(rng.integers(0, 4)), n_recent=int(rng.integers(0, 20)),
+                         dtype=str(rng.choice(["bf16", "f32"])), rope_style=int(rng.integers(0, 2)),
+                         theta=float(rng.choice([1e4, 5e5])), plant=int(rng.integers(0, 3)))
+        seq = rng.integers(0, S + 1, size=B).tolist()
+        seq[0] = S
+        _run(oracle, w, seq_lens=seq, label=f"random #{case}: B={B} S={S} H={w.H}/{H_kv} r={r}/{w.rs} k={top_k} "
+                                            f"{w.dtype} style={w.rope_style}")
+
+
 def test_maximum_sizes(oracle):
     """The descriptor's upper limits in one case: a 2^20-row cache (128 selection chunks, the largest
     cos/sin table), 65536 selected tokens with sinks and a recent window, at the smallest rank."""
