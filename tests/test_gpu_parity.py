@@ -307,6 +307,47 @@ def test_query_position_beyond_the_cache(oracle):
     ctx.close()
 
 
+def test_graph_replays_match_eager(oracle):
+    """decode_step captured in a HIP graph: every replay (with eager work and synchronisations of the same
+    context in between, and the inputs changed between replays) equals the eager result bit for bit."""
+    w = synth.shrink(SMALL, B=2, S=1500, top_k=300, plant=1)
+    ctx = gu.make_ctx(w)
+    Ls = [synth.make_layer(w, layer) for layer in range(3)]
+    Gs = [gu.upload(L, ctx) for L in Ls]
+    eager = []
+    for G in Gs:
+        o = torch.empty((w.B, w.H, w.d), dtype=gu.out_dtype(w), device=gu.DEV)
+        ctx.decode_step(G["q"], G["q_pos"], G["Kc"], G["Vc"], G["W"], G["seq_len"], o)
+        eager.append(o)
+    torch.cuda.synchronize()
+    # static buffers the graph reads; refilled before every replay
+    S = {k: Gs[0][k].clone() for k in ("q", "q_pos", "Kc", "Vc", "W", "seq_len")}
+    out = torch.empty_like(eager[0])
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ctx.decode_step(S["q"], S["q_pos"], S["Kc"], S["Vc"], S["W"], S["seq_len"], out)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            ctx.decode_step(S["q"], S["q_pos"], S["Kc"], S["Vc"], S["W"], S["seq_len"], out)
+    torch.cuda.synchronize()
+    for rep in (1, 2, 0, 1):
+        for k in S:
+            S[k].copy_(Gs[rep][k])
+        out.fill_(7.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager[rep].view(torch.int16)), f"replay on layer {rep} differs"
+        # eager work of the same context between the replays
+        tmp = torch.empty_like(out)
+        ctx.decode_step(Gs[2]["q"], Gs[2]["q_pos"], Gs[2]["Kc"], Gs[2]["Vc"], Gs[2]["W"], Gs[2]["seq_len"], tmp)
+        torch.cuda.synchronize()
+        assert torch.equal(tmp.view(torch.int16), eager[2].view(torch.int16))
+    ctx.close()
+
+
 def test_repeatable_bit_for_bit(oracle):
     w = synth.shrink(SMALL, B=2)
     L = synth.make_layer(w)
