@@ -83,6 +83,22 @@ def test_bf16_scale_is_storage_exact_and_bound_holds(oracle):
     assert np.all(err <= scale[..., None] * (0.5 + 15 * 2.0 ** -9 + 1e-6))
 
 
+def test_bf16_scale_rounds_to_nearest(oracle):
+    # min 0, max 15.1875 (exact in bf16): 15.1875 / 15 = 1.0125 lies above the midpoint 1.01171875 of the
+    # bf16 neighbours 1.0078125 and 1.015625, so the stored step is 1.015625 (truncation would give 1.0078125);
+    # with that step 8.0 / 1.015625 = 7.88 -> code 8 and 7.6 -> 7.48 -> code 7
+    v = np.zeros((1, 32))
+    v[0, 1] = 15.1875
+    v[0, 2] = 8.0
+    v[0, 3] = 7.59375
+    codes, scale, zero = oracle.quantize_values(v, 4, "bf16")
+    assert scale[0, 0] == 1.015625 and zero[0, 0] == 0.0
+    assert codes[0, :4].tolist() == [0, 15, 8, 7]
+    # the same group stored in fp32 keeps the unrounded step
+    _, scale32, _ = oracle.quantize_values(v, 4, "f32")
+    assert scale32[0, 0] == float(np.float32(15.1875) / np.float32(15.0))
+
+
 def test_pack_layout(oracle):
     c = np.array([[1, 2, 3, 4, 15, 0, 7, 8]], dtype=np.uint8)
     assert oracle.pack_codes(c, 4).tolist() == [[0x21, 0x43, 0x0F, 0x87]]
