@@ -149,12 +149,20 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
             const int q = tid + 256 * i, jj = q / PPR, pc = q % PPR;
             unsigned char* dst = sVt[buf] + (size_t)(pc * VEC) * PITCH + jj * ES;
             const uint32_t w[4] = {S.R[i].x, S.R[i].y, S.R[i].z, S.R[i].w};
+            if constexpr (kSplit) {
+                // lanes l and l^8 hold the same columns of tokens jj and jj^1: they swap halves, so that each
+                // writes four whole 32-bit words {token even, token odd} instead of eight 16-bit ones
+                const bool odd = (jj & 1) != 0;
+                unsigned char* dst2 = dst - (odd ? ES : 0);
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                if constexpr (kSplit)
-                    *reinterpret_cast<uint16_t*>(dst + (size_t)e * PITCH) = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
-                else
-                    *reinterpret_cast<uint32_t*>(dst + (size_t)e * PITCH) = w[e];
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[k], 0x128, 0xf, 0xf, false);  // row_ror:8
+                    const uint32_t word = odd ? ((other >> 16) | (w[k] & 0xffff0000u)) : ((w[k] & 0xffffu) | (other << 16));
+                    *reinterpret_cast<uint32_t*>(dst2 + (size_t)(2 * k + (odd ? 1 : 0)) * PITCH) = word;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) *reinterpret_cast<uint32_t*>(dst + (size_t)e * PITCH) = w[e];
             }
         }
     };
@@ -171,6 +179,10 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
             const int tok = (kq * 4 + wave) * KG + hi * VEC;  // first of this lane's VEC tokens within the step
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb) {
+                if (mb >= n_mb) {  // uniform: no heads in this block
+                    ah[kq][mb] = al[kq][mb] = u32x4{0, 0, 0, 0};
+                    continue;
+                }
                 float pj[VEC];
 #pragma unroll
                 for (int v = 0; v < VEC; v += 4) {
