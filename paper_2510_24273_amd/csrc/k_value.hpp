@@ -4,7 +4,7 @@
 //
 //   attend_pv   per (sequence, token range, 64 latent columns):
 //               T[h,:] = sum_j p_hj V~[C_j,:]  on the matrix cores, tokens being the
-//               contraction axis (each 64-token step split over the four waves); the gathered
+//               contraction axis (each step split over the eight waves); the gathered
 //               rows are transposed through LDS on the way.  The softmax weights are formed
 //               on the fly, p = exp(logit - m_h) / Z_h, with m_h and Z_h merged in the prologue
 //               from the per-tile statistics the logits kernel left.  Each token range writes an
@@ -21,14 +21,16 @@
 
 namespace sals {
 
-constexpr int kPvTJ = 64;          // tokens per step
+constexpr int kPvTJ = 64;          // token ranges are whole multiples of this (of twice this for the eight-wave kernel)
 constexpr int kPvCols = 64;        // latent columns per workgroup
 constexpr int kPvMaxHeads = 64;    // H_q limit of these kernels
 constexpr int kMaxRanges = 8;      // token ranges per sequence (the output projection adds them up)
 constexpr int kPvMaxTok = 4096;    // tokens per workgroup, at most (their cache rows sit in LDS)
 
-template <typename T>
-__global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__ Vc,
+// NW waves (4 or 8), each with one MFMA token group of every step: the eight-wave form halves the number of
+// steps (a step is a chain of dependent latencies), the four-wave form starts and finishes faster.
+template <typename T, int NW>
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(const T* __restrict__ Vc,
                                                         const int32_t* __restrict__ idx,
                                                         const int32_t* __restrict__ n_sel,
                                                         const float* __restrict__ logits,
@@ -37,14 +39,17 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
                                                         int B, int S_max, int r, int H, int k_tot, int lk,
                                                         int tok_per_wg, int n_tr)
 {
+    static_assert(NW == 4 || NW == 8, "four or eight waves");
+    constexpr int kPvThreads = NW * 64, kPvWaves = NW;
     constexpr int ES = (int)sizeof(T);
     constexpr int VEC = elem<T>::vec;        // tokens per lane per MFMA group = elements per 16 bytes
     constexpr int KG = 2 * VEC;              // tokens per MFMA group (both half-waves)
-    constexpr int NKG = kPvTJ / KG;          // MFMA groups per step, dealt to the four waves
+    constexpr int TJ = kPvWaves * KG;        // tokens per step: one MFMA group per wave
+    constexpr int NKG = TJ / KG;             // MFMA groups per step, dealt to the waves
     constexpr bool kSplit = ES == 2;
     constexpr int PPR = kPvCols * ES / 16;   // 16-byte pieces per gathered row
-    constexpr int NPC = kPvTJ * PPR / 256;   // pieces per thread per step
-    constexpr int PITCH = kPvTJ * ES + 8;    // bytes per column of the transposed tile (8-byte reads stay aligned)
+    constexpr int NPC = TJ * PPR / kPvThreads;  // pieces per thread per step
+    constexpr int PITCH = TJ * ES + 8;       // bytes per column of the transposed tile (8-byte reads stay aligned)
 
     // V~ rows arrive as they lie in memory (16 bytes = VEC columns of one token per lane) and are
     // written to LDS transposed, [column][token], so that an MFMA operand (one column, VEC consecutive
@@ -76,7 +81,7 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
     const int32_t* ib = idx + (size_t)b * k_tot;
 
     // (the index loads only depend on the nominal range, so they are in flight together with n)
-    for (int t = tid; t < tok_per_wg; t += 256) {
+    for (int t = tid; t < tok_per_wg; t += kPvThreads) {
         const int j = tr * tok_per_wg + t;
         const int v = j < k_tot ? ib[j] : 0;
         if (t < ntok) sRow[t] = min(max(v, 0), S_max - 1);
@@ -99,7 +104,7 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
         }
         st = stat_merge(st, make_float2(__shfl_xor(st.x, 1, kWave), __shfl_xor(st.y, 1, kWave)));
         st = stat_merge(st, make_float2(__shfl_xor(st.x, 2, kWave), __shfl_xor(st.y, 2, kWave)));
-        if (sub == 0) sMZ[h] = make_float2(st.x > -INFINITY ? st.x : 0.f, st.y > 0.f ? 1.f / st.y : 0.f);
+        if (sub == 0 && h < kPvMaxHeads) sMZ[h] = make_float2(st.x > -INFINITY ? st.x : 0.f, st.y > 0.f ? 1.f / st.y : 0.f);
     }
     __syncthreads();
     float2 mz[2];
@@ -116,26 +121,26 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
 
     const unsigned char* vbytes = reinterpret_cast<const unsigned char*>(Vc + (size_t)b * S_max * r + col0);
     const size_t row_bytes = (size_t)r * ES;
-    constexpr int NKQ = (NKG + 3) / 4;       // MFMA groups per wave per step
+    constexpr int NKQ = (NKG + kPvWaves - 1) / kPvWaves;  // MFMA groups per wave per step (1)
     // what a step needs from global memory: the gathered row pieces and this lane's logits; two
     // such sets alternate, so the loads run two steps ahead
     struct Stage { u32x4 R[NPC]; f32x4 X[NKQ][2][VEC / 4]; };
     auto g_load = [&](Stage& S, int step) {
 #pragma unroll
         for (int i = 0; i < NPC; ++i) {
-            const int q = tid + 256 * i, jj = q / PPR, pc = q % PPR;
+            const int q = tid + kPvThreads * i, jj = q / PPR, pc = q % PPR;
             // tokens past the range re-read its last row; their weights are zero
-            const int row = sRow[min(step * kPvTJ + jj, ntok - 1)];
+            const int row = sRow[min(step * TJ + jj, ntok - 1)];
             S.R[i] = ld16(vbytes + (size_t)row * row_bytes + pc * 16);
         }
 #pragma unroll
         for (int kq = 0; kq < NKQ; ++kq) {
-            const int ks = kq * 4 + wave;
+            const int ks = kq * kPvWaves + wave;
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb) {
                 const int h = mb * 32 + l32;
                 const bool ok = ks < NKG && mb < n_mb && h < H;
-                const size_t off = (size_t)h * lk + j_begin + step * kPvTJ + ks * KG + hi * VEC;
+                const size_t off = (size_t)h * lk + j_begin + step * TJ + ks * KG + hi * VEC;
 #pragma unroll
                 for (int v = 0; v < VEC / 4; ++v)
                     S.X[kq][mb][v] = ok ? *reinterpret_cast<const f32x4*>(lg + off + 4 * v)
@@ -146,7 +151,7 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
     auto l_store = [&](const Stage& S, int buf) {
 #pragma unroll
         for (int i = 0; i < NPC; ++i) {
-            const int q = tid + 256 * i, jj = q / PPR, pc = q % PPR;
+            const int q = tid + kPvThreads * i, jj = q / PPR, pc = q % PPR;
             unsigned char* dst = sVt[buf] + (size_t)(pc * VEC) * PITCH + jj * ES;
             const uint32_t w[4] = {S.R[i].x, S.R[i].y, S.R[i].z, S.R[i].w};
             if constexpr (kSplit) {
@@ -167,16 +172,16 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
         }
     };
 
-    const int n_steps = (ntok + kPvTJ - 1) / kPvTJ;
+    const int n_steps = (ntok + TJ - 1) / TJ;
     auto do_step = [&](Stage& S, int step) {
         const int buf = step & 1;
         l_store(S, buf);
         // softmax weights of this step from the logits fetched a step ahead
-        const int j0 = j_begin + step * kPvTJ;
+        const int j0 = j_begin + step * TJ;
         u32x4 ah[NKQ][2], al[NKQ][2];
 #pragma unroll
         for (int kq = 0; kq < NKQ; ++kq) {
-            const int tok = (kq * 4 + wave) * KG + hi * VEC;  // first of this lane's VEC tokens within the step
+            const int tok = (kq * kPvWaves + wave) * KG + hi * VEC;  // first of this lane's VEC tokens within the step
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb) {
                 if (mb >= n_mb) {  // uniform: no heads in this block
@@ -216,7 +221,7 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
         __syncthreads();  // tile `buf` complete; the other tile was last read a barrier ago
 #pragma unroll
         for (int kq = 0; kq < NKQ; ++kq) {
-            const int ks = kq * 4 + wave;
+            const int ks = kq * kPvWaves + wave;
             if (ks < NKG) {  // uniform
                 const int tok = ks * KG + hi * VEC;
 #pragma unroll
@@ -244,28 +249,49 @@ __global__ __launch_bounds__(256, 2) void attend_pv_kernel(const T* __restrict__
         if (step + 1 < n_steps) do_step(S1, step + 1);
     }
 
-    // add the four waves' sums in wave order, one column block at a time; every wave finishes a
-    // quarter of the heads.  acc[mb][nb][4a+c] is head mb*32+8a+4hi+c, column nb*32+l32
+    // The waves' sums, one column block at a time: of eight waves, 4..7 first hand theirs to waves 0..3, which
+    // add them (wave w + wave w+4); the four then share out the final sum in wave order, wave w finishing heads
+    // 8w..8w+7 of each head block.  acc[mb][nb][4a+c] is head mb*32+8a+4hi+c, column nb*32+l32
     float* out_t = Tpart + (((size_t)tr * B + b) * H) * r;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
         __syncthreads();
+        if constexpr (NW == 8) {
+            if (wave >= 4) {
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+                for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) red[wave][lane][mb * 16 + v] = acc[mb][nb][v];
-        __syncthreads();
-        const int col = col0 + nb * 32 + l32;
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int v = wave * 4 + c;  // a = wave
-                const int h = mb * 32 + wave * 8 + hi * 4 + c;
-                if (h < H)
-                    out_t[(size_t)h * r + col] = ((red[0][lane][mb * 16 + v] + red[1][lane][mb * 16 + v]) +
-                                                  red[2][lane][mb * 16 + v]) + red[3][lane][mb * 16 + v];
+                    for (int v = 0; v < 16; ++v) red[wave - 4][lane][mb * 16 + v] = acc[mb][nb][v];
             }
+            __syncthreads();
+            if (wave < 4) {
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[mb][nb][v] += red[wave][lane][mb * 16 + v];
+            }
+            __syncthreads();
+        }
+        if (wave < 4) {
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) red[wave][lane][mb * 16 + v] = acc[mb][nb][v];
+        }
+        __syncthreads();
+        if (wave < 4) {
+            const int col = col0 + nb * 32 + l32;
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int v = wave * 4 + c;  // a = wave
+                    const int h = mb * 32 + wave * 8 + hi * 4 + c;
+                    if (h < H)
+                        out_t[(size_t)h * r + col] = ((red[0][lane][mb * 16 + v] + red[1][lane][mb * 16 + v]) +
+                                                      red[2][lane][mb * 16 + v]) + red[3][lane][mb * 16 + v];
+                }
+        }
     }
 }
 

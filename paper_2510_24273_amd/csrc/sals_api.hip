@@ -34,7 +34,7 @@ struct Layout {  // byte offsets into the workspace
     size_t qt, scores, idx, n_sel, logits, stats, rope, tpart, qv_part, dn_part, tm_part, tm_hist, tm_meta, tm_cand, total;
     int lk;                      // logits row stride (floats)
     int max_parts;               // token tiles per head of the logits kernel, at most
-    int pv_tok_per_wg, pv_ntr;   // value-sum token ranges
+    int pv_tok_per_wg, pv_ntr, pv_waves;  // value-sum token ranges, waves per workgroup (4 | 8)
     int qv_tok_per_wg, qv_ntr;   // quantised-value attention: token ranges
     int dn_chunks, dn_tok;       // dense baseline: token chunks per sequence, tokens per chunk
     int proj_np;                 // D-axis slices of the query projection
@@ -110,7 +110,7 @@ Layout make_layout(const sals_desc& d)
     Layout L{};
     const int D = d.H_kv * d.d;
     const int k_tot = d.top_k + d.n_sink + d.n_recent;
-    L.lk = ceil_div(k_tot, 64) * 64;
+    L.lk = ceil_div(k_tot, 128) * 128;  // whole steps of the value kernel (its last step may read up to the row end)
     L.w_section = (size_t)D * d.r;
     {   // query projection: slice the D axis until about 256 workgroups stream U_k^T
         int nks = D / (d.dtype == SALS_BF16 ? 32 : 16);
@@ -128,6 +128,9 @@ Layout make_layout(const sals_desc& d)
         if (const char* e = std::getenv("SALS_TUNE_PV_RANGES")) n_tr = std::max(1, std::min(64, std::atoi(e)));  // tuning aid
         n_tr = std::max(n_tr, ceil_div(k_tot, kPvMaxTok));
         int tok = ceil_div(ceil_div(k_tot, n_tr), kPvTJ) * kPvTJ;
+        // long ranges go to the eight-wave kernel, whose steps are twice as long
+        L.pv_waves = tok >= 4 * kPvTJ ? 8 : 4;
+        if (L.pv_waves == 8) tok = ceil_div(tok, 2 * kPvTJ) * 2 * kPvTJ;
         L.pv_tok_per_wg = tok;
         L.pv_ntr = ceil_div(k_tot, tok);
     }
@@ -414,9 +417,15 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     {
         ProfScope ps(c, SALS_K_ATTEND_PV, st);
         const int n_items = (d.r / kPvCols) * L.pv_ntr * d.B;
-        hipLaunchKernelGGL((attend_pv_kernel<T>), dim3(n_items), dim3(256), 0, st,
-                           static_cast<const T*>(Vc), idx, n_sel, logits, stats, n_parts, tpart, d.B, d.S_max,
-                           d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr);
+        if (L.pv_waves == 8) {
+            hipLaunchKernelGGL((attend_pv_kernel<T, 8>), dim3(n_items), dim3(512), 0, st,
+                               static_cast<const T*>(Vc), idx, n_sel, logits, stats, n_parts, tpart, d.B, d.S_max,
+                               d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr);
+        } else {
+            hipLaunchKernelGGL((attend_pv_kernel<T, 4>), dim3(n_items), dim3(256), 0, st,
+                               static_cast<const T*>(Vc), idx, n_sel, logits, stats, n_parts, tpart, d.B, d.S_max,
+                               d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr);
+        }
     }
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     {
