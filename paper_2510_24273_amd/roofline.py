@@ -59,10 +59,10 @@ def stage_flops(w, seq_len=None) -> dict:
 # summaries profiles/hbm_traffic_<workload>.txt.  The scaling assumes full 128-byte requests, so
 # kernels that fetch 64-byte pieces are over-counted by up to 2x.
 MEASURED_TRAFFIC: dict = {
-    ("cfg2", "attend_logits"): 12_828_000, ("cfg2", "attend_out"): 5_709_000, ("cfg2", "scores"): 5_480_000,
-    ("cfg2", "project"): 5_454_000, ("cfg2", "attend_pv"): 1_310_000, ("cfg2", "topk"): 35_000,
-    ("cfg3a", "attend_logits"): 100_014_000, ("cfg3a", "scores"): 86_831_000, ("cfg3a", "attend_pv"): 14_366_000,
-    ("cfg3a", "attend_out"): 8_125_000, ("cfg3a", "project"): 6_745_000, ("cfg3a", "topk"): 428_000,
-    ("cfg4", "scores"): 169_028_000, ("cfg4", "attend_logits"): 100_022_000, ("cfg4", "attend_pv"): 14_217_000,
-    ("cfg4", "attend_out"): 7_699_000, ("cfg4", "project"): 5_713_000, ("cfg4", "topk"): 763_000,
+    ("cfg2", "attend_logits"): 12_829_000, ("cfg2", "attend_out"): 5_707_000, ("cfg2", "scores"): 5_479_000,
+    ("cfg2", "project"): 5_443_000, ("cfg2", "attend_pv"): 1_318_000, ("cfg2", "topk"): 36_000,
+    ("cfg3a", "attend_logits"): 100_022_000, ("cfg3a", "scores"): 86_830_000, ("cfg3a", "attend_pv"): 13_095_000,
+    ("cfg3a", "attend_out"): 6_814_000, ("cfg3a", "project"): 6_734_000, ("cfg3a", "topk"): 432_000,
+    ("cfg4", "scores"): 169_027_000, ("cfg4", "attend_logits"): 100_029_000, ("cfg4", "attend_pv"): 13_758_000,
+    ("cfg4", "attend_out"): 7_371_000, ("cfg4", "project"): 5_702_000, ("cfg4", "topk"): 766_000,
 }
