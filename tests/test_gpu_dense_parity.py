@@ -70,6 +70,22 @@ def test_interleaved_rope_and_query_beyond_the_table(oracle):
     _case(oracle, w, q_pos=[w.S + 1, 1_000_003])
 
 
+def test_random_shapes(oracle):
+    """Seeded sweep over head layouts, cache lengths (one and several chunks), storage types, RoPE pairings and
+    ragged lengths."""
+    rng = np.random.default_rng(123)
+    for case in range(10):
+        H_kv = int(rng.choice([1, 2, 3, 4, 8, 16, 32]))
+        G = int(rng.choice([g for g in (1, 2, 3, 4, 8) if g * H_kv <= 64]))
+        B = int(rng.integers(1, 4))
+        S = int(rng.integers(1, 6000))
+        w = synth.shrink(SMALL, B=B, S=S, H=H_kv * G, H_kv=H_kv, top_k=1, dtype=str(rng.choice(["bf16", "f32"])),
+                         rope_style=int(rng.integers(0, 2)), theta=float(rng.choice([1e4, 5e5])))
+        seq = rng.integers(0, S + 1, size=B).tolist()
+        seq[0] = S
+        _case(oracle, w, seq_lens=seq, q_pos=[int(x) + int(rng.integers(0, 3)) for x in seq])
+
+
 def test_maximum_cache_length(oracle):
     """2^20 cached tokens (64 chunks of 16384)."""
     _case(oracle, synth.shrink(SMALL, B=1, S=1 << 20, H=8, H_kv=1, r=64))

@@ -87,6 +87,25 @@ def test_many_token_ranges_and_window(oracle):
     _attend_case(oracle, w, 2)
 
 
+def test_random_shapes(oracle):
+    """Seeded sweep over head layouts, budgets (one and several token ranges), windows, code widths, storage
+    types and ragged lengths."""
+    rng = np.random.default_rng(99)
+    for case in range(12):
+        H_kv = int(rng.choice([1, 2, 3, 4, 8, 16, 32]))
+        G = int(rng.choice([g for g in (1, 2, 3, 4, 8) if g * H_kv <= 64]))
+        B = int(rng.integers(1, 4))
+        S = int(rng.integers(50, 3000))
+        top_k = int(rng.integers(1, min(S, 1500)))
+        w = synth.shrink(SMALL, B=B, S=S, H=H_kv * G, H_kv=H_kv, r=64 * int(rng.integers(1, 5)), top_k=top_k,
+                         n_sink=int(rng.integers(0, 4)), n_recent=int(rng.integers(0, 20)),
+                         dtype=str(rng.choice(["bf16", "f32"])), rope_style=int(rng.integers(0, 2)), plant=0)
+        seq = rng.integers(0, S + 1, size=B).tolist()
+        seq[0] = S
+        _attend_case(oracle, w, int(rng.choice([2, 4])), seq_lens=seq,
+                     label=f"random #{case}: B={B} S={S} H={w.H}/{H_kv} k={top_k} {w.dtype}")
+
+
 def test_maximum_sizes(oracle):
     """2^20 cache rows and 65536 selected tokens (32 token ranges of 2048)."""
     w = synth.shrink(SMALL, B=1, S=1 << 20, H=8, H_kv=1, r=64, top_k=65536 - 16 - 64, n_sink=16, n_recent=64)
