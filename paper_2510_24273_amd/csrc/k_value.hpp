@@ -4,7 +4,7 @@
 //
 //   attend_pv   per (sequence, token range, 64 latent columns):
 //               T[h,:] = sum_j p_hj V~[C_j,:]  on the matrix cores, tokens being the
-//               contraction axis (each step split over the eight waves); the gathered
+//               contraction axis (each step split over the workgroup's four or eight waves); the gathered
 //               rows are transposed through LDS on the way.  The softmax weights are formed
 //               on the fly, p = exp(logit - m_h) / Z_h, with m_h and Z_h merged in the prologue
 //               from the per-tile statistics the logits kernel left.  Each token range writes an
