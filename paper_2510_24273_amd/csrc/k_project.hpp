@@ -80,29 +80,37 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(ProjArgs a)
             int ks = ks0 + u * kProjWaves;
             af[u] = ks < nks ? ld16(arow + (size_t)(ks_first + ks) * KS) : u32x4{0, 0, 0, 0};
         }
+        // the x operands of two column blocks are requested together, ahead of their products: a round costs
+        // one memory round trip per pair of column blocks
 #pragma unroll
-        for (int nb = 0; nb < kProjMaxCols / 16; ++nb) {
-            if (nb < n_nblk) {
-                const int n = nb * 16 + l16;
-                u32x4 bf[kProjBatch];
+        for (int nb0 = 0; nb0 < kProjMaxCols / 16; nb0 += 2) {
+            if (nb0 < n_nblk) {  // uniform
+                u32x4 bf[2][kProjBatch];
 #pragma unroll
-                for (int u = 0; u < kProjBatch; ++u) {
-                    int ks = ks0 + u * kProjWaves;
-                    bf[u] = u32x4{0, 0, 0, 0};
-                    if (ks < nks && n < ncols) {
-                        int c = (ks_first + ks) * KS + kg * VEC;
-                        const T* xp;
-                        if (QUERY) {
-                            int b = n / G, m = n - b * G, g = c / a.d;
-                            xp = X + ((size_t)b * a.H + g * G + m) * a.d + (c - g * a.d);
-                        } else {
-                            xp = X + (size_t)n * a.D + c;
+                for (int h = 0; h < 2; ++h) {
+                    const int n = (nb0 + h) * 16 + l16;
+#pragma unroll
+                    for (int u = 0; u < kProjBatch; ++u) {
+                        int ks = ks0 + u * kProjWaves;
+                        bf[h][u] = u32x4{0, 0, 0, 0};
+                        if (ks < nks && n < ncols) {
+                            int c = (ks_first + ks) * KS + kg * VEC;
+                            const T* xp;
+                            if (QUERY) {
+                                int b = n / G, m = n - b * G, g = c / a.d;
+                                xp = X + ((size_t)b * a.H + g * G + m) * a.d + (c - g * a.d);
+                            } else {
+                                xp = X + (size_t)n * a.D + c;
+                            }
+                            bf[h][u] = ld16(xp);
                         }
-                        bf[u] = ld16(xp);
                     }
                 }
+                asm volatile("" ::: "memory");  // (keeps the loads above from sinking towards their products)
 #pragma unroll
-                for (int u = 0; u < kProjBatch; ++u) mma16_op<T>::run(af[u], bf[u], acc[nb]);
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int u = 0; u < kProjBatch; ++u) mma16_op<T>::run(af[u], bf[h][u], acc[nb0 + h]);
             }
         }
     }
