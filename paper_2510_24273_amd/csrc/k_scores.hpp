@@ -3,7 +3,8 @@
 // A pure HBM stream over the latent key cache: 16 lanes (one DPP row) own a cache row and
 // read it in 16-byte pieces, so each load instruction of a wave covers four rows with 256
 // contiguous bytes each; the 16 partial dot products are folded with DPP row rotations.
-// The loads of the next four rows are issued before the current ones are consumed.  q~
+// The loads of the next four rows are issued before the current ones are consumed (two register sets
+// take turns).  q~
 // arrives as NP partial sums of the projection kernel (slices of the D axis); they are added
 // in slice order into LDS while the first cache loads are in flight, then kept in registers.
 // fp32 accumulation in a fixed order.
@@ -15,6 +16,7 @@ namespace sals {
 constexpr int kScoreThreads = 256;
 constexpr int kScoreRowsPerIter = (kScoreThreads / kWave) * 4;  // 16 rows per workgroup pass
 constexpr int kScoreMaxR = 1024;
+constexpr int kScoreMaxParts = 8;   // slices of the D axis the projection may split into
 
 // NCH = 16-byte pieces per lane = ceil(r_score / (vec*16))
 template <typename T, int NCH>
@@ -50,14 +52,20 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restri
     u32x4 cur[NCH], nxt[NCH];
     load_row(j_begin, cur);
 
-    // q~[b] = sum of the projection's partial sums, in slice order
-    for (int i = tid * 4; i < r_score; i += kScoreThreads * 4) {
+    // q~[b] = sum of the projection's partial sums (at most kScoreMaxParts slices), in slice order; all slices
+    // are requested together (a loop with one load per round would cost a memory round trip per slice)
+    static_assert(kScoreMaxR <= kScoreThreads * 4, "one 16-byte piece of q~ per thread");
+    {
+        const int i = tid * 4;
+        f32x4 t[kScoreMaxParts];
+#pragma unroll
+        for (int p = 0; p < kScoreMaxParts; ++p)
+            t[p] = (p < np && i < r_score) ? *reinterpret_cast<const f32x4*>(qt_part + ((size_t)p * B + b) * r + i)
+                                           : f32x4{0.f, 0.f, 0.f, 0.f};
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
-        for (int p = 0; p < np; ++p) {
-            f32x4 t = *reinterpret_cast<const f32x4*>(qt_part + ((size_t)p * B + b) * r + i);
-            s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
-        }
-        *reinterpret_cast<f32x4*>(&q_s[i]) = s;
+#pragma unroll
+        for (int p = 0; p < kScoreMaxParts; ++p) { s.x += t[p].x; s.y += t[p].y; s.z += t[p].z; s.w += t[p].w; }
+        if (i < r_score) *reinterpret_cast<f32x4*>(&q_s[i]) = s;
     }
     __syncthreads();
     float qf[NCH][VEC];
@@ -71,21 +79,28 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restri
         }
     }
 
-    for (int j0 = j_begin; j0 < j_end; j0 += kScoreRowsPerIter) {
-        if (j0 + kScoreRowsPerIter < j_end) load_row(j0 + kScoreRowsPerIter, nxt);
+    auto finish_rows = [&](int j0, const u32x4* piece) {
         const int j = j0 + wave * 4 + quad;
         float acc = 0.f;
 #pragma unroll
         for (int n = 0; n < NCH; ++n) {
             float kf[VEC];
-            elem<T>::unpack(cur[n], kf);
+            elem<T>::unpack(piece[n], kf);
 #pragma unroll
             for (int v = 0; v < VEC; ++v) acc = fmaf(qf[n][v], kf[v], acc);
         }
         acc = row16_sum(acc);
         if (li == 0 && j < j_end) scores[(size_t)b * S_max + j] = j < S ? acc : -INFINITY;
-#pragma unroll
-        for (int n = 0; n < NCH; ++n) cur[n] = nxt[n];
+    };
+    // two register sets take turns (no copy between them: a copy would wait for the loads it moves)
+    for (int j0 = j_begin; j0 < j_end; j0 += 2 * kScoreRowsPerIter) {
+        const bool second = j0 + kScoreRowsPerIter < j_end;
+        if (second) load_row(j0 + kScoreRowsPerIter, nxt);
+        finish_rows(j0, cur);
+        if (second) {
+            if (j0 + 2 * kScoreRowsPerIter < j_end) load_row(j0 + 2 * kScoreRowsPerIter, cur);
+            finish_rows(j0 + kScoreRowsPerIter, nxt);
+        }
     }
 }
 

@@ -115,7 +115,7 @@ Layout make_layout(const sals_desc& d)
     {   // query projection: slice the D axis until about 256 workgroups stream U_k^T
         int nks = D / (d.dtype == SALS_BF16 ? 32 : 16);
         int np = 1;
-        while (np < 8 && (d.r / 16) * np < 256 && nks % (np * 2) == 0 && nks / (np * 2) >= 4) np *= 2;
+        while (np < kScoreMaxParts && (d.r / 16) * np < 256 && nks % (np * 2) == 0 && nks / (np * 2) >= 4) np *= 2;
         L.proj_np = np;
     }
     // value sum: split the selected tokens into ranges of whole 64-token steps (at least two steps, at
