@@ -56,15 +56,17 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restri
     // are requested together (a loop with one load per round would cost a memory round trip per slice)
     static_assert(kScoreMaxR <= kScoreThreads * 4, "one 16-byte piece of q~ per thread");
     {
-        const int i = tid * 4;
+        const int i = tid * 4, ic = min(i, r - 4);  // (loads are unconditional, from clamped addresses: no branches)
         f32x4 t[kScoreMaxParts];
 #pragma unroll
         for (int p = 0; p < kScoreMaxParts; ++p)
-            t[p] = (p < np && i < r_score) ? *reinterpret_cast<const f32x4*>(qt_part + ((size_t)p * B + b) * r + i)
-                                           : f32x4{0.f, 0.f, 0.f, 0.f};
+            t[p] = *reinterpret_cast<const f32x4*>(qt_part + ((size_t)min(p, np - 1) * B + b) * r + ic);
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int p = 0; p < kScoreMaxParts; ++p) { s.x += t[p].x; s.y += t[p].y; s.z += t[p].z; s.w += t[p].w; }
+        for (int p = 0; p < kScoreMaxParts; ++p) {
+            const bool use = p < np;  // slices past the last one do not count
+            s.x += use ? t[p].x : 0.f; s.y += use ? t[p].y : 0.f; s.z += use ? t[p].z : 0.f; s.w += use ? t[p].w : 0.f;
+        }
         if (i < r_score) *reinterpret_cast<f32x4*>(&q_s[i]) = s;
     }
     __syncthreads();
