@@ -99,11 +99,10 @@ __global__ __launch_bounds__(256) void dense_attend_kernel(const T* __restrict__
             for (int v = 0; v < VEC; ++v) acc[m][n][v] = 0.f;
     }
 
-    for (int j = j0 + tg; j < j1; j += 16) {
-        load_rows(j + 16, kn, vn);
+    auto consume = [&](const u32x4* kp, const u32x4* vp) {
         float kf[NCH][VEC], vf[NCH][VEC];
 #pragma unroll
-        for (int n = 0; n < NCH; ++n) { elem<T>::unpack(kc[n], kf[n]); elem<T>::unpack(vc[n], vf[n]); }
+        for (int n = 0; n < NCH; ++n) { elem<T>::unpack(kp[n], kf[n]); elem<T>::unpack(vp[n], vf[n]); }
 #pragma unroll
         for (int m = 0; m < GMAX; ++m) {
             if (m < G) {  // uniform
@@ -123,8 +122,15 @@ __global__ __launch_bounds__(256) void dense_attend_kernel(const T* __restrict__
                     for (int v = 0; v < VEC; ++v) acc[m][n][v] = fmaf(p, vf[n][v], acc[m][n][v] * r);
             }
         }
-#pragma unroll
-        for (int n = 0; n < NCH; ++n) { kc[n] = kn[n]; vc[n] = vn[n]; }
+    };
+    // two register sets take turns (a copy between them would wait for the loads it moves)
+    for (int j = j0 + tg; j < j1; j += 32) {
+        load_rows(j + 16, kn, vn);
+        consume(kc, vc);
+        if (j + 16 < j1) {
+            load_rows(j + 32, kc, vc);
+            consume(kn, vn);
+        }
     }
 
     // the 16 lane groups of the workgroup, merged in group order by 128 threads (one per channel)
