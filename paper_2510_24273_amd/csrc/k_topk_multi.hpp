@@ -79,8 +79,21 @@ __device__ __forceinline__ int tm_token(int chunk, int i)
 // the sequence's linear map from its chunks' (min, max): every workgroup derives the same numbers
 __device__ __forceinline__ bool tm_range(const uint2* __restrict__ part, int n_chunk, float* flo, float* scale)
 {
+    // every wave reads all chunks' pairs itself, two per lane and round, and folds them with lane shuffles: no
+    // barrier, and one memory round trip instead of one per chunk
     uint32_t kmin = 0xffffffffu, kmax = 0u;
-    for (int c = 0; c < n_chunk; ++c) { kmin = min(kmin, part[c].x); kmax = max(kmax, part[c].y); }
+    const int lane = threadIdx.x & (kWave - 1);
+    for (int c0 = 0; c0 < n_chunk; c0 += 2 * kWave) {
+        const int ca = c0 + lane, cb = c0 + kWave + lane;
+        const uint2 a = part[min(ca, n_chunk - 1)], b = part[min(cb, n_chunk - 1)];  // (clamped: duplicates are harmless)
+        kmin = min(kmin, min(a.x, b.x));
+        kmax = max(kmax, max(a.y, b.y));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
+        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
+    }
     if (kmax == 0u) return false;  // no candidate at all
     const float a = key_to_score(kmin), span = key_to_score(kmax) - a;
     const float sc = (span > 0.f && span < 3.0e38f) ? (float)kTmBins / span : 0.f;
