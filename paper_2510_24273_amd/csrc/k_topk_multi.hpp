@@ -168,16 +168,22 @@ __device__ __forceinline__ TopkMeta tm_resolve(TopkShared& sh, uint32_t* s_above
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     TopkMeta m{};
+    // this thread's two bins, summed over the chunks; the first eight chunks' loads are requested together with
+    // the chunks' score ranges (from clamped chunk numbers: no load in a branch)
+    const uint32_t* hb = ws.hist + (size_t)b * n_chunk * kTmBins + 2 * tid;
+    uint2 v0[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v0[u] = *reinterpret_cast<const uint2*>(hb + (size_t)min(u, n_chunk - 1) * kTmBins);
     const bool ok = tm_range(ws.part + (size_t)b * n_chunk, n_chunk, &m.flo, &m.scale) &&
                     S > top_k + n_sink + n_recent && top_k > 0;
     if (!ok) {  // uniform
         m.fallback = 1u;
         return m;
     }
-    // this thread's two bins, summed over the chunks
-    const uint32_t* hb = ws.hist + (size_t)b * n_chunk * kTmBins + 2 * tid;
     uint32_t c0 = 0u, c1 = 0u;
-    for (int c = 0; c < n_chunk; c += 8) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { c0 += u < n_chunk ? v0[u].x : 0u; c1 += u < n_chunk ? v0[u].y : 0u; }
+    for (int c = 8; c < n_chunk; c += 8) {
         uint2 v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
@@ -276,6 +282,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_finish_kernel(const float* 
     __shared__ uint2 s_c[kTmCand];
     __shared__ uint32_t s_sel[kTmCand];
     const int b = blockIdx.x, tid = threadIdx.x;
+    // (requested together with the meta record; slots past the member count hold stale pairs and are masked)
+    const uint2 me_raw = tid < kTmCand ? ws.cand[(size_t)b * kTmCand + tid] : make_uint2(0u, 0u);
     const TopkMeta m = ws.meta[b];
     if (m.fallback) {  // uniform
         topk_select_sequence<0>(sh, scores, seq_len, idx, n_sel, b, S_max, top_k, n_sink, n_recent);
@@ -288,8 +296,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_finish_kernel(const float* 
     for (int t = tid; t < n_recent; t += kTopkThreads) out[n_sink + top_k + t] = S - n_recent + t;
     if (tid == 0) n_sel[b] = k_tot;
     const uint32_t nm = m.members;
-    uint2 me = make_uint2(0u, 0u);
-    if ((uint32_t)tid < nm) me = ws.cand[(size_t)b * kTmCand + tid];
+    const uint2 me = (uint32_t)tid < nm ? me_raw : make_uint2(0u, 0u);
     if (tid < kTmCand) s_c[tid] = me;
     __syncthreads();
     // rank among the members: larger key first, equal keys by smaller token index
