@@ -90,6 +90,31 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
     const int hh = wave / NTG, tg = wave % NTG;   // head of the tile, token group
     const int G = H / H_kv;
     const int g = g0 + hh;
+
+    // Everything the prologue needs from memory is requested before anything is waited for, from clamped
+    // addresses so that no load sits in a branch: the tile's token rows (slots at or past the selection count
+    // read whatever the index array holds there, clamped to a valid row; they get no weight), the raw query
+    // pairs of the tile's heads and the query position.
+    const int32_t* ib = idx + (size_t)b * k_tot;
+    auto row_of = [&](int slot) { return min(max(ib[min(slot, k_tot - 1)], 0), S_max - 1); };
+    int b_row[NBP];  // gathered rows: piece q = tid + i*NT -> token q/4 of the tile, column q%4
+#pragma unroll
+    for (int i = 0; i < NBP; ++i) b_row[i] = row_of(tok0 + ((tid + i * NT) >> 2));
+    constexpr int NSP = (C::TOK + NT - 1) / NT;
+    int pos_reg[NSP];
+#pragma unroll
+    for (int u = 0; u < NSP; ++u) pos_reg[u] = row_of(tok0 + min(tid + u * NT, C::TOK - 1));
+    constexpr int QP = (HEADS * kMaxGroup * kPairs + NT - 1) / NT;
+    float qa[QP], qb[QP];
+#pragma unroll
+    for (int u = 0; u < QP; ++u) {
+        const int t = min(tid + u * NT, HEADS * G * kPairs - 1), p = t & (kPairs - 1);
+        const T* qrow = q + ((size_t)b * H + (size_t)g0 * G + (t >> 6)) * kHeadDim;
+        qa[u] = elem<T>::load(qrow + pair_first(p, style));
+        qb[u] = elem<T>::load(qrow + pair_second(p, style));
+    }
+    const int qpos = q_pos[b];
+    asm volatile("" ::: "memory");  // (keeps the loads above ahead of the wait for the count)
     if (tok0 >= n) {  // no selected token in this tile: neutral statistics
         if (tid < HEADS * G)
             stats[((size_t)b * H + (size_t)g0 * G + tid) * n_parts + part] = make_float2(-INFINITY, 0.f);
@@ -102,26 +127,9 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
     __shared__ float2 sStat[HEADS][NTG][kMaxGroup];
     __shared__ int sPos[C::TOK];  // cache row (= RoPE position) of every token of the tile
 
-    const int32_t* ib = idx + (size_t)b * k_tot;
-    // rows past the selected tokens read the first selected row; they get no weight
-    auto row_of = [&](int slot) { return min(max(ib[slot < n ? slot : 0], 0), S_max - 1); };
-    for (int t = tid; t < C::TOK; t += NT) sPos[t] = row_of(tok0 + t);
-
-    // raw query pairs of this tile's heads; rotated once the first tile loads are issued
-    constexpr int QP = (HEADS * kMaxGroup * kPairs + NT - 1) / NT;
-    float qa[QP], qb[QP];
 #pragma unroll
-    for (int u = 0; u < QP; ++u) {
-        const int t = tid + u * NT;
-        qa[u] = qb[u] = 0.f;
-        if (t < HEADS * G * kPairs) {
-            const int p = t & (kPairs - 1);
-            const T* qrow = q + ((size_t)b * H + (size_t)g0 * G + (t >> 6)) * kHeadDim;
-            qa[u] = elem<T>::load(qrow + pair_first(p, style));
-            qb[u] = elem<T>::load(qrow + pair_second(p, style));
-        }
-    }
-    const int qpos = q_pos[b];
+    for (int u = 0; u < NSP; ++u)
+        if (tid + u * NT < C::TOK) sPos[tid + u * NT] = pos_reg[u];
     auto rotate_query = [&]() {
         if (tid < kPairs) {
             if (qpos >= 0 && qpos <= S_max) {  // the table holds exactly these values
@@ -160,10 +168,6 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
         const int qd = tid + i * NT;
         return (qd >> 9) * 128 * kLgStep + swz64((qd >> 2) & 127, qd & 3);
     };
-    // gathered rows: piece q -> token q/4 of the tile, column q%4
-    int b_row[NBP];
-#pragma unroll
-    for (int i = 0; i < NBP; ++i) b_row[i] = row_of(tok0 + ((tid + i * NT) >> 2));
     const unsigned char* b_base = reinterpret_cast<const unsigned char*>(Kc + (size_t)b * S_max * r) + (tid & 3) * 16;
     const size_t row_bytes = (size_t)r * ES;
     auto b_dst = [&](int i) { return C::A_BYTES + swz64((tid + i * NT) >> 2, tid & 3); };
