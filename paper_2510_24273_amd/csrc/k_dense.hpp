@@ -166,7 +166,8 @@ __global__ __launch_bounds__(256) void dense_attend_kernel(const T* __restrict__
     }
 }
 
-// out[b,h] = merged chunks / normaliser, rounded once to T.  grid (B*H), 128 threads.
+// out[b,h] = merged chunks / normaliser, rounded once to T.  grid (B*H), 128 threads.  The chunk records are
+// read eight at a time (a loop with one load per round would cost a memory round trip per chunk).
 template <typename T>
 __global__ __launch_bounds__(128) void dense_merge_kernel(const float* __restrict__ part, T* __restrict__ out,
                                                           int n_chunks)
@@ -175,13 +176,28 @@ __global__ __launch_bounds__(128) void dense_merge_kernel(const float* __restric
     const int c = threadIdx.x;
     const float* rec = part + bh * n_chunks * kDnRec;
     float M = -INFINITY;
-    for (int k = 0; k < n_chunks; ++k) M = fmaxf(M, rec[(size_t)k * kDnRec]);
+    for (int k0 = 0; k0 < n_chunks; k0 += 8) {
+        float m8[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) m8[u] = rec[(size_t)min(k0 + u, n_chunks - 1) * kDnRec];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) M = fmaxf(M, m8[u]);
+    }
     float L = 0.f, A = 0.f;
     if (M > -INFINITY) {
-        for (int k = 0; k < n_chunks; ++k) {
-            const float w = __expf(rec[(size_t)k * kDnRec] - M);
-            L = fmaf(rec[(size_t)k * kDnRec + 1], w, L);
-            A = fmaf(rec[(size_t)k * kDnRec + 2 + c], w, A);
+        for (int k0 = 0; k0 < n_chunks; k0 += 8) {
+            float m8[8], l8[8], a8[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float* r = rec + (size_t)min(k0 + u, n_chunks - 1) * kDnRec;
+                m8[u] = r[0]; l8[u] = r[1]; a8[u] = r[2 + c];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float w = k0 + u < n_chunks ? __expf(m8[u] - M) : 0.f;
+                L = fmaf(l8[u], w, L);
+                A = fmaf(a8[u], w, A);
+            }
         }
     }
     elem<T>::store(out + bh * kHeadDim + c, L > 0.f ? A / L : 0.f);
