@@ -303,9 +303,9 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(con
 // head of the group) pairs, columns the channels; the latent axis is split over the four
 // waves, every wave issuing all of its loads as one batch.
 // ---------------------------------------------------------------------------------
-constexpr int kOutBatch = 8;  // latent steps of loads kept in flight per round
-
-template <typename T>
+// BATCH latent steps of loads and RPR token ranges are in flight per round and wave: (8,2) covers any rank, (5,3)
+// and (4,4) merge more ranges per memory round trip when a wave has at most 5 / 4 steps.
+template <typename T, int BATCH, int RPR>
 __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ Uv, const float* __restrict__ Tpart,
                                                          T* __restrict__ out,
                                                          int B, int r, int H, int H_kv, int n_tr)
@@ -333,24 +333,24 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
         const int bb = row_ok ? row / G : 0, h = row_ok ? g * G + row % G : 0;
         const size_t trow = ((size_t)bb * H + h) * r + kg * VEC;
         f32x4v acc = {0.f, 0.f, 0.f, 0.f};
-        for (int ks0 = wave; ks0 < nks; ks0 += 4 * kOutBatch) {  // this wave: ks0, ks0+4, ...
-            u32x4 bf[kOutBatch], ah[kOutBatch], al[kOutBatch];
-            float tm[kOutBatch][VEC];  // T of this lane's row: the token ranges' partial sums, added in range order
+        for (int ks0 = wave; ks0 < nks; ks0 += 4 * BATCH) {  // this wave: ks0, ks0+4, ...
+            u32x4 bf[BATCH], ah[BATCH], al[BATCH];
+            float tm[BATCH][VEC];  // T of this lane's row: the token ranges' partial sums, added in range order
 #pragma unroll
-            for (int u = 0; u < kOutBatch; ++u) {
+            for (int u = 0; u < BATCH; ++u) {
                 const int ks = ks0 + 4 * u;
                 bf[u] = ks < nks ? ld16(urow + ks * KS) : u32x4{0, 0, 0, 0};
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) tm[u][v] = 0.f;
             }
-            // two ranges per round, the loads of all kOutBatch steps in flight together
-            for (int t0 = 0; t0 < n_tr; t0 += 2) {
-                f32x4 x[kOutBatch][2][VEC / 4];
+            // RPR ranges per round, the loads of all BATCH steps in flight together
+            for (int t0 = 0; t0 < n_tr; t0 += RPR) {
+                f32x4 x[BATCH][RPR][VEC / 4];
 #pragma unroll
-                for (int u = 0; u < kOutBatch; ++u) {
+                for (int u = 0; u < BATCH; ++u) {
                     const int ks = ks0 + 4 * u;
 #pragma unroll
-                    for (int w = 0; w < 2; ++w)
+                    for (int w = 0; w < RPR; ++w)
 #pragma unroll
                         for (int v = 0; v < VEC / 4; ++v)
                             x[u][w][v] = (ks < nks && row_ok && t0 + w < n_tr)
@@ -359,9 +359,9 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
                                              : f32x4{0.f, 0.f, 0.f, 0.f};
                 }
 #pragma unroll
-                for (int u = 0; u < kOutBatch; ++u)
+                for (int u = 0; u < BATCH; ++u)
 #pragma unroll
-                    for (int w = 0; w < 2; ++w)
+                    for (int w = 0; w < RPR; ++w)
 #pragma unroll
                         for (int v = 0; v < VEC / 4; ++v) {
                             tm[u][4 * v] += x[u][w][v].x; tm[u][4 * v + 1] += x[u][w][v].y;
@@ -369,7 +369,7 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
                         }
             }
 #pragma unroll
-            for (int u = 0; u < kOutBatch; ++u) {
+            for (int u = 0; u < BATCH; ++u) {
                 if constexpr (kSplit) {
                     uint32_t hw[8], lw[8];
 #pragma unroll
@@ -388,7 +388,7 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
                 }
             }
 #pragma unroll
-            for (int u = 0; u < kOutBatch; ++u) {
+            for (int u = 0; u < BATCH; ++u) {
                 mma16_op<T>::run(ah[u], bf[u], acc);
                 if constexpr (kSplit) mma16_op<T>::run(al[u], bf[u], acc);
             }

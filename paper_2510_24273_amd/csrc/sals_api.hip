@@ -430,10 +430,17 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     {
         ProfScope ps(c, SALS_K_ATTEND_OUT, st);
-        hipLaunchKernelGGL((attend_out_kernel<T>), dim3(d.H_kv, kHeadDim / 16, ceil_div(d.B * (d.H_q / d.H_kv), 16)),
-                           dim3(256), 0, st,
-                           w_section<T>(c, W, 3), tpart, static_cast<T*>(out), d.B, d.r, d.H_q, d.H_kv,
-                           L.pv_ntr);
+        // steps of the latent axis per wave decide how many token ranges fit in one round of loads
+        const int spw = ceil_div(d.r / (4 * elem<T>::vec), 4);
+        const dim3 grid(d.H_kv, kHeadDim / 16, ceil_div(d.B * (d.H_q / d.H_kv), 16));
+#define SALS_OUT(BATCH, RPR)                                                                                     \
+    hipLaunchKernelGGL((attend_out_kernel<T, BATCH, RPR>), grid, dim3(256), 0, st, w_section<T>(c, W, 3), tpart, \
+                       static_cast<T*>(out), d.B, d.r, d.H_q, d.H_kv, L.pv_ntr)
+        if (sizeof(T) == 2 && spw <= 4 && L.pv_ntr > 2) SALS_OUT(4, 4);
+        else if (sizeof(T) == 2 && spw <= 5 && L.pv_ntr > 2) SALS_OUT(5, 3);
+        else SALS_OUT(8, 2);
+#undef SALS_OUT
+
     }
     return launch_status();
 }
