@@ -59,10 +59,10 @@ def stage_flops(w, seq_len=None) -> dict:
 # summaries profiles/hbm_traffic_<workload>.txt.  The scaling assumes full 128-byte requests, so
 # kernels that fetch 64-byte pieces are over-counted by up to 2x.
 MEASURED_TRAFFIC: dict = {
-    ("cfg2", "attend_logits"): 12_829_000, ("cfg2", "attend_out"): 5_707_000, ("cfg2", "scores"): 5_479_000,
-    ("cfg2", "project"): 5_443_000, ("cfg2", "attend_pv"): 1_318_000, ("cfg2", "topk"): 36_000,
-    ("cfg3a", "attend_logits"): 100_022_000, ("cfg3a", "scores"): 86_830_000, ("cfg3a", "attend_pv"): 13_095_000,
-    ("cfg3a", "attend_out"): 6_814_000, ("cfg3a", "project"): 6_734_000, ("cfg3a", "topk"): 432_000,
-    ("cfg4", "scores"): 169_027_000, ("cfg4", "attend_logits"): 100_029_000, ("cfg4", "attend_pv"): 13_758_000,
-    ("cfg4", "attend_out"): 7_371_000, ("cfg4", "project"): 5_702_000, ("cfg4", "topk"): 766_000,
+    ("cfg2", "attend_logits"): 12_831_000, ("cfg2", "attend_out"): 5_679_000, ("cfg2", "scores"): 5_505_000,
+    ("cfg2", "project"): 5_485_000, ("cfg2", "attend_pv"): 1_318_000, ("cfg2", "topk"): 34_000,
+    ("cfg3a", "attend_logits"): 100_020_000, ("cfg3a", "scores"): 86_819_000, ("cfg3a", "attend_pv"): 13_095_000,
+    ("cfg3a", "attend_out"): 6_815_000, ("cfg3a", "project"): 6_775_000, ("cfg3a", "topk"): 423_000,
+    ("cfg4", "scores"): 168_996_000, ("cfg4", "attend_logits"): 100_029_000, ("cfg4", "attend_pv"): 13_759_000,
+    ("cfg4", "attend_out"): 7_342_000, ("cfg4", "project"): 5_743_000, ("cfg4", "topk"): 761_000,
 }
