@@ -155,11 +155,8 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
     {
         uint32_t kmin = 0xffffffffu, kmax = 0u;
         for_each_key([&](uint32_t k, int) { if (k != 0u) { kmin = min(kmin, k); kmax = max(kmax, k); } });
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
-            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
-        }
+        kmin = wave_min_u32(kmin);
+        kmax = wave_max_u32(kmax);
         if (lane == 0) { sh.wave_a[wave] = kmin; sh.wave_b[wave] = kmax; }
         for (uint32_t t = tid; t < kTopkBins; t += kTopkThreads) sh.hist[t] = 0u;
         if (tid < kTopkCand) sh.cand[tid] = 0u;  // key 0 ranks below every candidate

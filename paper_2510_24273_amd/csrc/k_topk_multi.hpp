@@ -89,11 +89,8 @@ __device__ __forceinline__ bool tm_range(const uint2* __restrict__ part, int n_c
         kmin = min(kmin, min(a.x, b.x));
         kmax = max(kmax, max(a.y, b.y));
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
-        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
-    }
+    kmin = wave_min_u32(kmin);
+    kmax = wave_max_u32(kmax);
     if (kmax == 0u) return false;  // no candidate at all
     const float a = key_to_score(kmin), span = key_to_score(kmax) - a;
     const float sc = (span > 0.f && span < 3.0e38f) ? (float)kTmBins / span : 0.f;
@@ -121,11 +118,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_range_kernel(const float* _
 #pragma unroll
     for (int i = 0; i < 4 * kTmF4; ++i)
         if (keys[i] != 0u) { kmin = min(kmin, keys[i]); kmax = max(kmax, keys[i]); }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
-        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
-    }
+    kmin = wave_min_u32(kmin);
+    kmax = wave_max_u32(kmax);
     if ((tid & 63) == 0) { s_min[tid >> 6] = kmin; s_max[tid >> 6] = kmax; }
     __syncthreads();
     if (tid == 0) {
@@ -214,8 +208,7 @@ __device__ __forceinline__ TopkMeta tm_resolve(TopkShared& sh, uint32_t* s_above
             sum += (s0 < m.t_slot ? v[i].x : 0u) + (s0 + 1 < m.t_slot ? v[i].y : 0u) + (s0 + 2 < m.t_slot ? v[i].z : 0u) +
                    (s0 + 3 < m.t_slot ? v[i].w : 0u);
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) sum += (uint32_t)__shfl_xor((int)sum, o, kWave);
+        sum = wave_sum_u32(sum);
         if (lane == 0) { s_above[c] = sum; s_memb[c] = hc[m.t_slot]; }
     }
     __syncthreads();
