@@ -7,8 +7,10 @@ Every function takes and returns float64 numpy arrays (int32 for indices) and
 forwards to the plain C implementation in ``sals_oracle.c``, one call per step
 of Algorithm 1 of the paper (arXiv 2510.24273).  The quantised value cache of
 Sec. 5.1 (quantise, de-quantise, byte packing, attention over it) is plain
-numpy at the end of this file; its pins are in ``tests/test_oracle_qv_pins.py``,
-those of everything else in ``tests/test_oracle_pins.py``.
+numpy further down; its pins are in ``tests/test_oracle_qv_pins.py``.  The dense
+baseline, the overlap score of Sec. 3.2 and the recent window of Sec. 5.1 follow,
+composed from the same C steps; their pins are in ``tests/test_oracle_window_pins.py``
+and, with those of everything else, in ``tests/test_oracle_pins.py``.
 """
 from __future__ import annotations
 
@@ -292,3 +294,69 @@ def dense_decode(q, q_pos, KR, V, theta, rope_style=0):
         return np.zeros((H, d))
     qR = rope(q.reshape(1, H, d), [q_pos], theta, rope_style).reshape(H, d)
     return attend(qR, KR, V)
+
+
+# ---------------------------------------------------------------------------
+# Overlap score (Sec. 3.2): the share of the full attention mass that a selected
+# index set captures, OS = sum_{i in C} p_i / sum_i p_i with p the attention
+# distribution over all cached tokens.
+# ---------------------------------------------------------------------------
+
+def overlap_score(q, q_pos, KR, idx, theta, rope_style=0):
+    """q [H,d] pre-RoPE, KR [S,H_kv,d] rotated keys of every cached token, idx [n] -> OS [H]."""
+    q = np.asarray(q, dtype=np.float64)
+    KR = np.asarray(KR, dtype=np.float64)
+    H, d = q.shape
+    S = KR.shape[0]
+    if S == 0:
+        return np.zeros(H)
+    qR = rope(q.reshape(1, H, d), [q_pos], theta, rope_style).reshape(H, d)
+    _, p = attend(qR, KR, np.zeros_like(KR), return_p=True)   # p [H,S], rows sum to one
+    idx = np.asarray(idx, dtype=np.int64)
+    return p[:, idx].sum(axis=1) / p.sum(axis=1)
+
+
+# ---------------------------------------------------------------------------
+# Mixed-precision recent window (Sec. 5.1): the most recent w tokens are kept at
+# a milder compression than the rest, and this window coincides with the recent
+# tokens the selection always keeps (Sec. 5.2).  Reading taken where the paper
+# is silent: the window is a second latent cache of rank r_hi > r with its own
+# projectors (the leading r_hi principal directions; r_hi = D_kv/2 is the 50 %
+# setting), held as a ring of w rows: token t lives in row t mod w while
+# S - w <= t < S.  A token is written to both caches when it is appended (the
+# low-rank row is what remains once the ring row is overwritten), so nothing is
+# re-compressed when a token leaves the window.  Attention runs one softmax
+# over the union of the selected tokens, each reconstructed from the cache that
+# holds it.
+# ---------------------------------------------------------------------------
+
+def window_append(Kw, Vw, k_new, v_new, Uk_hi, Uv_hi, t):
+    """Writes token t (its latent images under the window's projectors) into ring row t mod w
+    of Kw, Vw [w, r_hi], in place."""
+    w = Kw.shape[0]
+    Kw[t % w] = project(k_new, Uk_hi)
+    Vw[t % w] = project(v_new, Uv_hi)
+
+
+def sparse_attend_window(q, q_pos, Kc, Vc, Uk, Uv, Kw, Vw, Uk_hi, Uv_hi, idx, S, H_kv, theta,
+                         rope_style=0):
+    """Algorithm 1 from the reconstruction step on with the recent window of Sec. 5.1.
+    Kc, Vc [S_max, r] with Uk, Uv [D_kv, r]; Kw, Vw [w, r_hi] with Uk_hi, Uv_hi [D_kv, r_hi];
+    idx [n] selected tokens of a cache of S tokens.  Token t is read from ring row t mod w if
+    S - w <= t < S, else from row t of the low-rank caches."""
+    q = np.asarray(q, dtype=np.float64)
+    H, d = q.shape
+    idx = np.asarray(idx, dtype=np.int32)
+    n = idx.shape[0]
+    w = np.asarray(Kw).shape[0]
+    in_win = (idx >= S - w) & (idx < S)
+    K_C = np.empty((n, H_kv * d))
+    V_C = np.empty((n, H_kv * d))
+    lo, hi = idx[~in_win], idx[in_win]
+    K_C[~in_win] = reconstruct(Kc, lo, Uk)
+    V_C[~in_win] = reconstruct(Vc, lo, Uv)
+    K_C[in_win] = reconstruct(Kw, hi % w, Uk_hi)
+    V_C[in_win] = reconstruct(Vw, hi % w, Uv_hi)
+    KR = rope(K_C.reshape(n, H_kv, d), idx, theta, rope_style) if n else K_C.reshape(n, H_kv, d)
+    qR = rope(q.reshape(1, H, d), [q_pos], theta, rope_style).reshape(H, d)
+    return attend(qR, KR, V_C.reshape(n, H_kv, d))
