@@ -230,6 +230,57 @@ sals_status sals_decode_step_qv(sals_ctx* ctx, const void* q, const int32_t* q_p
 sals_status sals_dense_attend(sals_ctx* ctx, const void* q, const int32_t* q_pos, const void* K,
                               const void* V, const int32_t* seq_len, void* out, void* hip_stream);
 
+/* ---- high-precision recent window ----------------------------------------------------
+ * The mixed-precision scheme of Sec. 5.1: the most recent w tokens are compressed less than the
+ * rest, and this window is the set of recent tokens the selection always keeps (Sec. 5.2).
+ * Where the paper gives no detail the format is: a second pair of latent caches Kw, Vw of rank
+ * r_hi > r with projectors of their own (the leading r_hi principal directions of the same
+ * calibration; r_hi = D_kv/2 is the paper's 50 % setting, the kernels cover r_hi <= 1024), held as
+ * a ring of w rows per sequence: token t lies in row t mod w while it is among the last w tokens.
+ * Every token is written to both caches when it is appended, so nothing is re-compressed when it
+ * leaves the window: its ring row is simply overwritten w tokens later.
+ *
+ * The window has a context of its own, `win`, created from a descriptor that equals the main
+ * one in B, S_max, H_q, H_kv, d, rope_theta, rope_style and dtype and has r = r_hi, top_k = w
+ * (= the main descriptor's n_recent >= 1), n_sink = n_recent = 0 (r_score: any valid value, unused), with its
+ * own workspace and its own packed projectors W_hi (sals_pack_weights on `win`).
+ *   Kw, Vw [B, w, r_hi] T */
+
+/* Eq. 1 for the window: k~ = Uk_hi^T k_new, v~ = Uv_hi^T v_new into row seq_len[b] mod w of
+ * Kw[b] / Vw[b].  seq_len is only read: call this BEFORE the sals_compress_append that writes the
+ * same token to the main caches and advances seq_len.  A sequence with seq_len[b] >= S_max is left
+ * untouched, as there. */
+sals_status sals_window_append(sals_ctx* win, const void* k_new, const void* v_new, const void* W_hi,
+                               void* Kw, void* Vw, const int32_t* seq_len, void* hip_stream);
+
+/* sals_sparse_attend with the window: idx / n_sel are a selection in the order sals_topk_select
+ * writes it on `ctx` (recent tokens last).  The last n_w = min(w, n_sel[b]) entries of idx[b] are
+ * reconstructed from ring rows idx mod w of Kw / Vw through W_hi, all entries before them from Kc / Vc
+ * through W; one softmax (Eq. 5) runs over the union.  Evaluated as two passes whose outputs are
+ * merged by their softmax statistics in fp32, rounded once to T. */
+sals_status sals_sparse_attend_window(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos,
+                                      const void* Kc, const void* Vc, const void* W, const void* Kw,
+                                      const void* Vw, const void* W_hi, const int32_t* idx,
+                                      const int32_t* n_sel, void* out, void* hip_stream);
+
+/* sals_latent_scores and sals_topk_select on `ctx` (scores over the low-rank key cache, which holds
+ * every token), then sals_sparse_attend_window.  `scores`, `idx`, `n_sel` may each be NULL. */
+sals_status sals_decode_step_window(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos,
+                                    const void* Kc, const void* Vc, const void* W, const void* Kw,
+                                    const void* Vw, const void* W_hi, const int32_t* seq_len, void* out,
+                                    float* scores, int32_t* idx, int32_t* n_sel, void* hip_stream);
+
+/* ---- overlap score -------------------------------------------------------------------
+ * The diagnostic of Sec. 3.2: the share of the dense attention mass that a selected set captures,
+ *   os[b,h] = sum_{j < n_sel[b]} p[idx[b,j]] / sum_{j < seq_len[b]} p[j],
+ *   p[j] = exp( RoPE(q[b,h], q_pos[b]) . K[b,j,g(h)] / sqrt(d) ),
+ * over the dense baseline's rotated full-rank key cache.  idx entries must be unique tokens below
+ * seq_len[b]; os[b,:] is zero for an empty cache or selection.
+ *   q [B,H_q,d] T pre-RoPE;  K [B,S_max,H_kv,d] T;  idx [B,k_tot] int32;  os [B,H_q] fp32 out */
+sals_status sals_overlap_score(sals_ctx* ctx, const void* q, const int32_t* q_pos, const void* K,
+                               const int32_t* seq_len, const int32_t* idx, const int32_t* n_sel,
+                               float* os, void* hip_stream);
+
 /* ---- measurement aid --------------------------------------------------------------
  * Per-stage timing for roofline figures.  While enabled, every stage below (one kernel;
  * for the selection of sequences above 32768 tokens a chain of four) is bracketed by a

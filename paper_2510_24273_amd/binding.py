@@ -29,6 +29,7 @@ EXPORTS = (
     "sals_packed_weight_bytes", "sals_pack_weights",
     "sals_qv_row_bytes", "sals_compress_append_qv", "sals_sparse_attend_qv", "sals_decode_step_qv",
     "sals_dense_attend",
+    "sals_window_append", "sals_sparse_attend_window", "sals_decode_step_window", "sals_overlap_score",
 )
 N_KERNELS = 8
 
@@ -71,6 +72,10 @@ def load_library() -> ctypes.CDLL:
     lib.sals_sparse_attend_qv.argtypes = [vp, vp, i32p, vp, vp, vp, ctypes.c_int, vp, i32p, i32p, vp, vp]
     lib.sals_decode_step_qv.argtypes = [vp, vp, i32p, vp, vp, vp, ctypes.c_int, vp, i32p, vp, f32p, i32p, i32p, vp]
     lib.sals_dense_attend.argtypes = [vp, vp, i32p, vp, vp, i32p, vp, vp]
+    lib.sals_window_append.argtypes = [vp, vp, vp, vp, vp, vp, i32p, vp]
+    lib.sals_sparse_attend_window.argtypes = [vp, vp, vp, i32p, vp, vp, vp, vp, vp, vp, i32p, i32p, vp, vp]
+    lib.sals_decode_step_window.argtypes = [vp, vp, vp, i32p, vp, vp, vp, vp, vp, vp, i32p, vp, f32p, i32p, i32p, vp]
+    lib.sals_overlap_score.argtypes = [vp, vp, i32p, vp, i32p, i32p, i32p, f32p, vp]
     lib.sals_kernel_name.restype = ctypes.c_char_p
     lib.sals_kernel_name.argtypes = [ctypes.c_int]
     lib.sals_profile_enable.argtypes = [vp, ctypes.c_int]
@@ -213,3 +218,25 @@ class Sals:
     def dense_attend(self, q, q_pos, K, V, seq_len, out):
         self._check(_lib.sals_dense_attend(self._h, _p(q), _p(q_pos), _p(K), _p(V), _p(seq_len), _p(out),
                                            _stream()), "sals_dense_attend")
+
+    # ---- high-precision recent window: `win` is the window's own context (rank r_hi, top_k = w) ----
+    def window_append(self, k_new, v_new, W_hi, Kw, Vw, seq_len):
+        """Called on the window's context, before the compress_append that advances seq_len."""
+        self._check(_lib.sals_window_append(self._h, _p(k_new), _p(v_new), _p(W_hi), _p(Kw), _p(Vw), _p(seq_len),
+                                            _stream()), "sals_window_append")
+
+    def sparse_attend_window(self, win, q, q_pos, Kc, Vc, W, Kw, Vw, W_hi, idx, n_sel, out):
+        self._check(_lib.sals_sparse_attend_window(self._h, win._h, _p(q), _p(q_pos), _p(Kc), _p(Vc), _p(W), _p(Kw),
+                                                   _p(Vw), _p(W_hi), _p(idx), _p(n_sel), _p(out), _stream()),
+                    "sals_sparse_attend_window")
+
+    def decode_step_window(self, win, q, q_pos, Kc, Vc, W, Kw, Vw, W_hi, seq_len, out, scores=None, idx=None,
+                           n_sel=None):
+        self._check(_lib.sals_decode_step_window(self._h, win._h, _p(q), _p(q_pos), _p(Kc), _p(Vc), _p(W), _p(Kw),
+                                                 _p(Vw), _p(W_hi), _p(seq_len), _p(out), _p(scores), _p(idx),
+                                                 _p(n_sel), _stream()), "sals_decode_step_window")
+
+    # ---- overlap score of a selection against dense attention over rotated full-rank keys ----
+    def overlap_score(self, q, q_pos, K, seq_len, idx, n_sel, os):
+        self._check(_lib.sals_overlap_score(self._h, _p(q), _p(q_pos), _p(K), _p(seq_len), _p(idx), _p(n_sel),
+                                            _p(os), _stream()), "sals_overlap_score")

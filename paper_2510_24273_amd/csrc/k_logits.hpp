@@ -56,7 +56,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
     const int32_t* __restrict__ n_sel, const T* __restrict__ q, const int32_t* __restrict__ q_pos,
     const float2* __restrict__ rope, InvFreq inv,
     float* __restrict__ logits, float2* __restrict__ stats, int B, int S_max, int r, int H, int H_kv,
-    int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale)
+    int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale, int ring)
 {
     typedef logits_cfg<HEADS, NTG, NB> C;
     constexpr int NT = C::NT, NA = C::NA, NBP = C::NBP, NCS = C::NCS;
@@ -99,7 +99,10 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
     auto row_of = [&](int slot) { return min(max(ib[min(slot, k_tot - 1)], 0), S_max - 1); };
     int b_row[NBP];  // gathered rows: piece q = tid + i*NT -> token q/4 of the tile, column q%4
 #pragma unroll
-    for (int i = 0; i < NBP; ++i) b_row[i] = row_of(tok0 + ((tid + i * NT) >> 2));
+    for (int i = 0; i < NBP; ++i) {
+        b_row[i] = row_of(tok0 + ((tid + i * NT) >> 2));
+        if (ring > 0) b_row[i] %= ring;  // ring cache: token t lies in row t mod ring
+    }
     constexpr int NSP = (C::TOK + NT - 1) / NT;
     int pos_reg[NSP];
 #pragma unroll
@@ -168,7 +171,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
         const int qd = tid + i * NT;
         return (qd >> 9) * 128 * kLgStep + swz64((qd >> 2) & 127, qd & 3);
     };
-    const unsigned char* b_base = reinterpret_cast<const unsigned char*>(Kc + (size_t)b * S_max * r) + (tid & 3) * 16;
+    const unsigned char* b_base = reinterpret_cast<const unsigned char*>(Kc + (size_t)b * (ring > 0 ? ring : S_max) * r) + (tid & 3) * 16;
     const size_t row_bytes = (size_t)r * ES;
     auto b_dst = [&](int i) { return C::A_BYTES + swz64((tid + i * NT) >> 2, tid & 3); };
 

@@ -31,7 +31,7 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     const int32_t* __restrict__ n_sel, const T* __restrict__ q, const int32_t* __restrict__ q_pos,
     const float2* __restrict__ rope, InvFreq inv,
     float* __restrict__ logits, float2* __restrict__ stats, int B, int S_max, int r, int H, int H_kv,
-    int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale)
+    int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale, int ring)
 {
     constexpr int ES = (int)sizeof(T);
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -120,8 +120,10 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
         return;
     }
     // slots past the selected tokens read the first selected row; they get no weight
-    const int my_row = min(max(my_slot < n ? idx_my : idx_0, 0), S_max - 1);
-    const unsigned char* b_src = reinterpret_cast<const unsigned char*>(Kc + ((size_t)b * S_max + my_row) * r) + pcol * 16;
+    const int my_pos = min(max(my_slot < n ? idx_my : idx_0, 0), S_max - 1);
+    const int my_row = ring > 0 ? my_pos % ring : my_pos;  // ring cache: token t lies in row t mod ring
+    const unsigned char* b_src =
+        reinterpret_cast<const unsigned char*>(Kc + ((size_t)b * (ring > 0 ? ring : S_max) + my_row) * r) + pcol * 16;
 #pragma unroll
     for (int s = 0; s < NST; ++s) P[s][2] = ld16(b_src + (size_t)s * kLgChunk);
 #pragma unroll

@@ -42,10 +42,11 @@ constexpr int kProjBatch = 8;      // row pieces a wave keeps in flight per roun
 struct ProjArgs {
     const void* UT[2];   // transposed projectors [r, D]
     const void* X[2];    // QUERY: q [B,H,d] (X[0]); else new key / value [B,D]
-    void* cache[2];      // append: [B,S_max,r]
+    void* cache[2];      // append: [B,S_max,r], or [B,ring,r] when ring > 0
     float* out_f32;      // QUERY: partial q~ [np,B,r], one slice of the D axis each
     const int32_t* seq_len;  // append: [B] row to write
     int B, D, r, H, H_kv, d, S_max, nproj, np;
+    int ring;            // append: > 0 = the cache is a ring of this many rows, token t in row t mod ring
 };
 
 template <typename T, bool QUERY>
@@ -142,9 +143,11 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(ProjArgs a)
         if (QUERY) {
             a.out_f32[((size_t)slice * a.B + b) * a.r + i0 + rr] = s;
         } else {
-            int row = a.seq_len[b];
-            if (row < a.S_max)
-                elem<T>::store(static_cast<T*>(a.cache[proj]) + ((size_t)b * a.S_max + row) * a.r + i0 + rr, s);
+            const int t_new = a.seq_len[b];
+            const int rows = a.ring > 0 ? a.ring : a.S_max;
+            const int row = a.ring > 0 ? t_new % a.ring : t_new;
+            if (t_new >= 0 && t_new < a.S_max)
+                elem<T>::store(static_cast<T*>(a.cache[proj]) + ((size_t)b * rows + row) * a.r + i0 + rr, s);
         }
     }
 }

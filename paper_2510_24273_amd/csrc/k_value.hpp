@@ -37,7 +37,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(con
                                                         const float2* __restrict__ stats, int n_parts,
                                                         float* __restrict__ Tpart,
                                                         int B, int S_max, int r, int H, int k_tot, int lk,
-                                                        int tok_per_wg, int n_tr)
+                                                        int tok_per_wg, int n_tr, int ring)
 {
     static_assert(NW == 4 || NW == 8, "four or eight waves");
     constexpr int kPvThreads = NW * 64, kPvWaves = NW;
@@ -84,7 +84,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(con
     for (int t = tid; t < tok_per_wg; t += kPvThreads) {
         const int j = tr * tok_per_wg + t;
         const int v = j < k_tot ? ib[j] : 0;
-        if (t < ntok) sRow[t] = min(max(v, 0), S_max - 1);
+        const int pos = min(max(v, 0), S_max - 1);
+        if (t < ntok) sRow[t] = ring > 0 ? pos % ring : pos;  // ring cache: token t lies in row t mod ring
     }
     // softmax maximum and normaliser of every head: four lanes share a head's tiles and merge
     // them in a fixed order
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(con
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
 
-    const unsigned char* vbytes = reinterpret_cast<const unsigned char*>(Vc + (size_t)b * S_max * r + col0);
+    const unsigned char* vbytes = reinterpret_cast<const unsigned char*>(Vc + (size_t)b * (ring > 0 ? ring : S_max) * r + col0);
     const size_t row_bytes = (size_t)r * ES;
     constexpr int NKQ = (NKG + kPvWaves - 1) / kPvWaves;  // MFMA groups per wave per step (1)
     // what a step needs from global memory: the gathered row pieces and this lane's logits; two
@@ -307,7 +308,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(con
 // and (4,4) merge more ranges per memory round trip when a wave has at most 5 / 4 steps.
 template <typename T, int BATCH, int RPR>
 __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ Uv, const float* __restrict__ Tpart,
-                                                         T* __restrict__ out,
+                                                         T* __restrict__ out, float* __restrict__ out_f32,
                                                          int B, int r, int H, int H_kv, int n_tr)
 {
     constexpr int VEC = elem<T>::vec;
@@ -407,7 +408,9 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
                 int orow = row0 + kg * 4 + v;
                 if (orow < n_rows) {
                     int ob = orow / G, oh = g * G + orow % G;
-                    elem<T>::store(out + ((size_t)ob * H + oh) * kHeadDim + cb * 16 + l16, y);
+                    const size_t o = ((size_t)ob * H + oh) * kHeadDim + cb * 16 + l16;
+                    if (out_f32 != nullptr) out_f32[o] = y;  // unrounded, for a later merge with another pass
+                    else elem<T>::store(out + o, y);
                 }
             }
         }

@@ -15,12 +15,14 @@
 #include "k_dense.hpp"
 #include "k_logits.hpp"
 #include "k_logits_small.hpp"
+#include "k_overlap.hpp"
 #include "k_project.hpp"
 #include "k_scores.hpp"
 #include "k_topk.hpp"
 #include "k_topk_multi.hpp"
 #include "k_qvalue.hpp"
 #include "k_value.hpp"
+#include "k_window.hpp"
 
 using namespace sals;
 
@@ -31,7 +33,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Layout {  // byte offsets into the workspace
-    size_t qt, scores, idx, n_sel, logits, stats, rope, tpart, qv_part, dn_part, tm_part, tm_hist, tm_meta, tm_cand, total;
+    size_t qt, scores, idx, n_sel, n_lo, out32, logits, stats, rope, tpart, qv_part, dn_part, tm_part, tm_hist, tm_meta, tm_cand, total;
     int lk;                      // logits row stride (floats)
     int max_parts;               // token tiles per head of the logits kernel, at most
     int pv_tok_per_wg, pv_ntr, pv_waves;  // value-sum token ranges, waves per workgroup (4 | 8)
@@ -140,6 +142,8 @@ Layout make_layout(const sals_desc& d)
     L.scores = take((size_t)d.B * d.S_max * 4);
     L.idx = take((size_t)d.B * k_tot * 4);
     L.n_sel = take((size_t)d.B * 4);
+    L.n_lo = take((size_t)d.B * 4);                          // recent-window attention: tokens of the low-rank pass
+    L.out32 = take((size_t)d.B * d.H_q * kHeadDim * 4);      // recent-window attention: a pass's unrounded output
     L.logits = take((size_t)d.B * d.H_q * L.lk * 4);
     L.max_parts = ceil_div(k_tot, 32);
     L.stats = take((size_t)d.B * d.H_q * L.max_parts * 8);
@@ -186,10 +190,10 @@ template <typename T> inline const T* w_section(const sals_ctx* c, const void* W
 }
 
 // QUERY: x0 = q.  Otherwise x0 / x1 = new key / value rows (x1 may be null: keys only); `bump` advances
-// the sequence lengths afterwards.
+// the sequence lengths afterwards; ring > 0: the caches are rings of that many rows.
 template <typename T, bool QUERY>
 sals_status launch_project(const sals_ctx* c, const void* W, const void* x0, const void* x1, void* cache0,
-                           void* cache1, int32_t* seq_len, hipStream_t st, bool bump = true)
+                           void* cache1, int32_t* seq_len, hipStream_t st, bool bump = true, int ring = 0)
 {
     const sals_desc& d = c->d;
     ProjArgs a{};
@@ -201,6 +205,7 @@ sals_status launch_project(const sals_ctx* c, const void* W, const void* x0, con
     a.seq_len = seq_len;
     a.B = d.B; a.D = d.H_kv * d.d; a.r = d.r; a.H = d.H_q; a.H_kv = d.H_kv; a.d = d.d;
     a.S_max = d.S_max; a.nproj = (QUERY || x1 == nullptr) ? 1 : 2; a.np = QUERY ? c->L.proj_np : 1;
+    a.ring = ring;
     {
         ProfScope ps(c, SALS_K_PROJECT, st);
         hipLaunchKernelGGL((project_kernel<T, QUERY>), dim3(d.r / 16, a.np, a.nproj), dim3(kProjThreads), 0, st, a);
@@ -315,10 +320,14 @@ struct QvCache { const void* codes; const void* meta; int bits; };  // quantised
 
 // qv == nullptr: latent value cache Vc, value sum in latent space and output projection through U_v.
 // Otherwise: values are the de-quantised rows of the quantised cache (Vc unused).
+// ring > 0: Kc, Vc are rings of that many rows per sequence (token t in row t mod ring).  out32 != nullptr
+// (latent value path only): the output goes there unrounded instead of to `out`; *parts_out receives the number
+// of statistics tiles per head the logits kernel left in the workspace.
 template <typename T>
 sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos, const void* Kc,
                           const void* Vc, const void* W, const int32_t* idx, const int32_t* n_sel, void* out,
-                          hipStream_t st, const QvCache* qv = nullptr)
+                          hipStream_t st, const QvCache* qv = nullptr, int ring = 0, float* out32 = nullptr,
+                          int* parts_out = nullptr)
 {
     const sals_desc& d = c->d;
     const Layout& L = c->L;
@@ -348,7 +357,7 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
                            static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,                     \
                            static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats, d.B,                \
                            d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk, n_parts, heads_fastest, d.rope_style,   \
-                           1.0f / std::sqrt((float)d.d));                                                    \
+                           1.0f / std::sqrt((float)d.d), ring);                                              \
     } while (0)
         // the 64-token kernel while its workgroups fit the chip in one round (or too few large tiles exist)
         int pick = (d.H_kv % 2 == 0 && n_wg(2, 256) >= 384) ? 1 : ((n_wg(1, 64) > 256 && n_wg(1, 256) >= 96) ? 2 : 3);
@@ -364,7 +373,7 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
             int nst = kLsMaxChunk;  // steps loaded ahead: the largest divisor of the step count
             while (nkc % nst != 0) --nst;
             void (*kern)(const T*, const T*, const int32_t*, const int32_t*, const T*, const int32_t*, const float2*,
-                         InvFreq, float*, float2*, int, int, int, int, int, int, int, int, int, int, float) = nullptr;
+                         InvFreq, float*, float2*, int, int, int, int, int, int, int, int, int, int, float, int) = nullptr;
             switch (nst) {
                 case 1: kern = attend_logits_small_kernel<T, 1>; break;
                 case 2: kern = attend_logits_small_kernel<T, 2>; break;
@@ -385,10 +394,11 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
                                static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,
                                static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats, d.B, d.S_max, d.r,
                                d.H_q, d.H_kv, k_tot, L.lk, n_parts, heads_fastest, d.rope_style,
-                               1.0f / std::sqrt((float)d.d));
+                               1.0f / std::sqrt((float)d.d), ring);
         }
 #undef SALS_LOGITS
         if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+        if (parts_out) *parts_out = n_parts;
     }
     if (qv != nullptr) {
         ProfScope ps(c, SALS_K_ATTEND_QV, st);
@@ -420,11 +430,11 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
         if (L.pv_waves == 8) {
             hipLaunchKernelGGL((attend_pv_kernel<T, 8>), dim3(n_items), dim3(512), 0, st,
                                static_cast<const T*>(Vc), idx, n_sel, logits, stats, n_parts, tpart, d.B, d.S_max,
-                               d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr);
+                               d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr, ring);
         } else {
             hipLaunchKernelGGL((attend_pv_kernel<T, 4>), dim3(n_items), dim3(256), 0, st,
                                static_cast<const T*>(Vc), idx, n_sel, logits, stats, n_parts, tpart, d.B, d.S_max,
-                               d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr);
+                               d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr, ring);
         }
     }
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
@@ -435,7 +445,7 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
         const dim3 grid(d.H_kv, kHeadDim / 16, ceil_div(d.B * (d.H_q / d.H_kv), 16));
 #define SALS_OUT(BATCH, RPR)                                                                                     \
     hipLaunchKernelGGL((attend_out_kernel<T, BATCH, RPR>), grid, dim3(256), 0, st, w_section<T>(c, W, 3), tpart, \
-                       static_cast<T*>(out), d.B, d.r, d.H_q, d.H_kv, L.pv_ntr)
+                       static_cast<T*>(out), out32, d.B, d.r, d.H_q, d.H_kv, L.pv_ntr)
         if (sizeof(T) == 2 && spw <= 4 && L.pv_ntr > 2) SALS_OUT(4, 4);
         else if (sizeof(T) == 2 && spw <= 5 && L.pv_ntr > 2) SALS_OUT(5, 3);
         else SALS_OUT(8, 2);
@@ -690,6 +700,128 @@ sals_status sals_dense_attend(sals_ctx* ctx, const void* q, const int32_t* q_pos
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     return ctx->d.dtype == SALS_BF16 ? launch_dense<bf16_t>(ctx, q, q_pos, K, V, seq_len, out, st)
                                      : launch_dense<float>(ctx, q, q_pos, K, V, seq_len, out, st);
+}
+
+// ---- recent window (second, higher-rank ring cache) ------------------------------------------------
+
+namespace {
+// `win` must describe the same model and batch as `ctx`, at another rank, and select exactly the recent tokens
+sals_status window_pair_ok(const sals_ctx* ctx, const sals_ctx* win)
+{
+    if (!ctx || !win || ctx == win) return SALS_ERR_INVALID_ARG;
+    const sals_desc &a = ctx->d, &b = win->d;
+    if (a.B != b.B || a.S_max != b.S_max || a.H_q != b.H_q || a.H_kv != b.H_kv || a.d != b.d ||
+        a.rope_theta != b.rope_theta || a.rope_style != b.rope_style || a.dtype != b.dtype)
+        return SALS_ERR_INVALID_ARG;
+    if (b.n_sink != 0 || b.n_recent != 0 || a.n_recent < 1 || b.top_k != a.n_recent) return SALS_ERR_INVALID_ARG;
+    return SALS_OK;
+}
+}  // namespace
+
+sals_status sals_window_append(sals_ctx* win, const void* k_new, const void* v_new, const void* W_hi, void* Kw,
+                               void* Vw, const int32_t* seq_len, void* hip_stream)
+{
+    if (!win || bad(k_new) || bad(v_new) || bad(W_hi) || bad(Kw) || bad(Vw) || !seq_len) return SALS_ERR_INVALID_ARG;
+    if (win->d.n_sink != 0 || win->d.n_recent != 0) return SALS_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    int32_t* sl = const_cast<int32_t*>(seq_len);  // read only: no length is advanced here
+    const int ring = win->d.top_k;
+    return win->d.dtype == SALS_BF16
+               ? launch_project<bf16_t, false>(win, W_hi, k_new, v_new, Kw, Vw, sl, st, false, ring)
+               : launch_project<float, false>(win, W_hi, k_new, v_new, Kw, Vw, sl, st, false, ring);
+}
+
+sals_status sals_sparse_attend_window(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos,
+                                      const void* Kc, const void* Vc, const void* W, const void* Kw,
+                                      const void* Vw, const void* W_hi, const int32_t* idx, const int32_t* n_sel,
+                                      void* out, void* hip_stream)
+{
+    sals_status s = window_pair_ok(ctx, win);
+    if (s != SALS_OK) return s;
+    if (bad(q) || !q_pos || bad(Kc) || bad(Vc) || bad(W) || bad(Kw) || bad(Vw) || bad(W_hi) || !idx || !n_sel ||
+        bad(out))
+        return SALS_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const sals_desc& d = ctx->d;
+    const int k_tot = d.top_k + d.n_sink + d.n_recent, w = win->d.top_k;
+    int32_t* idx_hi = reinterpret_cast<int32_t*>(win->ws + win->L.idx);
+    int32_t* n_hi = reinterpret_cast<int32_t*>(win->ws + win->L.n_sel);
+    int32_t* n_lo = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_lo);
+    float* y_lo = reinterpret_cast<float*>(ctx->ws + ctx->L.out32);
+    float* y_hi = reinterpret_cast<float*>(win->ws + win->L.out32);
+    hipLaunchKernelGGL(window_split_kernel, dim3(d.B), dim3(256), 0, st, idx, n_sel, k_tot, w, idx_hi, n_lo, n_hi);
+    if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+    int parts_lo = 0, parts_hi = 0;
+    const bool bf = d.dtype == SALS_BF16;
+    s = bf ? launch_attend<bf16_t>(ctx, q, q_pos, Kc, Vc, W, idx, n_lo, nullptr, st, nullptr, 0, y_lo, &parts_lo)
+           : launch_attend<float>(ctx, q, q_pos, Kc, Vc, W, idx, n_lo, nullptr, st, nullptr, 0, y_lo, &parts_lo);
+    if (s != SALS_OK) return s;
+    s = bf ? launch_attend<bf16_t>(win, q, q_pos, Kw, Vw, W_hi, idx_hi, n_hi, nullptr, st, nullptr, w, y_hi, &parts_hi)
+           : launch_attend<float>(win, q, q_pos, Kw, Vw, W_hi, idx_hi, n_hi, nullptr, st, nullptr, w, y_hi, &parts_hi);
+    if (s != SALS_OK) return s;
+    const float2* st_lo = reinterpret_cast<const float2*>(ctx->ws + ctx->L.stats);
+    const float2* st_hi = reinterpret_cast<const float2*>(win->ws + win->L.stats);
+    if (bf)
+        hipLaunchKernelGGL((window_merge_kernel<bf16_t>), dim3(d.B * d.H_q), dim3(128), 0, st, y_lo, st_lo, parts_lo,
+                           y_hi, st_hi, parts_hi, static_cast<bf16_t*>(out));
+    else
+        hipLaunchKernelGGL((window_merge_kernel<float>), dim3(d.B * d.H_q), dim3(128), 0, st, y_lo, st_lo, parts_lo,
+                           y_hi, st_hi, parts_hi, static_cast<float*>(out));
+    return launch_status();
+}
+
+sals_status sals_decode_step_window(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos,
+                                    const void* Kc, const void* Vc, const void* W, const void* Kw, const void* Vw,
+                                    const void* W_hi, const int32_t* seq_len, void* out, float* scores,
+                                    int32_t* idx, int32_t* n_sel, void* hip_stream)
+{
+    sals_status s = window_pair_ok(ctx, win);
+    if (s != SALS_OK) return s;
+    if (bad(q) || !q_pos || bad(Kc) || bad(Vc) || bad(W) || bad(Kw) || bad(Vw) || bad(W_hi) || !seq_len || bad(out))
+        return SALS_ERR_INVALID_ARG;
+    if (scores && !aligned16(scores)) return SALS_ERR_INVALID_ARG;
+    if (!scores) scores = reinterpret_cast<float*>(ctx->ws + ctx->L.scores);
+    if (!idx) idx = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.idx);
+    if (!n_sel) n_sel = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_sel);
+    s = sals_latent_scores(ctx, q, W, Kc, seq_len, scores, hip_stream);
+    if (s != SALS_OK) return s;
+    s = sals_topk_select(ctx, scores, seq_len, idx, n_sel, hip_stream);
+    if (s != SALS_OK) return s;
+    return sals_sparse_attend_window(ctx, win, q, q_pos, Kc, Vc, W, Kw, Vw, W_hi, idx, n_sel, out, hip_stream);
+}
+
+// ---- overlap score ----------------------------------------------------------------------------------
+
+sals_status sals_overlap_score(sals_ctx* ctx, const void* q, const int32_t* q_pos, const void* K,
+                               const int32_t* seq_len, const int32_t* idx, const int32_t* n_sel, float* os,
+                               void* hip_stream)
+{
+    if (!ctx || bad(q) || !q_pos || bad(K) || !seq_len || !idx || !n_sel || !os) return SALS_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const sals_desc& d = ctx->d;
+    const Layout& L = ctx->L;
+    if (ensure_rope_table(ctx, st) != SALS_OK) return SALS_ERR_HIP;
+    const int k_tot = d.top_k + d.n_sink + d.n_recent;
+    float2* part = reinterpret_cast<float2*>(ctx->ws + L.dn_part);  // the dense baseline's partials: larger
+    const float2* rope = reinterpret_cast<const float2*>(ctx->ws + L.rope);
+    const int G = d.H_q / d.H_kv;
+    const dim3 grid(L.dn_chunks, d.H_kv, d.B);
+    const float scale = 1.0f / std::sqrt((float)d.d);
+#define SALS_OS(T, GMAX)                                                                                          \
+    hipLaunchKernelGGL((overlap_stats_kernel<T, GMAX>), grid, dim3(256), 0, st, static_cast<const T*>(q), q_pos,     \
+                       static_cast<const T*>(K), seq_len, idx, n_sel, rope, ctx->inv, part, d.S_max, d.H_q, d.H_kv, \
+                       k_tot, L.dn_chunks, L.dn_tok, ceil_div(k_tot, L.dn_chunks), d.rope_style, scale)
+#define SALS_OS_G(T)                                                                                              \
+    do {                                                                                                          \
+        if (G <= 1) SALS_OS(T, 1); else if (G <= 2) SALS_OS(T, 2); else if (G <= 4) SALS_OS(T, 4); else SALS_OS(T, 8); \
+    } while (0)
+    if (d.dtype == SALS_BF16) SALS_OS_G(bf16_t); else SALS_OS_G(float);
+#undef SALS_OS_G
+#undef SALS_OS
+    if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+    hipLaunchKernelGGL(overlap_merge_kernel, dim3(ceil_div(d.B * d.H_q, 256)), dim3(256), 0, st, part, os,
+                       d.B * d.H_q, L.dn_chunks);
+    return launch_status();
 }
 
 }  // extern "C"

@@ -42,6 +42,7 @@ class Workload:
     corr_rho: float = 0.3
     scale: float = 1.0           # extra cache scale (stress cases only)
     qv_bits: int = 0             # > 0: values live in the quantised full-rank cache (2 | 4 bits)
+    r_hi: int = 0                # > 0: the n_recent last tokens live in a ring cache of this rank (Sec. 5.1)
 
     @property
     def D_kv(self):
@@ -91,6 +92,15 @@ VARIANTS = {
 VARIANTS.update({
     f"{name}_qv{bits}": replace(w, name=f"{w.name}_qvalue{bits}bit", qv_bits=bits)
     for name, w in CONFIGS.items() if name in ("cfg2", "cfg3a", "cfg3b", "cfg4") for bits in (4, 2)
+})
+
+
+# The paper's selection composition for LLaMA2-7B (Sec. 5.2: 16 sink + 432 critical + 64 recent tokens) with
+# the recent tokens in a high-precision window (Sec. 5.1) of the largest rank the kernels take.
+VARIANTS.update({
+    f"{name}_win": replace(w, name=f"{w.name}_sink16_crit432_win64_rhi1024", top_k=432, n_sink=16,
+                           n_recent=64, r_hi=1024)
+    for name, w in CONFIGS.items() if name in ("cfg2", "cfg3a")
 })
 
 
@@ -253,3 +263,36 @@ def make_dense_cache(w: Workload, layer: int = 0):
     K = rng.standard_normal((w.B, w.S, w.H_kv, w.d), dtype=np.float32)
     V = rng.standard_normal((w.B, w.S, w.H_kv, w.d), dtype=np.float32)
     return {"q": store(q, w.dtype), "K": store(K, w.dtype), "V": store(V, w.dtype)}
+
+
+# ---- high-precision recent window (Sec. 5.1) ----------------------------------------------
+
+def make_window(w: Workload, L: dict, layer: int = 0):
+    """The window caches that go with a layer `L` from make_layer: projectors Uk_hi, Uv_hi
+    [D_kv, r_hi] whose first r columns are the layer's (stored) projectors and whose other
+    columns are an orthonormal completion, and ring caches Kw, Vw [B, n_recent, r_hi]: for
+    each of a sequence's last n_recent tokens t, row t mod n_recent holds the token's low-rank
+    row followed by r_hi - r further coordinates drawn with the same decaying spectrum
+    ((c+1)^-1/2 at coordinate c); rows no token maps to stay zero.  Storage-rounded."""
+    assert w.r_hi > w.r and w.n_recent > 0
+    rng = np.random.default_rng(seed_of(w, layer, 88))
+    out = {}
+    for name in ("Uk", "Uv"):
+        U = widen(L[name])
+        E = rng.standard_normal((w.D_kv, w.r_hi - w.r))
+        E -= U @ (U.T @ E)
+        E, _ = np.linalg.qr(E)
+        out[name + "_hi"] = np.concatenate([L[name], store(E, w.dtype)], axis=1)
+    st = np.uint16 if w.dtype == "bf16" else np.float32
+    sigma = (np.arange(w.r + 1, w.r_hi + 1, dtype=np.float64)) ** -0.5 * w.scale
+    n_w = w.n_recent
+    for name, src in (("Kw", "Kc"), ("Vw", "Vc")):
+        ring = np.zeros((w.B, n_w, w.r_hi), dtype=st)
+        for b in range(w.B):
+            S = int(L["seq_len"][b])
+            for t in range(max(0, S - n_w), S):
+                extra = rng.standard_normal(w.r_hi - w.r, dtype=np.float32).astype(np.float64) * sigma
+                ring[b, t % n_w, : w.r] = L[src][b, t]
+                ring[b, t % n_w, w.r:] = store(extra, w.dtype)
+        out[name] = ring
+    return out

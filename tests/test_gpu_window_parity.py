@@ -1,0 +1,234 @@
+"""GPU parity of the high-precision recent window (Sec. 5.1: the recent tokens in a second,
+higher-rank ring cache) and of the overlap score (Sec. 3.2) against the oracle, through the C ABI.
+Same bounds as the sparse path: selection bit-exact under the shared rule, outputs within max-abs
+2e-2 (bf16) / 1e-4 (fp32) and the tighter derived bound of tests/gpu_util.py::out_tolerances;
+ring rows written by the append within one unit in the last place of the storage type; overlap scores within 1e-4."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+from paper_2510_24273_amd import binding, synth  # noqa: E402
+from tests import gpu_util as gu  # noqa: E402
+
+C = synth.CONFIGS
+SMALL = synth.shrink(C["cfg2"], B=3, S=1000, r=128, r_hi=256, top_k=100, n_sink=4, n_recent=40, n_layers=1,
+                     plant=2)
+
+
+def make_win_ctx(w):
+    desc = binding.make_desc(w.B, w.S, w.H, w.H_kv, w.d, w.r_hi, w.n_recent, w.dtype, rope_theta=w.theta,
+                             rope_style=w.rope_style)
+    return binding.Sals(desc, gu.DEV)
+
+
+def _case(oracle, w, seq_lens=None, seqs=None, label=""):
+    print(f"[case] window {label or w.name} B={w.B} S={w.S} r={w.r}/{w.r_hi} k={w.n_sink}+{w.top_k}+{w.n_recent} "
+          f"{w.dtype} seq_lens={seq_lens}", flush=True)
+    L = synth.make_layer(w, 0, seq_lens)
+    Wn = synth.make_window(w, L)
+    ctx, win = gu.make_ctx(w), make_win_ctx(w)
+    G = gu.upload(L, ctx)
+    Gw = {k: gu.to_dev(v) for k, v in Wn.items()}
+    W_hi = win.pack_weights(Gw["Uk_hi"], Gw["Uv_hi"])
+    idx = torch.full((w.B, w.k_tot), -7, dtype=torch.int32, device=gu.DEV)
+    n_sel = torch.full((w.B,), -7, dtype=torch.int32, device=gu.DEV)
+    scores = torch.empty((w.B, w.S), dtype=torch.float32, device=gu.DEV)
+    out = torch.empty((w.B, w.H, w.d), dtype=gu.out_dtype(w), device=gu.DEV)
+    ctx.decode_step_window(win, G["q"], G["q_pos"], G["Kc"], G["Vc"], G["W"], Gw["Kw"], Gw["Vw"], W_hi,
+                           G["seq_len"], out, scores, idx, n_sel)
+    # the staged call on the same selection, and a second whole step, must reproduce it bit for bit
+    out2, out3 = torch.empty_like(out), torch.empty_like(out)
+    ctx.sparse_attend_window(win, G["q"], G["q_pos"], G["Kc"], G["Vc"], G["W"], Gw["Kw"], Gw["Vw"], W_hi, idx,
+                             n_sel, out2)
+    ctx.decode_step_window(win, G["q"], G["q_pos"], G["Kc"], G["Vc"], G["W"], Gw["Kw"], Gw["Vw"], W_hi,
+                           G["seq_len"], out3)
+    torch.cuda.synchronize()
+    bits = (lambda t: t.view(torch.int16)) if out.dtype == torch.bfloat16 else (lambda t: t)
+    assert torch.equal(bits(out), bits(out2)) and torch.equal(bits(out), bits(out3))
+    R = {"scores": scores, "idx": idx, "n_sel": n_sel, "out": out}
+    wd = synth.widen
+    worst = 0.0
+    for b in (range(w.B) if seqs is None else seqs):
+        gu.check_sequence(oracle, w, L, R, b, check_out=False)   # scores and selection as in the plain path
+        S = int(L["seq_len"][b])
+        n = int(n_sel[b].item())
+        sel = gu.from_dev(idx[b])[:n].astype(np.int32)
+        y_gpu = gu.from_dev(out[b])
+        if n == 0:
+            assert np.all(y_gpu == 0)
+            continue
+        # the recent tokens come last in the selection, in token order
+        n_w = min(w.n_recent, n)
+        assert sel[n - n_w:].tolist() == list(range(S - n_w, S))
+        y_ref = oracle.sparse_attend_window(wd(L["q"][b]), int(L["q_pos"][b]), wd(L["Kc"][b][:S]), wd(L["Vc"][b][:S]),
+                                            wd(L["Uk"]), wd(L["Uv"]), wd(Wn["Kw"][b]), wd(Wn["Vw"][b]),
+                                            wd(Wn["Uk_hi"]), wd(Wn["Uv_hi"]), sel, S, w.H_kv, w.theta, w.rope_style)
+        star, tight = gu.out_tolerances(w, y_ref)
+        err = float(np.max(np.abs(y_gpu - y_ref)))
+        worst = max(worst, err)
+        assert err <= star, f"b={b}: output error {err:.3e} > {star}"
+        assert err <= tight, f"b={b}: output error {err:.3e} > derived bound {tight:.3e}"
+        # the window matters: the plain low-rank path over the same selection gives another answer
+        y_plain = oracle.sparse_attend(wd(L["q"][b]), int(L["q_pos"][b]), wd(L["Kc"][b][:S]), wd(L["Vc"][b][:S]),
+                                       wd(L["Uk"]), wd(L["Uv"]), sel, w.H_kv, w.theta, w.rope_style)
+        assert np.max(np.abs(y_plain - y_ref)) > 4 * tight
+    print(f"    worst output error {worst:.3e}", flush=True)
+    ctx.close(); win.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_small_ragged_batch(oracle, dtype):
+    # full; everything selected with some tokens outside the window; cache shorter than the window
+    _case(oracle, synth.shrink(SMALL, dtype=dtype), seq_lens=[1000, 141, 23])
+
+
+def test_edge_lengths(oracle):
+    # empty, one token, exactly the window, one more than the window, exactly the budget, one more
+    w = synth.shrink(SMALL, B=6, plant=0)
+    _case(oracle, w, seq_lens=[0, 1, 40, 41, 144, 145])
+
+
+def test_gqa_interleaved_rope_and_ring_wrap(oracle):
+    # window of 48 over lengths that are no multiple of it (the ring is entered mid-way)
+    w = synth.shrink(SMALL, B=2, S=777, H=32, H_kv=8, n_recent=48, rope_style=1, theta=500000.0)
+    _case(oracle, w, seq_lens=[777, 500])
+
+
+def test_largest_window_rank(oracle):
+    w = synth.shrink(SMALL, B=2, S=600, r=640, r_hi=1024, top_k=200, n_sink=16, n_recent=128, plant=0)
+    _case(oracle, w, seq_lens=[600, 345])
+
+
+def test_cfg2_with_the_papers_composition(oracle):
+    """Full size of the measured configuration: 16 sink + 432 critical + 64 recent tokens, window rank 1024."""
+    _case(oracle, synth.lookup("cfg2_win"))
+
+
+def test_cfg3a_with_the_papers_composition_sampled(oracle):
+    _case(oracle, synth.lookup("cfg3a_win"), seqs=[0, 7, 15])
+
+
+def test_window_append_matches_oracle_over_ring_wraps(oracle):
+    """25 tokens appended to both caches with a window of 8: the ring wraps three times, rows hold the last
+    eight tokens' latent images within one rounding, and the step over the result matches the oracle."""
+    w = synth.shrink(SMALL, B=2, S=64, r=64, r_hi=128, top_k=6, n_sink=2, n_recent=8, plant=0, H=8, H_kv=4)
+    print(f"[case] window append {w.name}", flush=True)
+    L = synth.make_layer(w, 0, [0, 0])
+    Wn = synth.make_window(w, L)
+    ctx, win = gu.make_ctx(w), make_win_ctx(w)
+    G = gu.upload(L, ctx)
+    W_hi = win.pack_weights(gu.to_dev(Wn["Uk_hi"]), gu.to_dev(Wn["Uv_hi"]))
+    dt = gu.out_dtype(w)
+    Kc = torch.zeros((w.B, w.S, w.r), dtype=dt, device=gu.DEV)
+    Vc = torch.zeros_like(Kc)
+    Kw = torch.zeros((w.B, w.n_recent, w.r_hi), dtype=dt, device=gu.DEV)
+    Vw = torch.zeros_like(Kw)
+    seq_len = torch.tensor([0, 5], dtype=torch.int32, device=gu.DEV)   # the second sequence starts mid-ring
+    rng = np.random.default_rng(4)
+    n_tok = 25
+    toks_k = synth.store(rng.standard_normal((n_tok, w.B, w.D_kv)), w.dtype)
+    toks_v = synth.store(rng.standard_normal((n_tok, w.B, w.D_kv)), w.dtype)
+    for t in range(n_tok):
+        k_new, v_new = gu.to_dev(toks_k[t]), gu.to_dev(toks_v[t])
+        win.window_append(k_new, v_new, W_hi, Kw, Vw, seq_len)
+        ctx.compress_append(k_new, v_new, G["W"], Kc, Vc, seq_len)
+    torch.cuda.synchronize()
+    assert seq_len.tolist() == [25, 30]
+    wd = synth.widen
+    Uk_hi, Uv_hi = wd(Wn["Uk_hi"]), wd(Wn["Uv_hi"])
+    ulp = 2.0 ** -7 if w.dtype == "bf16" else 2.0 ** -22   # one unit in the last place of the storage type
+    for b, start in enumerate((0, 5)):
+        Kw_ref, Vw_ref = np.zeros((w.n_recent, w.r_hi)), np.zeros((w.n_recent, w.r_hi))
+        for t in range(n_tok):
+            oracle.window_append(Kw_ref, Vw_ref, wd(toks_k[t, b]), wd(toks_v[t, b]), Uk_hi, Uv_hi, start + t)
+        for got, ref in ((Kw[b], Kw_ref), (Vw[b], Vw_ref)):
+            err = np.abs(gu.from_dev(got) - ref)
+            assert np.all(err <= ulp * np.abs(ref) + 1e-6), f"ring rows of sequence {b}: {err.max():.3e}"
+    # a decode step over the caches the appends built
+    q = gu.to_dev(synth.store(rng.standard_normal((w.B, w.H, w.d)), w.dtype))
+    out = torch.empty((w.B, w.H, w.d), dtype=dt, device=gu.DEV)
+    idx = torch.empty((w.B, w.k_tot), dtype=torch.int32, device=gu.DEV)
+    n_sel = torch.empty((w.B,), dtype=torch.int32, device=gu.DEV)
+    ctx.decode_step_window(win, q, seq_len, Kc, Vc, G["W"], Kw, Vw, W_hi, seq_len, out, None, idx, n_sel)
+    torch.cuda.synchronize()
+    for b in range(w.B):
+        S = int(seq_len[b].item())
+        sel = gu.from_dev(idx[b])[: int(n_sel[b].item())].astype(np.int32)
+        y_ref = oracle.sparse_attend_window(gu.from_dev(q[b]), S, gu.from_dev(Kc[b][:S]), gu.from_dev(Vc[b][:S]),
+                                            wd(L["Uk"]), wd(L["Uv"]), gu.from_dev(Kw[b]), gu.from_dev(Vw[b]), Uk_hi,
+                                            Uv_hi, sel, S, w.H_kv, w.theta, w.rope_style)
+        star, tight = gu.out_tolerances(w, y_ref)
+        assert float(np.max(np.abs(gu.from_dev(out[b]) - y_ref))) <= tight
+    ctx.close(); win.close()
+
+
+def test_window_argument_checks():
+    w = SMALL
+    ctx, win = gu.make_ctx(w), make_win_ctx(w)
+    bad_w = make_win_ctx(synth.shrink(w, n_recent=w.n_recent + 8))          # ring size differs from n_recent
+    bad_h = make_win_ctx(synth.shrink(w, H=16, H_kv=16))                    # another model
+    t = torch.zeros(64, dtype=torch.int32, device=gu.DEV)
+    for other in (bad_w, bad_h, ctx):
+        with pytest.raises(binding.SalsError):
+            ctx.decode_step_window(other, t, t, t, t, t, t, t, t, t, t)
+    with pytest.raises(binding.SalsError):
+        ctx.window_append(t, t, t, t, t, t)                                 # a context with sink / recent tokens
+    for c in (ctx, win, bad_w, bad_h):
+        c.close()
+
+
+# ---- overlap score ---------------------------------------------------------------------
+
+def _overlap_case(oracle, w, seq_lens, seed=0):
+    print(f"[case] overlap {w.name} B={w.B} S={w.S} H={w.H}/{w.H_kv} k={w.k_tot} {w.dtype} seq_lens={seq_lens}",
+          flush=True)
+    L = synth.make_dense_cache(w, 0)
+    sl = np.asarray(seq_lens, np.int32)
+    rng = np.random.default_rng(seed)
+    idx = np.zeros((w.B, w.k_tot), np.int32)
+    n_sel = np.zeros(w.B, np.int32)
+    for b in range(w.B):
+        n_sel[b] = min(int(sl[b]), int(rng.integers(0, w.k_tot + 1)) if b else w.k_tot)
+        idx[b, : n_sel[b]] = rng.choice(int(sl[b]), n_sel[b], replace=False) if n_sel[b] else []
+    ctx = gu.make_ctx(w)
+    os_gpu = torch.full((w.B, w.H), -1.0, dtype=torch.float32, device=gu.DEV)
+    ctx.overlap_score(gu.to_dev(L["q"]), gu.to_dev(sl), gu.to_dev(L["K"]), gu.to_dev(sl), gu.to_dev(idx),
+                      gu.to_dev(n_sel), os_gpu)
+    torch.cuda.synchronize()
+    wd = synth.widen
+    for b in range(w.B):
+        S = int(sl[b])
+        ref = oracle.overlap_score(wd(L["q"][b]), S, wd(L["K"][b][:S]), idx[b, : n_sel[b]], w.theta, w.rope_style)
+        err = np.abs(gu.from_dev(os_gpu[b]) - ref)
+        assert err.max() <= 1e-4, f"b={b}: overlap score error {err.max():.3e}"
+    print(f"    overlap of sequence 0: mean {float(os_gpu[0].mean()):.4f}", flush=True)
+    ctx.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_overlap_small(oracle, dtype):
+    w = synth.shrink(C["cfg2"], B=4, S=1000, r=128, top_k=100, n_layers=1, plant=0, dtype=dtype)
+    _overlap_case(oracle, w, [1000, 333, 0, 1])
+
+
+def test_overlap_gqa_and_long_cache(oracle):
+    w = synth.shrink(C["cfg3b"], B=2, S=9000, r=128, top_k=1000, plant=0, rope_style=1)
+    _overlap_case(oracle, w, [9000, 4097], seed=3)
+
+
+def test_overlap_of_the_whole_cache_is_one(oracle):
+    w = synth.shrink(C["cfg2"], B=1, S=300, r=128, top_k=300, n_layers=1, plant=0)
+    L = synth.make_dense_cache(w, 0)
+    ctx = gu.make_ctx(w)
+    sl = torch.tensor([300], dtype=torch.int32, device=gu.DEV)
+    idx = torch.arange(300, dtype=torch.int32, device=gu.DEV).reshape(1, 300)
+    os_gpu = torch.empty((1, w.H), dtype=torch.float32, device=gu.DEV)
+    ctx.overlap_score(gu.to_dev(L["q"]), sl, gu.to_dev(L["K"]), sl, idx, sl, os_gpu)
+    torch.cuda.synchronize()
+    assert float((os_gpu - 1).abs().max()) <= 1e-5
+    ctx.close()
