@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer buffer sets (0 = workload default)")
-    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg2_rhalf,cfg4_rhalf,cfg2_qv4,cfg4_qv4",
+    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg2_rhalf,cfg4_rhalf,cfg2_qv4,cfg4_qv4,cfg2_comp,cfg2_win,cfg3a_comp,cfg3a_win",
                     help="other configurations reported under 'extra' (comma list, '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
@@ -61,6 +61,10 @@ class LayerSet:
                                  n_recent=w.n_recent, n_sink=w.n_sink, rope_theta=w.theta,
                                  rope_style=w.rope_style)
         self.ctx = binding.Sals(desc, dev)
+        self.win = None
+        if w.r_hi:      # the recent tokens in a second, higher-rank ring cache with a context of its own
+            self.win = binding.Sals(binding.make_desc(w.B, w.S, w.H, w.H_kv, w.d, w.r_hi, w.n_recent, w.dtype,
+                                                      rope_theta=w.theta, rope_style=w.rope_style), dev)
         self.layers = []
         self.host0 = None
         for l in range(n_layers):
@@ -69,6 +73,10 @@ class LayerSet:
                 self.host0 = L
             G = {k: up(v) for k, v in L.items() if hasattr(v, "dtype")}
             G["W"] = self.ctx.pack_weights(G.pop("Uk"), G.pop("Uv"))   # one-time repack, as at model load
+            if w.r_hi:
+                Wn = synth.make_window(w, L, l)
+                G["Kw"], G["Vw"] = up(Wn["Kw"]), up(Wn["Vw"])
+                G["W_hi"] = self.win.pack_weights(up(Wn["Uk_hi"]), up(Wn["Uv_hi"]))
             if w.qv_bits:   # quantised full-rank value cache in place of the latent one
                 del G["Vc"]
                 codes, meta = synth.make_qv_cache(w, l, w.qv_bits)
@@ -81,6 +89,11 @@ class LayerSet:
         self.out = [torch.empty((w.B, w.H, w.d), dtype=odt, device=dev) for _ in range(n_layers)]
 
     def step(self):
+        if self.win is not None:
+            for G, o in zip(self.layers, self.out):
+                self.ctx.decode_step_window(self.win, G["q"], G["q_pos"], G["Kc"], G["Vc"], G["W"], G["Kw"], G["Vw"],
+                                            G["W_hi"], G["seq_len"], o)
+            return
         if self.w.qv_bits:
             for G, o in zip(self.layers, self.out):
                 self.ctx.decode_step_qv(G["q"], G["q_pos"], G["Kc"], G["Vq"], G["Vmeta"], self.w.qv_bits, G["W"],

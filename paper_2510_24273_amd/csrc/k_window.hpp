@@ -33,7 +33,8 @@ __global__ __launch_bounds__(256) void window_split_kernel(const int32_t* __rest
 }
 
 // out[b,h,:] from the two passes' unrounded outputs [B,H,d] and per-tile statistics [B,H,parts].
-// grid (B*H), 128 threads (one per channel); the tiles are merged in a fixed tree order.
+// grid (B*H), 128 threads (one per channel); the tiles are merged in a fixed order (in sequence when there are
+// at most eight per pass, else as a tree over the 128 threads).
 template <typename T>
 __global__ __launch_bounds__(128) void window_merge_kernel(const float* __restrict__ out_lo,
                                                            const float2* __restrict__ stats_lo, int parts_lo,
@@ -46,18 +47,33 @@ __global__ __launch_bounds__(128) void window_merge_kernel(const float* __restri
     const int c = threadIdx.x;
     const float y_lo = out_lo[bh * kHeadDim + c], y_hi = out_hi[bh * kHeadDim + c];
     float2 a = make_float2(-INFINITY, 0.f), h = a;
-    for (int t = c; t < parts_lo; t += 128) a = stat_merge(a, stats_lo[bh * parts_lo + t]);
-    for (int t = c; t < parts_hi; t += 128) h = stat_merge(h, stats_hi[bh * parts_hi + t]);
-    sm[0][c] = a; sm[1][c] = h;
-    __syncthreads();
-    for (int s = 64; s > 0; s >>= 1) {
-        if (c < s) {
-            sm[0][c] = stat_merge(sm[0][c], sm[0][c + s]);
-            sm[1][c] = stat_merge(sm[1][c], sm[1][c + s]);
+    if (parts_lo <= 8 && parts_hi <= 8) {
+        // few tiles (the usual case): every thread merges them itself, all loads in flight together
+        float2 ea[8], eh[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            ea[u] = stats_lo[bh * parts_lo + min(u, parts_lo - 1)];
+            eh[u] = stats_hi[bh * parts_hi + min(u, parts_hi - 1)];
         }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (u < parts_lo) a = stat_merge(a, ea[u]);
+            if (u < parts_hi) h = stat_merge(h, eh[u]);
+        }
+    } else {
+        for (int t = c; t < parts_lo; t += 128) a = stat_merge(a, stats_lo[bh * parts_lo + t]);
+        for (int t = c; t < parts_hi; t += 128) h = stat_merge(h, stats_hi[bh * parts_hi + t]);
+        sm[0][c] = a; sm[1][c] = h;
         __syncthreads();
+        for (int s = 64; s > 0; s >>= 1) {
+            if (c < s) {
+                sm[0][c] = stat_merge(sm[0][c], sm[0][c + s]);
+                sm[1][c] = stat_merge(sm[1][c], sm[1][c + s]);
+            }
+            __syncthreads();
+        }
+        a = sm[0][0]; h = sm[1][0];
     }
-    a = sm[0][0]; h = sm[1][0];
     const float m = fmaxf(a.x, h.x);
     const float w_lo = a.y > 0.f ? a.y * __expf(a.x - m) : 0.f;  // Z > 0 implies a finite maximum
     const float w_hi = h.y > 0.f ? h.y * __expf(h.x - m) : 0.f;

@@ -361,6 +361,9 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     } while (0)
         // the 64-token kernel while its workgroups fit the chip in one round (or too few large tiles exist)
         int pick = (d.H_kv % 2 == 0 && n_wg(2, 256) >= 384) ? 1 : ((n_wg(1, 64) > 256 && n_wg(1, 256) >= 96) ? 2 : 3);
+        // a selection that fills less than 60 % of its 256-token tiles (a short list such as a recent window) would
+        // spend the rest of every tile's matrix work on padding: 64-token tiles then
+        if ((long long)k_tot * 10 < (long long)ceil_div(k_tot, 256) * 256 * 6) pick = 3;
         if (const char* e = std::getenv("SALS_TUNE_LOGITS")) {  // tuning aid: 1 | 2 | 3
             const int v = std::atoi(e);
             if (v == 1 && d.H_kv % 2 == 0) pick = 1;
@@ -753,6 +756,8 @@ sals_status sals_sparse_attend_window(sals_ctx* ctx, sals_ctx* win, const void* 
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     int parts_lo = 0, parts_hi = 0;
     const bool bf = d.dtype == SALS_BF16;
+    // (the two passes are independent until the merge; running the window pass on a second stream, forked and
+    // joined by events, was measured and gained nothing)
     s = bf ? launch_attend<bf16_t>(ctx, q, q_pos, Kc, Vc, W, idx, n_lo, nullptr, st, nullptr, 0, y_lo, &parts_lo)
            : launch_attend<float>(ctx, q, q_pos, Kc, Vc, W, idx, n_lo, nullptr, st, nullptr, 0, y_lo, &parts_lo);
     if (s != SALS_OK) return s;

@@ -32,13 +32,15 @@ def stage_bytes(w, seq_len=None) -> dict:
         "attend_v": (w.B * n_sel * w.r * e + w.r * w.D_kv * e) if not getattr(w, "qv_bits", 0)
         else w.B * n_sel * (w.D_kv * w.qv_bits // 8 + w.D_kv // 32 * 2 * e),
         "small": small,
+        # high-precision recent window: ring rows of both caches for the recent tokens + the window's projectors
+        "window": (2 * w.B * min(S, w.n_recent) * w.r_hi * e + 2 * w.r_hi * w.D_kv * e) if getattr(w, "r_hi", 0) else 0,
     }
 
 
 def algorithmic_bytes(w, seq_len=None) -> int:
     """Pipeline bytes: U_k is counted once (projection and reconstruction share it)."""
     b = stage_bytes(w, seq_len)
-    return b["scores"] + b["select"] + b["attend_k"] + b["attend_v"] + b["small"]
+    return b["scores"] + b["select"] + b["attend_k"] + b["attend_v"] + b["small"] + b["window"]
 
 
 def stage_flops(w, seq_len=None) -> dict:

@@ -232,3 +232,86 @@ def test_overlap_of_the_whole_cache_is_one(oracle):
     torch.cuda.synchronize()
     assert float((os_gpu - 1).abs().max()) <= 1e-5
     ctx.close()
+
+
+def test_overlap_of_the_sals_selection_on_the_synthetic_cache(oracle):
+    """The diagnostic as Sec. 3.2 uses it: the selection that the latent, RoPE-free scores make, measured
+    against dense attention over the same tokens' full-rank rotated keys (here: the keys the latent cache
+    stands for, reconstructed and rotated by the oracle).  Checked against the oracle; the value itself
+    describes the synthetic data only."""
+    w = synth.shrink(C["cfg2"], n_layers=1)
+    print(f"[case] overlap of the selection, {w.name}", flush=True)
+    L = synth.make_layer(w, 0)
+    wd = synth.widen
+    ctx = gu.make_ctx(w)
+    G = gu.upload(L, ctx)
+    R = gu.run_stages(ctx, w, G)
+    S = w.S
+    K_full = np.zeros((w.B, S, w.H_kv, w.d), dtype=np.uint16)
+    for b in range(w.B):
+        rec = oracle.reconstruct(wd(L["Kc"][b]), np.arange(S, dtype=np.int32), wd(L["Uk"])).reshape(S, w.H_kv, w.d)
+        K_full[b] = synth.store(oracle.rope(rec, np.arange(S, dtype=np.int32), w.theta, w.rope_style), w.dtype)
+    os_gpu = torch.empty((w.B, w.H), dtype=torch.float32, device=gu.DEV)
+    ctx.overlap_score(G["q"], G["q_pos"], gu.to_dev(K_full), G["seq_len"], R["idx"], R["n_sel"], os_gpu)
+    torch.cuda.synchronize()
+    for b in range(w.B):
+        sel = gu.from_dev(R["idx"][b])[: int(R["n_sel"][b].item())]
+        ref = oracle.overlap_score(wd(L["q"][b]), S, wd(K_full[b]), sel, w.theta, w.rope_style)
+        assert np.abs(gu.from_dev(os_gpu[b]) - ref).max() <= 1e-4
+    frac = w.k_tot / S
+    print(f"    overlap score: mean {float(os_gpu.mean()):.4f}, min {float(os_gpu.min()):.4f} "
+          f"(selected fraction of the cache {frac:.4f})", flush=True)
+    assert 0.0 < float(os_gpu.min()) and float(os_gpu.max()) <= 1.0 + 1e-6
+    ctx.close()
+
+
+def test_window_graph_replays_match_eager(oracle):
+    """decode_step_window captured in a HIP graph: every replay, with eager work of the same contexts and
+    synchronisations in between and the inputs changed, equals the eager result bit for bit."""
+    w = synth.shrink(SMALL, B=2, S=1500, top_k=300, plant=1)
+    print(f"[case] window graph {w.name}", flush=True)
+    ctx, win = gu.make_ctx(w), make_win_ctx(w)
+    Gs = []
+    for layer in range(3):
+        L = synth.make_layer(w, layer)
+        Wn = synth.make_window(w, L, layer)
+        G = gu.upload(L, ctx)
+        G["Kw"], G["Vw"] = gu.to_dev(Wn["Kw"]), gu.to_dev(Wn["Vw"])
+        G["W_hi"] = win.pack_weights(gu.to_dev(Wn["Uk_hi"]), gu.to_dev(Wn["Uv_hi"]))
+        Gs.append(G)
+    keys = ("q", "q_pos", "Kc", "Vc", "W", "Kw", "Vw", "W_hi", "seq_len")
+
+    def step(G, o):
+        ctx.decode_step_window(win, G["q"], G["q_pos"], G["Kc"], G["Vc"], G["W"], G["Kw"], G["Vw"], G["W_hi"],
+                               G["seq_len"], o)
+
+    eager = []
+    for G in Gs:
+        o = torch.empty((w.B, w.H, w.d), dtype=gu.out_dtype(w), device=gu.DEV)
+        step(G, o)
+        eager.append(o)
+    torch.cuda.synchronize()
+    S = {k: Gs[0][k].clone() for k in keys}
+    out = torch.empty_like(eager[0])
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(S, out)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            step(S, out)
+    torch.cuda.synchronize()
+    for rep in (1, 2, 0, 1):
+        for k in S:
+            S[k].copy_(Gs[rep][k])
+        out.fill_(7.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager[rep].view(torch.int16)), f"replay on layer {rep} differs"
+        tmp = torch.empty_like(out)
+        step(Gs[2], tmp)
+        torch.cuda.synchronize()
+        assert torch.equal(tmp.view(torch.int16), eager[2].view(torch.int16))
+    ctx.close(); win.close()
