@@ -113,5 +113,26 @@ def test_create_checks_workspace_and_calls_check_pointers(sb):
         == sb.SALS_ERR_UNSUPPORTED
     assert lib.sals_dense_attend(h, ok, ok, ok, None, ok, ok, None) == sb.SALS_ERR_INVALID_ARG
     assert lib.sals_dense_attend(h, ok, None, ok, ok, ok, ok, None) == sb.SALS_ERR_INVALID_ARG
+    # recent window and overlap score: the pairing rules and pointers are checked ahead of any launch
+    dm = _desc(sb, n_recent=64)
+    dw = _desc(sb, r=1024, top_k=64)
+    hm, hw, hx = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+    assert lib.sals_create(ctypes.byref(dm), 4096, sb.workspace_bytes(dm), ctypes.byref(hm)) == sb.SALS_OK
+    assert lib.sals_create(ctypes.byref(dw), 4096, sb.workspace_bytes(dw), ctypes.byref(hw)) == sb.SALS_OK
+    dx = _desc(sb, r=1024, top_k=32)                      # ring size differs from the main context's n_recent
+    assert lib.sals_create(ctypes.byref(dx), 4096, sb.workspace_bytes(dx), ctypes.byref(hx)) == sb.SALS_OK
+    win_args = (ok,) * 10
+    for ctx_h, win_h in ((hm, hx), (hm, hm), (hm, None), (None, hw), (h, hw)):    # h: no recent tokens
+        assert lib.sals_decode_step_window(ctx_h, win_h, *win_args, None, None, None, None) == sb.SALS_ERR_INVALID_ARG
+        assert lib.sals_sparse_attend_window(ctx_h, win_h, *win_args, ok, None) == sb.SALS_ERR_INVALID_ARG
+    assert lib.sals_decode_step_window(hm, hw, ok, ok, ok, ok, ok, None, ok, ok, ok, ok, None, None, None, None) \
+        == sb.SALS_ERR_INVALID_ARG                                                 # Kw missing
+    assert lib.sals_window_append(hw, ok, ok, ok, ok, ok, None, None) == sb.SALS_ERR_INVALID_ARG
+    assert lib.sals_window_append(hm, ok, ok, ok, ok, ok, ok, None) == sb.SALS_ERR_INVALID_ARG   # not a window context
+    assert lib.sals_window_append(None, ok, ok, ok, ok, ok, ok, None) == sb.SALS_ERR_INVALID_ARG
+    assert lib.sals_overlap_score(h, ok, ok, ok, ok, ok, ok, None, None) == sb.SALS_ERR_INVALID_ARG
+    assert lib.sals_overlap_score(h, ok, ok, ok + 2, ok, ok, ok, ok, None) == sb.SALS_ERR_INVALID_ARG
+    for hh in (hm, hw, hx):
+        lib.sals_destroy(hh)
     lib.sals_destroy(h)
     lib.sals_destroy(None)
