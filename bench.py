@@ -64,7 +64,8 @@ class LayerSet:
         self.win = None
         if w.r_hi:      # the recent tokens in a second, higher-rank ring cache with a context of its own
             self.win = binding.Sals(binding.make_desc(w.B, w.S, w.H, w.H_kv, w.d, w.r_hi, w.n_recent, w.dtype,
-                                                      rope_theta=w.theta, rope_style=w.rope_style), dev)
+                                                      r_score=min(w.r_hi, 1024), rope_theta=w.theta,
+                                                      rope_style=w.rope_style), dev)
         self.layers = []
         self.host0 = None
         for l in range(n_layers):

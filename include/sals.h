@@ -60,8 +60,8 @@ enum { SALS_ROPE_HALF = 0,        /* pair (i, i+d/2) */
        SALS_ROPE_INTERLEAVED = 1  /* pair (2i, 2i+1) */ };  /* sals_desc.rope_style */
 
 /* Problem descriptor (plain data, host memory).
- * Supported by the kernels: d == 128; r a multiple of 64, 64 <= r <= 1024;
- * r_score a multiple of 8, 8 <= r_score <= r; H_q a multiple of H_kv with
+ * Supported by the kernels: d == 128; r a multiple of 64, 64 <= r <= 2048;
+ * r_score a multiple of 8, 8 <= r_score <= min(r, 1024); H_q a multiple of H_kv with
  * H_q/H_kv <= 8 and H_q <= 64; B >= 1 with B*(H_q/H_kv) <= 128; 1 <= S_max <= 2^20;
  * top_k >= 1; n_sink, n_recent >= 0; top_k + n_sink + n_recent <= 65536. */
 typedef struct {
@@ -235,14 +235,14 @@ sals_status sals_dense_attend(sals_ctx* ctx, const void* q, const int32_t* q_pos
  * rest, and this window is the set of recent tokens the selection always keeps (Sec. 5.2).
  * Where the paper gives no detail the format is: a second pair of latent caches Kw, Vw of rank
  * r_hi > r with projectors of their own (the leading r_hi principal directions of the same
- * calibration; r_hi = D_kv/2 is the paper's 50 % setting, the kernels cover r_hi <= 1024), held as
+ * calibration; r_hi = D_kv/2 is the paper's 50 % setting), held as
  * a ring of w rows per sequence: token t lies in row t mod w while it is among the last w tokens.
  * Every token is written to both caches when it is appended, so nothing is re-compressed when it
  * leaves the window: its ring row is simply overwritten w tokens later.
  *
  * The window has a context of its own, `win`, created from a descriptor that equals the main
  * one in B, S_max, H_q, H_kv, d, rope_theta, rope_style and dtype and has r = r_hi, top_k = w
- * (= the main descriptor's n_recent >= 1), n_sink = n_recent = 0 (r_score: any valid value, unused), with its
+ * (= the main descriptor's n_recent >= 1), n_sink = n_recent = 0 (r_score: any valid value <= 1024, unused), with its
  * own workspace and its own packed projectors W_hi (sals_pack_weights on `win`).
  *   Kw, Vw [B, w, r_hi] T */
 

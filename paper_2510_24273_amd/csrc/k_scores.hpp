@@ -15,7 +15,7 @@ namespace sals {
 
 constexpr int kScoreThreads = 256;
 constexpr int kScoreRowsPerIter = (kScoreThreads / kWave) * 4;  // 16 rows per workgroup pass
-constexpr int kScoreMaxR = 1024;
+constexpr int kScoreMaxR = 1024;  // scoring rank r* at most (q~[:r*] sits in LDS, one 16-byte piece per thread)
 constexpr int kScoreMaxParts = 8;   // slices of the D axis the projection may split into
 
 // NCH = 16-byte pieces per lane = ceil(r_score / (vec*16))

@@ -98,8 +98,8 @@ sals_status validate(const sals_desc* d)
     if (!(d->rope_theta > 0.f) || !std::isfinite(d->rope_theta)) return SALS_ERR_INVALID_ARG;
     // what the kernels cover
     if (d->d != kHeadDim) return SALS_ERR_UNSUPPORTED;
-    if (d->r % 64 != 0 || d->r > 1024) return SALS_ERR_UNSUPPORTED;
-    if (d->r_score % 8 != 0) return SALS_ERR_UNSUPPORTED;
+    if (d->r % 64 != 0 || d->r > 2048) return SALS_ERR_UNSUPPORTED;
+    if (d->r_score % 8 != 0 || d->r_score > kScoreMaxR) return SALS_ERR_UNSUPPORTED;
     if (d->H_q / d->H_kv > kMaxGroup || d->H_q > kPvMaxHeads) return SALS_ERR_UNSUPPORTED;
     if (d->S_max > (1 << 20)) return SALS_ERR_UNSUPPORTED;  // the RoPE table takes 512 B per position
     if ((long long)d->B * (d->H_q / d->H_kv) > kProjMaxCols) return SALS_ERR_UNSUPPORTED;

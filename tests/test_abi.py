@@ -58,7 +58,8 @@ def test_workspace_bytes_and_validation(sb):
         (dict(rope_style=2), sb.SALS_ERR_INVALID_ARG),
         (dict(d=64), sb.SALS_ERR_UNSUPPORTED),
         (dict(r=520), sb.SALS_ERR_UNSUPPORTED),
-        (dict(r=2048), sb.SALS_ERR_UNSUPPORTED),
+        (dict(r=4096), sb.SALS_ERR_UNSUPPORTED),
+        (dict(r=2048, r_score=2048), sb.SALS_ERR_UNSUPPORTED),   # scoring rank above 1024
         (dict(r_score=100), sb.SALS_ERR_UNSUPPORTED),
         (dict(H_q=128, H_kv=8), sb.SALS_ERR_UNSUPPORTED),
         (dict(B=64), sb.SALS_ERR_UNSUPPORTED),            # B * (H_q/H_kv) > 128

@@ -246,8 +246,12 @@ def test_maximum_sizes(oracle):
 
 
 def test_maximum_rank_and_batch_columns(oracle):
-    """r = r_score = 1024 (the largest rank), and B * (H_q / H_kv) = 128 (the widest projection)."""
+    """r = r_score = 1024 (the largest scoring rank), r = 2048 (the largest rank) in both storage types, and
+    B * (H_q / H_kv) = 128 (the widest projection)."""
     _run(oracle, synth.shrink(SMALL, B=2, S=700, r=1024, plant=0), seq_lens=[700, 257], label="r=1024")
+    _run(oracle, synth.shrink(SMALL, B=2, S=700, r=2048, r_score=1024, plant=0), seq_lens=[700, 257], label="r=2048")
+    _run(oracle, synth.shrink(SMALL, B=1, S=300, r=2048, r_score=512, top_k=70, H=16, H_kv=16, plant=0, dtype="f32"),
+         label="r=2048 f32")
     _run(oracle, synth.shrink(SMALL, B=16, S=300, H=8, H_kv=1, r=128, top_k=40, plant=0), seqs=[0, 15],
          label="B*G=128")
 

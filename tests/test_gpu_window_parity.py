@@ -21,8 +21,8 @@ SMALL = synth.shrink(C["cfg2"], B=3, S=1000, r=128, r_hi=256, top_k=100, n_sink=
 
 
 def make_win_ctx(w):
-    desc = binding.make_desc(w.B, w.S, w.H, w.H_kv, w.d, w.r_hi, w.n_recent, w.dtype, rope_theta=w.theta,
-                             rope_style=w.rope_style)
+    desc = binding.make_desc(w.B, w.S, w.H, w.H_kv, w.d, w.r_hi, w.n_recent, w.dtype, r_score=min(w.r_hi, 1024),
+                             rope_theta=w.theta, rope_style=w.rope_style)
     return binding.Sals(desc, gu.DEV)
 
 
@@ -100,12 +100,12 @@ def test_gqa_interleaved_rope_and_ring_wrap(oracle):
 
 
 def test_largest_window_rank(oracle):
-    w = synth.shrink(SMALL, B=2, S=600, r=640, r_hi=1024, top_k=200, n_sink=16, n_recent=128, plant=0)
+    w = synth.shrink(SMALL, B=2, S=600, r=640, r_hi=2048, top_k=200, n_sink=16, n_recent=128, plant=0)
     _case(oracle, w, seq_lens=[600, 345])
 
 
 def test_cfg2_with_the_papers_composition(oracle):
-    """Full size of the measured configuration: 16 sink + 432 critical + 64 recent tokens, window rank 1024."""
+    """Full size of the measured configuration: 16 sink + 432 critical + 64 recent tokens, window rank 2048."""
     _case(oracle, synth.lookup("cfg2_win"))
 
 
