@@ -283,7 +283,8 @@ sals_status sals_overlap_score(sals_ctx* ctx, const void* q, const int32_t* q_po
 
 /* ---- measurement aid --------------------------------------------------------------
  * Per-stage timing for roofline figures.  While enabled, every stage below (one kernel;
- * for the selection of sequences above 32768 tokens a chain of four) is bracketed by a
+ * for the selection of sequences above 32768 tokens a chain of four, for the logits of very
+ * short selections two) is bracketed by a
  * pair of HIP events on the call's stream (host-side event objects; no device memory).  sals_profile_collect waits for the recorded events, adds
  * the elapsed milliseconds and launch counts per kernel into total_ms / launches (host
  * arrays of SALS_N_KERNELS entries, overwritten) and forgets the records.  Timing with

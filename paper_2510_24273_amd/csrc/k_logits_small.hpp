@@ -11,6 +11,11 @@
 // iteration are multiplied concurrently.  Afterwards the two parities exchange halves of
 // their accumulators, every wave rotates and dots a quarter of the pairs, and the first wave
 // adds the four partial dot products per token and reduces the tile's softmax statistics.
+//
+// With very few tiles (a recent window at batch 1, a GQA model at batch 1) the latent axis is also split over
+// `ksplit` workgroups per tile: the logit is a sum over latent coordinates (reconstruction, rotation and the dot
+// product are all linear in K~), so every slice writes its partial logits and logits_finish_kernel adds the slices
+// in slice order and takes the statistics.
 #pragma once
 #include "common.hpp"
 #include "k_attend.hpp"
@@ -31,7 +36,8 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     const int32_t* __restrict__ n_sel, const T* __restrict__ q, const int32_t* __restrict__ q_pos,
     const float2* __restrict__ rope, InvFreq inv,
     float* __restrict__ logits, float2* __restrict__ stats, int B, int S_max, int r, int H, int H_kv,
-    int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale, int ring)
+    int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale, int ring, int ksplit,
+    float* __restrict__ plogits)
 {
     constexpr int ES = (int)sizeof(T);
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -40,12 +46,14 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     const int G = H / H_kv;
 
     // workgroup id -> (sequence, token tile, KV head), one contiguous range of the list per XCD
-    int b, g, part;
+    int b, g, part, kz;  // kz: this workgroup's slice of the latent axis (the slices of a tile are neighbours)
     {
-        const int N = n_parts * H_kv * B;
+        const int N = n_parts * H_kv * B * ksplit;
         const int id = blockIdx.x, xcd = id % kXcds, slot = id / kXcds;
         const int qn = N / kXcds, rem = N % kXcds;
-        const int w = (xcd < rem ? xcd * (qn + 1) : rem * (qn + 1) + (xcd - rem) * qn) + slot;
+        const int wk = (xcd < rem ? xcd * (qn + 1) : rem * (qn + 1) + (xcd - rem) * qn) + slot;
+        const int w = wk / ksplit;
+        kz = wk - w * ksplit;
         if (heads_fastest) {
             const int bt = w / H_kv;
             g = w - bt * H_kv; b = bt / n_parts; part = bt - b * n_parts;
@@ -84,7 +92,8 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
                                  (pcol >> 2) * (kHeadDim * 64) + prow * 64 + (pcol & 3) * 16;
     const int a_dst0 = swz(prow, pcol), a_dst1 = swz(64 + prow, pcol);
     const int b_dst = kHeadDim * kLgChunk + swz(prow, pcol);
-    const int nkc = r * ES / kLgChunk;
+    const int nkc = r * ES / kLgChunk / ksplit;  // 128-byte steps of this slice (the host makes it a whole number)
+    a_src += (size_t)kz * nkc * (kHeadDim * kLgChunk);
 
     f32x16 acc0, acc1;  // slots dh*32 + (8a + 4hi + c) and their pair partners (+64)
 #pragma unroll
@@ -115,15 +124,17 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     constexpr int EARLY = NST < 4 ? NST : 4;  // U_k steps requested before the row indices arrive
 #pragma unroll
     for (int s = 0; s < EARLY; ++s) load_a(0, s);
-    if (tok0 >= n) {  // no selected token in this tile: neutral statistics
-        if (tid < G) stats[((size_t)b * H + (size_t)g * G + tid) * n_parts + part] = make_float2(-INFINITY, 0.f);
+    if (tok0 >= n) {  // no selected token in this tile: neutral statistics (split tiles: the finishing kernel's job)
+        if (tid < G && ksplit == 1)
+            stats[((size_t)b * H + (size_t)g * G + tid) * n_parts + part] = make_float2(-INFINITY, 0.f);
         return;
     }
     // slots past the selected tokens read the first selected row; they get no weight
     const int my_pos = min(max(my_slot < n ? idx_my : idx_0, 0), S_max - 1);
     const int my_row = ring > 0 ? my_pos % ring : my_pos;  // ring cache: token t lies in row t mod ring
     const unsigned char* b_src =
-        reinterpret_cast<const unsigned char*>(Kc + ((size_t)b * (ring > 0 ? ring : S_max) + my_row) * r) + pcol * 16;
+        reinterpret_cast<const unsigned char*>(Kc + ((size_t)b * (ring > 0 ? ring : S_max) + my_row) * r) + pcol * 16 +
+        (size_t)kz * nkc * kLgChunk;
 #pragma unroll
     for (int s = 0; s < NST; ++s) P[s][2] = ld16(b_src + (size_t)s * kLgChunk);
 #pragma unroll
@@ -237,6 +248,10 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
                 const float* dp = sDot + ((size_t)(lane >> 5) * 4 * kMaxGroup + m) * 32 + (lane & 31);
                 const float d = (dp[0] + dp[kMaxGroup * 32]) + (dp[2 * kMaxGroup * 32] + dp[3 * kMaxGroup * 32]);
                 const size_t hrow = (size_t)b * H + (size_t)g * G + m;
+                if (ksplit > 1) {  // uniform: this slice's share of the logit
+                    if (slot < lk) plogits[((size_t)kz * B * H + hrow) * lk + slot] = d;
+                    continue;
+                }
                 if (slot < lk) logits[hrow * lk + slot] = valid ? d : -INFINITY;
                 const float mx = wave_max(valid ? d : -INFINITY);
                 const float se = wave_sum(valid ? __expf(d - mx) : 0.f);
@@ -244,6 +259,32 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
             }
         }
     }
+}
+
+// Split tiles: logits = sum of the latent slices' partial logits, in slice order, and the tile's softmax
+// statistics.  grid (n_parts, B*H), 64 threads (one per token of the tile).
+constexpr int kLsMaxSplit = 8;
+__global__ __launch_bounds__(64) void logits_finish_kernel(const float* __restrict__ plogits, int ksplit,
+                                                           const int32_t* __restrict__ n_sel,
+                                                           float* __restrict__ logits, float2* __restrict__ stats,
+                                                           int B, int H, int lk, int n_parts)
+{
+    const int part = blockIdx.x, lane = threadIdx.x;
+    const size_t hrow = blockIdx.y;
+    const int slot = part * kLsTok + lane;
+    float v[kLsMaxSplit];
+#pragma unroll
+    for (int u = 0; u < kLsMaxSplit; ++u)  // all slices requested together, from clamped addresses
+        v[u] = plogits[((size_t)min(u, ksplit - 1) * B * H + hrow) * lk + min(slot, lk - 1)];
+    const int n = n_sel[hrow / H];
+    float d = 0.f;
+#pragma unroll
+    for (int u = 0; u < kLsMaxSplit; ++u) d += u < ksplit ? v[u] : 0.f;
+    const bool valid = slot < n;
+    if (slot < lk) logits[hrow * lk + slot] = valid ? d : -INFINITY;
+    const float mx = wave_max(valid ? d : -INFINITY);
+    const float se = wave_sum(valid ? __expf(d - mx) : 0.f);
+    if (lane == 0) stats[hrow * n_parts + part] = make_float2(mx, se);
 }
 
 }  // namespace sals

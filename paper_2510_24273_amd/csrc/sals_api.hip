@@ -33,7 +33,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Layout {  // byte offsets into the workspace
-    size_t qt, scores, idx, n_sel, n_lo, out32, logits, stats, rope, tpart, qv_part, dn_part, tm_part, tm_hist, tm_meta, tm_cand, total;
+    size_t qt, scores, idx, n_sel, n_lo, out32, logits, plogits, stats, rope, tpart, qv_part, dn_part, tm_part, tm_hist, tm_meta, tm_cand, total;
     int lk;                      // logits row stride (floats)
     int max_parts;               // token tiles per head of the logits kernel, at most
     int pv_tok_per_wg, pv_ntr, pv_waves;  // value-sum token ranges, waves per workgroup (4 | 8)
@@ -145,6 +145,8 @@ Layout make_layout(const sals_desc& d)
     L.n_lo = take((size_t)d.B * 4);                          // recent-window attention: tokens of the low-rank pass
     L.out32 = take((size_t)d.B * d.H_q * kHeadDim * 4);      // recent-window attention: a pass's unrounded output
     L.logits = take((size_t)d.B * d.H_q * L.lk * 4);
+    // partial logits of the latent slices, for shapes with so few 64-token tiles that the latent axis is split too
+    L.plogits = take(ceil_div(k_tot, kLsTok) * d.H_kv * d.B <= 128 ? (size_t)kLsMaxSplit * d.B * d.H_q * L.lk * 4 : 0);
     L.max_parts = ceil_div(k_tot, 32);
     L.stats = take((size_t)d.B * d.H_q * L.max_parts * 8);
     L.rope = take((size_t)(d.S_max + 1) * kPairs * 8);  // positions 0 .. S_max (the query after a full cache)
@@ -152,6 +154,7 @@ Layout make_layout(const sals_desc& d)
     {   // quantised-value attention: one workgroup per (sequence, token range, KV head), 32 tokens side
         // by side; a second range (and with it the merge launch) only pays above ~32 tokens per slot
         int n_tr = k_tot <= 32 * kQvSlots ? 1 : std::min(kQvMaxRanges, ceil_div(k_tot, 16 * kQvSlots));
+        if (const char* e = std::getenv("SALS_TUNE_QV_RANGES")) n_tr = std::max(1, std::min(kQvMaxRanges, std::atoi(e)));  // tuning aid
         n_tr = std::max(n_tr, ceil_div(k_tot, kQvMaxTok));
         L.qv_tok_per_wg = ceil_div(k_tot, n_tr);
         L.qv_ntr = ceil_div(k_tot, L.qv_tok_per_wg);
@@ -372,11 +375,21 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
         if (pick == 1) SALS_LOGITS(2, 4, 2);        // 2 heads x 256 tokens, 8 waves
         else if (pick == 2) SALS_LOGITS(1, 4, 2);   // 1 head  x 256 tokens
         else {  // few tiles: 1 head x 64 tokens with the whole latent axis loaded ahead
-            const int nkc = d.r * (int)sizeof(T) / kLgChunk;
+            n_parts = ceil_div(k_tot, kLsTok);
+            int nkc = d.r * (int)sizeof(T) / kLgChunk;
+            // fewer workgroups than half the chip: the latent axis is split as well, as far as every slice keeps at
+            // least two steps and the workgroups still fit the chip in one round
+            int ksplit = 1;
+            const int n_wg1 = n_parts * d.H_kv * d.B;
+            static const bool allow_split = [] { const char* e = std::getenv("SALS_TUNE_LOGITS_KSPLIT"); return !e || std::atoi(e) != 0; }();  // tuning aid
+            if (allow_split && n_wg1 <= 128)
+                for (int ks = kLsMaxSplit; ks >= 2; ks /= 2)
+                    if (n_wg1 * ks <= 256 && nkc % ks == 0 && nkc / ks >= 2) { ksplit = ks; break; }
+            nkc /= ksplit;
             int nst = kLsMaxChunk;  // steps loaded ahead: the largest divisor of the step count
             while (nkc % nst != 0) --nst;
             void (*kern)(const T*, const T*, const int32_t*, const int32_t*, const T*, const int32_t*, const float2*,
-                         InvFreq, float*, float2*, int, int, int, int, int, int, int, int, int, int, float, int) = nullptr;
+                         InvFreq, float*, float2*, int, int, int, int, int, int, int, int, int, int, float, int, int, float*) = nullptr;
             switch (nst) {
                 case 1: kern = attend_logits_small_kernel<T, 1>; break;
                 case 2: kern = attend_logits_small_kernel<T, 2>; break;
@@ -392,12 +405,17 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)kLsLds) != hipSuccess)
                 return SALS_ERR_HIP;
-            n_parts = ceil_div(k_tot, kLsTok);
-            hipLaunchKernelGGL(kern, dim3(n_parts * d.H_kv * d.B), dim3(kLsThreads), kLsLds, st,
+            float* plogits = reinterpret_cast<float*>(c->ws + L.plogits);
+            hipLaunchKernelGGL(kern, dim3(n_parts * d.H_kv * d.B * ksplit), dim3(kLsThreads), kLsLds, st,
                                static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,
                                static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats, d.B, d.S_max, d.r,
                                d.H_q, d.H_kv, k_tot, L.lk, n_parts, heads_fastest, d.rope_style,
-                               1.0f / std::sqrt((float)d.d), ring);
+                               1.0f / std::sqrt((float)d.d), ring, ksplit, plogits);
+            if (ksplit > 1) {
+                if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+                hipLaunchKernelGGL(logits_finish_kernel, dim3(n_parts, d.B * d.H_q), dim3(64), 0, st, plogits, ksplit,
+                                   n_sel, logits, stats, d.B, d.H_q, L.lk, n_parts);
+            }
         }
 #undef SALS_LOGITS
         if (launch_status() != SALS_OK) return SALS_ERR_HIP;
