@@ -153,8 +153,10 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
 
     // ---- fast path: linear-range histogram ---------------------------------------------
     {
+        // key 0 (no candidate) never wins the maximum, and k - 1 turns it into the largest value for the minimum
         uint32_t kmin = 0xffffffffu, kmax = 0u;
-        for_each_key([&](uint32_t k, int) { if (k != 0u) { kmin = min(kmin, k); kmax = max(kmax, k); } });
+        for_each_key([&](uint32_t k, int) { kmin = min(kmin, k - 1u); kmax = max(kmax, k); });
+        kmin = kmin == 0xffffffffu ? kmin : kmin + 1u;
         kmin = wave_min_u32(kmin);
         kmax = wave_max_u32(kmax);
         if (lane == 0) { sh.wave_a[wave] = kmin; sh.wave_b[wave] = kmax; }
@@ -167,14 +169,31 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
         const float flo = key_to_score(kmin), fhi = key_to_score(kmax);
         const float span = fhi - flo;
         const float scale = (span > 0.f && span < 3.0e38f) ? (float)kTopkBins / span : 0.f;
-        const float off = -flo * scale;
+        const float off = fhi * scale;
         if (scale > 0.f && scale < 3.0e38f && fabsf(off) < 3.0e38f) {  // uniform
-            // a monotone map of the score onto slots; slot 0 is the top of the range
-            auto slot_of = [&](uint32_t k) {
-                int bin = (int)fmaf(key_to_score(k), scale, off);
-                return kTopkBins - 1 - min(max(bin, 0), kTopkBins - 1);
-            };
-            for_each_key([&](uint32_t k, int) { if (k != 0u) atomicAdd(&sh.hist[slot_of(k)], 1u); });
+            // a monotone map of the score onto slots, (max - score) * bins / span; slot 0 is the top of the range
+            auto slot_of_score = [&](float sc) { return min(max((int)fmaf(sc, -scale, off), 0), kTopkBins - 1); };
+            auto slot_of = [&](uint32_t k) { return slot_of_score(key_to_score(k)); };
+            // keys in registers: every key's slot is kept too (two per register; 0xffff for a non-candidate), so the
+            // pass that collects the threshold slot's members compares instead of mapping every score again
+            uint32_t slot2[F4 > 0 ? NREG / 2 : 1];
+            if constexpr (F4 > 0) {
+#pragma unroll
+                for (int i = 0; i < NREG; i += 2) {
+                    // up to 16 keys per thread the raw scores are still in registers and save the way back from the
+                    // key (same slot: the two only differ for -0, which maps like +0); with 32 they would spill
+                    constexpr bool kRaw = F4 <= 4;
+                    const uint32_t s0 = keys[i] == 0u ? 0xffffu
+                                        : (uint32_t)(kRaw ? slot_of_score(raw[i]) : slot_of(keys[i]));
+                    const uint32_t s1 = keys[i + 1] == 0u ? 0xffffu
+                                        : (uint32_t)(kRaw ? slot_of_score(raw[i + 1]) : slot_of(keys[i + 1]));
+                    if (keys[i] != 0u) atomicAdd(&sh.hist[s0], 1u);
+                    if (keys[i + 1] != 0u) atomicAdd(&sh.hist[s1], 1u);
+                    slot2[i >> 1] = s0 | (s1 << 16);
+                }
+            } else {
+                for_each_key([&](uint32_t k, int) { if (k != 0u) atomicAdd(&sh.hist[slot_of(k)], 1u); });
+            }
             __syncthreads();
             const u32x4 c4 = *reinterpret_cast<const u32x4*>(&sh.hist[tid * 4]);
             const uint32_t cnt[4] = {c4.x, c4.y, c4.z, c4.w};
@@ -193,9 +212,17 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
             const uint32_t kk = sh.sel_kk;
             const uint32_t members = sh.hist[t_slot];
             if (members <= (uint32_t)kTopkCand) {  // uniform
-                for_each_key([&](uint32_t k, int) {
-                    if (k != 0u && slot_of(k) == t_slot) sh.cand[atomicAdd(&sh.n_cand, 1u)] = k;
-                });
+                if constexpr (F4 > 0) {
+#pragma unroll
+                    for (int i = 0; i < NREG; ++i) {
+                        const uint32_t si = (i & 1) ? slot2[i >> 1] >> 16 : slot2[i >> 1] & 0xffffu;
+                        if (si == (uint32_t)t_slot) sh.cand[atomicAdd(&sh.n_cand, 1u)] = keys[i];
+                    }
+                } else {
+                    for_each_key([&](uint32_t k, int) {
+                        if (k != 0u && slot_of(k) == t_slot) sh.cand[atomicAdd(&sh.n_cand, 1u)] = k;
+                    });
+                }
                 __syncthreads();
                 // the member with  #(greater) < kk <= #(greater or equal)  carries the k-th key
                 if (tid < (int)members) {
