@@ -256,8 +256,10 @@ sals_status sals_window_append(sals_ctx* win, const void* k_new, const void* v_n
 /* sals_sparse_attend with the window: idx / n_sel are a selection in the order sals_topk_select
  * writes it on `ctx` (recent tokens last).  The last n_w = min(w, n_sel[b]) entries of idx[b] are
  * reconstructed from ring rows idx mod w of Kw / Vw through W_hi, all entries before them from Kc / Vc
- * through W; one softmax (Eq. 5) runs over the union.  Evaluated as two passes whose outputs are
- * merged by their softmax statistics in fp32, rounded once to T. */
+ * through W; one softmax (Eq. 5) runs over the union: both passes weight their tokens with the
+ * maximum and normaliser of the whole selection, and one output projection adds their latent value
+ * sums through Uv and Uv_hi (fp32, rounded once to T).  The call uses the workspaces of both
+ * contexts. */
 sals_status sals_sparse_attend_window(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos,
                                       const void* Kc, const void* Vc, const void* W, const void* Kw,
                                       const void* Vw, const void* W_hi, const int32_t* idx,

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
     const int32_t* __restrict__ n_sel, const T* __restrict__ q, const int32_t* __restrict__ q_pos,
     const float2* __restrict__ rope, InvFreq inv,
     float* __restrict__ logits, float2* __restrict__ stats, int B, int S_max, int r, int H, int H_kv,
-    int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale, int ring)
+    int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale, int ring, int stats_stride)
 {
     typedef logits_cfg<HEADS, NTG, NB> C;
     constexpr int NT = C::NT, NA = C::NA, NBP = C::NBP, NCS = C::NCS;
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
     asm volatile("" ::: "memory");  // (keeps the loads above ahead of the wait for the count)
     if (tok0 >= n) {  // no selected token in this tile: neutral statistics
         if (tid < HEADS * G)
-            stats[((size_t)b * H + (size_t)g0 * G + tid) * n_parts + part] = make_float2(-INFINITY, 0.f);
+            stats[((size_t)b * H + (size_t)g0 * G + tid) * stats_stride + part] = make_float2(-INFINITY, 0.f);
         return;
     }
 
@@ -376,7 +376,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
         float2 st = sStat[h2][0][m];
 #pragma unroll
         for (int t = 1; t < NTG; ++t) st = stat_merge(st, sStat[h2][t][m]);
-        stats[((size_t)b * H + (size_t)(g0 + h2) * G + m) * n_parts + part] = st;
+        stats[((size_t)b * H + (size_t)(g0 + h2) * G + m) * stats_stride + part] = st;
     }
 }
 

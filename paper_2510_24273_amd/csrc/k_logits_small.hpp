@@ -37,7 +37,7 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     const float2* __restrict__ rope, InvFreq inv,
     float* __restrict__ logits, float2* __restrict__ stats, int B, int S_max, int r, int H, int H_kv,
     int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale, int ring, int ksplit,
-    float* __restrict__ plogits)
+    float* __restrict__ plogits, int stats_stride)
 {
     constexpr int ES = (int)sizeof(T);
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     for (int s = 0; s < EARLY; ++s) load_a(0, s);
     if (tok0 >= n) {  // no selected token in this tile: neutral statistics (split tiles: the finishing kernel's job)
         if (tid < G && ksplit == 1)
-            stats[((size_t)b * H + (size_t)g * G + tid) * n_parts + part] = make_float2(-INFINITY, 0.f);
+            stats[((size_t)b * H + (size_t)g * G + tid) * stats_stride + part] = make_float2(-INFINITY, 0.f);
         return;
     }
     // slots past the selected tokens read the first selected row; they get no weight
@@ -255,7 +255,7 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
                 if (slot < lk) logits[hrow * lk + slot] = valid ? d : -INFINITY;
                 const float mx = wave_max(valid ? d : -INFINITY);
                 const float se = wave_sum(valid ? __expf(d - mx) : 0.f);
-                if (lane == 0) stats[hrow * n_parts + part] = make_float2(mx, se);
+                if (lane == 0) stats[hrow * stats_stride + part] = make_float2(mx, se);
             }
         }
     }
@@ -267,7 +267,7 @@ constexpr int kLsMaxSplit = 8;
 __global__ __launch_bounds__(64) void logits_finish_kernel(const float* __restrict__ plogits, int ksplit,
                                                            const int32_t* __restrict__ n_sel,
                                                            float* __restrict__ logits, float2* __restrict__ stats,
-                                                           int B, int H, int lk, int n_parts)
+                                                           int B, int H, int lk, int stats_stride)
 {
     const int part = blockIdx.x, lane = threadIdx.x;
     const size_t hrow = blockIdx.y;
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(64) void logits_finish_kernel(const float* __restri
     if (slot < lk) logits[hrow * lk + slot] = valid ? d : -INFINITY;
     const float mx = wave_max(valid ? d : -INFINITY);
     const float se = wave_sum(valid ? __expf(d - mx) : 0.f);
-    if (lane == 0) stats[hrow * n_parts + part] = make_float2(mx, se);
+    if (lane == 0) stats[hrow * stats_stride + part] = make_float2(mx, se);
 }
 
 }  // namespace sals

@@ -308,8 +308,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(con
 // and (4,4) merge more ranges per memory round trip when a wave has at most 5 / 4 steps.
 template <typename T, int BATCH, int RPR>
 __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ Uv, const float* __restrict__ Tpart,
-                                                         T* __restrict__ out, float* __restrict__ out_f32,
-                                                         int B, int r, int H, int H_kv, int n_tr)
+                                                         T* __restrict__ out,
+                                                         int B, int r, int H, int H_kv, int n_tr,
+                                                         const T* __restrict__ Uv2, const float* __restrict__ Tpart2,
+                                                         int r2, int n_tr2)
 {
     constexpr int VEC = elem<T>::vec;
     constexpr int KS = 4 * VEC;  // latent coordinates per MFMA step
@@ -323,17 +325,23 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
     const int l16 = lane & 15, kg = lane >> 4;
     const int G = H / H_kv;
     const int n_rows = B * G;  // (sequence, head of this group) pairs
-    const int nks = r / KS;
-    const T* urow = Uv + ((size_t)g * kHeadDim + cb * 16 + l16) * r + kg * VEC;
-    const size_t tstride = (size_t)B * H * r;
 
     {
         const int row0 = blockIdx.z * 16;  // this workgroup's tile of 16 rows
         const int row = row0 + l16;
         const bool row_ok = row < n_rows;
         const int bb = row_ok ? row / G : 0, h = row_ok ? g * G + row % G : 0;
-        const size_t trow = ((size_t)bb * H + h) * r + kg * VEC;
         f32x4v acc = {0.f, 0.f, 0.f, 0.f};
+        // A second pair (value sums of another latent cache, its projector) is added into the same output when
+        // r2 > 0: the recent window's higher-rank cache beside the low-rank one.
+        for (int pass = 0; pass < (r2 > 0 ? 2 : 1); ++pass) {
+        const T* const Uv_p = pass ? Uv2 : Uv;
+        const float* const Tpart_p = pass ? Tpart2 : Tpart;
+        const int r_p = pass ? r2 : r, n_tr_p = pass ? n_tr2 : n_tr;
+        const int nks = r_p / KS;
+        const T* urow = Uv_p + ((size_t)g * kHeadDim + cb * 16 + l16) * r_p + kg * VEC;
+        const size_t tstride = (size_t)B * H * r_p;
+        const size_t trow = ((size_t)bb * H + h) * r_p + kg * VEC;
         for (int ks0 = wave; ks0 < nks; ks0 += 4 * BATCH) {  // this wave: ks0, ks0+4, ...
             u32x4 bf[BATCH], ah[BATCH], al[BATCH];
             float tm[BATCH][VEC];  // T of this lane's row: the token ranges' partial sums, added in range order
@@ -345,7 +353,7 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
                 for (int v = 0; v < VEC; ++v) tm[u][v] = 0.f;
             }
             // RPR ranges per round, the loads of all BATCH steps in flight together
-            for (int t0 = 0; t0 < n_tr; t0 += RPR) {
+            for (int t0 = 0; t0 < n_tr_p; t0 += RPR) {
                 f32x4 x[BATCH][RPR][VEC / 4];
 #pragma unroll
                 for (int u = 0; u < BATCH; ++u) {
@@ -354,8 +362,8 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
                     for (int w = 0; w < RPR; ++w)
 #pragma unroll
                         for (int v = 0; v < VEC / 4; ++v)
-                            x[u][w][v] = (ks < nks && row_ok && t0 + w < n_tr)
-                                             ? *reinterpret_cast<const f32x4*>(Tpart + (size_t)(t0 + w) * tstride + trow +
+                            x[u][w][v] = (ks < nks && row_ok && t0 + w < n_tr_p)
+                                             ? *reinterpret_cast<const f32x4*>(Tpart_p + (size_t)(t0 + w) * tstride + trow +
                                                                                ks * KS + 4 * v)
                                              : f32x4{0.f, 0.f, 0.f, 0.f};
                 }
@@ -394,6 +402,7 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
                 if constexpr (kSplit) mma16_op<T>::run(al[u], bf[u], acc);
             }
         }
+        }
         // fold the four latent slices (waves) in order; acc[v] is tile row 4*kg+v, channel l16
         __syncthreads();
         if (wave > 0) {
@@ -408,9 +417,7 @@ __global__ __launch_bounds__(256) void attend_out_kernel(const T* __restrict__ U
                 int orow = row0 + kg * 4 + v;
                 if (orow < n_rows) {
                     int ob = orow / G, oh = g * G + orow % G;
-                    const size_t o = ((size_t)ob * H + oh) * kHeadDim + cb * 16 + l16;
-                    if (out_f32 != nullptr) out_f32[o] = y;  // unrounded, for a later merge with another pass
-                    else elem<T>::store(out + o, y);
+                    elem<T>::store(out + ((size_t)ob * H + oh) * kHeadDim + cb * 16 + l16, y);
                 }
             }
         }

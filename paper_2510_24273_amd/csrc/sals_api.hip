@@ -33,7 +33,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Layout {  // byte offsets into the workspace
-    size_t qt, scores, idx, n_sel, n_lo, out32, logits, plogits, stats, rope, tpart, qv_part, dn_part, tm_part, tm_hist, tm_meta, tm_cand, total;
+    size_t qt, scores, idx, n_sel, n_lo, logits, plogits, stats, rope, tpart, qv_part, dn_part, tm_part, tm_hist, tm_meta, tm_cand, total;
     int lk;                      // logits row stride (floats)
     int max_parts;               // token tiles per head of the logits kernel, at most
     int pv_tok_per_wg, pv_ntr, pv_waves;  // value-sum token ranges, waves per workgroup (4 | 8)
@@ -143,11 +143,10 @@ Layout make_layout(const sals_desc& d)
     L.idx = take((size_t)d.B * k_tot * 4);
     L.n_sel = take((size_t)d.B * 4);
     L.n_lo = take((size_t)d.B * 4);                          // recent-window attention: tokens of the low-rank pass
-    L.out32 = take((size_t)d.B * d.H_q * kHeadDim * 4);      // recent-window attention: a pass's unrounded output
     L.logits = take((size_t)d.B * d.H_q * L.lk * 4);
     // partial logits of the latent slices, for shapes with so few 64-token tiles that the latent axis is split too
     L.plogits = take(ceil_div(k_tot, kLsTok) * d.H_kv * d.B <= 128 ? (size_t)kLsMaxSplit * d.B * d.H_q * L.lk * 4 : 0);
-    L.max_parts = ceil_div(k_tot, 32);
+    L.max_parts = ceil_div(k_tot, 32) + 2;  // (room for the tiles of a recent-window pass beside the context's own)
     L.stats = take((size_t)d.B * d.H_q * L.max_parts * 8);
     L.rope = take((size_t)(d.S_max + 1) * kPairs * 8);  // positions 0 .. S_max (the query after a full cache)
     L.tpart = take((size_t)L.pv_ntr * d.B * d.H_q * d.r * 4);
@@ -323,26 +322,72 @@ struct QvCache { const void* codes; const void* meta; int bits; };  // quantised
 
 // qv == nullptr: latent value cache Vc, value sum in latent space and output projection through U_v.
 // Otherwise: values are the de-quantised rows of the quantised cache (Vc unused).
-// ring > 0: Kc, Vc are rings of that many rows per sequence (token t in row t mod ring).  out32 != nullptr
-// (latent value path only): the output goes there unrounded instead of to `out`; *parts_out receives the number
-// of statistics tiles per head the logits kernel left in the workspace.
+// ring > 0: Kc, Vc are rings of that many rows per sequence (token t in row t mod ring).
+// phases: which of the three launches to enqueue (all of them by default).  link: where the logits kernel leaves
+// its tile statistics and where the value kernel finds the statistics of the whole softmax, when two passes over
+// different caches share one softmax (recent window); by default the context's own array.
+enum { kPhaseLogits = 1, kPhaseValue = 2, kPhaseOut = 4, kPhaseAll = 7 };
+struct StatsLink { float2* stats; int stride; int part0; };  // [B*H][stride] records, this pass's tiles from part0 on
+
+// which logits kernel a context's shape gets: 1 = 2 heads x 256 tokens, 2 = 1 head x 256 tokens, 3 = 1 head x 64
+// tokens (then: slices of the latent axis per tile, 128-byte steps loaded ahead); n_parts = token tiles per head
+struct LogitsPlan { int pick, n_parts, ksplit, nst; };
+template <typename T> LogitsPlan plan_logits(const sals_ctx* c)
+{
+    const sals_desc& d = c->d;
+    const int k_tot = d.top_k + d.n_sink + d.n_recent;
+    auto n_wg = [&](int heads, int tok) { return (long long)ceil_div(k_tot, tok) * (d.H_kv / heads) * d.B; };
+    LogitsPlan P{3, 0, 1, 1};
+    // the largest tile (most operand reuse) that still gives the chip enough workgroups: the 64-token kernel while
+    // its workgroups fit the chip in one round (or too few large tiles exist)
+    P.pick = (d.H_kv % 2 == 0 && n_wg(2, 256) >= 384) ? 1 : ((n_wg(1, 64) > 256 && n_wg(1, 256) >= 96) ? 2 : 3);
+    // a selection that fills less than 60 % of its 256-token tiles (a short list such as a recent window) would
+    // spend the rest of every tile's matrix work on padding: 64-token tiles then
+    if ((long long)k_tot * 10 < (long long)ceil_div(k_tot, 256) * 256 * 6) P.pick = 3;
+    if (const char* e = std::getenv("SALS_TUNE_LOGITS")) {  // tuning aid: 1 | 2 | 3
+        const int v = std::atoi(e);
+        if (v == 1 && d.H_kv % 2 == 0) P.pick = 1;
+        if (v == 2 || v == 3) P.pick = v;
+    }
+    if (P.pick != 3) {
+        P.n_parts = ceil_div(k_tot, 256);
+        return P;
+    }
+    P.n_parts = ceil_div(k_tot, kLsTok);
+    int nkc = d.r * (int)sizeof(T) / kLgChunk;
+    // fewer workgroups than half the chip: the latent axis is split as well, as far as every slice keeps at
+    // least two steps and the workgroups still fit the chip in one round
+    const int n_wg1 = P.n_parts * d.H_kv * d.B;
+    static const bool allow_split = [] { const char* e = std::getenv("SALS_TUNE_LOGITS_KSPLIT"); return !e || std::atoi(e) != 0; }();  // tuning aid
+    if (allow_split && n_wg1 <= 128)
+        for (int ks = kLsMaxSplit; ks >= 2; ks /= 2)
+            if (n_wg1 * ks <= 256 && nkc % ks == 0 && nkc / ks >= 2) { P.ksplit = ks; break; }
+    nkc /= P.ksplit;
+    P.nst = kLsMaxChunk;  // steps loaded ahead: the largest divisor of the step count
+    while (nkc % P.nst != 0) --P.nst;
+    return P;
+}
+
 template <typename T>
 sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos, const void* Kc,
                           const void* Vc, const void* W, const int32_t* idx, const int32_t* n_sel, void* out,
-                          hipStream_t st, const QvCache* qv = nullptr, int ring = 0, float* out32 = nullptr,
-                          int* parts_out = nullptr)
+                          hipStream_t st, const QvCache* qv = nullptr, int ring = 0, int phases = kPhaseAll,
+                          const StatsLink* link = nullptr)
 {
     const sals_desc& d = c->d;
     const Layout& L = c->L;
     const int k_tot = d.top_k + d.n_sink + d.n_recent;
     float* logits = reinterpret_cast<float*>(c->ws + L.logits);
-    float2* stats = reinterpret_cast<float2*>(c->ws + L.stats);
+    const LogitsPlan P = plan_logits<T>(c);
+    // tile statistics: written by this pass's logits kernel from record `part0` on, read as a whole by the value kernel
+    float2* const stats_all = link ? link->stats : reinterpret_cast<float2*>(c->ws + L.stats);
+    float2* const stats = stats_all + (link ? link->part0 : 0);
+    const int stats_stride = link ? link->stride : P.n_parts;
     const float2* rope = reinterpret_cast<const float2*>(c->ws + L.rope);
     float* tpart = reinterpret_cast<float*>(c->ws + L.tpart);
-    int n_parts = 0;
+    const int n_parts = P.n_parts;
     if (ensure_rope_table(c, st) != SALS_OK) return SALS_ERR_HIP;
-    {   // logits: the largest tile (most operand reuse) that still gives the chip enough workgroups
-        auto n_wg = [&](int heads, int tok) { return (long long)ceil_div(k_tot, tok) * (d.H_kv / heads) * d.B; };
+    if (phases & kPhaseLogits) {
         // replicate the smaller operand across the XCDs' L2s: all of U_k, or the gathered rows
         const size_t a_bytes = (size_t)d.H_kv * kHeadDim * d.r, b_bytes = (size_t)d.B * k_tot * d.r;
         const int heads_fastest = a_bytes <= b_bytes ? 1 : 0;
@@ -355,41 +400,19 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
             hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                 (int)LC::LDS) != hipSuccess)                                                 \
             return SALS_ERR_HIP;                                                                             \
-        n_parts = ceil_div(k_tot, LC::TOK);                                                                  \
         hipLaunchKernelGGL(kern, dim3(n_parts * (d.H_kv / HEADS) * d.B), dim3(LC::NT), LC::LDS, st,          \
                            static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,                     \
                            static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats, d.B,                \
                            d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk, n_parts, heads_fastest, d.rope_style,   \
-                           1.0f / std::sqrt((float)d.d), ring);                                              \
+                           1.0f / std::sqrt((float)d.d), ring, stats_stride);                                \
     } while (0)
-        // the 64-token kernel while its workgroups fit the chip in one round (or too few large tiles exist)
-        int pick = (d.H_kv % 2 == 0 && n_wg(2, 256) >= 384) ? 1 : ((n_wg(1, 64) > 256 && n_wg(1, 256) >= 96) ? 2 : 3);
-        // a selection that fills less than 60 % of its 256-token tiles (a short list such as a recent window) would
-        // spend the rest of every tile's matrix work on padding: 64-token tiles then
-        if ((long long)k_tot * 10 < (long long)ceil_div(k_tot, 256) * 256 * 6) pick = 3;
-        if (const char* e = std::getenv("SALS_TUNE_LOGITS")) {  // tuning aid: 1 | 2 | 3
-            const int v = std::atoi(e);
-            if (v == 1 && d.H_kv % 2 == 0) pick = 1;
-            if (v == 2 || v == 3) pick = v;
-        }
+        const int pick = P.pick;
         if (pick == 1) SALS_LOGITS(2, 4, 2);        // 2 heads x 256 tokens, 8 waves
         else if (pick == 2) SALS_LOGITS(1, 4, 2);   // 1 head  x 256 tokens
         else {  // few tiles: 1 head x 64 tokens with the whole latent axis loaded ahead
-            n_parts = ceil_div(k_tot, kLsTok);
-            int nkc = d.r * (int)sizeof(T) / kLgChunk;
-            // fewer workgroups than half the chip: the latent axis is split as well, as far as every slice keeps at
-            // least two steps and the workgroups still fit the chip in one round
-            int ksplit = 1;
-            const int n_wg1 = n_parts * d.H_kv * d.B;
-            static const bool allow_split = [] { const char* e = std::getenv("SALS_TUNE_LOGITS_KSPLIT"); return !e || std::atoi(e) != 0; }();  // tuning aid
-            if (allow_split && n_wg1 <= 128)
-                for (int ks = kLsMaxSplit; ks >= 2; ks /= 2)
-                    if (n_wg1 * ks <= 256 && nkc % ks == 0 && nkc / ks >= 2) { ksplit = ks; break; }
-            nkc /= ksplit;
-            int nst = kLsMaxChunk;  // steps loaded ahead: the largest divisor of the step count
-            while (nkc % nst != 0) --nst;
+            const int ksplit = P.ksplit, nst = P.nst;
             void (*kern)(const T*, const T*, const int32_t*, const int32_t*, const T*, const int32_t*, const float2*,
-                         InvFreq, float*, float2*, int, int, int, int, int, int, int, int, int, int, float, int, int, float*) = nullptr;
+                         InvFreq, float*, float2*, int, int, int, int, int, int, int, int, int, int, float, int, int, float*, int) = nullptr;
             switch (nst) {
                 case 1: kern = attend_logits_small_kernel<T, 1>; break;
                 case 2: kern = attend_logits_small_kernel<T, 2>; break;
@@ -410,21 +433,20 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
                                static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,
                                static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats, d.B, d.S_max, d.r,
                                d.H_q, d.H_kv, k_tot, L.lk, n_parts, heads_fastest, d.rope_style,
-                               1.0f / std::sqrt((float)d.d), ring, ksplit, plogits);
+                               1.0f / std::sqrt((float)d.d), ring, ksplit, plogits, stats_stride);
             if (ksplit > 1) {
                 if (launch_status() != SALS_OK) return SALS_ERR_HIP;
                 hipLaunchKernelGGL(logits_finish_kernel, dim3(n_parts, d.B * d.H_q), dim3(64), 0, st, plogits, ksplit,
-                                   n_sel, logits, stats, d.B, d.H_q, L.lk, n_parts);
+                                   n_sel, logits, stats, d.B, d.H_q, L.lk, stats_stride);
             }
         }
 #undef SALS_LOGITS
         if (launch_status() != SALS_OK) return SALS_ERR_HIP;
-        if (parts_out) *parts_out = n_parts;
     }
     if (qv != nullptr) {
         ProfScope ps(c, SALS_K_ATTEND_QV, st);
-        QvArgs a{static_cast<const unsigned char*>(qv->codes), qv->meta, idx, n_sel, logits, stats,
-                 reinterpret_cast<float*>(c->ws + L.qv_part), out, n_parts, d.B, d.S_max, d.H_q, d.H_kv, k_tot, L.lk,
+        QvArgs a{static_cast<const unsigned char*>(qv->codes), qv->meta, idx, n_sel, logits, stats_all,
+                 reinterpret_cast<float*>(c->ws + L.qv_part), out, stats_stride, d.B, d.S_max, d.H_q, d.H_kv, k_tot, L.lk,
                  L.qv_tok_per_wg, L.qv_ntr};
         const dim3 grid(L.qv_ntr * d.H_kv * d.B);
         const int G = d.H_q / d.H_kv;
@@ -445,28 +467,29 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
         }
         return launch_status();
     }
-    {
+    if (phases & kPhaseValue) {
         ProfScope ps(c, SALS_K_ATTEND_PV, st);
         const int n_items = (d.r / kPvCols) * L.pv_ntr * d.B;
         if (L.pv_waves == 8) {
             hipLaunchKernelGGL((attend_pv_kernel<T, 8>), dim3(n_items), dim3(512), 0, st,
-                               static_cast<const T*>(Vc), idx, n_sel, logits, stats, n_parts, tpart, d.B, d.S_max,
+                               static_cast<const T*>(Vc), idx, n_sel, logits, stats_all, stats_stride, tpart, d.B, d.S_max,
                                d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr, ring);
         } else {
             hipLaunchKernelGGL((attend_pv_kernel<T, 4>), dim3(n_items), dim3(256), 0, st,
-                               static_cast<const T*>(Vc), idx, n_sel, logits, stats, n_parts, tpart, d.B, d.S_max,
+                               static_cast<const T*>(Vc), idx, n_sel, logits, stats_all, stats_stride, tpart, d.B, d.S_max,
                                d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr, ring);
         }
     }
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
-    {
+    if (phases & kPhaseOut) {
         ProfScope ps(c, SALS_K_ATTEND_OUT, st);
         // steps of the latent axis per wave decide how many token ranges fit in one round of loads
         const int spw = ceil_div(d.r / (4 * elem<T>::vec), 4);
         const dim3 grid(d.H_kv, kHeadDim / 16, ceil_div(d.B * (d.H_q / d.H_kv), 16));
 #define SALS_OUT(BATCH, RPR)                                                                                     \
     hipLaunchKernelGGL((attend_out_kernel<T, BATCH, RPR>), grid, dim3(256), 0, st, w_section<T>(c, W, 3), tpart, \
-                       static_cast<T*>(out), out32, d.B, d.r, d.H_q, d.H_kv, L.pv_ntr)
+                       static_cast<T*>(out), d.B, d.r, d.H_q, d.H_kv, L.pv_ntr, static_cast<const T*>(nullptr),     \
+                       static_cast<const float*>(nullptr), 0, 0)
         if (sizeof(T) == 2 && spw <= 4 && L.pv_ntr > 2) SALS_OUT(4, 4);
         else if (sizeof(T) == 2 && spw <= 5 && L.pv_ntr > 2) SALS_OUT(5, 3);
         else SALS_OUT(8, 2);
@@ -768,28 +791,39 @@ sals_status sals_sparse_attend_window(sals_ctx* ctx, sals_ctx* win, const void* 
     int32_t* idx_hi = reinterpret_cast<int32_t*>(win->ws + win->L.idx);
     int32_t* n_hi = reinterpret_cast<int32_t*>(win->ws + win->L.n_sel);
     int32_t* n_lo = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_lo);
-    float* y_lo = reinterpret_cast<float*>(ctx->ws + ctx->L.out32);
-    float* y_hi = reinterpret_cast<float*>(win->ws + win->L.out32);
     hipLaunchKernelGGL(window_split_kernel, dim3(d.B), dim3(256), 0, st, idx, n_sel, k_tot, w, idx_hi, n_lo, n_hi);
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
-    int parts_lo = 0, parts_hi = 0;
+    // One softmax over both caches: the two logits passes leave their tile statistics side by side in the main
+    // context's array, each value pass normalises with the statistics of all tiles, and one output projection adds
+    // both passes' value sums through their projectors.
     const bool bf = d.dtype == SALS_BF16;
-    // (the two passes are independent until the merge; running the window pass on a second stream, forked and
-    // joined by events, was measured and gained nothing)
-    s = bf ? launch_attend<bf16_t>(ctx, q, q_pos, Kc, Vc, W, idx, n_lo, nullptr, st, nullptr, 0, y_lo, &parts_lo)
-           : launch_attend<float>(ctx, q, q_pos, Kc, Vc, W, idx, n_lo, nullptr, st, nullptr, 0, y_lo, &parts_lo);
-    if (s != SALS_OK) return s;
-    s = bf ? launch_attend<bf16_t>(win, q, q_pos, Kw, Vw, W_hi, idx_hi, n_hi, nullptr, st, nullptr, w, y_hi, &parts_hi)
-           : launch_attend<float>(win, q, q_pos, Kw, Vw, W_hi, idx_hi, n_hi, nullptr, st, nullptr, w, y_hi, &parts_hi);
-    if (s != SALS_OK) return s;
-    const float2* st_lo = reinterpret_cast<const float2*>(ctx->ws + ctx->L.stats);
-    const float2* st_hi = reinterpret_cast<const float2*>(win->ws + win->L.stats);
-    if (bf)
-        hipLaunchKernelGGL((window_merge_kernel<bf16_t>), dim3(d.B * d.H_q), dim3(128), 0, st, y_lo, st_lo, parts_lo,
-                           y_hi, st_hi, parts_hi, static_cast<bf16_t*>(out));
-    else
-        hipLaunchKernelGGL((window_merge_kernel<float>), dim3(d.B * d.H_q), dim3(128), 0, st, y_lo, st_lo, parts_lo,
-                           y_hi, st_hi, parts_hi, static_cast<float*>(out));
+    const LogitsPlan p_lo = bf ? plan_logits<bf16_t>(ctx) : plan_logits<float>(ctx);
+    const LogitsPlan p_hi = bf ? plan_logits<bf16_t>(win) : plan_logits<float>(win);
+    if (p_lo.n_parts + p_hi.n_parts > ctx->L.max_parts) return SALS_ERR_UNSUPPORTED;
+    float2* shared = reinterpret_cast<float2*>(ctx->ws + ctx->L.stats);
+    const StatsLink l_lo{shared, p_lo.n_parts + p_hi.n_parts, 0}, l_hi{shared, p_lo.n_parts + p_hi.n_parts, p_lo.n_parts};
+    for (int phase : {(int)kPhaseLogits, (int)kPhaseValue}) {
+        s = bf ? launch_attend<bf16_t>(ctx, q, q_pos, Kc, Vc, W, idx, n_lo, nullptr, st, nullptr, 0, phase, &l_lo)
+               : launch_attend<float>(ctx, q, q_pos, Kc, Vc, W, idx, n_lo, nullptr, st, nullptr, 0, phase, &l_lo);
+        if (s != SALS_OK) return s;
+        s = bf ? launch_attend<bf16_t>(win, q, q_pos, Kw, Vw, W_hi, idx_hi, n_hi, nullptr, st, nullptr, w, phase, &l_hi)
+               : launch_attend<float>(win, q, q_pos, Kw, Vw, W_hi, idx_hi, n_hi, nullptr, st, nullptr, w, phase, &l_hi);
+        if (s != SALS_OK) return s;
+    }
+    {
+        ProfScope ps(ctx, SALS_K_ATTEND_OUT, st);
+        const dim3 grid(d.H_kv, kHeadDim / 16, ceil_div(d.B * (d.H_q / d.H_kv), 16));
+        const float* t_lo = reinterpret_cast<const float*>(ctx->ws + ctx->L.tpart);
+        const float* t_hi = reinterpret_cast<const float*>(win->ws + win->L.tpart);
+        if (bf)
+            hipLaunchKernelGGL((attend_out_kernel<bf16_t, 8, 2>), grid, dim3(256), 0, st, w_section<bf16_t>(ctx, W, 3), t_lo,
+                               static_cast<bf16_t*>(out), d.B, d.r, d.H_q, d.H_kv, ctx->L.pv_ntr,
+                               w_section<bf16_t>(win, W_hi, 3), t_hi, win->d.r, win->L.pv_ntr);
+        else
+            hipLaunchKernelGGL((attend_out_kernel<float, 8, 2>), grid, dim3(256), 0, st, w_section<float>(ctx, W, 3), t_lo,
+                               static_cast<float*>(out), d.B, d.r, d.H_q, d.H_kv, ctx->L.pv_ntr,
+                               w_section<float>(win, W_hi, 3), t_hi, win->d.r, win->L.pv_ntr);
+    }
     return launch_status();
 }
 
