@@ -338,12 +338,29 @@ template <typename T> LogitsPlan plan_logits(const sals_ctx* c)
     const int k_tot = d.top_k + d.n_sink + d.n_recent;
     auto n_wg = [&](int heads, int tok) { return (long long)ceil_div(k_tot, tok) * (d.H_kv / heads) * d.B; };
     LogitsPlan P{3, 0, 1, 1};
-    // the largest tile (most operand reuse) that still gives the chip enough workgroups: the 64-token kernel while
-    // its workgroups fit the chip in one round (or too few large tiles exist)
-    P.pick = (d.H_kv % 2 == 0 && n_wg(2, 256) >= 384) ? 1 : ((n_wg(1, 64) > 256 && n_wg(1, 256) >= 96) ? 2 : 3);
-    // a selection that fills less than 60 % of its 256-token tiles (a short list such as a recent window) would
-    // spend the rest of every tile's matrix work on padding: 64-token tiles then
-    if ((long long)k_tot * 10 < (long long)ceil_div(k_tot, 256) * 256 * 6) P.pick = 3;
+    // the 64-token kernel's split of the latent axis: with fewer workgroups than half the chip, as far as every slice
+    // keeps at least two steps and the workgroups still fit the chip in one round
+    const int nkc128 = d.r * (int)sizeof(T) / kLgChunk;
+    const long long n_wg1 = n_wg(1, kLsTok);
+    static const bool allow_split = [] { const char* e = std::getenv("SALS_TUNE_LOGITS_KSPLIT"); return !e || std::atoi(e) != 0; }();  // tuning aid
+    if (allow_split && n_wg1 <= 128)
+        for (int ks = kLsMaxSplit; ks >= 2; ks /= 2)
+            if (n_wg1 * ks <= 256 && nkc128 % ks == 0 && nkc128 / ks >= 2) { P.ksplit = ks; break; }
+    // Estimated duration of each kernel for this shape, from measured per-step and per-workgroup figures (microseconds):
+    // a 256-token tile walks the latent axis in 64-byte steps of 0.88 us (two heads) or 0.65 us (one head) whatever
+    // part of the tile is filled, workgroups beyond one per compute unit queue up, and the epilogue grows with the
+    // query heads per KV head; a 64-token tile is bound by pulling its operands (the head's projector slice and 64
+    // rows) into the compute unit at about 51 GB/s.
+    {
+        const double steps = (double)d.r * sizeof(T) / kLgStep, G = (double)(d.H_q / d.H_kv);
+        auto rounds = [](long long n) { return (double)((n + 255) / 256); };
+        const double over = 4.0 + 2.2 * G;
+        const double t1 = d.H_kv % 2 == 0 ? rounds(n_wg(2, 256)) * steps * 0.88 + over : 1e30;
+        const double t2 = rounds(n_wg(1, 256)) * steps * 0.65 + over;
+        const double bytes3 = (double)(kHeadDim + kLsTok) * d.r * sizeof(T) / P.ksplit;
+        const double t3 = rounds(n_wg1 * P.ksplit) * (bytes3 / 51e3 + 3.0 + 0.3 * G) + (P.ksplit > 1 ? 3.0 : 0.0);
+        P.pick = t1 <= t2 && t1 <= t3 ? 1 : (t2 <= t3 ? 2 : 3);
+    }
     if (const char* e = std::getenv("SALS_TUNE_LOGITS")) {  // tuning aid: 1 | 2 | 3
         const int v = std::atoi(e);
         if (v == 1 && d.H_kv % 2 == 0) P.pick = 1;
@@ -351,18 +368,11 @@ template <typename T> LogitsPlan plan_logits(const sals_ctx* c)
     }
     if (P.pick != 3) {
         P.n_parts = ceil_div(k_tot, 256);
+        P.ksplit = 1;
         return P;
     }
     P.n_parts = ceil_div(k_tot, kLsTok);
-    int nkc = d.r * (int)sizeof(T) / kLgChunk;
-    // fewer workgroups than half the chip: the latent axis is split as well, as far as every slice keeps at
-    // least two steps and the workgroups still fit the chip in one round
-    const int n_wg1 = P.n_parts * d.H_kv * d.B;
-    static const bool allow_split = [] { const char* e = std::getenv("SALS_TUNE_LOGITS_KSPLIT"); return !e || std::atoi(e) != 0; }();  // tuning aid
-    if (allow_split && n_wg1 <= 128)
-        for (int ks = kLsMaxSplit; ks >= 2; ks /= 2)
-            if (n_wg1 * ks <= 256 && nkc % ks == 0 && nkc / ks >= 2) { P.ksplit = ks; break; }
-    nkc /= P.ksplit;
+    const int nkc = nkc128 / P.ksplit;
     P.nst = kLsMaxChunk;  // steps loaded ahead: the largest divisor of the step count
     while (nkc % P.nst != 0) --P.nst;
     return P;

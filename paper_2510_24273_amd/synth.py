@@ -108,6 +108,18 @@ VARIANTS.update({
 })
 
 
+# The shapes of the paper's operator-latency table (Table 6: LLaMA2-7B, batch 8 / 16, 1k / 2k / 4k tokens, token
+# sparsity 1/8) in its two settings: SALS-25 % (rank D_kv/4, 4-bit values) and SALS-12.5 % (rank D_kv/8, 2-bit
+# values), scores over the leading half of the latent coordinates (Sec. 5.1), selection = 16 sink + critical +
+# 64 recent tokens = S/8 (Sec. 5.2).
+for _B in (8, 16):
+    for _S in (1024, 2048, 4096):
+        for _tag, _r, _bits in (("25", 1024, 4), ("12", 512, 2)):
+            VARIANTS[f"t6_b{_B}_s{_S}_{_tag}"] = Workload(
+                f"table6_llama2_7b_B{_B}_S{_S}_r{_r}_rscore{_r // 2}_k{_S // 8}_qvalue{_bits}bit", 6, _B, _S, 32, 32,
+                128, _r, _S // 8 - 80, r_score=_r // 2, n_sink=16, n_recent=64, plant=3, qv_bits=_bits)
+
+
 def lookup(name: str) -> Workload:
     """A measured configuration or one of its variants, by short name."""
     return CONFIGS[name] if name in CONFIGS else VARIANTS[name]

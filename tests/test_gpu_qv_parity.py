@@ -124,6 +124,15 @@ def test_cfg4_sampled_sequence(oracle):
     _attend_case(oracle, C["cfg4"], 4, seqs=[2])
 
 
+def test_operator_latency_table_shapes_sampled(oracle):
+    """Two corners of the paper's operator-latency table (Table 6) as bench.py times them: SALS-25 % at batch 8,
+    1k tokens and SALS-12.5 % at batch 16, 4k tokens."""
+    w = synth.lookup("t6_b8_s1024_25")
+    _attend_case(oracle, w, w.qv_bits, seqs=[0, 7])
+    w = synth.lookup("t6_b16_s4096_12")
+    _attend_case(oracle, w, w.qv_bits, seqs=[3])
+
+
 @pytest.mark.parametrize("bits", [4, 2])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_quantise_append_bit_exact(oracle, dtype, bits):
