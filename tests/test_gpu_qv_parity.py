@@ -125,12 +125,15 @@ def test_cfg4_sampled_sequence(oracle):
 
 
 def test_operator_latency_table_shapes_sampled(oracle):
-    """Two corners of the paper's operator-latency table (Table 6) as bench.py times them: SALS-25 % at batch 8,
-    1k tokens and SALS-12.5 % at batch 16, 4k tokens."""
+    """Shapes of the paper's operator-latency table (Table 6) as bench.py times them: SALS-25 % at batch 8 and 16,
+    1k tokens, and SALS-12.5 % at batch 16, 4k tokens."""
     w = synth.lookup("t6_b8_s1024_25")
     _attend_case(oracle, w, w.qv_bits, seqs=[0, 7])
     w = synth.lookup("t6_b16_s4096_12")
     _attend_case(oracle, w, w.qv_bits, seqs=[3])
+    # 128 selected tokens per sequence in two-head tiles of 256 tokens (half of every tile is padding)
+    w = synth.lookup("t6_b16_s1024_25")
+    _attend_case(oracle, w, w.qv_bits, seqs=[0, 15])
 
 
 @pytest.mark.parametrize("bits", [4, 2])
