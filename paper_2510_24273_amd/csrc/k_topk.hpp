@@ -321,6 +321,20 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
     });
 }
 
+// Recent-window attention splits a selection into the tokens before the window and the window's own list (the
+// last min(w, n_sel) entries, which are the most recent tokens in token order).  Both follow from the sequence length
+// alone, so the selection kernel can leave them beside its output: idx_hi [B, w] (zero beyond the count),
+// n_lo[b] = n_sel - n_w, n_hi[b] = n_w.  idx_hi == nullptr: nothing to do.
+struct WindowLists { int32_t* idx_hi; int32_t* n_lo; int32_t* n_hi; int w; };
+__device__ __forceinline__ void write_window_lists(const WindowLists& wl, const int32_t* __restrict__ seq_len, int b,
+                                                   int S_max, int k_tot, int n_threads)
+{
+    if (wl.idx_hi == nullptr) return;
+    const int S = min(max(seq_len[b], 0), S_max), n = min(S, k_tot), nw = min(wl.w, n);
+    for (int t = threadIdx.x; t < wl.w; t += n_threads) wl.idx_hi[(size_t)b * wl.w + t] = t < nw ? S - nw + t : 0;
+    if (threadIdx.x == 0) { wl.n_lo[b] = n - nw; wl.n_hi[b] = nw; }
+}
+
 // run_if: when not null, sequence b is only processed if run_if[b * run_stride] is non-zero.
 template <int F4>
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restrict__ scores,
@@ -333,6 +347,20 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
     __shared__ TopkShared sh;
     const int b = blockIdx.x;
     if (run_if != nullptr && run_if[(size_t)b * run_stride] == 0u) return;
+    topk_select_sequence<F4>(sh, scores, seq_len, idx, n_sel, b, S_max, top_k, n_sink, n_recent);
+}
+
+// The same with the recent-window lists (a kernel of its own: the plain one keeps its shorter argument list).
+template <int F4>
+__global__ __launch_bounds__(kTopkThreads) void topk_window_kernel(const float* __restrict__ scores,
+                                                                   const int32_t* __restrict__ seq_len,
+                                                                   int32_t* __restrict__ idx,
+                                                                   int32_t* __restrict__ n_sel, int S_max,
+                                                                   int top_k, int n_sink, int n_recent, WindowLists wl)
+{
+    __shared__ TopkShared sh;
+    const int b = blockIdx.x;
+    write_window_lists(wl, seq_len, b, S_max, top_k + n_sink + n_recent, kTopkThreads);
     topk_select_sequence<F4>(sh, scores, seq_len, idx, n_sel, b, S_max, top_k, n_sink, n_recent);
 }
 

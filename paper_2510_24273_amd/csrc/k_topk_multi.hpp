@@ -269,12 +269,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_finish_kernel(const float* 
                                                                    const int32_t* __restrict__ seq_len,
                                                                    TopkMultiWs ws, int32_t* __restrict__ idx,
                                                                    int32_t* __restrict__ n_sel, int S_max, int top_k,
-                                                                   int n_sink, int n_recent)
+                                                                   int n_sink, int n_recent, WindowLists wl)
 {
     __shared__ TopkShared sh;
     __shared__ uint2 s_c[kTmCand];
     __shared__ uint32_t s_sel[kTmCand];
     const int b = blockIdx.x, tid = threadIdx.x;
+    write_window_lists(wl, seq_len, b, S_max, top_k + n_sink + n_recent, kTopkThreads);
     // (requested together with the meta record; slots past the member count hold stale pairs and are masked)
     const uint2 me_raw = tid < kTmCand ? ws.cand[(size_t)b * kTmCand + tid] : make_uint2(0u, 0u);
     const TopkMeta m = ws.meta[b];

@@ -250,8 +250,9 @@ sals_status launch_scores(const sals_ctx* c, const void* Kc, const int32_t* seq_
     return launch_status();
 }
 
+// wl: also leave the recent-window lists (see WindowLists); by default none
 sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* seq_len, int32_t* idx,
-                        int32_t* n_sel, hipStream_t st)
+                        int32_t* n_sel, hipStream_t st, WindowLists wl = WindowLists{nullptr, nullptr, nullptr, 0})
 {
     const sals_desc& d = c->d;
     dim3 grid(d.B), block(kTopkThreads);
@@ -270,10 +271,21 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
         hipLaunchKernelGGL(topk_place_kernel, cgrid, block, 0, st, scores, seq_len, ws, idx, d.S_max, nc, d.top_k,
                            d.n_sink, d.n_recent);
         hipLaunchKernelGGL(topk_finish_kernel, grid, block, 0, st, scores, seq_len, ws, idx, n_sel, d.S_max, d.top_k,
-                           d.n_sink, d.n_recent);
+                           d.n_sink, d.n_recent, wl);
         return launch_status();
     }
     const uint32_t* always = nullptr;
+#define SALS_TOPK_W(F4)                                                                                    \
+    hipLaunchKernelGGL((topk_window_kernel<F4>), grid, block, 0, st, scores, seq_len, idx, n_sel, d.S_max, \
+                       d.top_k, d.n_sink, d.n_recent, wl)
+    if (wl.idx_hi != nullptr) {
+        if (d.S_max <= 4096) SALS_TOPK_W(1);
+        else if (d.S_max <= 8192) SALS_TOPK_W(2);
+        else if (d.S_max <= 16384) SALS_TOPK_W(4);
+        else SALS_TOPK_W(8);
+        return launch_status();
+    }
+#undef SALS_TOPK_W
     if (d.S_max <= 4096) SALS_TOPK(1, always);
     else if (d.S_max <= 8192) SALS_TOPK(2, always);
     else if (d.S_max <= 16384) SALS_TOPK(4, always);
@@ -785,24 +797,32 @@ sals_status sals_window_append(sals_ctx* win, const void* k_new, const void* v_n
                : launch_project<float, false>(win, W_hi, k_new, v_new, Kw, Vw, sl, st, false, ring);
 }
 
-sals_status sals_sparse_attend_window(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos,
-                                      const void* Kc, const void* Vc, const void* W, const void* Kw,
-                                      const void* Vw, const void* W_hi, const int32_t* idx, const int32_t* n_sel,
-                                      void* out, void* hip_stream)
+namespace {
+// where the two passes' token lists live: the window's list and count in the window context's workspace, the
+// low-rank pass's count in the main context's
+WindowLists window_lists(sals_ctx* ctx, sals_ctx* win)
 {
-    sals_status s = window_pair_ok(ctx, win);
-    if (s != SALS_OK) return s;
-    if (bad(q) || !q_pos || bad(Kc) || bad(Vc) || bad(W) || bad(Kw) || bad(Vw) || bad(W_hi) || !idx || !n_sel ||
-        bad(out))
-        return SALS_ERR_INVALID_ARG;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    return WindowLists{reinterpret_cast<int32_t*>(win->ws + win->L.idx), reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_lo),
+                       reinterpret_cast<int32_t*>(win->ws + win->L.n_sel), win->d.top_k};
+}
+
+// lists_ready: the selection kernel has already written the two passes' lists (decode step); otherwise they are
+// split off the caller's selection here
+sals_status window_attend(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos, const void* Kc,
+                          const void* Vc, const void* W, const void* Kw, const void* Vw, const void* W_hi,
+                          const int32_t* idx, const int32_t* n_sel, void* out, hipStream_t st, bool lists_ready)
+{
+    sals_status s = SALS_OK;
     const sals_desc& d = ctx->d;
     const int k_tot = d.top_k + d.n_sink + d.n_recent, w = win->d.top_k;
-    int32_t* idx_hi = reinterpret_cast<int32_t*>(win->ws + win->L.idx);
-    int32_t* n_hi = reinterpret_cast<int32_t*>(win->ws + win->L.n_sel);
-    int32_t* n_lo = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_lo);
-    hipLaunchKernelGGL(window_split_kernel, dim3(d.B), dim3(256), 0, st, idx, n_sel, k_tot, w, idx_hi, n_lo, n_hi);
-    if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+    const WindowLists wl = window_lists(ctx, win);
+    int32_t* idx_hi = wl.idx_hi;
+    int32_t* n_hi = wl.n_hi;
+    int32_t* n_lo = wl.n_lo;
+    if (!lists_ready) {
+        hipLaunchKernelGGL(window_split_kernel, dim3(d.B), dim3(256), 0, st, idx, n_sel, k_tot, w, idx_hi, n_lo, n_hi);
+        if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+    }
     // One softmax over both caches: the two logits passes leave their tile statistics side by side in the main
     // context's array, each value pass normalises with the statistics of all tiles, and one output projection adds
     // both passes' value sums through their projectors.
@@ -836,6 +856,21 @@ sals_status sals_sparse_attend_window(sals_ctx* ctx, sals_ctx* win, const void* 
     }
     return launch_status();
 }
+}  // namespace
+
+sals_status sals_sparse_attend_window(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos,
+                                      const void* Kc, const void* Vc, const void* W, const void* Kw,
+                                      const void* Vw, const void* W_hi, const int32_t* idx, const int32_t* n_sel,
+                                      void* out, void* hip_stream)
+{
+    sals_status s = window_pair_ok(ctx, win);
+    if (s != SALS_OK) return s;
+    if (bad(q) || !q_pos || bad(Kc) || bad(Vc) || bad(W) || bad(Kw) || bad(Vw) || bad(W_hi) || !idx || !n_sel ||
+        bad(out))
+        return SALS_ERR_INVALID_ARG;
+    return window_attend(ctx, win, q, q_pos, Kc, Vc, W, Kw, Vw, W_hi, idx, n_sel, out, static_cast<hipStream_t>(hip_stream),
+                         false);
+}
 
 sals_status sals_decode_step_window(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos,
                                     const void* Kc, const void* Vc, const void* W, const void* Kw, const void* Vw,
@@ -852,9 +887,11 @@ sals_status sals_decode_step_window(sals_ctx* ctx, sals_ctx* win, const void* q,
     if (!n_sel) n_sel = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_sel);
     s = sals_latent_scores(ctx, q, W, Kc, seq_len, scores, hip_stream);
     if (s != SALS_OK) return s;
-    s = sals_topk_select(ctx, scores, seq_len, idx, n_sel, hip_stream);
+    // the selection kernel also writes the two passes' token lists (they follow from the sequence lengths)
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    s = launch_topk(ctx, scores, seq_len, idx, n_sel, st, window_lists(ctx, win));
     if (s != SALS_OK) return s;
-    return sals_sparse_attend_window(ctx, win, q, q_pos, Kc, Vc, W, Kw, Vw, W_hi, idx, n_sel, out, hip_stream);
+    return window_attend(ctx, win, q, q_pos, Kc, Vc, W, Kw, Vw, W_hi, idx, n_sel, out, st, true);
 }
 
 // ---- overlap score ----------------------------------------------------------------------------------
