@@ -335,18 +335,15 @@ __device__ __forceinline__ void write_window_lists(const WindowLists& wl, const 
     if (threadIdx.x == 0) { wl.n_lo[b] = n - nw; wl.n_hi[b] = nw; }
 }
 
-// run_if: when not null, sequence b is only processed if run_if[b * run_stride] is non-zero.
 template <int F4>
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restrict__ scores,
                                                             const int32_t* __restrict__ seq_len,
                                                             int32_t* __restrict__ idx,
                                                             int32_t* __restrict__ n_sel, int S_max,
-                                                            int top_k, int n_sink, int n_recent,
-                                                            const uint32_t* __restrict__ run_if, int run_stride)
+                                                            int top_k, int n_sink, int n_recent)
 {
     __shared__ TopkShared sh;
     const int b = blockIdx.x;
-    if (run_if != nullptr && run_if[(size_t)b * run_stride] == 0u) return;
     topk_select_sequence<F4>(sh, scores, seq_len, idx, n_sel, b, S_max, top_k, n_sink, n_recent);
 }
 

@@ -257,9 +257,9 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
     const sals_desc& d = c->d;
     dim3 grid(d.B), block(kTopkThreads);
     ProfScope ps(c, SALS_K_TOPK, st);
-#define SALS_TOPK(F4, RUN_IF)                                                                        \
+#define SALS_TOPK(F4)                                                                                \
     hipLaunchKernelGGL((topk_kernel<F4>), grid, block, 0, st, scores, seq_len, idx, n_sel, d.S_max, \
-                       d.top_k, d.n_sink, d.n_recent, RUN_IF, (int)(sizeof(TopkMeta) / 4))
+                       d.top_k, d.n_sink, d.n_recent)
     if (c->L.tm_chunks > 0) {
         const Layout& L = c->L;
         TopkMultiWs ws{reinterpret_cast<uint2*>(c->ws + L.tm_part), reinterpret_cast<uint32_t*>(c->ws + L.tm_hist),
@@ -274,7 +274,6 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
                            d.n_sink, d.n_recent, wl);
         return launch_status();
     }
-    const uint32_t* always = nullptr;
 #define SALS_TOPK_W(F4)                                                                                    \
     hipLaunchKernelGGL((topk_window_kernel<F4>), grid, block, 0, st, scores, seq_len, idx, n_sel, d.S_max, \
                        d.top_k, d.n_sink, d.n_recent, wl)
@@ -286,10 +285,10 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
         return launch_status();
     }
 #undef SALS_TOPK_W
-    if (d.S_max <= 4096) SALS_TOPK(1, always);
-    else if (d.S_max <= 8192) SALS_TOPK(2, always);
-    else if (d.S_max <= 16384) SALS_TOPK(4, always);
-    else SALS_TOPK(8, always);
+    if (d.S_max <= 4096) SALS_TOPK(1);
+    else if (d.S_max <= 8192) SALS_TOPK(2);
+    else if (d.S_max <= 16384) SALS_TOPK(4);
+    else SALS_TOPK(8);
 #undef SALS_TOPK
     return launch_status();
 }
