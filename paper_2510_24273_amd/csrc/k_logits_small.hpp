@@ -32,11 +32,13 @@ constexpr size_t kLsLds = 2 * (size_t)kLsIterBytes;          // double buffered:
 
 template <typename T, int NST>
 __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
-    const T* __restrict__ Kc, const T* __restrict__ UkP, const int32_t* __restrict__ idx,
-    const int32_t* __restrict__ n_sel, const T* __restrict__ q, const int32_t* __restrict__ q_pos,
+    // (what the workgroup's first loads need comes first: those 14 words arrive preloaded in scalar registers)
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ n_sel, const T* __restrict__ UkP,
+    int B, int H_kv, int n_parts, int heads_fastest, int ksplit, int k_tot, int r, int H,
+    const T* __restrict__ Kc, const T* __restrict__ q, const int32_t* __restrict__ q_pos,
     const float2* __restrict__ rope, InvFreq inv,
-    float* __restrict__ logits, float2* __restrict__ stats, int B, int S_max, int r, int H, int H_kv,
-    int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale, int ring, int ksplit,
+    float* __restrict__ logits, float2* __restrict__ stats, int S_max,
+    int lk, int style, float scale, int ring,
     float* __restrict__ plogits, int stats_stride)
 {
     constexpr int ES = (int)sizeof(T);

@@ -39,14 +39,15 @@ constexpr int kProjThreads = 64 * kProjWaves;
 constexpr int kProjMaxCols = 128;  // B * (H_q / H_kv) handled per call
 constexpr int kProjBatch = 8;      // row pieces a wave keeps in flight per round
 
-struct ProjArgs {
+struct ProjArgs {  // (what the first loads need comes first: those 14 words arrive preloaded in scalar registers)
     const void* UT[2];   // transposed projectors [r, D]
     const void* X[2];    // QUERY: q [B,H,d] (X[0]); else new key / value [B,D]
+    int D, np, B, H, H_kv, r;
+    int d, S_max, nproj;
+    int ring;            // append: > 0 = the cache is a ring of this many rows, token t in row t mod ring
     void* cache[2];      // append: [B,S_max,r], or [B,ring,r] when ring > 0
     float* out_f32;      // QUERY: partial q~ [np,B,r], one slice of the D axis each
     const int32_t* seq_len;  // append: [B] row to write
-    int B, D, r, H, H_kv, d, S_max, nproj, np;
-    int ring;            // append: > 0 = the cache is a ring of this many rows, token t in row t mod ring
 };
 
 template <typename T, bool QUERY>

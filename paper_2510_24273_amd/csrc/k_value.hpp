@@ -30,14 +30,11 @@ constexpr int kPvMaxTok = 4096;    // tokens per workgroup, at most (their cache
 // NW waves (4 or 8), each with one MFMA token group of every step: the eight-wave form halves the number of
 // steps (a step is a chain of dependent latencies), the four-wave form starts and finishes faster.
 template <typename T, int NW>
-__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(const T* __restrict__ Vc,
-                                                        const int32_t* __restrict__ idx,
-                                                        const int32_t* __restrict__ n_sel,
-                                                        const float* __restrict__ logits,
-                                                        const float2* __restrict__ stats, int n_parts,
-                                                        float* __restrict__ Tpart,
-                                                        int B, int S_max, int r, int H, int k_tot, int lk,
-                                                        int tok_per_wg, int n_tr, int ring)
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(
+    // (what the workgroup's first loads need comes first: those 14 words arrive preloaded in scalar registers)
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ n_sel, const float2* __restrict__ stats,
+    int B, int r, int n_tr, int n_parts, int tok_per_wg, int k_tot, int H, int lk,
+    const T* __restrict__ Vc, const float* __restrict__ logits, float* __restrict__ Tpart, int S_max, int ring)
 {
     static_assert(NW == 4 || NW == 8, "four or eight waves");
     constexpr int kPvThreads = NW * 64, kPvWaves = NW;

@@ -432,8 +432,9 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
         else if (pick == 2) SALS_LOGITS(1, 4, 2);   // 1 head  x 256 tokens
         else {  // few tiles: 1 head x 64 tokens with the whole latent axis loaded ahead
             const int ksplit = P.ksplit, nst = P.nst;
-            void (*kern)(const T*, const T*, const int32_t*, const int32_t*, const T*, const int32_t*, const float2*,
-                         InvFreq, float*, float2*, int, int, int, int, int, int, int, int, int, int, float, int, int, float*, int) = nullptr;
+            void (*kern)(const int32_t*, const int32_t*, const T*, int, int, int, int, int, int, int, int, const T*,
+                         const T*, const int32_t*, const float2*, InvFreq, float*, float2*, int, int, int, float, int,
+                         float*, int) = nullptr;
             switch (nst) {
                 case 1: kern = attend_logits_small_kernel<T, 1>; break;
                 case 2: kern = attend_logits_small_kernel<T, 2>; break;
@@ -451,10 +452,10 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
                 return SALS_ERR_HIP;
             float* plogits = reinterpret_cast<float*>(c->ws + L.plogits);
             hipLaunchKernelGGL(kern, dim3(n_parts * d.H_kv * d.B * ksplit), dim3(kLsThreads), kLsLds, st,
-                               static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,
-                               static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats, d.B, d.S_max, d.r,
-                               d.H_q, d.H_kv, k_tot, L.lk, n_parts, heads_fastest, d.rope_style,
-                               1.0f / std::sqrt((float)d.d), ring, ksplit, plogits, stats_stride);
+                               idx, n_sel, w_section<T>(c, W, 2), d.B, d.H_kv, n_parts, heads_fastest, ksplit, k_tot,
+                               d.r, d.H_q, static_cast<const T*>(Kc), static_cast<const T*>(q), q_pos, rope, c->inv,
+                               logits, stats, d.S_max, L.lk, d.rope_style, 1.0f / std::sqrt((float)d.d), ring,
+                               plogits, stats_stride);
             if (ksplit > 1) {
                 if (launch_status() != SALS_OK) return SALS_ERR_HIP;
                 hipLaunchKernelGGL(logits_finish_kernel, dim3(n_parts, d.B * d.H_q), dim3(64), 0, st, plogits, ksplit,
@@ -493,12 +494,12 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
         const int n_items = (d.r / kPvCols) * L.pv_ntr * d.B;
         if (L.pv_waves == 8) {
             hipLaunchKernelGGL((attend_pv_kernel<T, 8>), dim3(n_items), dim3(512), 0, st,
-                               static_cast<const T*>(Vc), idx, n_sel, logits, stats_all, stats_stride, tpart, d.B, d.S_max,
-                               d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr, ring);
+                               idx, n_sel, stats_all, d.B, d.r, L.pv_ntr, stats_stride, L.pv_tok_per_wg, k_tot, d.H_q, L.lk,
+                               static_cast<const T*>(Vc), logits, tpart, d.S_max, ring);
         } else {
             hipLaunchKernelGGL((attend_pv_kernel<T, 4>), dim3(n_items), dim3(256), 0, st,
-                               static_cast<const T*>(Vc), idx, n_sel, logits, stats_all, stats_stride, tpart, d.B, d.S_max,
-                               d.r, d.H_q, k_tot, L.lk, L.pv_tok_per_wg, L.pv_ntr, ring);
+                               idx, n_sel, stats_all, d.B, d.r, L.pv_ntr, stats_stride, L.pv_tok_per_wg, k_tot, d.H_q, L.lk,
+                               static_cast<const T*>(Vc), logits, tpart, d.S_max, ring);
         }
     }
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
