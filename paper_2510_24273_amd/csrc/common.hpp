@@ -51,6 +51,17 @@ template <> struct elem<bf16_t> {
     }
 };
 
+// A wave-uniform 32-bit value read through the vector memory path (the compiler would use a scalar load for a
+// uniform address, and wait for it on its own before the wave's first vector load is issued): the request joins the
+// wave's other loads; wave_uniform() hands the value to the scalar side where it is first needed.
+__device__ __forceinline__ int ld_uniform_i32(const int32_t* p)
+{
+    int zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(zero));  // (opaque to the compiler: the address is no longer provably uniform)
+    return p[zero];
+}
+__device__ __forceinline__ int wave_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
 // 16-byte global load
 __device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
 

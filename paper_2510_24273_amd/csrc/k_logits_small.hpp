@@ -78,15 +78,12 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     const int e_slot = tok0 + tb * 32 + l32;  // token this lane finishes in the epilogue
     const int32_t* ib = idx + (size_t)b * k_tot;
     const int idx_my = ib[min(my_slot, k_tot - 1)], idx_e = ib[min(e_slot, k_tot - 1)], idx_0 = ib[0];
-    const int n = n_sel[b];
-    const int qpos = q_pos[b];
+    const int n_v = ld_uniform_i32(n_sel + b), qpos_v = ld_uniform_i32(q_pos + b);  // in flight with the loads around
     // raw query pair (m = tid / 64, p = tid % 64) and the cos/sin of the query position for pair p
     const int qp = tid & (kPairs - 1), qm = min(tid >> 6, G - 1);
     const T* qrow = q + ((size_t)b * H + (size_t)g * G + qm) * kHeadDim;
     const float qa = elem<T>::load(qrow + pair_first(qp, style));
     const float qb = elem<T>::load(qrow + pair_second(qp, style));
-    const bool q_in_table = qpos >= 0 && qpos <= S_max;  // the table holds exactly the needed values
-    float2 qcs = rope[(size_t)(q_in_table ? qpos : 0) * kPairs + qp];
 
     // the packed U_k panel is [64-byte block of the latent axis][128 slots][64 B]: a 128-byte step is two
     // blocks 8 KB apart, and piece (slot, column c) lies in block c/4 at slot*64 + (c%4)*16
@@ -126,6 +123,7 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     constexpr int EARLY = NST < 4 ? NST : 4;  // U_k steps requested before the row indices arrive
 #pragma unroll
     for (int s = 0; s < EARLY; ++s) load_a(0, s);
+    const int n = wave_uniform(n_v);
     if (tok0 >= n) {  // no selected token in this tile: neutral statistics (split tiles: the finishing kernel's job)
         if (tid < G && ksplit == 1)
             stats[((size_t)b * H + (size_t)g * G + tid) * stats_stride + part] = make_float2(-INFINITY, 0.f);
@@ -141,6 +139,9 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     for (int s = 0; s < NST; ++s) P[s][2] = ld16(b_src + (size_t)s * kLgChunk);
 #pragma unroll
     for (int s = EARLY; s < NST; ++s) load_a(0, s);
+    const int qpos = wave_uniform(qpos_v);
+    const bool q_in_table = qpos >= 0 && qpos <= S_max;  // the table holds exactly the needed values
+    float2 qcs = rope[(size_t)(q_in_table ? qpos : 0) * kPairs + qp];
     f32x4 cs0[2], cs1[2];  // cos/sin of this lane's pairs
     {
         const int e_pos = min(max(e_slot < n ? idx_e : idx_0, 0), S_max - 1);

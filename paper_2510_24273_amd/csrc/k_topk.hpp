@@ -100,13 +100,13 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
                 if (j + e < S_max) f[e] = s[j + e];
         }
     };
-    const int S_in = seq_len[b];
+    const int S_in_v = ld_uniform_i32(seq_len + b);  // (through the vector memory path: in flight with the scores)
     float raw[NREG];
     if (F4 > 0) {
 #pragma unroll
         for (int c = 0; c < (F4 > 0 ? F4 : 1); ++c) load_group(c, raw + 4 * c);
     }
-    const int S = min(S_in, S_max);
+    const int S = min(wave_uniform(S_in_v), S_max);
 
     if (S <= k_tot) {  // short cache: every token is selected
         for (int t = tid; t < k_tot; t += kTopkThreads) out[t] = t < S ? t : 0;

@@ -69,7 +69,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(
     const int cb = item % n_cb, tr = (item / n_cb) % n_tr, b = item / (n_cb * n_tr);
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
-    const int n = n_sel[b];
+    // the count and this thread's first index are requested together (both through the vector memory path)
+    const int n_v = ld_uniform_i32(n_sel + b);
+    const int v_first = idx[(size_t)b * k_tot + min(tr * tok_per_wg + tid, k_tot - 1)];
+    const int n = wave_uniform(n_v);
     const int j_begin = min(n, tr * tok_per_wg), j_end = min(n, j_begin + tok_per_wg);
     const int ntok = j_end - j_begin;
     const int col0 = cb * kPvCols;
@@ -80,7 +83,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(
     // (the index loads only depend on the nominal range, so they are in flight together with n)
     for (int t = tid; t < tok_per_wg; t += kPvThreads) {
         const int j = tr * tok_per_wg + t;
-        const int v = j < k_tot ? ib[j] : 0;
+        const int v = t == tid ? v_first : (j < k_tot ? ib[j] : 0);
         const int pos = min(max(v, 0), S_max - 1);
         if (t < ntok) sRow[t] = ring > 0 ? pos % ring : pos;  // ring cache: token t lies in row t mod ring
     }
