@@ -84,7 +84,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
         }
     }
     const int tok0 = part * C::TOK;
-    const int n = n_sel[b];
+    const int n_v = ld_uniform_i32(n_sel + b), qpos_v = ld_uniform_i32(q_pos + b);  // in flight with the loads below
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
     const int hh = wave / NTG, tg = wave % NTG;   // head of the tile, token group
@@ -116,8 +116,8 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
         qa[u] = elem<T>::load(qrow + pair_first(p, style));
         qb[u] = elem<T>::load(qrow + pair_second(p, style));
     }
-    const int qpos = q_pos[b];
     asm volatile("" ::: "memory");  // (keeps the loads above ahead of the wait for the count)
+    const int n = wave_uniform(n_v), qpos = wave_uniform(qpos_v);
     if (tok0 >= n) {  // no selected token in this tile: neutral statistics
         if (tid < HEADS * G)
             stats[((size_t)b * H + (size_t)g0 * G + tid) * stats_stride + part] = make_float2(-INFINITY, 0.f);

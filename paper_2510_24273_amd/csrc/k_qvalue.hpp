@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void attend_qv_kernel(QvArgs a)
     const float2* sp = a.stats + ((size_t)b * H + kvh * G + min(sm, G - 1)) * a.n_parts;
     constexpr unsigned long long kNeutral = 0x00000000ff800000ull;  // (-inf, 0)
     const unsigned long long st0 = (sm < G && sub < a.n_parts) ? *reinterpret_cast<const unsigned long long*>(sp + sub) : kNeutral;
-    const int n = a.n_sel[b];
+    const int n_v = ld_uniform_i32(a.n_sel + b);  // (vector memory path: in flight with the loads around)
     int iv[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -138,6 +138,7 @@ __global__ __launch_bounds__(256) void attend_qv_kernel(QvArgs a)
         iv[i] = (t < a.tok_per_wg && j < a.k_tot) ? ib[j] : 0;
     }
     asm volatile("" ::: "memory");
+    const int n = wave_uniform(n_v);
     const int j_begin = min(n, tr * a.tok_per_wg), j_end = min(n, j_begin + a.tok_per_wg);
     const int ntok = j_end - j_begin;
 #pragma unroll

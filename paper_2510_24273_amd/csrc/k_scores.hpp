@@ -32,7 +32,7 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restri
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int li = lane & 15, quad = lane >> 4;
     const int n_pieces = r_score / VEC;
-    const int S = min(seq_len[b], S_max);
+    const int S = min(ld_uniform_i32(seq_len + b), S_max);  // (vector memory path: only needed when scores are stored)
     const int j_begin = blockIdx.x * rows_per_wg;
     const int j_end = min(S_max, j_begin + rows_per_wg);
     const T* base = Kc + (size_t)b * S_max * r;
