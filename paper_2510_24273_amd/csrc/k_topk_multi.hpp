@@ -111,7 +111,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_range_kernel(const float* _
 {
     __shared__ uint32_t s_min[kTopkWaves], s_max[kTopkWaves];
     const int chunk = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-    const int S = min(seq_len[b], S_max);
+    const int S = min(ld_uniform_i32(seq_len + b), S_max);  // (vector memory path: in flight with the scores)
     uint32_t keys[4 * kTmF4];
     tm_load_keys(scores + (size_t)b * S_max, S_max, chunk, n_sink, S - n_recent, keys);
     uint32_t kmin = 0xffffffffu, kmax = 0u;
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(const float* __
 {
     __shared__ uint32_t hist[kTmBins];
     const int chunk = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-    const int S = min(seq_len[b], S_max);
+    const int S = min(ld_uniform_i32(seq_len + b), S_max);  // (vector memory path: in flight with the scores)
     uint32_t keys[4 * kTmF4];
     tm_load_keys(scores + (size_t)b * S_max, S_max, chunk, n_sink, S - n_recent, keys);
     for (int t = tid; t < kTmBins; t += kTopkThreads) hist[t] = 0u;
@@ -233,11 +233,11 @@ __global__ __launch_bounds__(kTopkThreads) void topk_place_kernel(const float* _
     __shared__ TopkShared sh;
     __shared__ uint32_t s_above[kTmMaxChunks], s_memb[kTmMaxChunks];
     const int chunk = blockIdx.x, b = blockIdx.y;
-    const int S = min(seq_len[b], S_max);
+    const int S = min(ld_uniform_i32(seq_len + b), S_max);  // (vector memory path: in flight with the scores)
     uint32_t keys[4 * kTmF4];
     tm_load_keys(scores + (size_t)b * S_max, S_max, chunk, n_sink, S - n_recent, keys);
     uint32_t base_above = 0u, base_cand = 0u;
-    const TopkMeta m = tm_resolve(sh, s_above, s_memb, ws, b, chunk, S, n_chunk, top_k, n_sink, n_recent,
+    const TopkMeta m = tm_resolve(sh, s_above, s_memb, ws, b, chunk, wave_uniform(S), n_chunk, top_k, n_sink, n_recent,
                                   &base_above, &base_cand);
     if (chunk == 0 && threadIdx.x == 0) ws.meta[b] = m;  // for the finish kernel
     if (m.fallback) return;
