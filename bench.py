@@ -304,7 +304,7 @@ def main():
     kern = res["kernels"]
     dom = max(kern, key=lambda k: kern[k]["us"])
     dk = kern[dom]
-    traffic = roofline.MEASURED_TRAFFIC.get((a.workload, dom))
+    traffic = roofline.measured_traffic(a.workload, dom)   # from profiles/hbm_traffic_<workload>.txt, None if absent
     out = {
         "metric": "sals_decode_attn_us_per_layer_step", "value": round(res["us_per_layer_step"], 3),
         "unit": "us", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,

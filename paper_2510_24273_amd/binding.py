@@ -13,7 +13,7 @@ import os
 import torch  # noqa: F401  (must be imported first: it brings the HIP runtime in)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsals.so")
+LIB_PATH = os.environ.get("SALS_LIB") or os.path.join(_HERE, "libsals.so")   # SALS_LIB: another build of the same library
 
 SALS_OK = 0
 SALS_ERR_INVALID_ARG = 1
@@ -148,14 +148,19 @@ class Sals:
         if st != SALS_OK:
             raise SalsError(st, "sals_create")
         self._h = h
+        self._destroy = _lib.sals_destroy   # kept on the instance: module globals may be gone at interpreter exit
 
     def close(self):
-        if getattr(self, "_h", None):
-            _lib.sals_destroy(self._h)
-            self._h = None
+        h, self._h = getattr(self, "_h", None), None
+        destroy = getattr(self, "_destroy", None)
+        if h and destroy is not None:
+            destroy(h)
 
     def __del__(self):
-        self.close()
+        try:
+            self.close()
+        except Exception:   # interpreter shutdown: the library may already be unloaded
+            pass
 
     @staticmethod
     def _check(st, where):

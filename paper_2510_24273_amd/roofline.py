@@ -57,14 +57,37 @@ def stage_flops(w, seq_len=None) -> dict:
 
 # HBM bytes per launch (read + written) measured with rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE,
 # each scaled by the same counter's reading for a 64 MiB device-to-device copy in the same run
-# (FETCH_SIZE reads half of the copied bytes on this chip, WRITE_SIZE all of them).  Source: the
-# summaries profiles/hbm_traffic_<workload>.txt.  The scaling assumes full 128-byte requests, so
-# kernels that fetch 64-byte pieces are over-counted by up to 2x.
-MEASURED_TRAFFIC: dict = {
-    ("cfg2", "attend_logits"): 12_831_000, ("cfg2", "attend_out"): 5_679_000, ("cfg2", "scores"): 5_505_000,
-    ("cfg2", "project"): 5_485_000, ("cfg2", "attend_pv"): 1_318_000, ("cfg2", "topk"): 34_000,
-    ("cfg3a", "attend_logits"): 100_020_000, ("cfg3a", "scores"): 86_819_000, ("cfg3a", "attend_pv"): 13_095_000,
-    ("cfg3a", "attend_out"): 6_815_000, ("cfg3a", "project"): 6_775_000, ("cfg3a", "topk"): 423_000,
-    ("cfg4", "scores"): 168_996_000, ("cfg4", "attend_logits"): 100_029_000, ("cfg4", "attend_pv"): 13_759_000,
-    ("cfg4", "attend_out"): 7_342_000, ("cfg4", "project"): 5_743_000, ("cfg4", "topk"): 761_000,
-}
+# (FETCH_SIZE reads half of the copied bytes on this chip, WRITE_SIZE all of them).  The figures are
+# read from the committed summaries profiles/hbm_traffic_<workload>.txt, so they change with those files;
+# a stage that runs as several kernels is the sum of their rows.  The scaling assumes full 128-byte
+# requests, so kernels that fetch 64-byte pieces are over-counted by up to 2x.
+_STAGE_OF_KERNEL = (
+    ("project_kernel", "project"), ("scores_kernel", "scores"), ("topk", "topk"),
+    ("attend_logits", "attend_logits"), ("logits_finish", "attend_logits"), ("attend_pv", "attend_pv"),
+    ("attend_out", "attend_out"), ("attend_qv", "attend_qv"), ("qv_merge", "attend_qv"),
+)
+
+
+def measured_traffic(workload: str, stage: str, profiles_dir: str | None = None):
+    """HBM bytes per launch of `stage` at `workload` from profiles/hbm_traffic_<workload>.txt, or None when
+    that summary (or a row for the stage) does not exist."""
+    import os
+    if profiles_dir is None:
+        profiles_dir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "profiles")
+    path = os.path.join(profiles_dir, f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    total, seen = 0.0, False
+    with open(path) as f:
+        for line in f:
+            name = line.split("<")[0].split(" ")[0]
+            st = next((s for k, s in _STAGE_OF_KERNEL if name.startswith(k)), None)
+            cols = line.split()
+            if st != stage or len(cols) < 6:
+                continue
+            try:
+                total += (float(cols[-2]) + float(cols[-1])) * 1e6   # scaled MB read + scaled MB written
+                seen = True
+            except ValueError:
+                continue
+    return int(round(total)) if seen else None

@@ -376,14 +376,14 @@ def test_cfg2_full(oracle):
 
 
 @pytest.mark.parametrize("name", ["cfg3a", "cfg3b"])
-def test_cfg3_full_sampled_sequences(oracle, name):
-    L, R, _ = _run(oracle, C[name], seqs=[0, 7, 15])
-    for b in (0, 7, 15):
+def test_cfg3_full_every_sequence(oracle, name):
+    L, R, _ = _run(oracle, C[name])
+    for b in range(C[name].B):
         assert set(L["planted"][b].tolist()) <= set(gu.from_dev(R["idx"][b]).tolist())
 
 
-def test_cfg4_full_sampled_sequences(oracle):
-    _run(oracle, C["cfg4"], seqs=[0, 3])
+def test_cfg4_full_every_sequence(oracle):
+    _run(oracle, C["cfg4"])
 
 
 def test_cfg5_full(oracle):

@@ -410,3 +410,87 @@ def test_traffic_model_fixture():
         model = roofline.paper_traffic_elements(s, r, r // 2, k)
         assert model == s * (r // 2) + 2 * k * r
         assert abs(2 * s * nd / model - 1.0 / ((r / 2 / nd) / 2 + d_r * k_s)) < 1e-12
+
+
+# ---------------------------------------------------------------------------
+# interleaved RoPE pairing (pairs (2i, 2i+1)) through the composed functions:
+# brute force written here with explicit 2x2 rotations, independent of oracle.rope
+# ---------------------------------------------------------------------------
+
+def _rope_interleaved(x, pos, theta):
+    """Pairs (2i, 2i+1), angle pos * theta^(-2i/d), as a plain 2x2 rotation per pair."""
+    d = x.shape[-1]
+    y = np.array(x, dtype=np.float64, copy=True)
+    for i in range(d // 2):
+        ang = pos * theta ** (-2.0 * i / d)
+        c, s = math.cos(ang), math.sin(ang)
+        a, b = x[..., 2 * i], x[..., 2 * i + 1]
+        y[..., 2 * i] = a * c - b * s
+        y[..., 2 * i + 1] = b * c + a * s
+    return y
+
+
+def _attention_interleaved(q, K, V, tokens, q_pos, theta, rotate_keys=True):
+    """Softmax attention of q [H,d] over the rows `tokens` of K, V [S,H_kv,d] (keys rotated here
+    unless they already are), interleaved pairing, 1/sqrt(d) scaling."""
+    H, d = q.shape
+    G = H // K.shape[1]
+    y = np.zeros((H, d))
+    for h in range(H):
+        g = h // G
+        qr = _rope_interleaved(q[h], q_pos, theta)
+        lg = np.array([qr @ (_rope_interleaved(K[t, g], int(t), theta) if rotate_keys else K[t, g])
+                       for t in tokens]) / math.sqrt(d)
+        w = np.exp(lg - lg.max())
+        w /= w.sum()
+        for m, t in enumerate(tokens):
+            y[h] += w[m] * V[t, g]
+    return y
+
+
+@pytest.mark.parametrize("H,H_kv", [(4, 4), (6, 2)])
+def test_interleaved_rope_through_sparse_attend_and_decode_step(oracle, H, H_kv):
+    rng = np.random.default_rng(31 + H)
+    d, S, theta = 8, 15, 500000.0
+    D = H_kv * d
+    q = rng.standard_normal((H, d))
+    K = rng.standard_normal((S, H_kv, d))
+    V = rng.standard_normal((S, H_kv, d))
+    Uk, Uv = _orthogonal(rng, D), _orthogonal(rng, D)
+    Kc, Vc = K.reshape(S, D) @ Uk, V.reshape(S, D) @ Uv
+    C = np.array([12, 0, 7, 3, 14, 9], dtype=np.int32)
+    y = oracle.sparse_attend(q, 21, Kc, Vc, Uk, Uv, C, H_kv, theta, 1)
+    np.testing.assert_allclose(y, _attention_interleaved(q, K, V, C, 21, theta), atol=1e-11, rtol=0)
+    # the two pairings are different functions of the same inputs: a swapped flag must show
+    assert np.max(np.abs(y - oracle.sparse_attend(q, 21, Kc, Vc, Uk, Uv, C, H_kv, theta, 0))) > 1e-3
+    out = oracle.decode_step(q, S, Kc, Vc, Uk, Uv, H_kv, top_k=S, theta=theta, rope_style=1)
+    assert sorted(out["idx"].tolist()) == list(range(S))
+    np.testing.assert_allclose(out["y"], _attention_interleaved(q, K, V, range(S), S, theta), atol=1e-11, rtol=0)
+    # a proper subset chosen by the scores (which do not depend on the pairing) with sink and recent tokens
+    out2 = oracle.decode_step(q, S, Kc, Vc, Uk, Uv, H_kv, top_k=4, theta=theta, n_sink=1, n_recent=2, rope_style=1)
+    assert len(out2["idx"]) == 7
+    np.testing.assert_allclose(out2["y"], _attention_interleaved(q, K, V, out2["idx"], S, theta), atol=1e-11, rtol=0)
+
+
+def test_interleaved_rope_through_quantised_values_and_dense_decode(oracle):
+    rng = np.random.default_rng(41)
+    H, H_kv, d, S, theta = 4, 2, 32, 11, 10000.0    # d = 32: one quantisation group per head
+    D = H_kv * d
+    q = rng.standard_normal((H, d))
+    K = rng.standard_normal((S, H_kv, d))
+    Uk = _orthogonal(rng, D)
+    Kc = K.reshape(S, D) @ Uk
+    # values that lie on a 4-bit grid survive quantisation exactly: zero + scale * code
+    codes = rng.integers(0, 16, size=(S, D)).astype(np.uint8)
+    scale = 0.25 * np.ones((S, D // 32))
+    zero = -1.5 * np.ones((S, D // 32))
+    V = (zero.repeat(32, axis=1) + scale.repeat(32, axis=1) * codes).reshape(S, H_kv, d)
+    C = np.array([10, 2, 5, 6], dtype=np.int32)
+    y = oracle.sparse_attend_qv(q, 13, Kc, Uk, codes, scale, zero, C, H_kv, theta, 1)
+    np.testing.assert_allclose(y, _attention_interleaved(q, K, V, C, 13, theta), atol=1e-11, rtol=0)
+    # dense baseline: the cache holds keys already rotated at their positions
+    KR = np.stack([_rope_interleaved(K[t], t, theta) for t in range(S)])
+    y_d = oracle.dense_decode(q, S, KR, V, theta, 1)
+    np.testing.assert_allclose(y_d, _attention_interleaved(q, KR, V, range(S), S, theta, rotate_keys=False),
+                               atol=1e-11, rtol=0)
+    assert np.max(np.abs(y_d - oracle.dense_decode(q, S, KR, V, theta, 0))) > 1e-3
