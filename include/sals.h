@@ -135,6 +135,25 @@ sals_status sals_compress_append(sals_ctx* ctx, const void* k_new, const void* v
 sals_status sals_latent_scores(sals_ctx* ctx, const void* q, const void* W, const void* Kc,
                                const int32_t* seq_len, float* scores, void* hip_stream);
 
+/* sals_latent_scores for callers that cannot allocate or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and the same results
+ * as sals_latent_scores, bit for bit; no context is needed.  The partial sums of q~ (one per slice of
+ * the D axis, the only scratch this stage uses) live in an array of SALS_NOALLOC_SCRATCH_BYTES that is
+ * part of the library's device image: every GPU the library runs on holds its own copy until the process
+ * ends, and its address on the current device is looked up once, on the first call there.
+ *   - allocates nothing: no hipMalloc / hipFree, no allocating library routine;
+ *   - descriptors whose partial sums need more than SALS_NOALLOC_SCRATCH_BYTES are rejected with
+ *     SALS_ERR_WORKSPACE before anything is enqueued (the need is slices * B * r * 4 bytes, at most
+ *     8 slices: e.g. 320 KB at B = 16, r = 640);
+ *   - every call on a GPU shares that GPU's array, which keeps the last call's contents (each call
+ *     overwrites all the entries it later reads, so nothing has to be cleared): calls that overlap on one
+ *     GPU, on different streams or from different threads, race.  Calls on one stream are ordered.
+ * Arguments as sals_latent_scores; `desc` is read on the host. */
+#define SALS_NOALLOC_SCRATCH_BYTES (1u << 20)
+sals_status sals_latent_scores_noalloc(const sals_desc* desc, const void* q, const void* W,
+                                       const void* Kc, const int32_t* seq_len, float* scores,
+                                       void* hip_stream);
+
 /* Stage 2b, critical-token selection (Algorithm 1, TopK step; composition with sink
  * and recent tokens as in Sec. 5.2).  With S = seq_len[b] and
  * k_tot = top_k + n_sink + n_recent:

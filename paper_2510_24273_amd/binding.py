@@ -30,6 +30,7 @@ EXPORTS = (
     "sals_qv_row_bytes", "sals_compress_append_qv", "sals_sparse_attend_qv", "sals_decode_step_qv",
     "sals_dense_attend",
     "sals_window_append", "sals_sparse_attend_window", "sals_decode_step_window", "sals_overlap_score",
+    "sals_latent_scores_noalloc",
 )
 N_KERNELS = 8
 
@@ -63,6 +64,7 @@ def load_library() -> ctypes.CDLL:
     lib.sals_pack_weights.argtypes = [vp, vp, vp, vp, vp]
     lib.sals_compress_append.argtypes = [vp, vp, vp, vp, vp, vp, i32p, vp]
     lib.sals_latent_scores.argtypes = [vp, vp, vp, vp, i32p, f32p, vp]
+    lib.sals_latent_scores_noalloc.argtypes = [ctypes.POINTER(SalsDesc), vp, vp, vp, i32p, f32p, vp]
     lib.sals_topk_select.argtypes = [vp, f32p, i32p, i32p, i32p, vp]
     lib.sals_sparse_attend.argtypes = [vp, vp, i32p, vp, vp, vp, i32p, i32p, vp, vp]
     lib.sals_decode_step.argtypes = [vp, vp, i32p, vp, vp, vp, i32p, vp, f32p, i32p, i32p, vp]
@@ -123,6 +125,13 @@ def qv_row_bytes(desc: SalsDesc, bits: int):
     if st != SALS_OK:
         raise SalsError(st, "sals_qv_row_bytes")
     return int(c.value), int(m.value)
+
+
+def latent_scores_noalloc(desc: SalsDesc, q, W, Kc, seq_len, scores):
+    """sals_latent_scores without a context or workspace (scratch inside the library's device image)."""
+    st = _lib.sals_latent_scores_noalloc(ctypes.byref(desc), _p(q), _p(W), _p(Kc), _p(seq_len), _p(scores), _stream())
+    if st != SALS_OK:
+        raise SalsError(st, "sals_latent_scores_noalloc")
 
 
 def _p(t):

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -25,6 +26,10 @@
 #include "k_window.hpp"
 
 using namespace sals;
+
+// Scratch of sals_latent_scores_noalloc: part of the device image, one copy per GPU.  In host code the
+// name is only a handle for hipGetSymbolAddress; kernels are given the address looked up there.
+static __device__ __align__(256) unsigned char scratch[SALS_NOALLOC_SCRATCH_BYTES];
 
 namespace {
 
@@ -653,6 +658,52 @@ sals_status sals_latent_scores(sals_ctx* ctx, const void* q, const void* W, cons
     if (s != SALS_OK) return s;
     return ctx->d.dtype == SALS_BF16 ? launch_scores<bf16_t>(ctx, Kc, seq_len, scores, st)
                                      : launch_scores<float>(ctx, Kc, seq_len, scores, st);
+}
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices];  // per device: address of `scratch` there (nullptr: not looked up yet)
+
+// address of the current device's copy of `scratch`; looked up once per device, with that device current
+sals_status scratch_on_current_device(unsigned char** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SALS_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return SALS_ERR_HIP;
+        g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return SALS_OK;
+}
+}  // namespace
+
+sals_status sals_latent_scores_noalloc(const sals_desc* desc, const void* q, const void* W, const void* Kc,
+                                       const int32_t* seq_len, float* scores, void* hip_stream)
+{
+    sals_status s = validate(desc);
+    if (s != SALS_OK) return s;
+    if (bad(q) || bad(W) || bad(Kc) || !seq_len || bad(scores)) return SALS_ERR_INVALID_ARG;
+    // a context on the stack whose "workspace" is the static array: these two launches only use the slot of
+    // the partial sums of q~, placed at offset 0
+    sals_ctx tmp;
+    tmp.d = *desc;
+    tmp.L = make_layout(*desc);
+    tmp.L.qt = 0;
+    const size_t need = (size_t)tmp.L.proj_np * desc->B * desc->r * 4;
+    if (need > (size_t)SALS_NOALLOC_SCRATCH_BYTES) return SALS_ERR_WORKSPACE;
+    s = scratch_on_current_device(&tmp.ws);
+    if (s != SALS_OK) return s;
+    tmp.ws_bytes = SALS_NOALLOC_SCRATCH_BYTES;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    s = desc->dtype == SALS_BF16 ? launch_project<bf16_t, true>(&tmp, W, q, nullptr, nullptr, nullptr, nullptr, st)
+                                 : launch_project<float, true>(&tmp, W, q, nullptr, nullptr, nullptr, nullptr, st);
+    if (s != SALS_OK) return s;
+    return desc->dtype == SALS_BF16 ? launch_scores<bf16_t>(&tmp, Kc, seq_len, scores, st)
+                                    : launch_scores<float>(&tmp, Kc, seq_len, scores, st);
 }
 
 sals_status sals_topk_select(sals_ctx* ctx, const float* scores, const int32_t* seq_len, int32_t* idx,
