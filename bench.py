@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer buffer sets (0 = workload default)")
-    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg2_rhalf,cfg4_rhalf,cfg2_qv4,cfg4_qv4,cfg2_comp,cfg2_win,cfg3a_comp,cfg3a_win",
+    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg2_rhalf,cfg4_rhalf,cfg2_qv4,cfg4_qv4,cfg2_comp,cfg2_win,cfg3a_comp,cfg3a_win,cfg4_cap2x",
                     help="other configurations reported under 'extra' (comma list, '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
@@ -127,7 +127,7 @@ class DenseSet:
                 "K": torch.randn((w.B, w.S, w.H_kv, w.d), generator=gen, device=dev, dtype=dt),
                 "V": torch.randn((w.B, w.S, w.H_kv, w.d), generator=gen, device=dev, dtype=dt),
             })
-        self.seq_len = torch.full((w.B,), w.S, dtype=torch.int32, device=dev)
+        self.seq_len = torch.full((w.B,), w.S_live, dtype=torch.int32, device=dev)
         self.out = [torch.empty((w.B, w.H, w.d), dtype=dt, device=dev) for _ in range(n_layers)]
         torch.cuda.synchronize()
 
@@ -139,7 +139,7 @@ class DenseSet:
 def measure_dense(w, steps, warmup, use_graph, torch, binding):
     """us per layer-step of the dense baseline at w's shape (best of eager and graph replay) and its
     achieved HBM rate over the 2*B*S*D_kv cache elements it has to read."""
-    per = 2 * w.B * w.S * w.D_kv * w.esize
+    per = 2 * w.B * w.S_live * w.D_kv * w.esize
     nl = max(2, min(8, int(600e6 // per) + 1))
     ds = DenseSet(w, nl, torch, binding)
     ms = timed(torch, ds.step, steps, warmup)
@@ -328,7 +328,7 @@ def main():
         log("[bench] dense baseline at the same shape")
         out["dense_baseline"] = measure_dense(w, max(5, a.steps // 2), 2, not a.no_graph, torch, binding)
         out["dense_baseline"]["speedup_of_sals"] = round(out["dense_baseline"]["us_per_layer_step"] / out["value"], 3)
-        dense_done[(w.B, w.S, w.H, w.H_kv, w.dtype)] = out["dense_baseline"]
+        dense_done[(w.B, w.S, w.S_live, w.H, w.H_kv, w.dtype)] = out["dense_baseline"]
     if not a.no_cpu_baseline:
         log("[bench] timing the CPU oracle")
         host = [ls.host0] + [synth.make_layer(w, l) for l in range(1, min(3, n_layers))] if w.B == 1 else [ls.host0]
@@ -351,7 +351,7 @@ def main():
         del lse
         torch.cuda.empty_cache()
         if not a.no_dense:
-            key = (we.B, we.S, we.H, we.H_kv, we.dtype)
+            key = (we.B, we.S, we.S_live, we.H, we.H_kv, we.dtype)
             if key not in dense_done:
                 dense_done[key] = measure_dense(we, max(5, a.steps // 3), 2, not a.no_graph, torch, binding)
             extra[name]["dense_us_per_layer_step"] = dense_done[key]["us_per_layer_step"]

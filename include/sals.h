@@ -92,12 +92,22 @@ sals_status sals_workspace_bytes(const sals_desc* desc, size_t* bytes);
  * sals_workspace_bytes) and return a context in *out.  No initial contents are
  * required; after this call the workspace belongs to the library and the caller
  * must not write to it.  Part of it holds a constant table (RoPE cos/sin of every
- * position 0 .. S_max, 512 bytes per position) that the first sals_sparse_attend /
- * sals_decode_step call on the context fills with one extra kernel on that call's
- * stream.  Host-only, allocates only host memory. */
+ * position 0 .. S_max, 512 bytes per position), see sals_prepare.  The launch shapes
+ * of every stage are fixed here.  Host-only, allocates only host memory. */
 sals_status sals_create(const sals_desc* desc, void* d_workspace, size_t workspace_bytes,
                         sals_ctx** out);
 void sals_destroy(sals_ctx* ctx);
+
+/* One-time device set-up of a context: fills the cos/sin table of the workspace with one
+ * kernel on `hip_stream`, WAITS for it (the only call of this library that blocks the host),
+ * and raises the LDS limit of the kernels the context will launch.  Afterwards calls on the
+ * context may come from any stream and may be captured into HIP graphs.
+ * A context that was never prepared still works: the first call that needs the table
+ * enqueues the fill on its own stream, calls on the same stream follow by stream order and
+ * calls on other streams wait for an event; but such a context must not be used under
+ * graph capture (SALS_ERR_INVALID_ARG) until a call outside capture has seen the fill
+ * complete.  Idempotent. */
+sals_status sals_prepare(sals_ctx* ctx, void* hip_stream);
 
 /* Bytes of one layer's packed projectors (4 * D_kv * r elements of T).  Host-only. */
 sals_status sals_packed_weight_bytes(const sals_desc* desc, size_t* bytes);

@@ -23,7 +23,7 @@ SALS_ERR_HIP = 4
 SALS_F32, SALS_BF16 = 0, 1
 
 EXPORTS = (
-    "sals_status_string", "sals_workspace_bytes", "sals_create", "sals_destroy",
+    "sals_status_string", "sals_workspace_bytes", "sals_create", "sals_prepare", "sals_destroy",
     "sals_compress_append", "sals_latent_scores", "sals_topk_select", "sals_sparse_attend",
     "sals_decode_step", "sals_kernel_name", "sals_profile_enable", "sals_profile_collect",
     "sals_packed_weight_bytes", "sals_pack_weights",
@@ -58,6 +58,7 @@ def load_library() -> ctypes.CDLL:
     lib.sals_status_string.argtypes = [ctypes.c_int]
     lib.sals_workspace_bytes.argtypes = [ctypes.POINTER(SalsDesc), ctypes.POINTER(ctypes.c_size_t)]
     lib.sals_create.argtypes = [ctypes.POINTER(SalsDesc), vp, ctypes.c_size_t, ctypes.POINTER(vp)]
+    lib.sals_prepare.argtypes = [vp, vp]
     lib.sals_destroy.argtypes = [vp]
     lib.sals_destroy.restype = None
     lib.sals_packed_weight_bytes.argtypes = [ctypes.POINTER(SalsDesc), ctypes.POINTER(ctypes.c_size_t)]
@@ -157,6 +158,12 @@ class Sals:
         if st != SALS_OK:
             raise SalsError(st, "sals_create")
         self._h = h
+        # one-time device set-up (cos/sin table, kernel attributes): afterwards any stream, graph capture included
+        st = _lib.sals_prepare(h, torch.cuda.current_stream(self.device).cuda_stream)
+        if st != SALS_OK:
+            _lib.sals_destroy(h)
+            self._h = None
+            raise SalsError(st, "sals_prepare")
         self._destroy = _lib.sals_destroy   # kept on the instance: module globals may be gone at interpreter exit
 
     def close(self):

@@ -32,14 +32,14 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restri
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int li = lane & 15, quad = lane >> 4;
     const int n_pieces = r_score / VEC;
-    const int S = min(ld_uniform_i32(seq_len + b), S_max);  // (vector memory path: only needed when scores are stored)
+    const int S_v = ld_uniform_i32(seq_len + b);  // (vector memory path: requested ahead of the first cache rows)
     const int j_begin = blockIdx.x * rows_per_wg;
     const int j_end = min(S_max, j_begin + rows_per_wg);
     const T* base = Kc + (size_t)b * S_max * r;
 
     auto load_row = [&](int j0, u32x4* piece) {
         const int j = j0 + wave * 4 + quad;
-        // every row below S_max is readable, so the loads do not wait for the sequence length;
+        // every row below S_max is readable, so the first pass of loads does not wait for the sequence length;
         // rows past it are overwritten with -inf when the score is stored
         const bool live = j < S_max;
 #pragma unroll
@@ -70,6 +70,12 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restri
         if (i < r_score) *reinterpret_cast<f32x4*>(&q_s[i]) = s;
     }
     __syncthreads();
+    // The stream is paid for the sequence, not for the capacity: after the first pass (requested before the length
+    // was known) only rows below the length are loaded; the rest of the workgroup's range is filled with -inf.
+    const int S = min(wave_uniform(S_v), S_max);
+    const int j_live = min(j_end, max(S, j_begin + kScoreRowsPerIter));
+    const int j_tail = min(j_end, j_begin + (j_live - j_begin + kScoreRowsPerIter - 1) / kScoreRowsPerIter * kScoreRowsPerIter);
+    for (int j = j_tail + tid; j < j_end; j += kScoreThreads) scores[(size_t)b * S_max + j] = -INFINITY;
     float qf[NCH][VEC];
 #pragma unroll
     for (int n = 0; n < NCH; ++n) {
@@ -95,12 +101,12 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restri
         if (li == 0 && j < j_end) scores[(size_t)b * S_max + j] = j < S ? acc : -INFINITY;
     };
     // two register sets take turns (no copy between them: a copy would wait for the loads it moves)
-    for (int j0 = j_begin; j0 < j_end; j0 += 2 * kScoreRowsPerIter) {
-        const bool second = j0 + kScoreRowsPerIter < j_end;
+    for (int j0 = j_begin; j0 < j_live; j0 += 2 * kScoreRowsPerIter) {
+        const bool second = j0 + kScoreRowsPerIter < j_live;
         if (second) load_row(j0 + kScoreRowsPerIter, nxt);
         finish_rows(j0, cur);
         if (second) {
-            if (j0 + 2 * kScoreRowsPerIter < j_end) load_row(j0 + 2 * kScoreRowsPerIter, cur);
+            if (j0 + 2 * kScoreRowsPerIter < j_live) load_row(j0 + 2 * kScoreRowsPerIter, cur);
             finish_rows(j0 + kScoreRowsPerIter, nxt);
         }
     }

@@ -54,14 +54,27 @@ struct Layout {  // byte offsets into the workspace
 
 struct ProfRecord { int kernel; hipEvent_t start, stop; };
 
+// which logits kernel a context's shape gets: 1 = 2 heads x 256 tokens, 2 = 1 head x 256 tokens, 3 = 1 head x 64
+// tokens (then: slices of the latent axis per tile, 128-byte steps loaded ahead); n_parts = token tiles per head
+struct LogitsPlan { int pick, n_parts, ksplit, nst; };
+
 struct sals_ctx {
     sals_desc d;
     Layout L;
     unsigned char* ws;
     size_t ws_bytes;
     InvFreq inv;
+    // launch shapes, fixed when the context is made (sals_create): nothing on the launch path reads the
+    // environment, plans or sets kernel attributes
+    LogitsPlan plan{3, 0, 1, 1};
+    int score_rows = 16;         // cache rows per workgroup of the score kernel
+    // cos/sin table over the positions 0 .. S_max (in the workspace): 0 = not filled, 1 = fill enqueued on
+    // rope_stream and marked by rope_ev, 2 = known to be complete
+    int rope_state = 0;
+    hipStream_t rope_stream = nullptr;
+    hipEvent_t rope_ev = nullptr;
+    bool lds_allowed = false;    // the logits kernels' dynamic-LDS attribute has been raised
     bool profiling = false;
-    bool rope_ready = false;     // the cos/sin table in the workspace has been enqueued
     std::vector<ProfRecord> prof;
 };
 
@@ -230,11 +243,7 @@ sals_status launch_scores(const sals_ctx* c, const void* Kc, const int32_t* seq_
     const sals_desc& d = c->d;
     constexpr int VEC = elem<T>::vec;
     const int nch = ceil_div(d.r_score / VEC, 16);
-    // rows per workgroup: a multiple of 16 giving roughly 1024 workgroups, 16..128 rows (measured optimum)
-    long long total_rows = (long long)d.B * d.S_max;
-    int rows = (int)std::min<long long>(128, std::max<long long>(16, total_rows / 1024));
-    if (const char* e = std::getenv("SALS_TUNE_SCORE_ROWS")) rows = std::max(16, std::min(1 << 16, std::atoi(e)));  // tuning aid
-    rows = ceil_div(rows, kScoreRowsPerIter) * kScoreRowsPerIter;
+    const int rows = c->score_rows;
     dim3 grid(ceil_div(d.S_max, rows), d.B);
     const float* qt = reinterpret_cast<const float*>(c->ws + c->L.qt);
     const T* K = static_cast<const T*>(Kc);
@@ -298,15 +307,56 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
     return launch_status();
 }
 
-// first use of a context: cos/sin of every cache position 0 .. S_max, ahead of the kernels that read it
-sals_status ensure_rope_table(const sals_ctx* c, hipStream_t st)
+// rows per workgroup of the score kernel: a multiple of 16 giving roughly 1024 workgroups, 16..128 rows
+// (measured optimum)
+int plan_score_rows(const sals_desc& d)
 {
-    if (c->rope_ready) return SALS_OK;
+    long long total_rows = (long long)d.B * d.S_max;
+    int rows = (int)std::min<long long>(128, std::max<long long>(16, total_rows / 1024));
+    if (const char* e = std::getenv("SALS_TUNE_SCORE_ROWS")) rows = std::max(16, std::min(1 << 16, std::atoi(e)));  // tuning aid
+    return ceil_div(rows, kScoreRowsPerIter) * kScoreRowsPerIter;
+}
+
+// Enqueues the fill of the context's cos/sin table on `st` and marks it with an event.
+sals_status enqueue_rope_table(sals_ctx* c, hipStream_t st)
+{
     const size_t n = (size_t)(c->d.S_max + 1) * kPairs;
     hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
                        reinterpret_cast<float2*>(c->ws + c->L.rope), c->inv, c->d.S_max + 1);
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
-    const_cast<sals_ctx*>(c)->rope_ready = true;
+    if (!c->rope_ev && hipEventCreateWithFlags(&c->rope_ev, hipEventDisableTiming) != hipSuccess) return SALS_ERR_HIP;
+    if (hipEventRecord(c->rope_ev, st) != hipSuccess) return SALS_ERR_HIP;
+    c->rope_stream = st;
+    c->rope_state = 1;
+    return SALS_OK;
+}
+
+// Before a kernel that reads the cos/sin table is enqueued on `st`.  A prepared context (sals_prepare) costs one
+// comparison.  Otherwise the fill is enqueued on first use and later calls are ordered behind it: same stream by
+// stream order, another stream by waiting for the event.  A stream under graph capture needs a prepared context
+// (a captured fill would not run before eager work, and events of other streams cannot be consulted there).
+sals_status ensure_rope_table(const sals_ctx* cc, hipStream_t st)
+{
+    sals_ctx* c = const_cast<sals_ctx*>(cc);
+    if (c->rope_state == 2) return SALS_OK;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) != hipSuccess) return SALS_ERR_HIP;
+    if (cap != hipStreamCaptureStatusNone) return SALS_ERR_INVALID_ARG;
+    if (c->rope_state == 0) return enqueue_rope_table(c, st);
+    if (hipEventQuery(c->rope_ev) == hipSuccess) { c->rope_state = 2; return SALS_OK; }
+    (void)hipGetLastError();  // (hipErrorNotReady is not an error here)
+    if (st == c->rope_stream) return SALS_OK;
+    return hipStreamWaitEvent(st, c->rope_ev, 0) == hipSuccess ? SALS_OK : SALS_ERR_HIP;
+}
+
+// the logits kernels use more than the default 48 KB of dynamic LDS: raised once per context, on first use
+template <typename T> sals_status allow_logits_lds(const LogitsPlan& P);
+template <typename T> sals_status ensure_lds_attr(const sals_ctx* cc)
+{
+    sals_ctx* c = const_cast<sals_ctx*>(cc);
+    if (c->lds_allowed) return SALS_OK;
+    if (allow_logits_lds<T>(c->plan) != SALS_OK) return SALS_ERR_HIP;
+    c->lds_allowed = true;
     return SALS_OK;
 }
 
@@ -345,12 +395,8 @@ struct QvCache { const void* codes; const void* meta; int bits; };  // quantised
 enum { kPhaseLogits = 1, kPhaseValue = 2, kPhaseOut = 4, kPhaseAll = 7 };
 struct StatsLink { float2* stats; int stride; int part0; };  // [B*H][stride] records, this pass's tiles from part0 on
 
-// which logits kernel a context's shape gets: 1 = 2 heads x 256 tokens, 2 = 1 head x 256 tokens, 3 = 1 head x 64
-// tokens (then: slices of the latent axis per tile, 128-byte steps loaded ahead); n_parts = token tiles per head
-struct LogitsPlan { int pick, n_parts, ksplit, nst; };
-template <typename T> LogitsPlan plan_logits(const sals_ctx* c)
+template <typename T> LogitsPlan plan_logits(const sals_desc& d)
 {
-    const sals_desc& d = c->d;
     const int k_tot = d.top_k + d.n_sink + d.n_recent;
     auto n_wg = [&](int heads, int tok) { return (long long)ceil_div(k_tot, tok) * (d.H_kv / heads) * d.B; };
     LogitsPlan P{3, 0, 1, 1};
@@ -358,7 +404,7 @@ template <typename T> LogitsPlan plan_logits(const sals_ctx* c)
     // keeps at least two steps and the workgroups still fit the chip in one round
     const int nkc128 = d.r * (int)sizeof(T) / kLgChunk;
     const long long n_wg1 = n_wg(1, kLsTok);
-    static const bool allow_split = [] { const char* e = std::getenv("SALS_TUNE_LOGITS_KSPLIT"); return !e || std::atoi(e) != 0; }();  // tuning aid
+    const bool allow_split = [] { const char* e = std::getenv("SALS_TUNE_LOGITS_KSPLIT"); return !e || std::atoi(e) != 0; }();  // tuning aid
     if (allow_split && n_wg1 <= 128)
         for (int ks = kLsMaxSplit; ks >= 2; ks /= 2)
             if (n_wg1 * ks <= 256 && nkc128 % ks == 0 && nkc128 / ks >= 2) { P.ksplit = ks; break; }
@@ -394,6 +440,34 @@ template <typename T> LogitsPlan plan_logits(const sals_ctx* c)
     return P;
 }
 
+template <typename T> sals_status allow_logits_lds(const LogitsPlan& P)
+{
+    auto allow = [](const void* kern, size_t bytes) {
+        return bytes <= 48 * 1024 ||
+               hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+    };
+    bool ok = true;
+    if (P.pick == 1) ok = allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 2, 4, 2>), logits_cfg<2, 4, 2>::LDS);
+    else if (P.pick == 2) ok = allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 1, 4, 2>), logits_cfg<1, 4, 2>::LDS);
+    else {
+        const void* k = nullptr;
+        switch (P.nst) {
+            case 1: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 1>); break;
+            case 2: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 2>); break;
+            case 3: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 3>); break;
+            case 4: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 4>); break;
+            case 5: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 5>); break;
+            case 6: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 6>); break;
+            case 7: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 7>); break;
+            case 8: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 8>); break;
+            case 9: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 9>); break;
+            default: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 10>); break;
+        }
+        ok = allow(k, kLsLds);
+    }
+    return ok ? SALS_OK : SALS_ERR_HIP;
+}
+
 template <typename T>
 sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos, const void* Kc,
                           const void* Vc, const void* W, const int32_t* idx, const int32_t* n_sel, void* out,
@@ -404,7 +478,7 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     const Layout& L = c->L;
     const int k_tot = d.top_k + d.n_sink + d.n_recent;
     float* logits = reinterpret_cast<float*>(c->ws + L.logits);
-    const LogitsPlan P = plan_logits<T>(c);
+    const LogitsPlan P = c->plan;
     // tile statistics: written by this pass's logits kernel from record `part0` on, read as a whole by the value kernel
     float2* const stats_all = link ? link->stats : reinterpret_cast<float2*>(c->ws + L.stats);
     float2* const stats = stats_all + (link ? link->part0 : 0);
@@ -412,8 +486,10 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     const float2* rope = reinterpret_cast<const float2*>(c->ws + L.rope);
     float* tpart = reinterpret_cast<float*>(c->ws + L.tpart);
     const int n_parts = P.n_parts;
-    if (ensure_rope_table(c, st) != SALS_OK) return SALS_ERR_HIP;
     if (phases & kPhaseLogits) {
+        sals_status rs = ensure_rope_table(c, st);
+        if (rs == SALS_OK) rs = ensure_lds_attr<T>(c);
+        if (rs != SALS_OK) return rs;
         // replicate the smaller operand across the XCDs' L2s: all of U_k, or the gathered rows
         const size_t a_bytes = (size_t)d.H_kv * kHeadDim * d.r, b_bytes = (size_t)d.B * k_tot * d.r;
         const int heads_fastest = a_bytes <= b_bytes ? 1 : 0;
@@ -422,10 +498,6 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     do {                                                                                                     \
         typedef logits_cfg<HEADS, NTG, NB> LC;                                                               \
         auto kern = attend_logits_kernel<T, HEADS, NTG, NB>;                                                 \
-        if (LC::LDS > 48 * 1024 &&                                                                           \
-            hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                (int)LC::LDS) != hipSuccess)                                                 \
-            return SALS_ERR_HIP;                                                                             \
         hipLaunchKernelGGL(kern, dim3(n_parts * (d.H_kv / HEADS) * d.B), dim3(LC::NT), LC::LDS, st,          \
                            static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,                     \
                            static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats, d.B,                \
@@ -452,9 +524,6 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
                 case 9: kern = attend_logits_small_kernel<T, 9>; break;
                 default: kern = attend_logits_small_kernel<T, 10>; break;
             }
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)kLsLds) != hipSuccess)
-                return SALS_ERR_HIP;
             float* plogits = reinterpret_cast<float*>(c->ws + L.plogits);
             hipLaunchKernelGGL(kern, dim3(n_parts * d.H_kv * d.B * ksplit), dim3(kLsThreads), kLsLds, st,
                                idx, n_sel, w_section<T>(c, W, 2), d.B, d.H_kv, n_parts, heads_fastest, ksplit, k_tot,
@@ -577,14 +646,33 @@ sals_status sals_create(const sals_desc* desc, void* d_workspace, size_t workspa
     c->ws_bytes = workspace_bytes;
     for (int p = 0; p < kPairs; ++p)
         c->inv.f[p] = std::pow((double)desc->rope_theta, -2.0 * (double)p / (double)desc->d);
+    const bool bf = desc->dtype == SALS_BF16;
+    c->plan = bf ? plan_logits<bf16_t>(c->d) : plan_logits<float>(c->d);
+    c->score_rows = plan_score_rows(c->d);
     *out = c;
     return SALS_OK;
+}
+
+sals_status sals_prepare(sals_ctx* ctx, void* hip_stream)
+{
+    if (!ctx) return SALS_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (ctx->rope_state != 2) {
+        if (ctx->rope_state == 0) {
+            sals_status s = enqueue_rope_table(ctx, st);
+            if (s != SALS_OK) return s;
+        }
+        if (hipEventSynchronize(ctx->rope_ev) != hipSuccess) return SALS_ERR_HIP;
+        ctx->rope_state = 2;
+    }
+    return ctx->d.dtype == SALS_BF16 ? ensure_lds_attr<bf16_t>(ctx) : ensure_lds_attr<float>(ctx);
 }
 
 void sals_destroy(sals_ctx* ctx)
 {
     if (!ctx) return;
     for (auto& r : ctx->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    if (ctx->rope_ev) (void)hipEventDestroy(ctx->rope_ev);
     delete ctx;
 }
 
@@ -693,6 +781,7 @@ sals_status sals_latent_scores_noalloc(const sals_desc* desc, const void* q, con
     tmp.d = *desc;
     tmp.L = make_layout(*desc);
     tmp.L.qt = 0;
+    tmp.score_rows = plan_score_rows(*desc);
     const size_t need = (size_t)tmp.L.proj_np * desc->B * desc->r * 4;
     if (need > (size_t)SALS_NOALLOC_SCRATCH_BYTES) return SALS_ERR_WORKSPACE;
     s = scratch_on_current_device(&tmp.ws);
@@ -878,8 +967,7 @@ sals_status window_attend(sals_ctx* ctx, sals_ctx* win, const void* q, const int
     // context's array, each value pass normalises with the statistics of all tiles, and one output projection adds
     // both passes' value sums through their projectors.
     const bool bf = d.dtype == SALS_BF16;
-    const LogitsPlan p_lo = bf ? plan_logits<bf16_t>(ctx) : plan_logits<float>(ctx);
-    const LogitsPlan p_hi = bf ? plan_logits<bf16_t>(win) : plan_logits<float>(win);
+    const LogitsPlan p_lo = ctx->plan, p_hi = win->plan;
     if (p_lo.n_parts + p_hi.n_parts > ctx->L.max_parts) return SALS_ERR_UNSUPPORTED;
     float2* shared = reinterpret_cast<float2*>(ctx->ws + ctx->L.stats);
     const StatsLink l_lo{shared, p_lo.n_parts + p_hi.n_parts, 0}, l_hi{shared, p_lo.n_parts + p_hi.n_parts, p_lo.n_parts};

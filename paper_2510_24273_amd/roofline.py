@@ -20,7 +20,7 @@ def paper_traffic_elements(s: int, r: int, r_score: int, k: int) -> int:
 def stage_bytes(w, seq_len=None) -> dict:
     """Algorithmic HBM bytes per layer-step of workload w, by stage."""
     e = w.esize
-    S = w.S if seq_len is None else seq_len
+    S = getattr(w, "S_live", w.S) if seq_len is None else seq_len
     n_sel = min(S, w.k_tot)
     small = w.B * (w.H * w.d * e * 2 + w.r * 4 + n_sel * 4)   # q, out, q~, idx
     return {
@@ -44,7 +44,7 @@ def algorithmic_bytes(w, seq_len=None) -> int:
 
 
 def stage_flops(w, seq_len=None) -> dict:
-    S = w.S if seq_len is None else seq_len
+    S = getattr(w, "S_live", w.S) if seq_len is None else seq_len
     n_sel = min(S, w.k_tot)
     return {
         "project": 2 * w.B * w.r * w.D_kv,

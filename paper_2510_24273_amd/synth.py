@@ -43,6 +43,7 @@ class Workload:
     scale: float = 1.0           # extra cache scale (stress cases only)
     qv_bits: int = 0             # > 0: values live in the quantised full-rank cache (2 | 4 bits)
     r_hi: int = 0                # > 0: the n_recent last tokens live in a ring cache of this rank (Sec. 5.1)
+    fill: float = 1.0            # share of the cache capacity S that holds tokens (sequence length = S * fill)
 
     @property
     def D_kv(self):
@@ -55,6 +56,11 @@ class Workload:
     @property
     def rs(self):
         return self.r if self.r_score is None else self.r_score
+
+    @property
+    def S_live(self):
+        """Tokens per sequence (the cache holds S rows, the first S_live of them are written)."""
+        return int(self.S * self.fill)
 
     @property
     def esize(self):
@@ -118,6 +124,11 @@ for _B in (8, 16):
             VARIANTS[f"t6_b{_B}_s{_S}_{_tag}"] = Workload(
                 f"table6_llama2_7b_B{_B}_S{_S}_r{_r}_rscore{_r // 2}_k{_S // 8}_qvalue{_bits}bit", 6, _B, _S, 32, 32,
                 128, _r, _S // 8 - 80, r_score=_r // 2, n_sink=16, n_recent=64, plant=3, qv_bits=_bits)
+
+
+# A decode loop's cache is allocated for more tokens than it holds: the long-context shape with twice the capacity
+# (the score stream and the selection must cost the 32768 tokens present, not the 65536 rows allocated).
+VARIANTS["cfg4_cap2x"] = replace(CONFIGS["cfg4"], name="cfg4_long_B4_S32768_capacity65536_r640_k2048", S=65536, fill=0.5)
 
 
 def lookup(name: str) -> Workload:
@@ -219,7 +230,7 @@ def make_layer(w: Workload, layer: int = 0, seq_lens=None):
     q [B,H,d], Kc/Vc [B,S,r] (rows past seq_len[b] are zero), Uk/Uv [D_kv,r],
     seq_len [B] int32, q_pos [B] int32 (= seq_len: the query follows the cache)."""
     Uk, Uv = make_weights(w, layer)
-    seq_lens = [w.S] * w.B if seq_lens is None else list(seq_lens)
+    seq_lens = [w.S_live] * w.B if seq_lens is None else list(seq_lens)
     assert len(seq_lens) == w.B and max(seq_lens) <= w.S
     st = np.uint16 if w.dtype == "bf16" else np.float32
     q = np.zeros((w.B, w.H, w.d), dtype=st)

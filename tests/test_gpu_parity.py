@@ -74,6 +74,18 @@ def test_gqa_groups(oracle):
         _run(oracle, w, seq_lens=[600, 333], label=f"gqa H={H} H_kv={H_kv}")
 
 
+@pytest.mark.parametrize("rows", [16, 48, 128])
+def test_capacity_above_length(oracle, rows, monkeypatch):
+    """A cache allocated for more tokens than it holds: the score kernel stops loading at the sequence length
+    (after the first 16-row pass of each workgroup, which is requested before the length is known) and fills the
+    rest with -inf.  Lengths on both sides of every boundary of that logic: inside a workgroup's first pass, at a
+    pass boundary, at a workgroup boundary, mid-range, empty, full; `rows` = cache rows per workgroup."""
+    monkeypatch.setenv("SALS_TUNE_SCORE_ROWS", str(rows))
+    w = synth.shrink(SMALL, B=6, S=3000, r=128, top_k=40, plant=0)
+    _run(oracle, w, seq_lens=[3000, 2 * rows, 2 * rows + 1, 2 * rows + 16, 5, 1537], label=f"capacity rows={rows} a")
+    _run(oracle, w, seq_lens=[0, 2999, 2 * rows - 1, 3 * rows + 17, 16, 2048], label=f"capacity rows={rows} b")
+
+
 def test_odd_sizes(oracle):
     """A cache capacity that is not a multiple of 4 (score rows of later sequences start unaligned), an odd
     selection budget, an odd multiple of 8 as scoring rank."""
