@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer buffer sets (0 = workload default)")
-    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg2_rhalf,cfg4_rhalf,cfg2_qv4,cfg4_qv4,cfg2_comp,cfg2_win,cfg3a_comp,cfg3a_win,cfg4_cap2x",
+    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg2_rhalf,cfg4_rhalf,cfg2_qv4,cfg4_qv4,cfg2_comp,cfg2_win,cfg3a_comp,cfg3a_win,cfg4_cap2x,prefill_cfg2,prefill_cfg3b",
                     help="other configurations reported under 'extra' (comma list, '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
@@ -159,6 +159,45 @@ def measure_dense(w, steps, warmup, use_graph, torch, binding):
     torch.cuda.empty_cache()
     return {"us_per_layer_step": round(us, 2), "cache_bytes": per, "achieved_GBps": round(per / (us * 1e-6) / 1e9, 1),
             "hbm_frac": round(per / (us * 1e-6) / 1e9 / 8000.0, 4)}
+
+
+def measure_prefill(w, steps, torch, binding, roofline):
+    """Bulk compression of a whole prompt of w.S tokens per sequence (the prefill-time GEMM K~ = K U_k, V~ = V U_v):
+    average kernel duration from the library's own event pairs, against the bf16 matrix peak."""
+    dev = "cuda:0"
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    desc = binding.make_desc(w.B, w.S, w.H, w.H_kv, w.d, w.r, w.top_k, w.dtype, rope_theta=w.theta)
+    ctx = binding.Sals(desc, dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(10_000 * w.cfg_id + 81)
+    U = [torch.randn((w.D_kv, w.r), generator=gen, device=dev, dtype=torch.float32).to(dt) * (w.D_kv ** -0.5) for _ in range(2)]
+    W = ctx.pack_weights(U[0], U[1])
+    nset = max(2, min(6, int(600e6 // (2 * w.B * w.S * w.D_kv * w.esize)) + 1))
+    X = [[torch.randn((w.B, w.S, w.D_kv), generator=gen, device=dev, dtype=dt) for _ in range(2)] for _ in range(nset)]
+    Kc = torch.empty((w.B, w.S, w.r), dtype=dt, device=dev)
+    Vc = torch.empty_like(Kc)
+    sl = torch.zeros((w.B,), dtype=torch.int32, device=dev)
+    for i in range(2):
+        sl.zero_()
+        ctx.compress_prefill(X[i % nset][0], X[i % nset][1], W, Kc, Vc, sl, w.S)
+    torch.cuda.synchronize()
+    ctx.profile(True)
+    for i in range(steps):
+        sl.zero_()
+        ctx.compress_prefill(X[i % nset][0], X[i % nset][1], W, Kc, Vc, sl, w.S)
+    torch.cuda.synchronize()
+    ms, n = ctx.profile_collect()["prefill"]
+    ctx.profile(False)
+    us = ms * 1e3 / max(n, 1)
+    flops = 2 * 2 * w.B * w.S * w.D_kv * w.r
+    byts = 2 * (w.B * w.S * (w.D_kv + w.r) + w.D_kv * w.r) * w.esize
+    peak = roofline.MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else roofline.VALU_F32_PEAK_TFLOPS
+    ctx.close()
+    del X
+    torch.cuda.empty_cache()
+    return {"workload": f"prefill_{w.name}", "tokens": w.B * w.S, "us_per_call": round(us, 2), "flops": flops,
+            "achieved_TFLOPs": round(flops / (us * 1e-6) / 1e12, 1), "mfma_frac": round(flops / (us * 1e-6) / 1e12 / peak, 4),
+            "bytes": byts, "hbm_frac": round(byts / (us * 1e-6) / 1e9 / roofline.HBM_PEAK_GBPS, 4)}
 
 
 def timed(torch, fn, steps, warmup):
@@ -337,6 +376,10 @@ def main():
     torch.cuda.empty_cache()
     extra = {}
     for name in [x for x in a.extras.split(",") if x and x != a.workload]:
+        if name.startswith("prefill_"):   # the prompt of that configuration compressed in one call
+            log(f"[bench] extra {name}")
+            extra[name] = measure_prefill(synth.lookup(name[len("prefill_"):]), max(5, a.steps // 3), torch, binding, roofline)
+            continue
         we = synth.lookup(name)
         per = roofline.algorithmic_bytes(we) + we.r * we.D_kv * we.esize
         nl = max(2, min(8, int(600e6 // per) + 1))

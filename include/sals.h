@@ -133,6 +133,23 @@ sals_status sals_compress_append(sals_ctx* ctx, const void* k_new, const void* v
                                  const void* W, void* Kc, void* Vc, int32_t* seq_len,
                                  void* hip_stream);
 
+/* Bulk compression of a whole prompt (Eq. 1, K~ = K U_r; Algorithm 1, projection and append steps
+ * for n_tok tokens at once; the prefill-time counterpart of sals_compress_append):
+ *   Kc[b, seq_len[b] + t, :] = Uk^T k_new[b, t],   Vc[b, seq_len[b] + t, :] = Uv^T v_new[b, t]
+ * for t < n_new[b], as one GEMM per projection on the matrix cores (fp32 accumulation, one rounding
+ * to T, so a row equals what sals_compress_append writes for the same token up to the order of the
+ * fp32 sum); then seq_len[b] += n_new[b].  Rows that would fall past S_max are dropped and the length
+ * stops at S_max.
+ *   k_new, v_new [B, n_tok, D_kv] T   pre-RoPE keys / values of the prompt tokens
+ *   W                                 packed projectors of this layer
+ *   Kc, Vc       [B, S_max, r] T      in/out
+ *   seq_len      [B] int32            in/out (device)
+ *   n_new        [B] int32 (device) tokens of each sequence, clamped to [0, n_tok]; NULL: n_tok everywhere
+ *   n_tok        1 .. S_max (host)    token capacity of k_new / v_new per sequence */
+sals_status sals_compress_prefill(sals_ctx* ctx, const void* k_new, const void* v_new,
+                                  const void* W, void* Kc, void* Vc, int32_t* seq_len,
+                                  const int32_t* n_new, int32_t n_tok, void* hip_stream);
+
 /* Stage 2a, query projection and latent scores (Sec. 4.3; Algorithm 1, score step):
  *   q~ = Uk^T (sum of the query heads of each KV group, stacked)     [r], fp32
  *   scores[b, j] = sum_{i < r_score} q~[i] * Kc[b, j, i]   for j <  seq_len[b]
@@ -329,7 +346,8 @@ enum {
     SALS_K_ATTEND_OUT = 5,     /* output projection through U_v                */
     SALS_K_ATTEND_QV = 6,      /* softmax + sum over the quantised value cache */
     SALS_K_DENSE = 7,          /* dense baseline attention (+ its chunk merge)  */
-    SALS_N_KERNELS = 8
+    SALS_K_PREFILL = 8,        /* bulk compression of a prompt (MFMA GEMM)     */
+    SALS_N_KERNELS = 9
 };
 const char* sals_kernel_name(int kernel);
 sals_status sals_profile_enable(sals_ctx* ctx, int on);

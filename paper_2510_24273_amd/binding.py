@@ -30,9 +30,9 @@ EXPORTS = (
     "sals_qv_row_bytes", "sals_compress_append_qv", "sals_sparse_attend_qv", "sals_decode_step_qv",
     "sals_dense_attend",
     "sals_window_append", "sals_sparse_attend_window", "sals_decode_step_window", "sals_overlap_score",
-    "sals_latent_scores_noalloc",
+    "sals_latent_scores_noalloc", "sals_compress_prefill",
 )
-N_KERNELS = 8
+N_KERNELS = 9
 
 
 class SalsDesc(ctypes.Structure):
@@ -64,6 +64,7 @@ def load_library() -> ctypes.CDLL:
     lib.sals_packed_weight_bytes.argtypes = [ctypes.POINTER(SalsDesc), ctypes.POINTER(ctypes.c_size_t)]
     lib.sals_pack_weights.argtypes = [vp, vp, vp, vp, vp]
     lib.sals_compress_append.argtypes = [vp, vp, vp, vp, vp, vp, i32p, vp]
+    lib.sals_compress_prefill.argtypes = [vp, vp, vp, vp, vp, vp, i32p, i32p, ctypes.c_int32, vp]
     lib.sals_latent_scores.argtypes = [vp, vp, vp, vp, i32p, f32p, vp]
     lib.sals_latent_scores_noalloc.argtypes = [ctypes.POINTER(SalsDesc), vp, vp, vp, i32p, f32p, vp]
     lib.sals_topk_select.argtypes = [vp, f32p, i32p, i32p, i32p, vp]
@@ -202,6 +203,11 @@ class Sals:
     def compress_append(self, k_new, v_new, W, Kc, Vc, seq_len):
         self._check(_lib.sals_compress_append(self._h, _p(k_new), _p(v_new), _p(W), _p(Kc), _p(Vc),
                                               _p(seq_len), _stream()), "sals_compress_append")
+
+    def compress_prefill(self, k_new, v_new, W, Kc, Vc, seq_len, n_tok, n_new=None):
+        """Bulk compression of n_tok prompt tokens per sequence (k_new, v_new [B, n_tok, D_kv])."""
+        self._check(_lib.sals_compress_prefill(self._h, _p(k_new), _p(v_new), _p(W), _p(Kc), _p(Vc), _p(seq_len),
+                                               _p(n_new), int(n_tok), _stream()), "sals_compress_prefill")
 
     def latent_scores(self, q, W, Kc, seq_len, scores):
         self._check(_lib.sals_latent_scores(self._h, _p(q), _p(W), _p(Kc), _p(seq_len), _p(scores),

@@ -17,6 +17,7 @@
 #include "k_logits.hpp"
 #include "k_logits_small.hpp"
 #include "k_overlap.hpp"
+#include "k_prefill.hpp"
 #include "k_project.hpp"
 #include "k_scores.hpp"
 #include "k_topk.hpp"
@@ -81,7 +82,7 @@ struct sals_ctx {
 namespace {
 
 const char* const kKernelNames[SALS_N_KERNELS] = {
-    "project", "scores", "topk", "attend_logits", "attend_pv", "attend_out", "attend_qv", "dense_attend"};
+    "project", "scores", "topk", "attend_logits", "attend_pv", "attend_out", "attend_qv", "dense_attend", "prefill"};
 
 // Brackets one kernel launch with a pair of events while profiling is on.
 struct ProfScope {
@@ -733,6 +734,43 @@ sals_status sals_compress_append(sals_ctx* ctx, const void* k_new, const void* v
     return ctx->d.dtype == SALS_BF16
                ? launch_project<bf16_t, false>(ctx, W, k_new, v_new, Kc, Vc, seq_len, st)
                : launch_project<float, false>(ctx, W, k_new, v_new, Kc, Vc, seq_len, st);
+}
+
+sals_status sals_compress_prefill(sals_ctx* ctx, const void* k_new, const void* v_new, const void* W, void* Kc,
+                                  void* Vc, int32_t* seq_len, const int32_t* n_new, int32_t n_tok, void* hip_stream)
+{
+    if (!ctx || bad(k_new) || bad(v_new) || bad(W) || bad(Kc) || bad(Vc) || !seq_len) return SALS_ERR_INVALID_ARG;
+    if (n_tok < 1 || n_tok > ctx->d.S_max) return SALS_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const sals_desc& d = ctx->d;
+    const bool bf = d.dtype == SALS_BF16;
+    PrefillArgs a{};
+    a.X[0] = k_new; a.X[1] = v_new;
+    a.cache[0] = Kc; a.cache[1] = Vc;
+    a.seq_len = seq_len; a.n_new = n_new;
+    a.n_tok = n_tok; a.D = d.H_kv * d.d; a.r = d.r; a.S_max = d.S_max; a.B = d.B; a.nproj = 2;
+    for (int p = 0; p < 2; ++p)
+        a.UT[p] = bf ? static_cast<const void*>(w_section<bf16_t>(ctx, W, p)) : static_cast<const void*>(w_section<float>(ctx, W, p));
+    const int nl = d.r % 128 == 0 ? 128 : 64;
+    const dim3 grid(ceil_div(n_tok, kPfTok), d.r / nl, d.B * 2);
+    const size_t lds = prefill_lds_bytes(nl);
+#define SALS_PREFILL(T, NLT)                                                                                      \
+    do {                                                                                                          \
+        auto kern = prefill_compress_kernel<T, NLT>;                                                              \
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,  \
+                                (int)lds) != hipSuccess)                                                          \
+            return SALS_ERR_HIP;                                                                                  \
+        hipLaunchKernelGGL(kern, grid, dim3(kPfThreads), lds, st, a);                                             \
+    } while (0)
+    {
+        ProfScope ps(ctx, SALS_K_PREFILL, st);
+        if (bf) { if (nl == 128) SALS_PREFILL(bf16_t, 128); else SALS_PREFILL(bf16_t, 64); }
+        else    { if (nl == 128) SALS_PREFILL(float, 128); else SALS_PREFILL(float, 64); }
+    }
+#undef SALS_PREFILL
+    if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+    hipLaunchKernelGGL(advance_seq_len_kernel, dim3(ceil_div(d.B, 128)), dim3(128), 0, st, seq_len, n_new, n_tok, d.B, d.S_max);
+    return launch_status();
 }
 
 sals_status sals_latent_scores(sals_ctx* ctx, const void* q, const void* W, const void* Kc,
