@@ -223,7 +223,7 @@ def quantize_values(v, bits, dtype):
     scale float64 [n, D/32], zero float64 [n, D/32]); scale and zero are exact in `dtype`."""
     v32 = np.ascontiguousarray(v, dtype=np.float32)
     n, D = v32.shape
-    assert D % QV_GROUP == 0 and bits in (2, 4)
+    assert D % QV_GROUP == 0 and bits in (2, 4, 8)   # 8: the recent window's rows (Sec. 5.1: half the size of 16-bit values)
     levels = np.float32((1 << bits) - 1)
     g = v32.reshape(n, D // QV_GROUP, QV_GROUP)
     mn, mx = g.min(axis=-1), g.max(axis=-1)
@@ -357,6 +357,39 @@ def sparse_attend_window(q, q_pos, Kc, Vc, Uk, Uv, Kw, Vw, Uk_hi, Uv_hi, idx, S,
     V_C[~in_win] = reconstruct(Vc, lo, Uv)
     K_C[in_win] = reconstruct(Kw, hi % w, Uk_hi)
     V_C[in_win] = reconstruct(Vw, hi % w, Uv_hi)
+    KR = rope(K_C.reshape(n, H_kv, d), idx, theta, rope_style) if n else K_C.reshape(n, H_kv, d)
+    qR = rope(q.reshape(1, H, d), [q_pos], theta, rope_style).reshape(H, d)
+    return attend(qR, KR, V_C.reshape(n, H_kv, d))
+
+
+# ---------------------------------------------------------------------------
+# Recent window of the paper's own setting (Sec. 5.1): latent keys + quantised
+# full-rank values, with the most recent w tokens kept at half their original
+# size.  Reading taken where the paper is silent: for keys that is the rank-r_hi
+# ring of the window above (r_hi = D_kv/2); for values, whose codes take 16 bits
+# per channel uncompressed, it is the same group quantiser at 8 bits, in a ring of
+# w rows (token t in row t mod w).  One softmax runs over the union.
+# ---------------------------------------------------------------------------
+
+def sparse_attend_qv_window(q, q_pos, Kc, Uk, codes, scale, zero, Kw, Uk_hi, codes_w, scale_w, zero_w, idx, S,
+                            H_kv, theta, rope_style=0):
+    """Kc [S_max, r] with Uk [D_kv, r]; codes [S_max, D_kv], scale / zero [S_max, D_kv/32] (low-bit cache);
+    Kw [w, r_hi] with Uk_hi [D_kv, r_hi]; codes_w [w, D_kv], scale_w / zero_w [w, D_kv/32] (8-bit ring);
+    idx [n] selected tokens of a cache of S tokens.  Token t is read from ring row t mod w if S - w <= t < S,
+    else from row t of the main caches."""
+    q = np.asarray(q, dtype=np.float64)
+    H, d = q.shape
+    idx = np.asarray(idx, dtype=np.int32)
+    n = idx.shape[0]
+    w = np.asarray(Kw).shape[0]
+    in_win = (idx >= S - w) & (idx < S)
+    K_C = np.empty((n, H_kv * d))
+    V_C = np.empty((n, H_kv * d))
+    lo, hi = idx[~in_win], idx[in_win]
+    K_C[~in_win] = reconstruct(Kc, lo, Uk)
+    K_C[in_win] = reconstruct(Kw, hi % w, Uk_hi)
+    V_C[~in_win] = dequantize_values(np.asarray(codes)[lo], np.asarray(scale)[lo], np.asarray(zero)[lo])
+    V_C[in_win] = dequantize_values(np.asarray(codes_w)[hi % w], np.asarray(scale_w)[hi % w], np.asarray(zero_w)[hi % w])
     KR = rope(K_C.reshape(n, H_kv, d), idx, theta, rope_style) if n else K_C.reshape(n, H_kv, d)
     qR = rope(q.reshape(1, H, d), [q_pos], theta, rope_style).reshape(H, d)
     return attend(qR, KR, V_C.reshape(n, H_kv, d))
