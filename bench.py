@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer buffer sets (0 = workload default)")
-    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg2_rhalf,cfg4_rhalf,cfg2_qv4,cfg4_qv4,cfg2_comp,cfg2_win,cfg3a_comp,cfg3a_win,cfg4_cap2x,prefill_cfg2,prefill_cfg3b",
+    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg2_rhalf,cfg4_rhalf,cfg2_qv4,cfg4_qv4,cfg2_comp,cfg2_win,cfg3a_comp,cfg3a_win,cfg4_cap2x,cfg2_qvwin,t6_b16_s4096_12,t6w_b16_s4096_12,t6w_b16_s4096_25,prefill_cfg2,prefill_cfg3b",
                     help="other configurations reported under 'extra' (comma list, '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
@@ -78,6 +78,10 @@ class LayerSet:
                 Wn = synth.make_window(w, L, l)
                 G["Kw"], G["Vw"] = up(Wn["Kw"]), up(Wn["Vw"])
                 G["W_hi"] = self.win.pack_weights(up(Wn["Uk_hi"]), up(Wn["Uv_hi"]))
+                if w.qv_bits:   # the window's values as an 8-bit ring instead of the latent one
+                    del G["Vw"]
+                    cw, mw = synth.make_qv_window(w, l)
+                    G["Vqw"], G["Vmeta_w"] = torch.from_numpy(cw).to(dev), up(mw)
             if w.qv_bits:   # quantised full-rank value cache in place of the latent one
                 del G["Vc"]
                 codes, meta = synth.make_qv_cache(w, l, w.qv_bits)
@@ -90,6 +94,11 @@ class LayerSet:
         self.out = [torch.empty((w.B, w.H, w.d), dtype=odt, device=dev) for _ in range(n_layers)]
 
     def step(self):
+        if self.win is not None and self.w.qv_bits:
+            for G, o in zip(self.layers, self.out):
+                self.ctx.decode_step_qv_window(self.win, G["q"], G["q_pos"], G["Kc"], G["Vq"], G["Vmeta"], self.w.qv_bits,
+                                               G["W"], G["Kw"], G["Vqw"], G["Vmeta_w"], G["W_hi"], G["seq_len"], o)
+            return
         if self.win is not None:
             for G, o in zip(self.layers, self.out):
                 self.ctx.decode_step_window(self.win, G["q"], G["q_pos"], G["Kc"], G["Vc"], G["W"], G["Kw"], G["Vw"],

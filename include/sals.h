@@ -318,6 +318,41 @@ sals_status sals_decode_step_window(sals_ctx* ctx, sals_ctx* win, const void* q,
                                     const void* Vw, const void* W_hi, const int32_t* seq_len, void* out,
                                     float* scores, int32_t* idx, int32_t* n_sel, void* hip_stream);
 
+/* ---- the recent window over the paper's own cache formats (Sec. 5.1, Sec. 5.2) --------------------
+ * The paper's setting keeps latent keys and group-quantised full-rank values, and lets the most recent
+ * window of tokens keep half of its original size.  Where the paper gives no detail the format is: the
+ * window's keys are the rank-r_hi ring Kw of the calls above (r_hi = D_kv/2), the window's values the same
+ * group quantiser at 8 bits (half of a 16-bit channel) in a ring of w rows,
+ *   Vqw     [B, w, D_kv] bytes        code of channel c of token t in row t mod w, byte c
+ *   Vmeta_w [B, w, D_kv/32, 2] T      (scale, zero) of each group, scale = T((max - min) / 255)
+ * with codes decided in fp32 exactly as for 2 / 4 bits.  `win` is the window's context as above. */
+
+/* The new token into ring row seq_len[b] mod w: k~ = Uk_hi^T k_new into Kw, the 8-bit quantised v_new into
+ * Vqw / Vmeta_w.  Reads seq_len, does not advance it: call before the sals_compress_append_qv of the same
+ * token.   k_new, v_new [B, D_kv] T */
+sals_status sals_window_append_qv(sals_ctx* win, const void* k_new, const void* v_new, const void* W_hi,
+                                  void* Kw, void* Vqw, void* Vmeta_w, const int32_t* seq_len,
+                                  void* hip_stream);
+
+/* sals_sparse_attend_qv with the window: the last n_w = min(w, n_sel[b]) entries of idx[b] (the recent tokens,
+ * in the order sals_topk_select writes them) take their keys from ring rows idx mod w of Kw through W_hi and
+ * their values from the 8-bit ring, all entries before them from Kc through W and from the `bits`-bit cache
+ * Vq / Vmeta; one softmax (Eq. 5) over the union, fp32 accumulation, one rounding to T. */
+sals_status sals_sparse_attend_qv_window(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos,
+                                         const void* Kc, const void* Vq, const void* Vmeta, int bits,
+                                         const void* W, const void* Kw, const void* Vqw, const void* Vmeta_w,
+                                         const void* W_hi, const int32_t* idx, const int32_t* n_sel, void* out,
+                                         void* hip_stream);
+
+/* The paper's whole decode step in its own setting: sals_latent_scores and sals_topk_select on `ctx`
+ * (16 sink + critical + w recent tokens, Sec. 5.2), then sals_sparse_attend_qv_window.  `scores`, `idx`,
+ * `n_sel` may each be NULL. */
+sals_status sals_decode_step_qv_window(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos,
+                                       const void* Kc, const void* Vq, const void* Vmeta, int bits,
+                                       const void* W, const void* Kw, const void* Vqw, const void* Vmeta_w,
+                                       const void* W_hi, const int32_t* seq_len, void* out, float* scores,
+                                       int32_t* idx, int32_t* n_sel, void* hip_stream);
+
 /* ---- overlap score -------------------------------------------------------------------
  * The diagnostic of Sec. 3.2: the share of the dense attention mass that a selected set captures,
  *   os[b,h] = sum_{j < n_sel[b]} p[idx[b,j]] / sum_{j < seq_len[b]} p[j],

@@ -31,6 +31,7 @@ EXPORTS = (
     "sals_dense_attend",
     "sals_window_append", "sals_sparse_attend_window", "sals_decode_step_window", "sals_overlap_score",
     "sals_latent_scores_noalloc", "sals_compress_prefill",
+    "sals_window_append_qv", "sals_sparse_attend_qv_window", "sals_decode_step_qv_window",
 )
 N_KERNELS = 9
 
@@ -79,6 +80,11 @@ def load_library() -> ctypes.CDLL:
     lib.sals_window_append.argtypes = [vp, vp, vp, vp, vp, vp, i32p, vp]
     lib.sals_sparse_attend_window.argtypes = [vp, vp, vp, i32p, vp, vp, vp, vp, vp, vp, i32p, i32p, vp, vp]
     lib.sals_decode_step_window.argtypes = [vp, vp, vp, i32p, vp, vp, vp, vp, vp, vp, i32p, vp, f32p, i32p, i32p, vp]
+    lib.sals_window_append_qv.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32p, vp]
+    lib.sals_sparse_attend_qv_window.argtypes = [vp, vp, vp, i32p, vp, vp, vp, ctypes.c_int, vp, vp, vp, vp, vp, i32p,
+                                                 i32p, vp, vp]
+    lib.sals_decode_step_qv_window.argtypes = [vp, vp, vp, i32p, vp, vp, vp, ctypes.c_int, vp, vp, vp, vp, vp, i32p, vp,
+                                               f32p, i32p, i32p, vp]
     lib.sals_overlap_score.argtypes = [vp, vp, i32p, vp, i32p, i32p, i32p, f32p, vp]
     lib.sals_kernel_name.restype = ctypes.c_char_p
     lib.sals_kernel_name.argtypes = [ctypes.c_int]
@@ -262,6 +268,24 @@ class Sals:
         self._check(_lib.sals_decode_step_window(self._h, win._h, _p(q), _p(q_pos), _p(Kc), _p(Vc), _p(W), _p(Kw),
                                                  _p(Vw), _p(W_hi), _p(seq_len), _p(out), _p(scores), _p(idx),
                                                  _p(n_sel), _stream()), "sals_decode_step_window")
+
+    # ---- the window over latent keys + quantised values: keys in the ring Kw, values as 8-bit codes Vqw / Vmeta_w ----
+    def window_append_qv(self, k_new, v_new, W_hi, Kw, Vqw, Vmeta_w, seq_len):
+        """Called on the window's context, before the compress_append_qv that advances seq_len."""
+        self._check(_lib.sals_window_append_qv(self._h, _p(k_new), _p(v_new), _p(W_hi), _p(Kw), _p(Vqw), _p(Vmeta_w),
+                                               _p(seq_len), _stream()), "sals_window_append_qv")
+
+    def sparse_attend_qv_window(self, win, q, q_pos, Kc, Vq, Vmeta, bits, W, Kw, Vqw, Vmeta_w, W_hi, idx, n_sel, out):
+        self._check(_lib.sals_sparse_attend_qv_window(self._h, win._h, _p(q), _p(q_pos), _p(Kc), _p(Vq), _p(Vmeta),
+                                                      int(bits), _p(W), _p(Kw), _p(Vqw), _p(Vmeta_w), _p(W_hi), _p(idx),
+                                                      _p(n_sel), _p(out), _stream()), "sals_sparse_attend_qv_window")
+
+    def decode_step_qv_window(self, win, q, q_pos, Kc, Vq, Vmeta, bits, W, Kw, Vqw, Vmeta_w, W_hi, seq_len, out,
+                              scores=None, idx=None, n_sel=None):
+        self._check(_lib.sals_decode_step_qv_window(self._h, win._h, _p(q), _p(q_pos), _p(Kc), _p(Vq), _p(Vmeta),
+                                                    int(bits), _p(W), _p(Kw), _p(Vqw), _p(Vmeta_w), _p(W_hi),
+                                                    _p(seq_len), _p(out), _p(scores), _p(idx), _p(n_sel), _stream()),
+                    "sals_decode_step_qv_window")
 
     # ---- overlap score of a selection against dense attention over rotated full-rank keys ----
     def overlap_score(self, q, q_pos, K, seq_len, idx, n_sel, os):

@@ -18,6 +18,8 @@
 // registers; with  p*v^ = (p*zero) + (p*scale)*code  a token costs one multiply per head and one
 // fused multiply-add per (head, channel).
 #pragma once
+#include <type_traits>
+
 #include "common.hpp"
 #include "k_attend.hpp"
 
@@ -49,10 +51,11 @@ template <> struct qv_meta<bf16_t> {
 
 // One group per 32 lanes: row seq_len[b] of the quantised cache from the new token's value.
 // A sequence whose cache is full is left untouched.  grid (D/32/8, B), 256 threads.
+// ring > 0: the cache is a ring of that many rows per sequence (recent window), token t in row t mod ring.
 template <typename T, int BITS>
 __global__ __launch_bounds__(256) void qv_quantize_kernel(const T* __restrict__ v_new, unsigned char* __restrict__ Vq,
                                                           T* __restrict__ Vmeta, const int32_t* __restrict__ seq_len,
-                                                          int D, int S_max)
+                                                          int D, int S_max, int ring)
 {
     constexpr float kLevels = (float)((1 << BITS) - 1);
     constexpr int PER = 32 / BITS;  // codes per 32-bit word
@@ -74,7 +77,7 @@ __global__ __launch_bounds__(256) void qv_quantize_kernel(const T* __restrict__ 
     uint32_t w = (uint32_t)t << ((l % PER) * BITS);
 #pragma unroll
     for (int o = 1; o < PER; o <<= 1) w |= (uint32_t)__shfl_xor((int)w, o, 32);
-    const size_t tok = (size_t)b * S_max + row;
+    const size_t tok = ring > 0 ? (size_t)b * ring + row % ring : (size_t)b * S_max + row;
     if (l % PER == 0)
         *reinterpret_cast<uint32_t*>(Vq + tok * ((size_t)D * BITS / 8) + (size_t)(gi * kQvGroup + l) * BITS / 8) = w;
     if (l == 0) qv_meta<T>::store(Vmeta + (tok * n_groups + gi) * 2, scale, mn);
@@ -90,6 +93,14 @@ struct QvArgs {
     float* part;   // [n_tr, B, H, 128] fp32 partial outputs; unused when n_tr == 1
     void* out;     // [B, H, 128] T
     int n_parts, B, S_max, H, H_kv, k_tot, lk, tok_per_wg, n_tr;
+    // recent window (kernels with WIN): the last n_sel - n_lo[b] selected tokens are read from a ring of `ring` rows
+    // per sequence with 8-bit codes (token t in row t mod ring); their logits are those of the window's logits pass
+    const unsigned char* Vq_w;
+    const void* Vmeta_w;
+    const float* logits_w;   // [B, H, lk_w], slot j - n_lo[b]
+    const int32_t* n_lo;     // [B] tokens of the low-precision pass
+    int lk_w, ring;
+    int part0, n_tr_all;     // partial outputs: this launch writes ranges part0 .. of n_tr_all (n_tr_all == 1: straight to out)
 };
 
 constexpr int kQvTpt = kHeadDim / kQvCh;  // threads per token: 8
@@ -100,11 +111,9 @@ constexpr int kQvSlots = 256 / kQvTpt;    // tokens in progress side by side: 32
 // in slot order.  1-D grid of B * n_tr * H_kv workgroups; ids are dealt round-robin to the XCDs and
 // mapped so that each XCD gets a contiguous run of the work list (KV head fastest): the heads of a
 // token range read neighbouring pieces of the same cache rows and meet in one L2.
-template <typename T, int BITS, int GMAX>
+template <typename T, int BITS, int GMAX, bool WIN = false>
 __global__ __launch_bounds__(256) void attend_qv_kernel(QvArgs a)
 {
-    constexpr int CB = kQvCh * BITS / 8;  // code bytes per thread and token: 8 or 4
-    constexpr int NW = CB / 4;
     constexpr int UN = GMAX > 4 ? 4 : 8;  // tokens whose loads are in flight together, per thread
     __shared__ int sRow[kQvMaxTok];
     __shared__ float2 sMZ[kMaxGroup];
@@ -131,6 +140,7 @@ __global__ __launch_bounds__(256) void attend_qv_kernel(QvArgs a)
     constexpr unsigned long long kNeutral = 0x00000000ff800000ull;  // (-inf, 0)
     const unsigned long long st0 = (sm < G && sub < a.n_parts) ? *reinterpret_cast<const unsigned long long*>(sp + sub) : kNeutral;
     const int n_v = ld_uniform_i32(a.n_sel + b);  // (vector memory path: in flight with the loads around)
+    const int nlo_v = WIN ? ld_uniform_i32(a.n_lo + b) : 0;
     int iv[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -141,13 +151,19 @@ __global__ __launch_bounds__(256) void attend_qv_kernel(QvArgs a)
     const int n = wave_uniform(n_v);
     const int j_begin = min(n, tr * a.tok_per_wg), j_end = min(n, j_begin + a.tok_per_wg);
     const int ntok = j_end - j_begin;
+    // tokens [0, nlow) of the range come from the main cache, [nlow, ntok) from the window's ring
+    const int nlow = WIN ? min(max(wave_uniform(nlo_v) - j_begin, 0), ntok) : ntok;
+    auto row_of = [&](int t, int token) {
+        if (WIN && t >= nlow) return max(token, 0) % a.ring;
+        return min(max(token, 0), a.S_max - 1);
+    };
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int t = tid + 256 * i;
-        if (t < ntok) sRow[t] = min(max(iv[i], 0), a.S_max - 1);
+        if (t < ntok) sRow[t] = row_of(t, iv[i]);
     }
     for (int t = tid + 1024; t < ntok; t += 256)  // long ranges: the rest, one load per round
-        sRow[t] = min(max(ib[tr * a.tok_per_wg + t], 0), a.S_max - 1);
+        sRow[t] = row_of(t, ib[tr * a.tok_per_wg + t]);
     {   // softmax maximum and normaliser per query head: the head's tile statistics merged in a fixed order
         float2 st = make_float2(__uint_as_float((uint32_t)st0), __uint_as_float((uint32_t)(st0 >> 32)));
         if (sm < G)
@@ -171,46 +187,64 @@ __global__ __launch_bounds__(256) void attend_qv_kernel(QvArgs a)
     }
 
     const int n_groups = a.H_kv * (kHeadDim / kQvGroup);
-    const size_t row_bytes = (size_t)a.H_kv * kHeadDim * BITS / 8;
-    const unsigned char* vq = a.Vq + (size_t)b * a.S_max * row_bytes + (size_t)(kvh * kHeadDim + c0) * BITS / 8;
-    const T* vm = static_cast<const T*>(a.Vmeta) + ((size_t)b * a.S_max * n_groups + kvh * (kHeadDim / kQvGroup) + c0 / kQvGroup) * 2;
-    const float* lg = a.logits + ((size_t)b * H + (size_t)kvh * G) * a.lk + j_begin;
-
-    for (int t0 = slot; t0 < ntok; t0 += kQvSlots * UN) {
-        uint32_t cw[UN][NW];
-        float2 sz[UN];
-        float x[UN][GMAX];
+    // One pass over tokens [t_lo, t_hi) of the range, whose rows lie in a cache of `rows` rows per sequence with
+    // NBITS-bit codes; lgp points at the logit of token t_lo for the group's first query head.
+    auto pass = [&](auto nbits_tag, const unsigned char* codes, const void* meta, int rows, const float* lgp, int lk,
+                    int t_lo, int t_hi) {
+        constexpr int NBITS = decltype(nbits_tag)::value;
+        constexpr int CB = kQvCh * NBITS / 8;  // code bytes per thread and token: 16, 8 or 4
+        constexpr int NW = CB / 4;
+        const size_t row_bytes = (size_t)a.H_kv * kHeadDim * NBITS / 8;
+        const unsigned char* vq = codes + (size_t)b * rows * row_bytes + (size_t)(kvh * kHeadDim + c0) * NBITS / 8;
+        const T* vm = static_cast<const T*>(meta) + ((size_t)b * rows * n_groups + kvh * (kHeadDim / kQvGroup) + c0 / kQvGroup) * 2;
+        for (int t0 = t_lo + slot; t0 < t_hi; t0 += kQvSlots * UN) {
+            uint32_t cw[UN][NW];
+            float2 sz[UN];
+            float x[UN][GMAX];
 #pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            const int t = t0 + i * kQvSlots;
-            const int tc = min(t, ntok - 1);  // a token past the range re-reads the last row with weight zero
-            const size_t row = (size_t)sRow[tc];
-            if (NW == 2) {
-                const uint2 w2 = *reinterpret_cast<const uint2*>(vq + row * row_bytes);
-                cw[i][0] = w2.x; cw[i][NW - 1] = w2.y;
-            } else {
-                cw[i][0] = *reinterpret_cast<const uint32_t*>(vq + row * row_bytes);
+            for (int i = 0; i < UN; ++i) {
+                const int t = t0 + i * kQvSlots;
+                const int tc = min(t, t_hi - 1);  // a token past the range re-reads the last row with weight zero
+                const size_t row = (size_t)sRow[tc];
+                if (NW == 4) {
+                    const u32x4 w4 = *reinterpret_cast<const u32x4*>(vq + row * row_bytes);
+                    cw[i][0] = w4.x; cw[i][1 % NW] = w4.y; cw[i][2 % NW] = w4.z; cw[i][3 % NW] = w4.w;
+                } else if (NW == 2) {
+                    const uint2 w2 = *reinterpret_cast<const uint2*>(vq + row * row_bytes);
+                    cw[i][0] = w2.x; cw[i][NW - 1] = w2.y;
+                } else {
+                    cw[i][0] = *reinterpret_cast<const uint32_t*>(vq + row * row_bytes);
+                }
+                sz[i] = qv_meta<T>::load(vm + row * n_groups * 2);
+#pragma unroll
+                for (int m = 0; m < GMAX; ++m) x[i][m] = (m < G && t < t_hi) ? lgp[(size_t)m * lk + (tc - t_lo)] : -INFINITY;
             }
-            sz[i] = qv_meta<T>::load(vm + row * n_groups * 2);
 #pragma unroll
-            for (int m = 0; m < GMAX; ++m) x[i][m] = (m < G && t < ntok) ? lg[(size_t)m * a.lk + tc] : -INFINITY;
-        }
+            for (int i = 0; i < UN; ++i) {
+                float cf[kQvCh];
 #pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            float cf[kQvCh];
+                for (int c = 0; c < kQvCh; ++c)
+                    cf[c] = (float)((cw[i][(c * NBITS) / 32] >> ((c * NBITS) % 32)) & ((1u << NBITS) - 1u));
 #pragma unroll
-            for (int c = 0; c < kQvCh; ++c)
-                cf[c] = (float)((cw[i][(c * BITS) / 32] >> ((c * BITS) % 32)) & ((1u << BITS) - 1u));
+                for (int m = 0; m < GMAX; ++m) {
+                    if (m < G) {  // uniform
+                        const float p = __expf(x[i][m] - mz[m].x) * mz[m].y;  // exp(-inf) = 0 masks the padding
+                        const float ps = p * sz[i].x;
+                        bias[m] = fmaf(p, sz[i].y, bias[m]);
 #pragma unroll
-            for (int m = 0; m < GMAX; ++m) {
-                if (m < G) {  // uniform
-                    const float p = __expf(x[i][m] - mz[m].x) * mz[m].y;  // exp(-inf) = 0 masks the padding
-                    const float ps = p * sz[i].x;
-                    bias[m] = fmaf(p, sz[i].y, bias[m]);
-#pragma unroll
-                    for (int c = 0; c < kQvCh; ++c) acc[m][c] = fmaf(ps, cf[c], acc[m][c]);
+                        for (int c = 0; c < kQvCh; ++c) acc[m][c] = fmaf(ps, cf[c], acc[m][c]);
+                    }
                 }
             }
+        }
+    };
+    pass(std::integral_constant<int, BITS>{}, a.Vq, a.Vmeta, a.S_max, a.logits + ((size_t)b * H + (size_t)kvh * G) * a.lk + j_begin,
+         a.lk, 0, nlow);
+    if constexpr (WIN) {
+        if (nlow < ntok) {  // uniform: the window's tokens, slot j - n_lo of the window's logits
+            const int nlo = wave_uniform(nlo_v);
+            pass(std::integral_constant<int, 8>{}, a.Vq_w, a.Vmeta_w, a.ring,
+                 a.logits_w + ((size_t)b * H + (size_t)kvh * G) * a.lk_w + (j_begin + nlow - nlo), a.lk_w, nlow, ntok);
         }
     }
 #pragma unroll
@@ -232,7 +266,7 @@ __global__ __launch_bounds__(256) void attend_qv_kernel(QvArgs a)
 #pragma unroll 8
                 for (int sl = 0; sl < kQvSlots; ++sl) s += red[sl * kQvTpt + uu][cc];
                 const int h = kvh * G + m;
-                if (a.n_tr > 1) a.part[(((size_t)tr * a.B + b) * H + h) * kHeadDim + tid] = s;
+                if (a.n_tr_all > 1) a.part[(((size_t)(a.part0 + tr) * a.B + b) * H + h) * kHeadDim + tid] = s;
                 else elem<T>::store(static_cast<T*>(a.out) + ((size_t)b * H + h) * kHeadDim + tid, s);
             }
         }

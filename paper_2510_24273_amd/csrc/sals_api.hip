@@ -385,7 +385,13 @@ sals_status launch_dense(const sals_ctx* c, const void* q, const int32_t* q_pos,
     return launch_status();
 }
 
-struct QvCache { const void* codes; const void* meta; int bits; };  // quantised full-rank value cache
+// quantised full-rank value cache; codes_w != nullptr: plus the recent window's ring of 8-bit rows (the last
+// n_sel - n_lo[b] selected tokens), whose logits a second logits pass left in logits_w [B, H, lk_w]
+struct QvCache {
+    const void* codes; const void* meta; int bits;
+    const void* codes_w = nullptr; const void* meta_w = nullptr; const float* logits_w = nullptr;
+    const int32_t* n_lo = nullptr; int lk_w = 0, ring = 0;
+};
 
 // qv == nullptr: latent value cache Vc, value sum in latent space and output projection through U_v.
 // Otherwise: values are the de-quantised rows of the quantised cache (Vc unused).
@@ -542,12 +548,21 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
     }
     if (qv != nullptr) {
         ProfScope ps(c, SALS_K_ATTEND_QV, st);
-        QvArgs a{static_cast<const unsigned char*>(qv->codes), qv->meta, idx, n_sel, logits, stats_all,
-                 reinterpret_cast<float*>(c->ws + L.qv_part), out, stats_stride, d.B, d.S_max, d.H_q, d.H_kv, k_tot, L.lk,
-                 L.qv_tok_per_wg, L.qv_ntr};
+        QvArgs a{};
+        a.Vq = static_cast<const unsigned char*>(qv->codes); a.Vmeta = qv->meta; a.idx = idx; a.n_sel = n_sel;
+        a.logits = logits; a.stats = stats_all; a.part = reinterpret_cast<float*>(c->ws + L.qv_part); a.out = out;
+        a.n_parts = stats_stride; a.B = d.B; a.S_max = d.S_max; a.H = d.H_q; a.H_kv = d.H_kv; a.k_tot = k_tot; a.lk = L.lk;
+        a.tok_per_wg = L.qv_tok_per_wg; a.n_tr = L.qv_ntr; a.part0 = 0; a.n_tr_all = L.qv_ntr;
+        a.Vq_w = static_cast<const unsigned char*>(qv->codes_w); a.Vmeta_w = qv->meta_w; a.logits_w = qv->logits_w;
+        a.n_lo = qv->n_lo; a.lk_w = qv->lk_w; a.ring = qv->ring;
+        const bool win = qv->codes_w != nullptr;
         const dim3 grid(L.qv_ntr * d.H_kv * d.B);
         const int G = d.H_q / d.H_kv;
-#define SALS_QV(BITS, GMAX) hipLaunchKernelGGL((attend_qv_kernel<T, BITS, GMAX>), grid, dim3(256), 0, st, a)
+#define SALS_QV(BITS, GMAX)                                                                             \
+    do {                                                                                                \
+        if (win) hipLaunchKernelGGL((attend_qv_kernel<T, BITS, GMAX, true>), grid, dim3(256), 0, st, a); \
+        else hipLaunchKernelGGL((attend_qv_kernel<T, BITS, GMAX, false>), grid, dim3(256), 0, st, a);   \
+    } while (0)
 #define SALS_QV_G(BITS)                                                                                 \
     do {                                                                                                \
         if (G <= 1) SALS_QV(BITS, 1); else if (G <= 2) SALS_QV(BITS, 2);                                \
@@ -897,7 +912,7 @@ sals_status sals_compress_append_qv(sals_ctx* ctx, const void* k_new, const void
     unsigned char* codes = static_cast<unsigned char*>(Vq);
 #define SALS_QUANT(T, BITS)                                                                                   \
     hipLaunchKernelGGL((qv_quantize_kernel<T, BITS>), grid, dim3(256), 0, st, static_cast<const T*>(v_new), codes, \
-                       static_cast<T*>(Vmeta), seq_len, D, d.S_max)
+                       static_cast<T*>(Vmeta), seq_len, D, d.S_max, 0)
     if (bf) { if (bits == 4) SALS_QUANT(bf16_t, 4); else SALS_QUANT(bf16_t, 2); }
     else    { if (bits == 4) SALS_QUANT(float, 4); else SALS_QUANT(float, 2); }
 #undef SALS_QUANT
@@ -1069,6 +1084,108 @@ sals_status sals_decode_step_window(sals_ctx* ctx, sals_ctx* win, const void* q,
     s = launch_topk(ctx, scores, seq_len, idx, n_sel, st, window_lists(ctx, win));
     if (s != SALS_OK) return s;
     return window_attend(ctx, win, q, q_pos, Kc, Vc, W, Kw, Vw, W_hi, idx, n_sel, out, st, true);
+}
+
+// ---- recent window of the quantised value path: keys in the rank-r_hi ring, values as 8-bit codes ----
+
+sals_status sals_window_append_qv(sals_ctx* win, const void* k_new, const void* v_new, const void* W_hi, void* Kw,
+                                  void* Vqw, void* Vmeta_w, const int32_t* seq_len, void* hip_stream)
+{
+    if (!win || bad(k_new) || bad(v_new) || bad(W_hi) || bad(Kw) || bad(Vqw) || bad(Vmeta_w) || !seq_len)
+        return SALS_ERR_INVALID_ARG;
+    if (win->d.n_sink != 0 || win->d.n_recent != 0) return SALS_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    int32_t* sl = const_cast<int32_t*>(seq_len);  // read only: no length is advanced here
+    const sals_desc& d = win->d;
+    const int ring = d.top_k;
+    const bool bf = d.dtype == SALS_BF16;
+    sals_status s = bf ? launch_project<bf16_t, false>(win, W_hi, k_new, nullptr, Kw, nullptr, sl, st, false, ring)
+                       : launch_project<float, false>(win, W_hi, k_new, nullptr, Kw, nullptr, sl, st, false, ring);
+    if (s != SALS_OK) return s;
+    const int D = d.H_kv * d.d;
+    const dim3 grid(ceil_div(D / kQvGroup, 8), d.B);
+    if (bf)
+        hipLaunchKernelGGL((qv_quantize_kernel<bf16_t, 8>), grid, dim3(256), 0, st, static_cast<const bf16_t*>(v_new),
+                           static_cast<unsigned char*>(Vqw), static_cast<bf16_t*>(Vmeta_w), seq_len, D, d.S_max, ring);
+    else
+        hipLaunchKernelGGL((qv_quantize_kernel<float, 8>), grid, dim3(256), 0, st, static_cast<const float*>(v_new),
+                           static_cast<unsigned char*>(Vqw), static_cast<float*>(Vmeta_w), seq_len, D, d.S_max, ring);
+    return launch_status();
+}
+
+namespace {
+sals_status window_attend_qv(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos, const void* Kc,
+                             const void* Vq, const void* Vmeta, int bits, const void* W, const void* Kw, const void* Vqw,
+                             const void* Vmeta_w, const void* W_hi, const int32_t* idx, const int32_t* n_sel, void* out,
+                             hipStream_t st, bool lists_ready)
+{
+    const sals_desc& d = ctx->d;
+    const int k_tot = d.top_k + d.n_sink + d.n_recent, w = win->d.top_k;
+    const WindowLists wl = window_lists(ctx, win);
+    if (!lists_ready) {
+        hipLaunchKernelGGL(window_split_kernel, dim3(d.B), dim3(256), 0, st, idx, n_sel, k_tot, w, wl.idx_hi, wl.n_lo, wl.n_hi);
+        if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+    }
+    // two logits passes (low-rank cache, ring) with their tile statistics side by side, then one pass over the values
+    // of the whole selection: the tokens before the window from the low-bit cache, the window's from its 8-bit ring
+    const bool bf = d.dtype == SALS_BF16;
+    const LogitsPlan p_lo = ctx->plan, p_hi = win->plan;
+    if (p_lo.n_parts + p_hi.n_parts > ctx->L.max_parts) return SALS_ERR_UNSUPPORTED;
+    float2* shared = reinterpret_cast<float2*>(ctx->ws + ctx->L.stats);
+    const int n_all = p_lo.n_parts + p_hi.n_parts;
+    const StatsLink l_lo{shared, n_all, 0}, l_hi{shared, n_all, p_lo.n_parts};
+    sals_status s = bf ? launch_attend<bf16_t>(ctx, q, q_pos, Kc, nullptr, W, idx, wl.n_lo, nullptr, st, nullptr, 0, kPhaseLogits, &l_lo)
+                       : launch_attend<float>(ctx, q, q_pos, Kc, nullptr, W, idx, wl.n_lo, nullptr, st, nullptr, 0, kPhaseLogits, &l_lo);
+    if (s != SALS_OK) return s;
+    s = bf ? launch_attend<bf16_t>(win, q, q_pos, Kw, nullptr, W_hi, wl.idx_hi, wl.n_hi, nullptr, st, nullptr, w, kPhaseLogits, &l_hi)
+           : launch_attend<float>(win, q, q_pos, Kw, nullptr, W_hi, wl.idx_hi, wl.n_hi, nullptr, st, nullptr, w, kPhaseLogits, &l_hi);
+    if (s != SALS_OK) return s;
+    QvCache qv{Vq, Vmeta, bits};
+    qv.codes_w = Vqw; qv.meta_w = Vmeta_w;
+    qv.logits_w = reinterpret_cast<const float*>(win->ws + win->L.logits);
+    qv.n_lo = wl.n_lo; qv.lk_w = win->L.lk; qv.ring = w;
+    return bf ? launch_attend<bf16_t>(ctx, q, q_pos, Kc, nullptr, W, idx, n_sel, out, st, &qv, 0, 0, &l_lo)
+              : launch_attend<float>(ctx, q, q_pos, Kc, nullptr, W, idx, n_sel, out, st, &qv, 0, 0, &l_lo);
+}
+}  // namespace
+
+sals_status sals_sparse_attend_qv_window(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos,
+                                         const void* Kc, const void* Vq, const void* Vmeta, int bits, const void* W,
+                                         const void* Kw, const void* Vqw, const void* Vmeta_w, const void* W_hi,
+                                         const int32_t* idx, const int32_t* n_sel, void* out, void* hip_stream)
+{
+    sals_status s = window_pair_ok(ctx, win);
+    if (s != SALS_OK) return s;
+    if (bad(q) || !q_pos || bad(Kc) || bad(Vq) || bad(Vmeta) || bad(W) || bad(Kw) || bad(Vqw) || bad(Vmeta_w) || bad(W_hi) ||
+        !idx || !n_sel || bad(out))
+        return SALS_ERR_INVALID_ARG;
+    if (bits != 2 && bits != 4) return SALS_ERR_UNSUPPORTED;
+    return window_attend_qv(ctx, win, q, q_pos, Kc, Vq, Vmeta, bits, W, Kw, Vqw, Vmeta_w, W_hi, idx, n_sel, out,
+                            static_cast<hipStream_t>(hip_stream), false);
+}
+
+sals_status sals_decode_step_qv_window(sals_ctx* ctx, sals_ctx* win, const void* q, const int32_t* q_pos,
+                                       const void* Kc, const void* Vq, const void* Vmeta, int bits, const void* W,
+                                       const void* Kw, const void* Vqw, const void* Vmeta_w, const void* W_hi,
+                                       const int32_t* seq_len, void* out, float* scores, int32_t* idx, int32_t* n_sel,
+                                       void* hip_stream)
+{
+    sals_status s = window_pair_ok(ctx, win);
+    if (s != SALS_OK) return s;
+    if (bad(q) || !q_pos || bad(Kc) || bad(Vq) || bad(Vmeta) || bad(W) || bad(Kw) || bad(Vqw) || bad(Vmeta_w) || bad(W_hi) ||
+        !seq_len || bad(out))
+        return SALS_ERR_INVALID_ARG;
+    if (bits != 2 && bits != 4) return SALS_ERR_UNSUPPORTED;
+    if (scores && !aligned16(scores)) return SALS_ERR_INVALID_ARG;
+    if (!scores) scores = reinterpret_cast<float*>(ctx->ws + ctx->L.scores);
+    if (!idx) idx = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.idx);
+    if (!n_sel) n_sel = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_sel);
+    s = sals_latent_scores(ctx, q, W, Kc, seq_len, scores, hip_stream);
+    if (s != SALS_OK) return s;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    s = launch_topk(ctx, scores, seq_len, idx, n_sel, st, window_lists(ctx, win));
+    if (s != SALS_OK) return s;
+    return window_attend_qv(ctx, win, q, q_pos, Kc, Vq, Vmeta, bits, W, Kw, Vqw, Vmeta_w, W_hi, idx, n_sel, out, st, true);
 }
 
 // ---- overlap score ----------------------------------------------------------------------------------

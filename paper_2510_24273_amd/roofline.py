@@ -33,7 +33,10 @@ def stage_bytes(w, seq_len=None) -> dict:
         else w.B * n_sel * (w.D_kv * w.qv_bits // 8 + w.D_kv // 32 * 2 * e),
         "small": small,
         # high-precision recent window: ring rows of both caches for the recent tokens + the window's projectors
-        "window": (2 * w.B * min(S, w.n_recent) * w.r_hi * e + 2 * w.r_hi * w.D_kv * e) if getattr(w, "r_hi", 0) else 0,
+        # (with the quantised value path the window's values are 8-bit rows and only the key projector is read)
+        "window": 0 if not getattr(w, "r_hi", 0) else
+        (2 * w.B * min(S, w.n_recent) * w.r_hi * e + 2 * w.r_hi * w.D_kv * e) if not getattr(w, "qv_bits", 0) else
+        (w.B * min(S, w.n_recent) * (w.r_hi * e + w.D_kv + w.D_kv // 32 * 2 * e) + w.r_hi * w.D_kv * e),
     }
 
 

@@ -131,6 +131,15 @@ for _B in (8, 16):
 VARIANTS["cfg4_cap2x"] = replace(CONFIGS["cfg4"], name="cfg4_long_B4_S32768_capacity65536_r640_k2048", S=65536, fill=0.5)
 
 
+# The same table shapes with the paper's mixed precision (Sec. 5.1): the 64 recent tokens in the window formats,
+# keys at rank D_kv/2 and values at 8 bits; and the LLaMA2 composition at the B = 1 shape in the 25 % setting.
+for _name in [n for n in VARIANTS if n.startswith("t6_")]:
+    _w = VARIANTS[_name]
+    VARIANTS["t6w_" + _name[3:]] = replace(_w, name=_w.name + "_win64_rhi2048_8bit", r_hi=2048)
+VARIANTS["cfg2_qvwin"] = replace(CONFIGS["cfg2"], name="cfg2_llama2_7b_B1_S4096_r1024_rscore512_sink16_crit432_win64_rhi2048_qvalue4bit",
+                                 r=1024, r_score=512, top_k=432, n_sink=16, n_recent=64, r_hi=2048, qv_bits=4)
+
+
 def lookup(name: str) -> Workload:
     """A measured configuration or one of its variants, by short name."""
     return CONFIGS[name] if name in CONFIGS else VARIANTS[name]
@@ -277,6 +286,18 @@ def make_qv_cache(w: Workload, layer: int, bits: int):
     zero = -2.0 + 0.5 * rng.standard_normal((w.B, w.S, ng), dtype=np.float32)
     meta = store(np.stack([scale, zero], axis=-1), w.dtype)
     return codes, meta
+
+
+def make_qv_window(w: Workload, layer: int = 0):
+    """The 8-bit value ring of the recent window, made directly in its stored form like make_qv_cache:
+    code bytes [B, n_recent, D_kv] uniformly random, (scale, zero) [B, n_recent, D_kv/32, 2] in the storage type with
+    scale = |N(0,1)| * 4/255 + a small floor and zero = -2 + 0.5 N(0,1)."""
+    rng = np.random.default_rng(seed_of(w, layer, 89))
+    codes = rng.integers(0, 256, size=(w.B, w.n_recent, w.D_kv), dtype=np.uint8)
+    ng = w.D_kv // QV_GROUP
+    scale = (np.abs(rng.standard_normal((w.B, w.n_recent, ng), dtype=np.float32)) + 0.05) * (4.0 / 255.0)
+    zero = -2.0 + 0.5 * rng.standard_normal((w.B, w.n_recent, ng), dtype=np.float32)
+    return codes, store(np.stack([scale, zero], axis=-1), w.dtype)
 
 
 # ---- dense baseline: a full-rank cache as a dense model keeps it ------------------------
