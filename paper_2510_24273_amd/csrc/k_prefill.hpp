@@ -5,9 +5,9 @@
 // A plain GEMM on the matrix cores, [tokens x D_kv] . [D_kv x r], both operands read along their
 // contiguous axis: the token rows as they lie in memory and the TRANSPOSED projector U^T [r x D_kv]
 // (section 0 / 1 of the packed weights, the same rows the one-token projection reads).  One workgroup
-// owns 256 tokens x NL latent coordinates of one sequence and one projection; its eight waves are
-// 4 token groups x 2 latent groups (NL = 128) or 8 token groups (NL = 64), a wave tile being 64 tokens
-// x 64 latent coordinates (NL = 128) or 32 x 64.  Both operand tiles walk the D axis in 64-byte steps
+// owns TOK tokens x NL latent coordinates of one sequence and one projection; its eight waves are
+// 4 token groups x 2 latent groups (NL = 128) or 8 token groups (NL = 64), a wave tile being TOK/4 (TOK/8) tokens
+// x 64 latent coordinates.  TOK = 256, or 128 when the larger tile would leave most of the chip without a workgroup.  Both operand tiles walk the D axis in 64-byte steps
 // through three swizzled LDS stages with the software pipeline of the logits kernel (fragments of the
 // next half step are read under the MFMAs of the current one; the step after next moves from registers
 // to the third stage).  fp32 accumulation, one rounding to the storage type at the store, so a row
@@ -19,9 +19,8 @@
 
 namespace sals {
 
-constexpr int kPfTok = 256;      // tokens per workgroup
 constexpr int kPfThreads = 512;
-constexpr size_t prefill_lds_bytes(int nl) { return 3 * (size_t)(kPfTok + nl) * kLgStep; }
+constexpr size_t prefill_lds_bytes(int tok, int nl) { return 3 * (size_t)(tok + nl) * kLgStep; }
 
 struct PrefillArgs {
     const void* X[2];        // new keys / values [B, n_tok, D]
@@ -32,10 +31,11 @@ struct PrefillArgs {
     int n_tok, D, r, S_max, B, nproj;
 };
 
-template <typename T, int NL>
+template <typename T, int TOK, int NL>
 __global__ __launch_bounds__(kPfThreads, 2) void prefill_compress_kernel(PrefillArgs a)
 {
-    static_assert(NL == 128 || NL == 64, "latent tile");
+    static_assert((NL == 128 || NL == 64) && (TOK == 256 || (TOK == 128 && NL == 128)), "tile");
+    constexpr int kPfTok = TOK;
     constexpr int ES = (int)sizeof(T);
     constexpr int WN = NL / 64;                 // latent groups of 64 among the waves
     constexpr int WM = 8 / WN;                  // token groups

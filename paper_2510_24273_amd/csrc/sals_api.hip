@@ -308,12 +308,13 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
     return launch_status();
 }
 
-// rows per workgroup of the score kernel: a multiple of 16 giving roughly 1024 workgroups, 16..128 rows
-// (measured optimum)
+// rows per workgroup of the score kernel: a multiple of 16 giving roughly 1024 workgroups, 16..64 rows
+// (measured optimum; the first 16 rows of a workgroup are requested before the sequence length is known, so
+// shorter ranges would pay more for the empty part of a cache)
 int plan_score_rows(const sals_desc& d)
 {
     long long total_rows = (long long)d.B * d.S_max;
-    int rows = (int)std::min<long long>(128, std::max<long long>(16, total_rows / 1024));
+    int rows = (int)std::min<long long>(64, std::max<long long>(16, total_rows / 1024));
     if (const char* e = std::getenv("SALS_TUNE_SCORE_ROWS")) rows = std::max(16, std::min(1 << 16, std::atoi(e)));  // tuning aid
     return ceil_div(rows, kScoreRowsPerIter) * kScoreRowsPerIter;
 }
@@ -767,21 +768,28 @@ sals_status sals_compress_prefill(sals_ctx* ctx, const void* k_new, const void* 
     for (int p = 0; p < 2; ++p)
         a.UT[p] = bf ? static_cast<const void*>(w_section<bf16_t>(ctx, W, p)) : static_cast<const void*>(w_section<float>(ctx, W, p));
     const int nl = d.r % 128 == 0 ? 128 : 64;
-    const dim3 grid(ceil_div(n_tok, kPfTok), d.r / nl, d.B * 2);
-    const size_t lds = prefill_lds_bytes(nl);
-#define SALS_PREFILL(T, NLT)                                                                                      \
+    // 256-token tiles unless they would fill less than three quarters of the chip's 512 workgroup slots
+    const int tok = (nl == 128 && (long long)ceil_div(n_tok, 256) * (d.r / nl) * d.B * 2 < 384) ? 128 : 256;
+    const dim3 grid(ceil_div(n_tok, tok), d.r / nl, d.B * 2);
+    const size_t lds = prefill_lds_bytes(tok, nl);
+#define SALS_PREFILL(T, TOKT, NLT)                                                                                \
     do {                                                                                                          \
-        auto kern = prefill_compress_kernel<T, NLT>;                                                              \
+        auto kern = prefill_compress_kernel<T, TOKT, NLT>;                                                        \
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,  \
                                 (int)lds) != hipSuccess)                                                          \
             return SALS_ERR_HIP;                                                                                  \
         hipLaunchKernelGGL(kern, grid, dim3(kPfThreads), lds, st, a);                                             \
     } while (0)
+#define SALS_PREFILL_T(T)                                                                                         \
+    do {                                                                                                          \
+        if (nl == 64) SALS_PREFILL(T, 256, 64); else if (tok == 128) SALS_PREFILL(T, 128, 128);                   \
+        else SALS_PREFILL(T, 256, 128);                                                                           \
+    } while (0)
     {
         ProfScope ps(ctx, SALS_K_PREFILL, st);
-        if (bf) { if (nl == 128) SALS_PREFILL(bf16_t, 128); else SALS_PREFILL(bf16_t, 64); }
-        else    { if (nl == 128) SALS_PREFILL(float, 128); else SALS_PREFILL(float, 64); }
+        if (bf) SALS_PREFILL_T(bf16_t); else SALS_PREFILL_T(float);
     }
+#undef SALS_PREFILL_T
 #undef SALS_PREFILL
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     hipLaunchKernelGGL(advance_seq_len_kernel, dim3(ceil_div(d.B, 128)), dim3(128), 0, st, seq_len, n_new, n_tok, d.B, d.S_max);

@@ -77,6 +77,12 @@ def test_prefill_latent_tiles_of_128_and_gqa(oracle):
     _prefill_case(oracle, w, 290, [3], None, "r=640")
 
 
+def test_prefill_large_grid_takes_the_256_token_tiles(oracle):
+    """Enough (token tile, latent tile, sequence) items for the 256 x 128 tile (smaller grids take 128 x 128)."""
+    w = synth.shrink(SMALL, B=4, S=2600, r=640)
+    _prefill_case(oracle, w, 2560, [0, 40, 0, 13], [2560, 2560, 2047, 2305], "256x128 tiles")
+
+
 def test_prefill_then_decode_matches_token_by_token_append(oracle):
     """A prompt compressed in one call, then a decode step on the resulting cache: every stage against the oracle,
     and the cache rows against the one-token append of the same tokens (same values up to one ulp)."""
