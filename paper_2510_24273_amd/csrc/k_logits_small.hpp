@@ -20,6 +20,7 @@
 #include "common.hpp"
 #include "k_attend.hpp"
 #include "k_logits.hpp"
+#include "k_topk.hpp"
 
 namespace sals {
 
@@ -30,7 +31,20 @@ constexpr int kLsStepBytes = (kHeadDim + kLsTok) * kLgChunk;  // U_k panel + gat
 constexpr int kLsIterBytes = 2 * kLsStepBytes;               // two steps per iteration
 constexpr size_t kLsLds = 2 * (size_t)kLsIterBytes;          // double buffered: 96 KB
 
-template <typename T, int NST>
+// FUSED: the kernel also selects.  With one short sequence the selection kernel is a launch of its own that costs more
+// than its work (a dependent launch is worth about 2.3 us, the kernel 4.4 us at 4096 tokens), so here every workgroup
+// of a sequence repeats the selection itself from the scores (S_max <= 4096: eight keys per thread, in LDS that the
+// stage buffers only need later) while its first U_k steps are in flight, and takes its tile from the list; the
+// workgroups of KV head 0 write the list and the count to `idx` / `n_sel` for the stages that follow.  The list is the
+// one topk_kernel would have written, entry for entry.
+struct FusedSelect {
+    const float* scores;      // [B, S_max]
+    const int32_t* seq_len;   // [B]
+    int top_k, n_sink, n_recent;
+};
+constexpr int kLsFusedMaxS = 4096, kLsFusedMaxK = 1024;
+
+template <typename T, int NST, bool FUSED = false>
 __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     // (what the workgroup's first loads need comes first: those 14 words arrive preloaded in scalar registers)
     const int32_t* __restrict__ idx, const int32_t* __restrict__ n_sel, const T* __restrict__ UkP,
@@ -39,7 +53,7 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     const float2* __restrict__ rope, InvFreq inv,
     float* __restrict__ logits, float2* __restrict__ stats, int S_max,
     int lk, int style, float scale, int ring,
-    float* __restrict__ plogits, int stats_stride)
+    float* __restrict__ plogits, int stats_stride, FusedSelect fs)
 {
     constexpr int ES = (int)sizeof(T);
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -77,8 +91,12 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
     const int my_slot = tok0 + prow;
     const int e_slot = tok0 + tb * 32 + l32;  // token this lane finishes in the epilogue
     const int32_t* ib = idx + (size_t)b * k_tot;
-    const int idx_my = ib[min(my_slot, k_tot - 1)], idx_e = ib[min(e_slot, k_tot - 1)], idx_0 = ib[0];
-    const int n_v = ld_uniform_i32(n_sel + b), qpos_v = ld_uniform_i32(q_pos + b);  // in flight with the loads around
+    int idx_my = 0, idx_e = 0, idx_0 = 0, n_v = 0;
+    if constexpr (!FUSED) {
+        idx_my = ib[min(my_slot, k_tot - 1)]; idx_e = ib[min(e_slot, k_tot - 1)]; idx_0 = ib[0];
+        n_v = ld_uniform_i32(n_sel + b);
+    }
+    const int qpos_v = ld_uniform_i32(q_pos + b);  // in flight with the loads around
     // raw query pair (m = tid / 64, p = tid % 64) and the cos/sin of the query position for pair p
     const int qp = tid & (kPairs - 1), qm = min(tid >> 6, G - 1);
     const T* qrow = q + ((size_t)b * H + (size_t)g * G + qm) * kHeadDim;
@@ -120,9 +138,28 @@ __global__ __launch_bounds__(kLsThreads) void attend_logits_small_kernel(
         P[s][0] = ld16(a_src + ao);
         P[s][1] = ld16(a_src + ao + 64 * 64);  // slot 64 + t/8
     };
-    constexpr int EARLY = NST < 4 ? NST : 4;  // U_k steps requested before the row indices arrive
+    // U_k steps requested before the row indices arrive (all of them when the selection runs here first: it takes
+    // longer than a load of the list)
+    constexpr int EARLY = FUSED ? NST : (NST < 4 ? NST : 4);
 #pragma unroll
     for (int s = 0; s < EARLY; ++s) load_a(0, s);
+    if constexpr (FUSED) {
+        // the selection, in LDS that the stage buffers take over afterwards
+        TopkShared& sh = *reinterpret_cast<TopkShared*>(lds);
+        int32_t* s_idx = reinterpret_cast<int32_t*>(lds + ((sizeof(TopkShared) + 255) & ~(size_t)255));  // [k_tot], then the count
+        topk_select_sequence<kLsFusedMaxS / (4 * kLsThreads), kLsThreads, true>(
+            sh, fs.scores + (size_t)b * S_max, fs.seq_len + b, s_idx, s_idx + kLsFusedMaxK, 0, S_max, fs.top_k, fs.n_sink,
+            fs.n_recent);
+        __syncthreads();
+        n_v = s_idx[kLsFusedMaxK];
+        idx_my = s_idx[min(my_slot, k_tot - 1)]; idx_e = s_idx[min(e_slot, k_tot - 1)]; idx_0 = s_idx[0];
+        if (g == 0 && kz == 0) {  // this tile's share of the list for the value stages (idx is an output here)
+            int32_t* ob = const_cast<int32_t*>(idx) + (size_t)b * k_tot;
+            if (tid < kLsTok && tok0 + tid < k_tot) ob[tok0 + tid] = s_idx[tok0 + tid];
+            if (part == 0 && tid == 0) const_cast<int32_t*>(n_sel)[b] = n_v;
+        }
+        __syncthreads();  // (the list has been read: the stage buffers may be written)
+    }
     const int n = wave_uniform(n_v);
     if (tok0 >= n) {  // no selected token in this tile: neutral statistics (split tiles: the finishing kernel's job)
         if (tid < G && ksplit == 1)

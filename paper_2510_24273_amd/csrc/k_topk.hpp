@@ -28,7 +28,7 @@ constexpr int kTopkBins = 4096;
 constexpr int kTopkCand = 512;  // members of the threshold bin handled by the fast path
 
 struct TopkShared {
-    uint32_t hist[kTopkBins];
+    __attribute__((aligned(16))) uint32_t hist[kTopkBins];
     __attribute__((aligned(16))) uint32_t cand[kTopkCand];
     uint32_t scan_a[2][kTopkWaves], scan_b[2][kTopkWaves];  // wave totals, double buffered
     uint32_t wave_a[kTopkWaves], wave_b[kTopkWaves];
@@ -40,8 +40,9 @@ __device__ __forceinline__ float key_to_score(uint32_t k)
     return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
 }
 
-// Exclusive prefix sums of a and b over the 1024 threads (one barrier); *ta, *tb get the block
-// sums.  `phase` alternates the LDS buffer, so back-to-back calls need no second barrier.
+// Exclusive prefix sums of a and b over the workgroup's NW waves (at most 16; one barrier); *ta, *tb get the
+// block sums.  `phase` alternates the LDS buffer, so back-to-back calls need no second barrier.
+template <int NW = kTopkWaves>
 __device__ __forceinline__ void block_excl_scan2(uint32_t& a, uint32_t& b, TopkShared& sh, int& phase,
                                                  uint32_t* ta, uint32_t* tb)
 {
@@ -49,8 +50,9 @@ __device__ __forceinline__ void block_excl_scan2(uint32_t& a, uint32_t& b, TopkS
     const uint32_t ia = wave_incl_scan(a), ib = wave_incl_scan(b);
     if (lane == kWave - 1) { sh.scan_a[phase][wave] = ia; sh.scan_b[phase][wave] = ib; }
     __syncthreads();
-    static_assert(kTopkWaves == 16, "one DPP row holds the wave totals");
-    const uint32_t wa = sh.scan_a[phase][lane & 15], wb = sh.scan_b[phase][lane & 15];
+    static_assert(kTopkWaves == 16 && NW <= 16, "one DPP row holds the wave totals");
+    const bool has = (lane & 15) < NW;  // (slots of waves that do not exist are never written)
+    const uint32_t wa = has ? sh.scan_a[phase][lane & 15] : 0u, wb = has ? sh.scan_b[phase][lane & 15] : 0u;
     const bool before = (lane & 15) < wave;
     *ta = row16_sum_u32(wa);
     *tb = row16_sum_u32(wb);
@@ -58,22 +60,27 @@ __device__ __forceinline__ void block_excl_scan2(uint32_t& a, uint32_t& b, TopkS
     b = row16_sum_u32(before ? wb : 0u) + ib - b;
     phase ^= 1;
 }
+template <int NW = kTopkWaves>
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, TopkShared& sh, int& phase, uint32_t* total)
 {
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     const uint32_t iv = wave_incl_scan(v);
     if (lane == kWave - 1) sh.scan_a[phase][wave] = iv;
     __syncthreads();
-    const uint32_t wv = sh.scan_a[phase][lane & 15];
+    const uint32_t wv = (lane & 15) < NW ? sh.scan_a[phase][lane & 15] : 0u;
     *total = row16_sum_u32(wv);
     const uint32_t r = row16_sum_u32((lane & 15) < wave ? wv : 0u) + iv - v;
     phase ^= 1;
     return r;
 }
 
-// Selection for sequence b by the calling workgroup (1024 threads, all of them must call).
+// Selection for sequence b by the calling workgroup (NTH threads, all of them must call).
 // F4 > 0: keys of F4 float4 groups per thread stay in registers.  F4 == 0: stream.
-template <int F4>
+// CONSEC: a thread's keys are 4*F4 consecutive tokens (otherwise group c of thread t covers tokens
+// 4*(c*NTH + t) .. +3): with it, selected indices come out in token order inside each score class whatever NTH is,
+// i.e. in the order the 1024-thread kernel with one group per thread produces.
+// `idx` / `n_sel` may point to LDS (the caller reads them after a barrier of its own).
+template <int F4, int NTH = kTopkThreads, bool CONSEC = false>
 __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float* __restrict__ scores,
                                                      const int32_t* __restrict__ seq_len,
                                                      int32_t* __restrict__ idx, int32_t* __restrict__ n_sel,
@@ -85,11 +92,17 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
     int32_t* out = idx + (size_t)b * k_tot;
     const bool vec_ok = (((size_t)b * S_max) & 3) == 0;  // this row starts 16-byte aligned
     constexpr int NREG = F4 > 0 ? F4 * 4 : 4;
+    constexpr int NW = NTH / kWave;              // waves
+    constexpr int BPT = kTopkBins / NTH;         // histogram bins per thread
+    static_assert(NTH % kWave == 0 && NTH >= kTopkCand && NTH <= kTopkThreads && kTopkBins % NTH == 0 && (!CONSEC || F4 > 0),
+                  "workgroup shape");
+    // token of this thread's key i (i = 4*group + element)
+    auto token_of = [&](int i) { return CONSEC ? tid * NREG + i : ((((i >> 2) * NTH) + tid) << 2) + (i & 3); };
 
     // group c of this thread covers tokens 4*(c*1024 + tid) .. +3  (coalesced float4 loads);
     // the loads depend on S_max only, so they are in flight together with the length
     auto load_group = [&](int c, float* f) {
-        const int j = (c * kTopkThreads + tid) << 2;
+        const int j = token_of(4 * c);
         f[0] = f[1] = f[2] = f[3] = 0.f;
         if (vec_ok && j + 3 < S_max) {
             f32x4 v = *reinterpret_cast<const f32x4*>(s + j);
@@ -109,13 +122,13 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
     const int S = min(wave_uniform(S_in_v), S_max);
 
     if (S <= k_tot) {  // short cache: every token is selected
-        for (int t = tid; t < k_tot; t += kTopkThreads) out[t] = t < S ? t : 0;
+        for (int t = tid; t < k_tot; t += NTH) out[t] = t < S ? t : 0;
         if (tid == 0) n_sel[b] = S > 0 ? S : 0;
         return;
     }
     const int lo = n_sink, hi = S - n_recent;
-    for (int t = tid; t < n_sink; t += kTopkThreads) out[t] = t;
-    for (int t = tid; t < n_recent; t += kTopkThreads) out[n_sink + top_k + t] = hi + t;
+    for (int t = tid; t < n_sink; t += NTH) out[t] = t;
+    for (int t = tid; t < n_recent; t += NTH) out[n_sink + top_k + t] = hi + t;
     if (tid == 0) n_sel[b] = k_tot;
     if (top_k <= 0) return;
 
@@ -124,23 +137,23 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
     if (F4 > 0) {
 #pragma unroll
         for (int i = 0; i < NREG; ++i) {
-            const int jj = (((i >> 2) * kTopkThreads + tid) << 2) + (i & 3);
+            const int jj = token_of(i);
             keys[i] = (jj >= lo && jj < hi) ? score_key(raw[i]) : 0u;
         }
     }
-    const int n_iter = F4 > 0 ? F4 : (((S + 3) >> 2) + kTopkThreads - 1) / kTopkThreads;
+    const int n_iter = F4 > 0 ? F4 : (((S + 3) >> 2) + NTH - 1) / NTH;
     // visit every (key, token index) of this thread
     auto for_each_key = [&](auto&& fn) {
         if (F4 > 0) {
 #pragma unroll
-            for (int i = 0; i < NREG; ++i) fn(keys[i], (((i >> 2) * kTopkThreads + tid) << 2) + (i & 3));
+            for (int i = 0; i < NREG; ++i) fn(keys[i], token_of(i));
         } else {
             for (int c = 0; c < n_iter; ++c) {
                 float f[4];
                 load_group(c, f);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int jj = ((c * kTopkThreads + tid) << 2) + e;
+                    const int jj = token_of(4 * c) + e;
                     fn((jj >= lo && jj < hi) ? score_key(f[e]) : 0u, jj);
                 }
             }
@@ -160,12 +173,12 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
         kmin = wave_min_u32(kmin);
         kmax = wave_max_u32(kmax);
         if (lane == 0) { sh.wave_a[wave] = kmin; sh.wave_b[wave] = kmax; }
-        for (uint32_t t = tid; t < kTopkBins; t += kTopkThreads) sh.hist[t] = 0u;
+        for (uint32_t t = tid; t < kTopkBins; t += NTH) sh.hist[t] = 0u;
         if (tid < kTopkCand) sh.cand[tid] = 0u;  // key 0 ranks below every candidate
         if (tid == 0) sh.n_cand = 0u;
         __syncthreads();
 #pragma unroll
-        for (int w = 0; w < kTopkWaves; ++w) { kmin = min(kmin, sh.wave_a[w]); kmax = max(kmax, sh.wave_b[w]); }
+        for (int w = 0; w < NW; ++w) { kmin = min(kmin, sh.wave_a[w]); kmax = max(kmax, sh.wave_b[w]); }
         const float flo = key_to_score(kmin), fhi = key_to_score(kmax);
         const float span = fhi - flo;
         const float scale = (span > 0.f && span < 3.0e38f) ? (float)kTopkBins / span : 0.f;
@@ -195,14 +208,19 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
                 for_each_key([&](uint32_t k, int) { if (k != 0u) atomicAdd(&sh.hist[slot_of(k)], 1u); });
             }
             __syncthreads();
-            const u32x4 c4 = *reinterpret_cast<const u32x4*>(&sh.hist[tid * 4]);
-            const uint32_t cnt[4] = {c4.x, c4.y, c4.z, c4.w};
-            uint32_t total;
-            uint32_t above = block_excl_scan(c4.x + c4.y + c4.z + c4.w, sh, phase, &total);
+            uint32_t cnt[BPT], mine = 0u;  // this thread's BPT consecutive slots
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i4 = 0; i4 < BPT; i4 += 4) {
+                const u32x4 c4 = *reinterpret_cast<const u32x4*>(&sh.hist[tid * BPT + i4]);
+                cnt[i4] = c4.x; cnt[i4 + 1] = c4.y; cnt[i4 + 2] = c4.z; cnt[i4 + 3] = c4.w;
+                mine += c4.x + c4.y + c4.z + c4.w;
+            }
+            uint32_t total;
+            uint32_t above = block_excl_scan<NW>(mine, sh, phase, &total);
+#pragma unroll
+            for (int i = 0; i < BPT; ++i) {
                 if (above < (uint32_t)top_k && (uint32_t)top_k <= above + cnt[i]) {
-                    sh.sel_prefix = (uint32_t)(tid * 4 + i);  // slot holding the k-th score
+                    sh.sel_prefix = (uint32_t)(tid * BPT + i);  // slot holding the k-th score
                     sh.sel_kk = (uint32_t)top_k - above;      // how many of its members are selected
                 }
                 above += cnt[i];
@@ -252,21 +270,21 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
             const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
             const uint32_t nb = 1u << bits;
             __syncthreads();
-            for (uint32_t t = tid; t < nb; t += kTopkThreads) sh.hist[t] = 0u;
+            for (uint32_t t = tid; t < nb; t += NTH) sh.hist[t] = 0u;
             __syncthreads();
             // histogram indexed from the top: slot 0 is the largest digit
             for_each_key([&](uint32_t k, int) {
                 if (k != 0u && (k & mask) == prefix) atomicAdd(&sh.hist[nb - 1u - ((k >> shift) & (nb - 1u))], 1u);
             });
             __syncthreads();
-            const int per = (int)(nb / kTopkThreads);  // 4 or 1
-            uint32_t cnt[4], mine = 0u;
+            const int per = (int)(nb / NTH);  // BPT for the 12-bit pass, a quarter of it for the 10-bit ones
+            uint32_t cnt[BPT], mine = 0u;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { cnt[i] = i < per ? sh.hist[tid * per + i] : 0u; mine += cnt[i]; }
+            for (int i = 0; i < BPT; ++i) { cnt[i] = i < per ? sh.hist[tid * per + i] : 0u; mine += cnt[i]; }
             uint32_t total;
-            uint32_t above = block_excl_scan(mine, sh, phase, &total);
+            uint32_t above = block_excl_scan<NW>(mine, sh, phase, &total);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < BPT; ++i) {
                 if (i < per && above < kk && kk <= above + cnt[i]) {
                     uint32_t digit = nb - 1u - (uint32_t)(tid * per + i);
                     sh.sel_prefix = prefix | (digit << shift);
@@ -288,7 +306,7 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
     uint32_t pos_gt = 0u, pos_eq = 0u;
     for_each_key([&](uint32_t k, int) { pos_gt += k > tau; pos_eq += k == tau; });
     uint32_t tot_gt, tot_eq;
-    block_excl_scan2(pos_gt, pos_eq, sh, phase, &tot_gt, &tot_eq);
+    block_excl_scan2<NW>(pos_gt, pos_eq, sh, phase, &tot_gt, &tot_eq);
 
     // ties that straddle the cut: keep the need_eq smallest token indices among them
     int j_cut = hi;  // select ties with index < j_cut
@@ -299,13 +317,13 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
             uint32_t c_mine = 0u;
             for_each_key([&](uint32_t k, int jj) { c_mine += (k == tau && jj < mid); });
             uint32_t c_tot;
-            block_excl_scan(c_mine, sh, phase, &c_tot);
+            block_excl_scan<NW>(c_mine, sh, phase, &c_tot);
             if (c_tot >= need_eq) hi_j = mid; else lo_j = mid + 1;
         }
         j_cut = lo_j;
         uint32_t my_eq = 0u;
         for_each_key([&](uint32_t k, int jj) { my_eq += (k == tau && jj < j_cut); });
-        pos_eq = block_excl_scan(my_eq, sh, phase, &tot_eq);
+        pos_eq = block_excl_scan<NW>(my_eq, sh, phase, &tot_eq);
     }
 
     // greater-than keys fill [0, n_gt), ties [n_gt, top_k), each in token order.  (The limits

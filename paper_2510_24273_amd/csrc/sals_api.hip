@@ -69,6 +69,7 @@ struct sals_ctx {
     // environment, plans or sets kernel attributes
     LogitsPlan plan{3, 0, 1, 1};
     int score_rows = 16;         // cache rows per workgroup of the score kernel
+    bool fuse_select = true;     // decode steps may select inside the logits kernel (tuning aid SALS_TUNE_FUSE_SELECT=0)
     // cos/sin table over the positions 0 .. S_max (in the workspace): 0 = not filled, 1 = fill enqueued on
     // rope_stream and marked by rope_ev, 2 = known to be complete
     int rope_state = 0;
@@ -448,6 +449,32 @@ template <typename T> LogitsPlan plan_logits(const sals_desc& d)
     return P;
 }
 
+// the 64-token logits kernel for a number of steps loaded ahead, with or without the selection inside
+template <typename T> struct SmallLogits {
+    typedef void (*Fn)(const int32_t*, const int32_t*, const T*, int, int, int, int, int, int, int, int, const T*, const T*,
+                       const int32_t*, const float2*, InvFreq, float*, float2*, int, int, int, float, int, float*, int,
+                       FusedSelect);
+    static Fn get(int nst, bool fused)
+    {
+#define SALS_LS(N) case N: return fused ? (Fn)attend_logits_small_kernel<T, N, true> : (Fn)attend_logits_small_kernel<T, N, false>;
+        switch (nst) {
+            SALS_LS(1) SALS_LS(2) SALS_LS(3) SALS_LS(4) SALS_LS(5) SALS_LS(6) SALS_LS(7) SALS_LS(8) SALS_LS(9)
+            default: return fused ? (Fn)attend_logits_small_kernel<T, 10, true> : (Fn)attend_logits_small_kernel<T, 10, false>;
+        }
+#undef SALS_LS
+    }
+};
+
+// Whether a whole decode step on this context lets the logits kernel select by itself (no selection launch): the
+// 64-token kernel without a split of the latent axis, a cache of at most 4096 rows whose score rows start 16-byte
+// aligned, a selection that fits the kernel's list.
+bool fused_selection(const sals_ctx* c)
+{
+    const sals_desc& d = c->d;
+    return c->plan.pick == 3 && c->plan.ksplit == 1 && d.S_max <= kLsFusedMaxS && d.S_max % 4 == 0 &&
+           d.top_k + d.n_sink + d.n_recent <= kLsFusedMaxK && c->fuse_select;
+}
+
 template <typename T> sals_status allow_logits_lds(const LogitsPlan& P)
 {
     auto allow = [](const void* kern, size_t bytes) {
@@ -458,20 +485,8 @@ template <typename T> sals_status allow_logits_lds(const LogitsPlan& P)
     if (P.pick == 1) ok = allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 2, 4, 2>), logits_cfg<2, 4, 2>::LDS);
     else if (P.pick == 2) ok = allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 1, 4, 2>), logits_cfg<1, 4, 2>::LDS);
     else {
-        const void* k = nullptr;
-        switch (P.nst) {
-            case 1: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 1>); break;
-            case 2: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 2>); break;
-            case 3: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 3>); break;
-            case 4: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 4>); break;
-            case 5: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 5>); break;
-            case 6: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 6>); break;
-            case 7: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 7>); break;
-            case 8: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 8>); break;
-            case 9: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 9>); break;
-            default: k = reinterpret_cast<const void*>(attend_logits_small_kernel<T, 10>); break;
-        }
-        ok = allow(k, kLsLds);
+        ok = allow(reinterpret_cast<const void*>(SmallLogits<T>::get(P.nst, false)), kLsLds) &&
+             allow(reinterpret_cast<const void*>(SmallLogits<T>::get(P.nst, true)), kLsLds);
     }
     return ok ? SALS_OK : SALS_ERR_HIP;
 }
@@ -480,7 +495,7 @@ template <typename T>
 sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos, const void* Kc,
                           const void* Vc, const void* W, const int32_t* idx, const int32_t* n_sel, void* out,
                           hipStream_t st, const QvCache* qv = nullptr, int ring = 0, int phases = kPhaseAll,
-                          const StatsLink* link = nullptr)
+                          const StatsLink* link = nullptr, const FusedSelect* fs = nullptr)
 {
     const sals_desc& d = c->d;
     const Layout& L = c->L;
@@ -517,27 +532,15 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
         else if (pick == 2) SALS_LOGITS(1, 4, 2);   // 1 head  x 256 tokens
         else {  // few tiles: 1 head x 64 tokens with the whole latent axis loaded ahead
             const int ksplit = P.ksplit, nst = P.nst;
-            void (*kern)(const int32_t*, const int32_t*, const T*, int, int, int, int, int, int, int, int, const T*,
-                         const T*, const int32_t*, const float2*, InvFreq, float*, float2*, int, int, int, float, int,
-                         float*, int) = nullptr;
-            switch (nst) {
-                case 1: kern = attend_logits_small_kernel<T, 1>; break;
-                case 2: kern = attend_logits_small_kernel<T, 2>; break;
-                case 3: kern = attend_logits_small_kernel<T, 3>; break;
-                case 4: kern = attend_logits_small_kernel<T, 4>; break;
-                case 5: kern = attend_logits_small_kernel<T, 5>; break;
-                case 6: kern = attend_logits_small_kernel<T, 6>; break;
-                case 7: kern = attend_logits_small_kernel<T, 7>; break;
-                case 8: kern = attend_logits_small_kernel<T, 8>; break;
-                case 9: kern = attend_logits_small_kernel<T, 9>; break;
-                default: kern = attend_logits_small_kernel<T, 10>; break;
-            }
+            // fs: idx / n_sel are outputs of this launch (the kernel selects from fs->scores itself)
+            const typename SmallLogits<T>::Fn kern = SmallLogits<T>::get(nst, fs != nullptr);
+            const FusedSelect fsel = fs ? *fs : FusedSelect{nullptr, nullptr, 0, 0, 0};
             float* plogits = reinterpret_cast<float*>(c->ws + L.plogits);
             hipLaunchKernelGGL(kern, dim3(n_parts * d.H_kv * d.B * ksplit), dim3(kLsThreads), kLsLds, st,
                                idx, n_sel, w_section<T>(c, W, 2), d.B, d.H_kv, n_parts, heads_fastest, ksplit, k_tot,
                                d.r, d.H_q, static_cast<const T*>(Kc), static_cast<const T*>(q), q_pos, rope, c->inv,
                                logits, stats, d.S_max, L.lk, d.rope_style, 1.0f / std::sqrt((float)d.d), ring,
-                               plogits, stats_stride);
+                               plogits, stats_stride, fsel);
             if (ksplit > 1) {
                 if (launch_status() != SALS_OK) return SALS_ERR_HIP;
                 hipLaunchKernelGGL(logits_finish_kernel, dim3(n_parts, d.B * d.H_q), dim3(64), 0, st, plogits, ksplit,
@@ -666,6 +669,7 @@ sals_status sals_create(const sals_desc* desc, void* d_workspace, size_t workspa
     const bool bf = desc->dtype == SALS_BF16;
     c->plan = bf ? plan_logits<bf16_t>(c->d) : plan_logits<float>(c->d);
     c->score_rows = plan_score_rows(c->d);
+    if (const char* e = std::getenv("SALS_TUNE_FUSE_SELECT")) c->fuse_select = std::atoi(e) != 0;  // tuning aid
     *out = c;
     return SALS_OK;
 }
@@ -886,6 +890,14 @@ sals_status sals_decode_step(sals_ctx* ctx, const void* q, const int32_t* q_pos,
     if (!n_sel) n_sel = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_sel);
     sals_status s = sals_latent_scores(ctx, q, W, Kc, seq_len, scores, hip_stream);
     if (s != SALS_OK) return s;
+    if (fused_selection(ctx)) {  // one launch fewer: the logits kernel selects and leaves idx / n_sel behind
+        if (bad(Vc)) return SALS_ERR_INVALID_ARG;
+        const FusedSelect fs{scores, seq_len, ctx->d.top_k, ctx->d.n_sink, ctx->d.n_recent};
+        hipStream_t st = static_cast<hipStream_t>(hip_stream);
+        return ctx->d.dtype == SALS_BF16
+                   ? launch_attend<bf16_t>(ctx, q, q_pos, Kc, Vc, W, idx, n_sel, out, st, nullptr, 0, kPhaseAll, nullptr, &fs)
+                   : launch_attend<float>(ctx, q, q_pos, Kc, Vc, W, idx, n_sel, out, st, nullptr, 0, kPhaseAll, nullptr, &fs);
+    }
     s = sals_topk_select(ctx, scores, seq_len, idx, n_sel, hip_stream);
     if (s != SALS_OK) return s;
     return sals_sparse_attend(ctx, q, q_pos, Kc, Vc, W, idx, n_sel, out, hip_stream);
@@ -955,6 +967,14 @@ sals_status sals_decode_step_qv(sals_ctx* ctx, const void* q, const int32_t* q_p
     if (!n_sel) n_sel = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_sel);
     sals_status s = sals_latent_scores(ctx, q, W, Kc, seq_len, scores, hip_stream);
     if (s != SALS_OK) return s;
+    if (fused_selection(ctx)) {  // one launch fewer: the logits kernel selects and leaves idx / n_sel behind
+        const FusedSelect fs{scores, seq_len, ctx->d.top_k, ctx->d.n_sink, ctx->d.n_recent};
+        const QvCache qv{Vq, Vmeta, bits};
+        hipStream_t st = static_cast<hipStream_t>(hip_stream);
+        return ctx->d.dtype == SALS_BF16
+                   ? launch_attend<bf16_t>(ctx, q, q_pos, Kc, nullptr, W, idx, n_sel, out, st, &qv, 0, kPhaseAll, nullptr, &fs)
+                   : launch_attend<float>(ctx, q, q_pos, Kc, nullptr, W, idx, n_sel, out, st, &qv, 0, kPhaseAll, nullptr, &fs);
+    }
     s = sals_topk_select(ctx, scores, seq_len, idx, n_sel, hip_stream);
     if (s != SALS_OK) return s;
     return sals_sparse_attend_qv(ctx, q, q_pos, Kc, Vq, Vmeta, bits, W, idx, n_sel, out, hip_stream);
