@@ -308,30 +308,34 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
             const int ml = ps >> 1, ah = ps & 1;
             const unsigned char* cb = lds + (size_t)(ps & 1) * C::CS_BYTES;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const int row = (tg * NB + nb) * 32 + l32;
+            for (int al = 0; al < 2; ++al) {
+                const int a = 2 * ah + al;
+                const int p0 = ml * 32 + a * 8 + hi * 4;
+                // the rotated key elements of this lane's NB tokens first, then every query head's pieces are read
+                // from LDS once and used for all NB tokens
+                float k1[NB][4], k2[NB][4];
 #pragma unroll
-                for (int al = 0; al < 2; ++al) {
-                    const int a = 2 * ah + al;
-                    const int p0 = ml * 32 + a * 8 + hi * 4;
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int row = (tg * NB + nb) * 32 + l32;
                     const f32x4 t0 = *reinterpret_cast<const f32x4*>(cb + swz(row, al * 4 + hi * 2));      // pairs p0, p0+1
                     const f32x4 t1 = *reinterpret_cast<const f32x4*>(cb + swz(row, al * 4 + hi * 2 + 1));  // p0+2, p0+3
                     const float cc[4] = {t0.x, t0.z, t1.x, t1.z}, ss[4] = {t0.y, t0.w, t1.y, t1.w};
-                    float k1[4], k2[4];
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const float x1 = acc[ml][nb][a * 4 + c], x2 = acc[ml + 2][nb][a * 4 + c];
-                        k1[c] = x1 * cc[c] - x2 * ss[c];
-                        k2[c] = x2 * cc[c] + x1 * ss[c];
+                        k1[nb][c] = x1 * cc[c] - x2 * ss[c];
+                        k2[nb][c] = x2 * cc[c] + x1 * ss[c];
                     }
+                }
 #pragma unroll
-                    for (int m = 0; m < kMaxGroup; ++m) {
-                        if (m < G) {
-                            const f32x4 q1 = *reinterpret_cast<const f32x4*>(&sQ[hh][m][p0]);
-                            const f32x4 q2 = *reinterpret_cast<const f32x4*>(&sQ[hh][m][kPairs + p0]);
-                            dot[m][nb] += q1.x * k1[0] + q1.y * k1[1] + q1.z * k1[2] + q1.w * k1[3] +
-                                          q2.x * k2[0] + q2.y * k2[1] + q2.z * k2[2] + q2.w * k2[3];
-                        }
+                for (int m = 0; m < kMaxGroup; ++m) {
+                    if (m < G) {
+                        const f32x4 q1 = *reinterpret_cast<const f32x4*>(&sQ[hh][m][p0]);
+                        const f32x4 q2 = *reinterpret_cast<const f32x4*>(&sQ[hh][m][kPairs + p0]);
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            dot[m][nb] += q1.x * k1[nb][0] + q1.y * k1[nb][1] + q1.z * k1[nb][2] + q1.w * k1[nb][3] +
+                                          q2.x * k2[nb][0] + q2.y * k2[nb][1] + q2.z * k2[nb][2] + q2.w * k2[nb][3];
                     }
                 }
             }
