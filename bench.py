@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer buffer sets (0 = workload default)")
-    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg2_rhalf,cfg4_rhalf,cfg2_qv4,cfg4_qv4,cfg2_comp,cfg2_win,cfg3a_comp,cfg3a_win,cfg4_cap2x,cfg2_qvwin,t6_b16_s4096_12,t6w_b16_s4096_12,t6w_b16_s4096_25,prefill_cfg2,prefill_cfg3b",
+    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg4_rhalf,cfg2_qv4,cfg4_qv4,cfg2_comp,cfg2_win,cfg3a_win,cfg4_cap2x,cfg2_qvwin,t6_b16_s4096_12,t6w_b16_s4096_12,prefill_cfg2,prefill_cfg3b",
                     help="other configurations reported under 'extra' (comma list, '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
@@ -402,7 +402,7 @@ def main():
                        "kernels_frac": {k: v["frac"] for k, v in r["kernels"].items()}}
         del lse
         torch.cuda.empty_cache()
-        if not a.no_dense:
+        if not a.no_dense and we.fill == 1.0:   # (a cache with spare capacity: the dense baseline of the full one applies)
             key = (we.B, we.S, we.S_live, we.H, we.H_kv, we.dtype)
             if key not in dense_done:
                 dense_done[key] = measure_dense(we, max(5, a.steps // 3), 2, not a.no_graph, torch, binding)

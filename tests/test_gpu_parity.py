@@ -403,3 +403,67 @@ def test_cfg5_full(oracle):
     idx = gu.from_dev(R["idx"][0])
     S = C["cfg5"].S
     assert idx[-64:].tolist() == list(range(S - 64, S)) and len(idx) == 4160
+
+
+# ---- context set-up: the cos/sin table -------------------------------------------------
+
+def test_unprepared_context_fills_its_table_lazily_and_refuses_capture(oracle):
+    """A context made through the C ABI without sals_prepare: the first attend call fills the table on its own
+    stream, a call on another stream is ordered behind it, results equal a prepared context's; under graph capture
+    an unprepared context is refused before anything is enqueued."""
+    import ctypes
+    from paper_2510_24273_amd import binding
+    w = synth.shrink(SMALL, B=2, plant=0)
+    L = synth.make_layer(w)
+    ctx = gu.make_ctx(w)                      # prepared (the binding does it)
+    G = gu.upload(L, ctx)
+    want = gu.run_stages(ctx, w, G)
+    lib = binding._lib
+
+    def raw_ctx():
+        ws = torch.zeros(binding.workspace_bytes(ctx.desc), dtype=torch.uint8, device=gu.DEV)
+        h = ctypes.c_void_p()
+        assert lib.sals_create(ctypes.byref(ctx.desc), ws.data_ptr(), ws.numel(), ctypes.byref(h)) == binding.SALS_OK
+        return h, ws
+
+    def attend(h, stream, out):
+        return lib.sals_sparse_attend(h, G["q"].data_ptr(), G["q_pos"].data_ptr(), G["Kc"].data_ptr(), G["Vc"].data_ptr(),
+                                      G["W"].data_ptr(), want["idx"].data_ptr(), want["n_sel"].data_ptr(), out.data_ptr(),
+                                      stream.cuda_stream)
+
+    # lazily, first on a side stream, then at once on the default stream
+    h, ws = raw_ctx()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    o1, o2 = torch.empty_like(want["out"]), torch.empty_like(want["out"])
+    assert attend(h, side, o1) == binding.SALS_OK
+    assert attend(h, torch.cuda.current_stream(), o2) == binding.SALS_OK
+    torch.cuda.synchronize()
+    for o in (o1, o2):
+        assert torch.equal(o.view(torch.int16), want["out"].view(torch.int16))
+    lib.sals_destroy(h)
+    # refused under capture while unprepared; accepted after sals_prepare
+    h, ws = raw_ctx()
+    o3 = torch.empty_like(want["out"])
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    codes = []
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            codes.append(attend(h, s, o3))
+            if codes[0] != binding.SALS_OK:
+                o3.fill_(0)              # (something to capture, so that the capture itself is well formed)
+    torch.cuda.synchronize()
+    assert codes[0] == binding.SALS_ERR_HIP or codes[0] == binding.SALS_ERR_INVALID_ARG
+    assert lib.sals_prepare(h, torch.cuda.current_stream().cuda_stream) == binding.SALS_OK
+    g2 = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g2, stream=s):
+            assert attend(h, s, o3) == binding.SALS_OK
+    o3.fill_(7.0)
+    g2.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(o3.view(torch.int16), want["out"].view(torch.int16))
+    lib.sals_destroy(h)
+    ctx.close()
