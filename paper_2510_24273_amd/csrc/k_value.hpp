@@ -4,8 +4,8 @@
 //
 //   attend_pv   per (sequence, token range, 64 latent columns):
 //               T[h,:] = sum_j p_hj V~[C_j,:]  on the matrix cores, tokens being the
-//               contraction axis (each step split over the workgroup's four or eight waves); the gathered
-//               rows are transposed through LDS on the way.  The softmax weights are formed
+//               contraction axis (dealt in groups to the workgroup's four or eight waves); the gathered
+//               rows are transposed in registers on the way.  The softmax weights are formed
 //               on the fly, p = exp(logit - m_h) / Z_h, with m_h and Z_h merged in the prologue
 //               from the per-tile statistics the logits kernel left.  Each token range writes an
 //               fp32 partial sum.
@@ -21,42 +21,39 @@
 
 namespace sals {
 
-constexpr int kPvTJ = 64;          // token ranges are whole multiples of this (of twice this for the eight-wave kernel)
+constexpr int kPvTJ = 64;          // token ranges are whole multiples of this
 constexpr int kPvCols = 64;        // latent columns per workgroup
 constexpr int kPvMaxHeads = 64;    // H_q limit of these kernels
 constexpr int kMaxRanges = 8;      // token ranges per sequence (the output projection adds them up)
 constexpr int kPvMaxTok = 4096;    // tokens per workgroup, at most (their cache rows sit in LDS)
+constexpr int kPvDepth = 4;        // token groups whose loads a wave keeps in flight
 
-// NW waves (4 or 8), each with one MFMA token group of every step: the eight-wave form halves the number of
-// steps (a step is a chain of dependent latencies), the four-wave form starts and finishes faster.
-template <typename T, int NW>
-__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(
-    // (what the workgroup's first loads need comes first: those 14 words arrive preloaded in scalar registers)
+// NW waves (4 or 8), MB blocks of 32 heads.  The range's tokens are dealt to the waves in groups of one MFMA
+// contraction step (16 tokens for bf16, 8 for fp32: half of them per half-wave); a wave works through its groups on
+// its own, no barrier inside the loop, and keeps the loads of kPvDepth groups in flight.
+//
+// The MFMA's second operand wants, per lane, consecutive TOKENS of one column, while memory holds consecutive
+// columns of one token.  bf16: lane l32 fetches the 32-bit word (columns 2 l32, 2 l32 + 1) of each of its eight
+// tokens, a half-wave thus a whole 128-byte piece per token, and two byte permutes per token pair turn the eight words
+// into the operand of the even column and the operand of the odd column: the transposition never leaves the
+// registers.  fp32 (two tokens per MFMA, one per half-wave): the loaded words are the operands as they are.
+template <typename T, int NW, int MB>
+__global__ __launch_bounds__(NW * 64) void attend_pv_kernel(
     const int32_t* __restrict__ idx, const int32_t* __restrict__ n_sel, const float2* __restrict__ stats,
     int B, int r, int n_tr, int n_parts, int tok_per_wg, int k_tot, int H, int lk,
     const T* __restrict__ Vc, const float* __restrict__ logits, float* __restrict__ Tpart, int S_max, int ring)
 {
-    static_assert(NW == 4 || NW == 8, "four or eight waves");
-    constexpr int kPvThreads = NW * 64, kPvWaves = NW;
+    static_assert((NW == 4 || NW == 8) && (MB == 1 || MB == 2), "four or eight waves, one or two head blocks");
+    constexpr int kPvThreads = NW * 64;
     constexpr int ES = (int)sizeof(T);
-    constexpr int VEC = elem<T>::vec;        // tokens per lane per MFMA group = elements per 16 bytes
-    constexpr int KG = 2 * VEC;              // tokens per MFMA group (both half-waves)
-    constexpr int TJ = kPvWaves * KG;        // tokens per step: one MFMA group per wave
-    constexpr int NKG = TJ / KG;             // MFMA groups per step, dealt to the waves
+    constexpr int VEC = elem<T>::vec;        // tokens per lane per group = elements per 16 bytes
+    constexpr int KG = 2 * VEC;              // tokens per group (both half-waves)
     constexpr bool kSplit = ES == 2;
-    constexpr int PPR = kPvCols * ES / 16;   // 16-byte pieces per gathered row
-    constexpr int NPC = TJ * PPR / kPvThreads;  // pieces per thread per step
-    constexpr int PITCH = TJ * ES + 8;       // bytes per column of the transposed tile (8-byte reads stay aligned)
+    constexpr int ND = 8;                    // gathered words per lane and group: 8 tokens (bf16) | 4 tokens x 2 column blocks (fp32)
 
-    // V~ rows arrive as they lie in memory (16 bytes = VEC columns of one token per lane) and are
-    // written to LDS transposed, [column][token], so that an MFMA operand (one column, VEC consecutive
-    // tokens per lane) is two 8-byte reads.
-    constexpr int VT_BYTES = 2 * kPvCols * PITCH, RED_BYTES = 4 * 64 * 33 * 4;
-    __shared__ __attribute__((aligned(16))) unsigned char sBuf[VT_BYTES > RED_BYTES ? VT_BYTES : RED_BYTES];
-    unsigned char (*sVt)[kPvCols * PITCH] = reinterpret_cast<unsigned char (*)[kPvCols * PITCH]>(sBuf);
-    float (*red)[64][33] = reinterpret_cast<float (*)[64][33]>(sBuf);  // cross-wave sums, after the loop
-    __shared__ int sRow[kPvMaxTok];          // cache row of every token of the range
+    __shared__ __attribute__((aligned(16))) int sRow[kPvMaxTok];  // cache row of every token of the nominal range
     __shared__ float2 sMZ[kPvMaxHeads];      // per head: softmax maximum, 1 / normaliser
+    __shared__ float red[NW][64][17];        // cross-wave sums, after the loop
 
     // Work items are ordered (sequence, token range, column block) with the column block fastest.
     // Workgroup ids are dealt round-robin to the XCDs; the map below gives each XCD a contiguous run of
@@ -69,32 +66,72 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(
     const int cb = item % n_cb, tr = (item / n_cb) % n_tr, b = item / (n_cb * n_tr);
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
-    // the count and this thread's first index are requested together (both through the vector memory path)
-    const int n_v = ld_uniform_i32(n_sel + b);
-    const int v_first = idx[(size_t)b * k_tot + min(tr * tok_per_wg + tid, k_tot - 1)];
-    const int n = wave_uniform(n_v);
-    const int j_begin = min(n, tr * tok_per_wg), j_end = min(n, j_begin + tok_per_wg);
-    const int ntok = j_end - j_begin;
     const int col0 = cb * kPvCols;
-    const int n_mb = (H + 31) >> 5;
     const float* lg = logits + (size_t)b * H * lk;
     const int32_t* ib = idx + (size_t)b * k_tot;
 
-    // (the index loads only depend on the nominal range, so they are in flight together with n)
+    // everything that depends on nothing is requested at once: the count, the range's indices, the tile statistics
+    const int n_v = ld_uniform_i32(n_sel + b);
     for (int t = tid; t < tok_per_wg; t += kPvThreads) {
         const int j = tr * tok_per_wg + t;
-        const int v = t == tid ? v_first : (j < k_tot ? ib[j] : 0);
+        const int v = ib[min(j, k_tot - 1)];
         const int pos = min(max(v, 0), S_max - 1);
-        if (t < ntok) sRow[t] = ring > 0 ? pos % ring : pos;  // ring cache: token t lies in row t mod ring
+        sRow[t] = ring > 0 ? pos % ring : pos;  // ring cache: token t lies in row t mod ring
     }
-    // softmax maximum and normaliser of every head: four lanes share a head's tiles and merge
-    // them in a fixed order
+    const int sh = tid >> 2, sub = tid & 3;     // four lanes share a head's tiles
+    float2 st8[8];
     {
-        const int h = tid >> 2, sub = tid & 3;
+        const float2* sp = stats + ((size_t)b * H + min(sh, H - 1)) * n_parts;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) st8[u] = sub + 4 * u < n_parts ? sp[sub + 4 * u] : make_float2(-INFINITY, 0.f);
+    }
+    __syncthreads();  // rows of the range in LDS
+
+    const unsigned char* vbytes =
+        reinterpret_cast<const unsigned char*>(Vc + (size_t)b * (ring > 0 ? ring : S_max) * r + col0) + l32 * 4;
+    const size_t row_bytes = (size_t)r * ES;
+    const int g_last = tok_per_wg / KG - 1;  // (the range is a whole number of groups)
+    // what a group needs from global memory: the gathered words and this lane's logits
+    struct Stage { uint32_t R[ND]; f32x4 X[MB][VEC / 4]; };
+    auto g_load = [&](Stage& S, int g) {
+        const int t0 = min(g, g_last) * KG + hi * VEC;  // first of this lane's VEC tokens within the range
+        int rows[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; v += 4) {
+            const int4 r4 = *reinterpret_cast<const int4*>(&sRow[t0 + v]);
+            rows[v] = r4.x; rows[v + 1] = r4.y; rows[v + 2] = r4.z; rows[v + 3] = r4.w;
+        }
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            const unsigned char* src = vbytes + (size_t)rows[v] * row_bytes;
+            if constexpr (kSplit) {
+                S.R[v] = *reinterpret_cast<const uint32_t*>(src);
+            } else {
+                S.R[v] = *reinterpret_cast<const uint32_t*>(src);
+                S.R[VEC + v] = *reinterpret_cast<const uint32_t*>(src + 32 * 4);
+            }
+        }
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const int h = min(mb * 32 + l32, H - 1);  // (rows past the last head: any head's logits, never stored)
+            const size_t off = (size_t)h * lk + tr * tok_per_wg + t0;
+#pragma unroll
+            for (int v = 0; v < VEC / 4; ++v) S.X[mb][v] = *reinterpret_cast<const f32x4*>(lg + off + 4 * v);
+        }
+    };
+    Stage S[kPvDepth];
+#pragma unroll
+    for (int u = 0; u < kPvDepth; ++u)
+        if (wave + NW * u <= g_last) g_load(S[u], wave + NW * u);  // (the count is not known yet: nominal groups)
+
+    // softmax maximum and normaliser of every head, merged in a fixed order (under the loads above)
+    {
         float2 st = make_float2(-INFINITY, 0.f);
-        if (h < H) {
-            const float2* sp = stats + ((size_t)b * H + h) * n_parts;
-            for (int t0 = sub; t0 < n_parts; t0 += 32) {  // eight loads in flight per round
+        if (sh < H) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) st = stat_merge(st, st8[u]);
+            const float2* sp = stats + ((size_t)b * H + sh) * n_parts;
+            for (int t0 = sub + 32; t0 < n_parts; t0 += 32) {  // (more than 32 tiles: further rounds of eight loads)
                 float2 e[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
@@ -105,195 +142,113 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attend_pv_kernel(
         }
         st = stat_merge(st, make_float2(__shfl_xor(st.x, 1, kWave), __shfl_xor(st.y, 1, kWave)));
         st = stat_merge(st, make_float2(__shfl_xor(st.x, 2, kWave), __shfl_xor(st.y, 2, kWave)));
-        if (sub == 0 && h < kPvMaxHeads) sMZ[h] = make_float2(st.x > -INFINITY ? st.x : 0.f, st.y > 0.f ? 1.f / st.y : 0.f);
+        if (sub == 0 && sh < kPvMaxHeads) sMZ[sh] = make_float2(st.x > -INFINITY ? st.x : 0.f, st.y > 0.f ? 1.f / st.y : 0.f);
     }
     __syncthreads();
-    float2 mz[2];
+    float2 mz[MB];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb) mz[mb] = sMZ[mb * 32 + l32];
+    for (int mb = 0; mb < MB; ++mb) mz[mb] = sMZ[mb * 32 + l32];
 
-    f32x16 acc[2][2];  // [head block][column block]
+    const int n = wave_uniform(n_v);
+    const int j_begin = min(n, tr * tok_per_wg), j_end = min(n, j_begin + tok_per_wg);
+    const int ntok = j_end - j_begin;        // (0 for a range past the selection: it still writes its zero sums)
+    const int n_groups = (ntok + KG - 1) / KG;
+
+    f32x16 acc[MB][2];  // [head block][column block]
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
 
-    const unsigned char* vbytes = reinterpret_cast<const unsigned char*>(Vc + (size_t)b * (ring > 0 ? ring : S_max) * r + col0);
-    const size_t row_bytes = (size_t)r * ES;
-    constexpr int NKQ = (NKG + kPvWaves - 1) / kPvWaves;  // MFMA groups per wave per step (1)
-    // what a step needs from global memory: the gathered row pieces and this lane's logits; two
-    // such sets alternate, so the loads run two steps ahead
-    struct Stage { u32x4 R[NPC]; f32x4 X[NKQ][2][VEC / 4]; };
-    auto g_load = [&](Stage& S, int step) {
+    auto do_group = [&](const Stage& S, int g) {
+        const int t0 = g * KG + hi * VEC;
+        // words of slots past the range count as zero (their rows may never have been written)
+        uint32_t w[ND];
 #pragma unroll
-        for (int i = 0; i < NPC; ++i) {
-            const int q = tid + kPvThreads * i, jj = q / PPR, pc = q % PPR;
-            // tokens past the range re-read its last row; their weights are zero
-            const int row = sRow[min(step * TJ + jj, ntok - 1)];
-            S.R[i] = ld16(vbytes + (size_t)row * row_bytes + pc * 16);
+        for (int v = 0; v < VEC; ++v) {
+            const bool ok = t0 + v < ntok;
+            w[v] = ok ? S.R[v] : 0u;
+            if constexpr (!kSplit) w[VEC + v] = ok ? S.R[VEC + v] : 0u;
+        }
+        u32x4 vf[2];
+        if constexpr (kSplit) {
+            vf[0] = u32x4{__builtin_amdgcn_perm(w[1], w[0], 0x05040100u), __builtin_amdgcn_perm(w[3], w[2], 0x05040100u),
+                          __builtin_amdgcn_perm(w[5], w[4], 0x05040100u), __builtin_amdgcn_perm(w[7], w[6], 0x05040100u)};
+            vf[1] = u32x4{__builtin_amdgcn_perm(w[1], w[0], 0x07060302u), __builtin_amdgcn_perm(w[3], w[2], 0x07060302u),
+                          __builtin_amdgcn_perm(w[5], w[4], 0x07060302u), __builtin_amdgcn_perm(w[7], w[6], 0x07060302u)};
+        } else {
+            vf[0] = u32x4{w[0], w[1], w[2], w[3]};
+            vf[1] = u32x4{w[4], w[5], w[6], w[7]};
         }
 #pragma unroll
-        for (int kq = 0; kq < NKQ; ++kq) {
-            const int ks = kq * kPvWaves + wave;
+        for (int mb = 0; mb < MB; ++mb) {
+            float pj[VEC];
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
-                const int h = mb * 32 + l32;
-                const bool ok = ks < NKG && mb < n_mb && h < H;
-                const size_t off = (size_t)h * lk + j_begin + step * TJ + ks * KG + hi * VEC;
-#pragma unroll
-                for (int v = 0; v < VEC / 4; ++v)
-                    S.X[kq][mb][v] = ok ? *reinterpret_cast<const f32x4*>(lg + off + 4 * v)
-                                      : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            for (int v = 0; v < VEC; v += 4) {
+                const f32x4 x = S.X[mb][v / 4];
+                // slots past the range carry no weight (their logits may be unwritten)
+                const int jt = t0 + v;
+                pj[v] = jt < ntok ? __expf(x.x - mz[mb].x) * mz[mb].y : 0.f;
+                pj[v + 1] = jt + 1 < ntok ? __expf(x.y - mz[mb].x) * mz[mb].y : 0.f;
+                pj[v + 2] = jt + 2 < ntok ? __expf(x.z - mz[mb].x) * mz[mb].y : 0.f;
+                pj[v + 3] = jt + 3 < ntok ? __expf(x.w - mz[mb].x) * mz[mb].y : 0.f;
             }
-        }
-    };
-    auto l_store = [&](const Stage& S, int buf) {
-#pragma unroll
-        for (int i = 0; i < NPC; ++i) {
-            const int q = tid + kPvThreads * i, jj = q / PPR, pc = q % PPR;
-            unsigned char* dst = sVt[buf] + (size_t)(pc * VEC) * PITCH + jj * ES;
-            const uint32_t w[4] = {S.R[i].x, S.R[i].y, S.R[i].z, S.R[i].w};
+            u32x4 ah, al;
             if constexpr (kSplit) {
-                // lanes l and l^8 hold the same columns of tokens jj and jj^1: they swap halves, so that each
-                // writes four whole 32-bit words {token even, token odd} instead of eight 16-bit ones
-                const bool odd = (jj & 1) != 0;
-                unsigned char* dst2 = dst - (odd ? ES : 0);
+                uint32_t ph[VEC], pl[VEC];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w[k], 0x128, 0xf, 0xf, false);  // row_ror:8
-                    const uint32_t word = odd ? ((other >> 16) | (w[k] & 0xffff0000u)) : ((w[k] & 0xffffu) | (other << 16));
-                    *reinterpret_cast<uint32_t*>(dst2 + (size_t)(2 * k + (odd ? 1 : 0)) * PITCH) = word;
+                for (int v = 0; v < VEC; ++v) {
+                    const bf16_t hb = f32_to_bf16(pj[v]);
+                    ph[v] = hb;
+                    pl[v] = f32_to_bf16(pj[v] - bf16_to_f32(hb));
                 }
+                ah = u32x4{ph[0] | (ph[1] << 16), ph[2] | (ph[3] << 16), ph[4] | (ph[5] << 16), ph[6] | (ph[7] << 16)};
+                al = u32x4{pl[0] | (pl[1] << 16), pl[2] | (pl[3] << 16), pl[4] | (pl[5] << 16), pl[6] | (pl[7] << 16)};
             } else {
+                ah = u32x4{__float_as_uint(pj[0]), __float_as_uint(pj[1]), __float_as_uint(pj[2]), __float_as_uint(pj[3])};
+            }
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) *reinterpret_cast<uint32_t*>(dst + (size_t)e * PITCH) = w[e];
+            for (int nb = 0; nb < 2; ++nb) {
+                mma_op<T>::run(ah, vf[nb], acc[mb][nb]);
+                if constexpr (kSplit) mma_op<T>::run(al, vf[nb], acc[mb][nb]);
             }
         }
     };
-
-    const int n_steps = (ntok + TJ - 1) / TJ;
-    auto do_step = [&](Stage& S, int step) {
-        const int buf = step & 1;
-        l_store(S, buf);
-        // softmax weights of this step from the logits fetched a step ahead
-        const int j0 = j_begin + step * TJ;
-        u32x4 ah[NKQ][2], al[NKQ][2];
+    for (int i0 = 0; wave + NW * i0 < n_groups; i0 += kPvDepth) {
 #pragma unroll
-        for (int kq = 0; kq < NKQ; ++kq) {
-            const int tok = (kq * kPvWaves + wave) * KG + hi * VEC;  // first of this lane's VEC tokens within the step
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
-                if (mb >= n_mb) {  // uniform: no heads in this block
-                    ah[kq][mb] = al[kq][mb] = u32x4{0, 0, 0, 0};
-                    continue;
-                }
-                float pj[VEC];
-#pragma unroll
-                for (int v = 0; v < VEC; v += 4) {
-                    const f32x4 x = S.X[kq][mb][v / 4];
-                    // slots past the range carry no weight (their logits may be unwritten)
-                    const int jt = j0 + tok + v;
-                    pj[v] = jt < j_end ? __expf(x.x - mz[mb].x) * mz[mb].y : 0.f;
-                    pj[v + 1] = jt + 1 < j_end ? __expf(x.y - mz[mb].x) * mz[mb].y : 0.f;
-                    pj[v + 2] = jt + 2 < j_end ? __expf(x.z - mz[mb].x) * mz[mb].y : 0.f;
-                    pj[v + 3] = jt + 3 < j_end ? __expf(x.w - mz[mb].x) * mz[mb].y : 0.f;
-                }
-                if constexpr (kSplit) {
-                    uint32_t ph[VEC], pl[VEC];
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        const bf16_t hb = f32_to_bf16(pj[v]);
-                        ph[v] = hb;
-                        pl[v] = f32_to_bf16(pj[v] - bf16_to_f32(hb));
-                    }
-                    ah[kq][mb] = u32x4{ph[0] | (ph[1] << 16), ph[2] | (ph[3] << 16), ph[4] | (ph[5] << 16),
-                                       ph[6] | (ph[7] << 16)};
-                    al[kq][mb] = u32x4{pl[0] | (pl[1] << 16), pl[2] | (pl[3] << 16), pl[4] | (pl[5] << 16),
-                                       pl[6] | (pl[7] << 16)};
-                } else {
-                    ah[kq][mb] = u32x4{__float_as_uint(pj[0]), __float_as_uint(pj[1]), __float_as_uint(pj[2]),
-                                       __float_as_uint(pj[3])};
-                }
-            }
+        for (int u = 0; u < kPvDepth; ++u) {
+            const int g = wave + NW * (i0 + u);  // wave-uniform
+            if (g < n_groups) do_group(S[u], g);
+            if (g + NW * kPvDepth < n_groups) g_load(S[u], g + NW * kPvDepth);
         }
-        if (step + 2 < n_steps) g_load(S, step + 2);
-        __syncthreads();  // tile `buf` complete; the other tile was last read a barrier ago
-#pragma unroll
-        for (int kq = 0; kq < NKQ; ++kq) {
-            const int ks = kq * kPvWaves + wave;
-            if (ks < NKG) {  // uniform
-                const int tok = ks * KG + hi * VEC;
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb) {
-                    const unsigned char* src = sVt[buf] + (size_t)(nb * 32 + l32) * PITCH + tok * ES;
-                    const uint2 lo8 = *reinterpret_cast<const uint2*>(src);
-                    const uint2 hi8 = *reinterpret_cast<const uint2*>(src + 8);
-                    const u32x4 vf = u32x4{lo8.x, lo8.y, hi8.x, hi8.y};
-#pragma unroll
-                    for (int mb = 0; mb < 2; ++mb) {
-                        if (mb < n_mb) {
-                            mma_op<T>::run(ah[kq][mb], vf, acc[mb][nb]);
-                            if constexpr (kSplit) mma_op<T>::run(al[kq][mb], vf, acc[mb][nb]);
-                        }
-                    }
-                }
-            }
-        }
-    };
-    Stage S0, S1;
-    if (n_steps > 0) g_load(S0, 0);
-    if (n_steps > 1) g_load(S1, 1);
-    for (int step = 0; step < n_steps; step += 2) {
-        do_step(S0, step);
-        if (step + 1 < n_steps) do_step(S1, step + 1);
     }
 
-    // The waves' sums, one column block at a time: of eight waves, 4..7 first hand theirs to waves 0..3, which
-    // add them (wave w + wave w+4); the four then share out the final sum in wave order, wave w finishing heads
-    // 8w..8w+7 of each head block.  acc[mb][nb][4a+c] is head mb*32+8a+4hi+c, column nb*32+l32
+    // The waves' sums, one (head block, column block) at a time, added in wave order; wave w finishes 16 / NW of a
+    // lane's 16 values.  acc[mb][nb][4a+c] is head mb*32 + 8a + 4hi + c; its column is 2 l32 + nb (bf16: even / odd
+    // operand) or nb*32 + l32 (fp32).
     float* out_t = Tpart + (((size_t)tr * B + b) * H) * r;
+    constexpr int PER = 16 / NW;
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        __syncthreads();
-        if constexpr (NW == 8) {
-            if (wave >= 4) {
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
+        for (int nb = 0; nb < 2; ++nb) {
+            if (mb + nb > 0) __syncthreads();
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) red[wave - 4][lane][mb * 16 + v] = acc[mb][nb][v];
-            }
+            for (int v = 0; v < 16; ++v) red[wave][lane][v] = acc[mb][nb][v];
             __syncthreads();
-            if (wave < 4) {
+            const int col = col0 + (kSplit ? 2 * l32 + nb : nb * 32 + l32);
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
+            for (int c = 0; c < PER; ++c) {
+                const int v = wave * PER + c;
+                const int h = mb * 32 + (v >> 2) * 8 + hi * 4 + (v & 3);
+                float sum = red[0][lane][v];
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[mb][nb][v] += red[wave][lane][mb * 16 + v];
+                for (int w = 1; w < NW; ++w) sum += red[w][lane][v];
+                if (h < H) out_t[(size_t)h * r + col] = sum;
             }
-            __syncthreads();
         }
-        if (wave < 4) {
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) red[wave][lane][mb * 16 + v] = acc[mb][nb][v];
-        }
-        __syncthreads();
-        if (wave < 4) {
-            const int col = col0 + nb * 32 + l32;
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const int v = wave * 4 + c;  // a = wave
-                    const int h = mb * 32 + wave * 8 + hi * 4 + c;
-                    if (h < H)
-                        out_t[(size_t)h * r + col] = ((red[0][lane][mb * 16 + v] + red[1][lane][mb * 16 + v]) +
-                                                      red[2][lane][mb * 16 + v]) + red[3][lane][mb * 16 + v];
-                }
-        }
-    }
 }
 
 // ---------------------------------------------------------------------------------
