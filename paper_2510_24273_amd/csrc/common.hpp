@@ -64,6 +64,9 @@ __device__ __forceinline__ int wave_uniform(int v) { return __builtin_amdgcn_rea
 
 // 16-byte global load
 __device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+// the same for a long stream that is read once: the caches are told not to keep it (measured: 10-13 % faster for
+// streams of 80 MB and more, slower for the few-MB weight streams and for gathered rows)
+__device__ __forceinline__ u32x4 ld16_stream(const void* p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)); }
 
 // Sum over each aligned group of 16 lanes (a DPP row); every lane gets the total.
 __device__ __forceinline__ float row16_sum(float v)

@@ -52,8 +52,8 @@ __global__ __launch_bounds__(256) void dense_attend_kernel(const T* __restrict__
         const size_t off = (size_t)(live ? j : 0) * row_stride;
 #pragma unroll
         for (int n = 0; n < NCH; ++n) {
-            kp[n] = live ? ld16(kb + off + (li + 16 * n) * VEC) : u32x4{0, 0, 0, 0};
-            vp[n] = live ? ld16(vb + off + (li + 16 * n) * VEC) : u32x4{0, 0, 0, 0};
+            kp[n] = live ? ld16_stream(kb + off + (li + 16 * n) * VEC) : u32x4{0, 0, 0, 0};
+            vp[n] = live ? ld16_stream(vb + off + (li + 16 * n) * VEC) : u32x4{0, 0, 0, 0};
         }
     };
     u32x4 kc[NCH], vc[NCH], kn[NCH], vn[NCH];

@@ -18,8 +18,8 @@ constexpr int kScoreRowsPerIter = (kScoreThreads / kWave) * 4;  // 16 rows per w
 constexpr int kScoreMaxR = 1024;  // scoring rank r* at most (q~[:r*] sits in LDS, one 16-byte piece per thread)
 constexpr int kScoreMaxParts = 8;   // slices of the D axis the projection may split into
 
-// NCH = 16-byte pieces per lane = ceil(r_score / (vec*16))
-template <typename T, int NCH>
+// NCH = 16-byte pieces per lane = ceil(r_score / (vec*16)); STREAM: cache rows are loaded with the read-once hint
+template <typename T, int NCH, bool STREAM>
 __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restrict__ Kc,
                                                                const float* __restrict__ qt_part, int np,
                                                                const int32_t* __restrict__ seq_len,
@@ -45,7 +45,8 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restri
 #pragma unroll
         for (int n = 0; n < NCH; ++n) {
             int p = li + 16 * n;
-            piece[n] = (live && p < n_pieces) ? ld16(base + (size_t)j * r + p * VEC) : u32x4{0, 0, 0, 0};
+            const T* src = base + (size_t)j * r + p * VEC;
+            piece[n] = (live && p < n_pieces) ? (STREAM ? ld16_stream(src) : ld16(src)) : u32x4{0, 0, 0, 0};
         }
     };
 

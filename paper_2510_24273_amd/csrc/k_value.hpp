@@ -104,12 +104,8 @@ __global__ __launch_bounds__(NW * 64) void attend_pv_kernel(
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
             const unsigned char* src = vbytes + (size_t)rows[v] * row_bytes;
-            if constexpr (kSplit) {
-                S.R[v] = *reinterpret_cast<const uint32_t*>(src);
-            } else {
-                S.R[v] = *reinterpret_cast<const uint32_t*>(src);
-                S.R[VEC + v] = *reinterpret_cast<const uint32_t*>(src + 32 * 4);
-            }
+            S.R[v] = *reinterpret_cast<const uint32_t*>(src);
+            if constexpr (!kSplit) S.R[VEC + v] = *reinterpret_cast<const uint32_t*>(src + 32 * 4);
         }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {

@@ -69,6 +69,7 @@ struct sals_ctx {
     // environment, plans or sets kernel attributes
     LogitsPlan plan{3, 0, 1, 1};
     int score_rows = 16;         // cache rows per workgroup of the score kernel
+    int score_stream = -1;       // read-once hint on the score kernel's cache loads: -1 by size, 0 / 1 forced (tuning aid)
     bool fuse_select = true;     // decode steps may select inside the logits kernel (tuning aid SALS_TUNE_FUSE_SELECT=0)
     // cos/sin table over the positions 0 .. S_max (in the workspace): 0 = not filled, 1 = fill enqueued on
     // rope_stream and marked by rope_ev, 2 = known to be complete
@@ -249,11 +250,19 @@ sals_status launch_scores(const sals_ctx* c, const void* Kc, const int32_t* seq_
     dim3 grid(ceil_div(d.S_max, rows), d.B);
     const float* qt = reinterpret_cast<const float*>(c->ws + c->L.qt);
     const T* K = static_cast<const T*>(Kc);
+    // a cache prefix of 32 MB and more is read as a stream the caches need not keep; a smaller one with plain loads (it
+    // may still be cached from the previous step)
+    bool stream = (size_t)d.B * d.S_max * d.r_score * sizeof(T) >= ((size_t)32 << 20);
+    if (c->score_stream >= 0) stream = c->score_stream != 0;
     ProfScope ps(c, SALS_K_SCORES, st);
 #define SALS_SCORES_CASE(N)                                                                         \
     case N:                                                                                         \
-        hipLaunchKernelGGL((scores_kernel<T, N>), grid, dim3(kScoreThreads), 0, st, K, qt, c->L.proj_np, \
-                           seq_len, scores, d.B, d.S_max, d.r, d.r_score, rows);                       \
+        if (stream)                                                                                  \
+            hipLaunchKernelGGL((scores_kernel<T, N, true>), grid, dim3(kScoreThreads), 0, st, K, qt,    \
+                               c->L.proj_np, seq_len, scores, d.B, d.S_max, d.r, d.r_score, rows);      \
+        else                                                                                         \
+            hipLaunchKernelGGL((scores_kernel<T, N, false>), grid, dim3(kScoreThreads), 0, st, K, qt,   \
+                               c->L.proj_np, seq_len, scores, d.B, d.S_max, d.r, d.r_score, rows);      \
         break;
     switch (nch) {
         SALS_SCORES_CASE(1) SALS_SCORES_CASE(2) SALS_SCORES_CASE(3) SALS_SCORES_CASE(4)
@@ -667,6 +676,7 @@ sals_status sals_create(const sals_desc* desc, void* d_workspace, size_t workspa
     const bool bf = desc->dtype == SALS_BF16;
     c->plan = bf ? plan_logits<bf16_t>(c->d) : plan_logits<float>(c->d);
     c->score_rows = plan_score_rows(c->d);
+    if (const char* e = std::getenv("SALS_TUNE_SCORE_STREAM")) c->score_stream = std::atoi(e) != 0;  // tuning aid
     if (const char* e = std::getenv("SALS_TUNE_FUSE_SELECT")) c->fuse_select = std::atoi(e) != 0;  // tuning aid
     *out = c;
     return SALS_OK;
