@@ -24,7 +24,8 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restri
                                                                const float* __restrict__ qt_part, int np,
                                                                const int32_t* __restrict__ seq_len,
                                                                float* __restrict__ scores, int B, int S_max,
-                                                               int r, int r_score, int rows_per_wg)
+                                                               int r, int r_score, int rows_per_wg,
+                                                               uint2* __restrict__ wg_range, int n_sink, int n_recent)
 {
     constexpr int VEC = elem<T>::vec;
     __shared__ __attribute__((aligned(16))) float q_s[kScoreMaxR];
@@ -88,6 +89,9 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restri
         }
     }
 
+    // smallest and largest key of the candidate scores (tokens that are neither sink nor recent) this thread stores;
+    // only used when the long-sequence selection asks for them
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
     auto finish_rows = [&](int j0, const u32x4* piece) {
         const int j = j0 + wave * 4 + quad;
         float acc = 0.f;
@@ -100,6 +104,11 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restri
         }
         acc = row16_sum(acc);
         if (li == 0 && j < j_end) scores[(size_t)b * S_max + j] = j < S ? acc : -INFINITY;
+        if (li == 0 && j < j_end && j >= n_sink && j < S - n_recent) {
+            const uint32_t key = score_key(acc);
+            kmin = min(kmin, key);
+            kmax = max(kmax, key);
+        }
     };
     // two register sets take turns (no copy between them: a copy would wait for the loads it moves)
     for (int j0 = j_begin; j0 < j_live; j0 += 2 * kScoreRowsPerIter) {
@@ -109,6 +118,20 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(const T* __restri
         if (second) {
             if (j0 + 2 * kScoreRowsPerIter < j_live) load_row(j0 + 2 * kScoreRowsPerIter, cur);
             finish_rows(j0 + kScoreRowsPerIter, nxt);
+        }
+    }
+    // The selection chain for long sequences bins the candidates' scores over their range: every workgroup leaves the
+    // key range of the candidates it scored (none: the neutral pair), which saves that chain a pass over the scores.
+    if (wg_range != nullptr) {  // uniform
+        __shared__ uint32_t s_min[kScoreThreads / kWave], s_max[kScoreThreads / kWave];
+        kmin = wave_min_u32(kmin);
+        kmax = wave_max_u32(kmax);
+        if (lane == 0) { s_min[wave] = kmin; s_max[wave] = kmax; }
+        __syncthreads();
+        if (tid == 0) {
+#pragma unroll
+            for (int w = 0; w < kScoreThreads / kWave; ++w) { kmin = min(kmin, s_min[w]); kmax = max(kmax, s_max[w]); }
+            wg_range[(size_t)b * gridDim.x + blockIdx.x] = make_uint2(kmin, kmax);
         }
     }
 }

@@ -6,12 +6,14 @@
 // into chunks of 8192 scores, one workgroup each, and the selection runs as a chain of small
 // kernels that exchange a few kilobytes:
 //   range    per chunk: minimum and maximum candidate key
-//   hist     per chunk: histogram over 2048 linear bins of the sequence's [min, max]
-//   place    per chunk: from all chunk histograms, the bin holding the top_k-th score, how many of
-//            its members are selected and where the chunk's output starts (every workgroup of the
-//            sequence derives the same numbers); then the indices of the scores in higher bins go
-//            to their final positions (chunk order, then token order) and the members of the
-//            threshold bin to a candidate list
+//   hist     per chunk: histogram over 2048 linear bins of the sequence's [min, max], stored as running
+//            counts from the top bin down (entry s = the chunk's scores in bins above s)
+//   place    per chunk: the bin holding the top_k-th score, how many of its members are selected and
+//            where the chunk's output starts (every workgroup of the sequence derives the same
+//            numbers, in two rounds over the chunks' running counts: at every 32nd bin, then at the
+//            32 bins of the step that holds the threshold); then the indices of the scores in
+//            higher bins go to their final positions (chunk order, then token order) and the
+//            members of the threshold bin to a candidate list
 //   finish   per sequence: ranks the candidates (ties towards the smaller index), writes the
 //            selected ones in token order, the sink / recent entries and n_sel
 // The result is the same set as topk_kernel's, a deterministic function of the scores; only
@@ -30,6 +32,9 @@ constexpr int kTmF4 = kTmChunk / (4 * kTopkThreads);  // float4 groups per threa
 constexpr int kTmBins = 2048;
 constexpr int kTmMaxChunks = 128;         // S_max <= 2^20
 constexpr int kTmCand = 512;              // candidates the finish kernel ranks
+constexpr int kTmCoarse = 32;             // bins per coarse step of the threshold search
+constexpr int kTmNC = kTmBins / kTmCoarse;   // coarse steps
+constexpr int kTmCum = kTmBins + 4;       // running counts per chunk: entries 0 .. kTmBins (rows stay 16-byte aligned)
 
 struct TopkMeta {        // per sequence, written by the place kernel
     uint32_t fallback;   // 1: topk_kernel must redo the sequence
@@ -43,8 +48,10 @@ struct TopkMeta {        // per sequence, written by the place kernel
 
 // workspace of the chain, per sequence
 struct TopkMultiWs {
+    const uint2* range;  // [B][n_range] (min key, max key) pairs that cover the sequence's candidates: `part`, or the
+    int n_range;         //   pairs the score kernel left per workgroup (then over all scores below the length)
     uint2* part;         // [B][n_chunk] (min key, max key) of the chunk's candidates
-    uint32_t* hist;      // [B][n_chunk][kTmBins]
+    uint32_t* hist;      // [B][n_chunk][kTmCum]: entry s = the chunk's candidates in slots above s (slot 0 = top bin)
     TopkMeta* meta;      // [B]
     uint2* cand;         // [B][kTmCand] (key, token index)
 };
@@ -76,21 +83,25 @@ __device__ __forceinline__ int tm_token(int chunk, int i)
     return chunk * kTmChunk + ((((i >> 2) * kTopkThreads) + threadIdx.x) << 2) + (i & 3);
 }
 
-// the sequence's linear map from its chunks' (min, max): every workgroup derives the same numbers
-__device__ __forceinline__ bool tm_range(const uint2* __restrict__ part, int n_chunk, float* flo, float* scale)
+// the sequence's linear map from the (min key, max key) pairs of its parts (the chunks of the range kernel, or the
+// workgroups of the score kernel): every workgroup derives the same numbers.  All threads of the workgroup must call
+// (one barrier); `red` is LDS scratch of 2 * kTopkWaves words.
+__device__ __forceinline__ bool tm_range(const uint2* __restrict__ part, int n_part, uint32_t* red, float* flo, float* scale)
 {
-    // every wave reads all chunks' pairs itself, two per lane and round, and folds them with lane shuffles: no
-    // barrier, and one memory round trip instead of one per chunk
     uint32_t kmin = 0xffffffffu, kmax = 0u;
-    const int lane = threadIdx.x & (kWave - 1);
-    for (int c0 = 0; c0 < n_chunk; c0 += 2 * kWave) {
-        const int ca = c0 + lane, cb = c0 + kWave + lane;
-        const uint2 a = part[min(ca, n_chunk - 1)], b = part[min(cb, n_chunk - 1)];  // (clamped: duplicates are harmless)
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    for (int c0 = 0; c0 < n_part; c0 += 2 * kTopkThreads) {  // two loads per thread and trip, from clamped part numbers
+        const uint2 a = part[min(c0 + tid, n_part - 1)], b = part[min(c0 + kTopkThreads + tid, n_part - 1)];
         kmin = min(kmin, min(a.x, b.x));
         kmax = max(kmax, max(a.y, b.y));
     }
     kmin = wave_min_u32(kmin);
     kmax = wave_max_u32(kmax);
+    if (lane == 0) { red[wave] = kmin; red[kTopkWaves + wave] = kmax; }
+    __syncthreads();
+    static_assert(kTopkWaves == 16, "one DPP row of wave results");
+    kmin = wave_min_u32(red[lane & 15]);
+    kmax = wave_max_u32(red[kTopkWaves + (lane & 15)]);
     if (kmax == 0u) return false;  // no candidate at all
     const float a = key_to_score(kmin), span = key_to_score(kmax) - a;
     const float sc = (span > 0.f && span < 3.0e38f) ? (float)kTmBins / span : 0.f;
@@ -133,93 +144,135 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(const float* __
                                                                  TopkMultiWs ws, int S_max, int n_chunk,
                                                                  int n_sink, int n_recent)
 {
-    __shared__ uint32_t hist[kTmBins];
+    __shared__ TopkShared sh;  // (its histogram array and scan buffers)
+    static_assert(kTmBins == 2 * kTopkThreads && kTmBins <= kTopkBins, "two bins per thread");
+    uint32_t* hist = sh.hist;
     const int chunk = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const int S = min(ld_uniform_i32(seq_len + b), S_max);  // (vector memory path: in flight with the scores)
     uint32_t keys[4 * kTmF4];
     tm_load_keys(scores + (size_t)b * S_max, S_max, chunk, n_sink, S - n_recent, keys);
     for (int t = tid; t < kTmBins; t += kTopkThreads) hist[t] = 0u;
     float flo, scale;
-    const bool ok = tm_range(ws.part + (size_t)b * n_chunk, n_chunk, &flo, &scale);
-    __syncthreads();
+    const bool ok = tm_range(ws.range + (size_t)b * ws.n_range, ws.n_range, sh.cand, &flo, &scale);  // (barrier inside)
     if (ok) {
 #pragma unroll
         for (int i = 0; i < 4 * kTmF4; ++i)
             if (keys[i] != 0u) atomicAdd(&hist[tm_slot(keys[i], flo, scale)], 1u);
     }
     __syncthreads();
-    uint32_t* out = ws.hist + ((size_t)b * n_chunk + chunk) * kTmBins;
-    for (int t = tid; t < kTmBins; t += kTopkThreads) out[t] = hist[t];
+    // running counts from the top: entry s = members of slots 0 .. s-1, entry kTmBins = all of the chunk's candidates
+    const uint2 c = *reinterpret_cast<const uint2*>(&hist[2 * tid]);
+    int phase = 0;
+    uint32_t total;
+    const uint32_t above = block_excl_scan(c.x + c.y, sh, phase, &total);
+    uint32_t* out = ws.hist + ((size_t)b * n_chunk + chunk) * kTmCum;
+    *reinterpret_cast<uint2*>(out + 2 * tid) = make_uint2(above, above + c.x);
+    if (tid == 0) out[kTmBins] = total;
 }
 
-// The sequence-level decisions, taken identically by every workgroup of the sequence from the
-// chunk histograms: threshold bin, selected members, and the first output position / candidate
-// slot of chunk `chunk`.  Returns the meta record (fallback set if the chain does not apply).
-__device__ __forceinline__ TopkMeta tm_resolve(TopkShared& sh, uint32_t* s_above, uint32_t* s_memb,
-                                               const TopkMultiWs& ws, int b, int chunk, int S, int n_chunk,
-                                               int top_k, int n_sink, int n_recent, uint32_t* base_above,
-                                               uint32_t* base_cand)
+// The sequence-level decisions, taken identically by every workgroup of the sequence from the chunks' running
+// counts: threshold bin, selected members, and the first output position / candidate slot of chunk `chunk`.
+// Returns the meta record (fallback set if the chain does not apply).
+struct TmResolveLds {
+    uint32_t coarse[kTmNC];                       // all chunks' candidates above slot 32 (p + 1)
+    uint32_t fine[kTmCoarse + 1];                 // ... above slot 32 P + i
+    uint32_t fv[kTmMaxChunks][kTmCoarse + 1];     // the chunks' own counts at those slots
+    uint32_t red[2 * kTopkWaves];
+    int P, I;
+};
+__device__ __forceinline__ TopkMeta tm_resolve(TmResolveLds& L, const TopkMultiWs& ws, int b, int chunk, int S,
+                                               int n_chunk, int top_k, int n_sink, int n_recent,
+                                               uint32_t* base_above, uint32_t* base_cand)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     TopkMeta m{};
-    // this thread's two bins, summed over the chunks; the first eight chunks' loads are requested together with
-    // the chunks' score ranges (from clamped chunk numbers: no load in a branch)
-    const uint32_t* hb = ws.hist + (size_t)b * n_chunk * kTmBins + 2 * tid;
-    uint2 v0[8];
+    const uint32_t* cum = ws.hist + (size_t)b * n_chunk * kTmCum;
+    // round 1: the counts at every 32nd slot, summed over the chunks (four loads per thread and trip in flight, from
+    // clamped element numbers: no load in a branch)
+    const int n1 = kTmNC * n_chunk;
+    for (int t = tid; t < kTmNC + kTmCoarse + 1; t += kTopkThreads) (t < kTmNC ? L.coarse[t] : L.fine[t - kTmNC]) = 0u;
+    if (tid == 0) { L.P = -1; L.I = -1; }
+    uint32_t v1[4];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v0[u] = *reinterpret_cast<const uint2*>(hb + (size_t)min(u, n_chunk - 1) * kTmBins);
-    const bool ok = tm_range(ws.part + (size_t)b * n_chunk, n_chunk, &m.flo, &m.scale) &&
+    for (int u = 0; u < 4; ++u) {
+        const int e = min(tid + u * kTopkThreads, n1 - 1);
+        v1[u] = cum[(size_t)(e / kTmNC) * kTmCum + (e % kTmNC + 1) * kTmCoarse];
+    }
+    const bool ok = tm_range(ws.range + (size_t)b * ws.n_range, ws.n_range, L.red, &m.flo, &m.scale) &&  // (barrier inside)
                     S > top_k + n_sink + n_recent && top_k > 0;
     if (!ok) {  // uniform
         m.fallback = 1u;
         return m;
     }
-    uint32_t c0 = 0u, c1 = 0u;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) { c0 += u < n_chunk ? v0[u].x : 0u; c1 += u < n_chunk ? v0[u].y : 0u; }
-    for (int c = 8; c < n_chunk; c += 8) {
-        uint2 v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-            v[u] = c + u < n_chunk ? *reinterpret_cast<const uint2*>(hb + (size_t)(c + u) * kTmBins) : make_uint2(0u, 0u);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) { c0 += v[u].x; c1 += v[u].y; }
+    for (int u = 0; u < 4; ++u) {
+        const int e = tid + u * kTopkThreads;
+        if (e < n1) atomicAdd(&L.coarse[e % kTmNC], v1[u]);
     }
-    int phase = 0;
-    uint32_t total;
-    uint32_t above = block_excl_scan(c0 + c1, sh, phase, &total);
-    if (above < (uint32_t)top_k && (uint32_t)top_k <= above + c0) {
-        sh.sel_prefix = 2 * tid; sh.sel_kk = (uint32_t)top_k - above; sh.n_cand = c0;
-    } else if (above + c0 < (uint32_t)top_k && (uint32_t)top_k <= above + c0 + c1) {
-        sh.sel_prefix = 2 * tid + 1; sh.sel_kk = (uint32_t)top_k - above - c0; sh.n_cand = c1;
-    }
-    __syncthreads();
-    m.t_slot = sh.sel_prefix; m.kk = sh.sel_kk; m.members = sh.n_cand;
-    // per chunk: scores in bins above the threshold, members of the threshold bin (a wave per chunk)
-    for (int c = wave; c < n_chunk; c += kTopkWaves) {
-        const uint32_t* hc = ws.hist + ((size_t)b * n_chunk + c) * kTmBins;
-        u32x4 v[kTmBins / (4 * kWave)];  // the whole histogram of the chunk, all loads in flight at once
+    for (int e0 = 4 * kTopkThreads; e0 < n1; e0 += 4 * kTopkThreads) {  // (more than 64 chunks)
+        uint32_t v[4];
 #pragma unroll
-        for (int i = 0; i < kTmBins / (4 * kWave); ++i) v[i] = *reinterpret_cast<const u32x4*>(hc + 4 * (lane + kWave * i));
-        uint32_t sum = 0u;
-#pragma unroll
-        for (int i = 0; i < kTmBins / (4 * kWave); ++i) {
-            const uint32_t s0 = 4u * (lane + kWave * i);
-            sum += (s0 < m.t_slot ? v[i].x : 0u) + (s0 + 1 < m.t_slot ? v[i].y : 0u) + (s0 + 2 < m.t_slot ? v[i].z : 0u) +
-                   (s0 + 3 < m.t_slot ? v[i].w : 0u);
+        for (int u = 0; u < 4; ++u) {
+            const int e = min(e0 + tid + u * kTopkThreads, n1 - 1);
+            v[u] = cum[(size_t)(e / kTmNC) * kTmCum + (e % kTmNC + 1) * kTmCoarse];
         }
-        sum = wave_sum_u32(sum);
-        if (lane == 0) { s_above[c] = sum; s_memb[c] = hc[m.t_slot]; }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + tid + u * kTopkThreads;
+            if (e < n1) atomicAdd(&L.coarse[e % kTmNC], v[u]);
+        }
     }
     __syncthreads();
-    uint32_t a = 0u, mm = 0u, a_here = 0u, m_here = 0u;
-    for (int c = 0; c < n_chunk; ++c) {
-        if (c == chunk) { a_here = a; m_here = mm; }
-        a += s_above[c]; mm += s_memb[c];
+    if (tid < kTmNC) {
+        const uint32_t lo = tid ? L.coarse[tid - 1] : 0u, hi = L.coarse[tid];
+        if (lo < (uint32_t)top_k && (uint32_t)top_k <= hi) L.P = tid;
     }
-    *base_above = a_here;
-    *base_cand = m_here;
-    m.n_above = a;
+    __syncthreads();
+    const int P = L.P;
+    if (P < 0) {  // uniform: fewer candidates than top_k in the histograms (cannot happen for a valid range)
+        m.fallback = 1u;
+        return m;
+    }
+    // round 2: the counts at the 33 slot boundaries of coarse step P, per chunk and summed
+    const int n2 = (kTmCoarse + 1) * n_chunk;
+    for (int e0 = 0; e0 < n2; e0 += 4 * kTopkThreads) {
+        uint32_t v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = min(e0 + tid + u * kTopkThreads, n2 - 1);
+            v[u] = cum[(size_t)(e / (kTmCoarse + 1)) * kTmCum + P * kTmCoarse + e % (kTmCoarse + 1)];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + tid + u * kTopkThreads;
+            if (e < n2) {
+                L.fv[e / (kTmCoarse + 1)][e % (kTmCoarse + 1)] = v[u];
+                atomicAdd(&L.fine[e % (kTmCoarse + 1)], v[u]);
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < kTmCoarse) {
+        const uint32_t lo = L.fine[tid], hi = L.fine[tid + 1];
+        if (lo < (uint32_t)top_k && (uint32_t)top_k <= hi) L.I = tid;
+    }
+    __syncthreads();
+    const int I = L.I;
+    if (I < 0) {  // uniform (as above)
+        m.fallback = 1u;
+        return m;
+    }
+    m.t_slot = (uint32_t)(P * kTmCoarse + I);
+    m.n_above = L.fine[I];
+    m.members = L.fine[I + 1] - L.fine[I];
+    m.kk = (uint32_t)top_k - m.n_above;
+    uint32_t a = 0u, mm = 0u;
+    for (int c = 0; c < chunk; ++c) {
+        a += L.fv[c][I];
+        mm += L.fv[c][I + 1] - L.fv[c][I];
+    }
+    *base_above = a;
+    *base_cand = mm;
     m.fallback = m.members > (uint32_t)kTmCand ? 1u : 0u;
     return m;
 }
@@ -231,14 +284,14 @@ __global__ __launch_bounds__(kTopkThreads) void topk_place_kernel(const float* _
                                                                   int n_recent)
 {
     __shared__ TopkShared sh;
-    __shared__ uint32_t s_above[kTmMaxChunks], s_memb[kTmMaxChunks];
+    __shared__ TmResolveLds rl;
     const int chunk = blockIdx.x, b = blockIdx.y;
     const int S = min(ld_uniform_i32(seq_len + b), S_max);  // (vector memory path: in flight with the scores)
     uint32_t keys[4 * kTmF4];
     tm_load_keys(scores + (size_t)b * S_max, S_max, chunk, n_sink, S - n_recent, keys);
     uint32_t base_above = 0u, base_cand = 0u;
-    const TopkMeta m = tm_resolve(sh, s_above, s_memb, ws, b, chunk, wave_uniform(S), n_chunk, top_k, n_sink, n_recent,
-                                  &base_above, &base_cand);
+    const TopkMeta m = tm_resolve(rl, ws, b, chunk, wave_uniform(S), n_chunk, top_k, n_sink, n_recent, &base_above,
+                                  &base_cand);
     if (chunk == 0 && threadIdx.x == 0) ws.meta[b] = m;  // for the finish kernel
     if (m.fallback) return;
     int slot[4 * kTmF4];

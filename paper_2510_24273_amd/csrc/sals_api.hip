@@ -39,7 +39,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Layout {  // byte offsets into the workspace
-    size_t qt, scores, idx, n_sel, n_lo, logits, plogits, stats, rope, tpart, qv_part, dn_part, tm_part, tm_hist, tm_meta, tm_cand, total;
+    size_t qt, scores, idx, n_sel, n_lo, logits, plogits, stats, rope, tpart, qv_part, dn_part, tm_part, tm_hist, tm_meta, tm_cand, tm_srange, total;
     int lk;                      // logits row stride (floats)
     int max_parts;               // token tiles per head of the logits kernel, at most
     int pv_tok_per_wg, pv_ntr, pv_waves;  // value-sum token ranges, waves per workgroup (4 | 8)
@@ -191,9 +191,11 @@ Layout make_layout(const sals_desc& d)
     L.tm_chunks = d.S_max > 32768 ? ceil_div(d.S_max, kTmChunk) : 0;
     if (L.tm_chunks > 0) {
         L.tm_part = take((size_t)d.B * L.tm_chunks * sizeof(uint2));
-        L.tm_hist = take((size_t)d.B * L.tm_chunks * kTmBins * 4);
+        L.tm_hist = take((size_t)d.B * L.tm_chunks * kTmCum * 4);
         L.tm_meta = take((size_t)d.B * sizeof(TopkMeta));
         L.tm_cand = take((size_t)d.B * kTmCand * sizeof(uint2));
+        // key ranges the score kernel leaves per workgroup inside a decode step (at least 16 rows per workgroup)
+        L.tm_srange = take((size_t)d.B * ceil_div(d.S_max, kScoreRowsPerIter) * sizeof(uint2));
     }
     L.total = o;
     return L;
@@ -240,8 +242,10 @@ sals_status launch_project(const sals_ctx* c, const void* W, const void* x0, con
 }
 
 template <typename T>
+// wg_range: where every workgroup leaves the key range of its scores (for the long-sequence selection of the same
+// step), or nullptr
 sals_status launch_scores(const sals_ctx* c, const void* Kc, const int32_t* seq_len, float* scores,
-                          hipStream_t st)
+                          hipStream_t st, uint2* wg_range = nullptr)
 {
     const sals_desc& d = c->d;
     constexpr int VEC = elem<T>::vec;
@@ -259,10 +263,12 @@ sals_status launch_scores(const sals_ctx* c, const void* Kc, const int32_t* seq_
     case N:                                                                                         \
         if (stream)                                                                                  \
             hipLaunchKernelGGL((scores_kernel<T, N, true>), grid, dim3(kScoreThreads), 0, st, K, qt,    \
-                               c->L.proj_np, seq_len, scores, d.B, d.S_max, d.r, d.r_score, rows);      \
+                               c->L.proj_np, seq_len, scores, d.B, d.S_max, d.r, d.r_score, rows,       \
+                               wg_range, d.n_sink, d.n_recent);                                                         \
         else                                                                                         \
             hipLaunchKernelGGL((scores_kernel<T, N, false>), grid, dim3(kScoreThreads), 0, st, K, qt,   \
-                               c->L.proj_np, seq_len, scores, d.B, d.S_max, d.r, d.r_score, rows);      \
+                               c->L.proj_np, seq_len, scores, d.B, d.S_max, d.r, d.r_score, rows,       \
+                               wg_range, d.n_sink, d.n_recent);                                                         \
         break;
     switch (nch) {
         SALS_SCORES_CASE(1) SALS_SCORES_CASE(2) SALS_SCORES_CASE(3) SALS_SCORES_CASE(4)
@@ -276,8 +282,11 @@ sals_status launch_scores(const sals_ctx* c, const void* Kc, const int32_t* seq_
 }
 
 // wl: also leave the recent-window lists (see WindowLists); by default none
+// score_ranges: the scores were written by this context's score kernel in the same step, which left its workgroups'
+// key ranges in the workspace (the chain then needs no range pass of its own)
 sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* seq_len, int32_t* idx,
-                        int32_t* n_sel, hipStream_t st, WindowLists wl = WindowLists{nullptr, nullptr, nullptr, 0})
+                        int32_t* n_sel, hipStream_t st, WindowLists wl = WindowLists{nullptr, nullptr, nullptr, 0},
+                        bool score_ranges = false)
 {
     const sals_desc& d = c->d;
     dim3 grid(d.B), block(kTopkThreads);
@@ -287,11 +296,19 @@ sals_status launch_topk(const sals_ctx* c, const float* scores, const int32_t* s
                        d.top_k, d.n_sink, d.n_recent)
     if (c->L.tm_chunks > 0) {
         const Layout& L = c->L;
-        TopkMultiWs ws{reinterpret_cast<uint2*>(c->ws + L.tm_part), reinterpret_cast<uint32_t*>(c->ws + L.tm_hist),
-                       reinterpret_cast<TopkMeta*>(c->ws + L.tm_meta), reinterpret_cast<uint2*>(c->ws + L.tm_cand)};
         const int nc = L.tm_chunks;
+        TopkMultiWs ws{};
+        ws.part = reinterpret_cast<uint2*>(c->ws + L.tm_part); ws.hist = reinterpret_cast<uint32_t*>(c->ws + L.tm_hist);
+        ws.meta = reinterpret_cast<TopkMeta*>(c->ws + L.tm_meta); ws.cand = reinterpret_cast<uint2*>(c->ws + L.tm_cand);
+        ws.range = ws.part; ws.n_range = nc;
         dim3 cgrid(nc, d.B);
-        hipLaunchKernelGGL(topk_range_kernel, cgrid, block, 0, st, scores, seq_len, ws, d.S_max, nc, d.n_sink, d.n_recent);
+        if (score_ranges) {
+            ws.range = reinterpret_cast<const uint2*>(c->ws + L.tm_srange);
+            ws.n_range = ceil_div(d.S_max, c->score_rows);
+        } else {
+            hipLaunchKernelGGL(topk_range_kernel, cgrid, block, 0, st, scores, seq_len, ws, d.S_max, nc, d.n_sink,
+                               d.n_recent);
+        }
         hipLaunchKernelGGL(topk_hist_kernel, cgrid, block, 0, st, scores, seq_len, ws, d.S_max, nc, d.n_sink, d.n_recent);
         hipLaunchKernelGGL(topk_place_kernel, cgrid, block, 0, st, scores, seq_len, ws, idx, d.S_max, nc, d.top_k,
                            d.n_sink, d.n_recent);
@@ -822,6 +839,23 @@ sals_status sals_latent_scores(sals_ctx* ctx, const void* q, const void* W, cons
 }
 
 namespace {
+// The score stage inside a decode step: as sals_latent_scores, and for sequences long enough for the selection
+// chain the score kernel also leaves its workgroups' key ranges for it.
+sals_status step_scores(sals_ctx* ctx, const void* q, const void* W, const void* Kc, const int32_t* seq_len,
+                        float* scores, hipStream_t st)
+{
+    if (!ctx || bad(q) || bad(W) || bad(Kc) || !seq_len || bad(scores)) return SALS_ERR_INVALID_ARG;
+    sals_status s = ctx->d.dtype == SALS_BF16
+                        ? launch_project<bf16_t, true>(ctx, W, q, nullptr, nullptr, nullptr, nullptr, st)
+                        : launch_project<float, true>(ctx, W, q, nullptr, nullptr, nullptr, nullptr, st);
+    if (s != SALS_OK) return s;
+    uint2* wg_range = ctx->L.tm_chunks > 0 ? reinterpret_cast<uint2*>(ctx->ws + ctx->L.tm_srange) : nullptr;
+    return ctx->d.dtype == SALS_BF16 ? launch_scores<bf16_t>(ctx, Kc, seq_len, scores, st, wg_range)
+                                     : launch_scores<float>(ctx, Kc, seq_len, scores, st, wg_range);
+}
+}  // namespace
+
+namespace {
 constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
 unsigned char* g_scratch_ptr[kMaxDevices];  // per device: address of `scratch` there (nullptr: not looked up yet)
@@ -896,7 +930,7 @@ sals_status sals_decode_step(sals_ctx* ctx, const void* q, const int32_t* q_pos,
     if (!scores) scores = reinterpret_cast<float*>(ctx->ws + ctx->L.scores);
     if (!idx) idx = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.idx);
     if (!n_sel) n_sel = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_sel);
-    sals_status s = sals_latent_scores(ctx, q, W, Kc, seq_len, scores, hip_stream);
+    sals_status s = step_scores(ctx, q, W, Kc, seq_len, scores, static_cast<hipStream_t>(hip_stream));
     if (s != SALS_OK) return s;
     if (fused_selection(ctx)) {  // one launch fewer: the logits kernel selects and leaves idx / n_sel behind
         if (bad(Vc)) return SALS_ERR_INVALID_ARG;
@@ -906,7 +940,8 @@ sals_status sals_decode_step(sals_ctx* ctx, const void* q, const int32_t* q_pos,
                    ? launch_attend<bf16_t>(ctx, q, q_pos, Kc, Vc, W, idx, n_sel, out, st, nullptr, 0, kPhaseAll, nullptr, &fs)
                    : launch_attend<float>(ctx, q, q_pos, Kc, Vc, W, idx, n_sel, out, st, nullptr, 0, kPhaseAll, nullptr, &fs);
     }
-    s = sals_topk_select(ctx, scores, seq_len, idx, n_sel, hip_stream);
+    s = launch_topk(ctx, scores, seq_len, idx, n_sel, static_cast<hipStream_t>(hip_stream),
+                    WindowLists{nullptr, nullptr, nullptr, 0}, ctx->L.tm_chunks > 0);
     if (s != SALS_OK) return s;
     return sals_sparse_attend(ctx, q, q_pos, Kc, Vc, W, idx, n_sel, out, hip_stream);
 }
@@ -973,7 +1008,7 @@ sals_status sals_decode_step_qv(sals_ctx* ctx, const void* q, const int32_t* q_p
     if (!scores) scores = reinterpret_cast<float*>(ctx->ws + ctx->L.scores);
     if (!idx) idx = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.idx);
     if (!n_sel) n_sel = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_sel);
-    sals_status s = sals_latent_scores(ctx, q, W, Kc, seq_len, scores, hip_stream);
+    sals_status s = step_scores(ctx, q, W, Kc, seq_len, scores, static_cast<hipStream_t>(hip_stream));
     if (s != SALS_OK) return s;
     if (fused_selection(ctx)) {  // one launch fewer: the logits kernel selects and leaves idx / n_sel behind
         const FusedSelect fs{scores, seq_len, ctx->d.top_k, ctx->d.n_sink, ctx->d.n_recent};
@@ -983,7 +1018,8 @@ sals_status sals_decode_step_qv(sals_ctx* ctx, const void* q, const int32_t* q_p
                    ? launch_attend<bf16_t>(ctx, q, q_pos, Kc, nullptr, W, idx, n_sel, out, st, &qv, 0, kPhaseAll, nullptr, &fs)
                    : launch_attend<float>(ctx, q, q_pos, Kc, nullptr, W, idx, n_sel, out, st, &qv, 0, kPhaseAll, nullptr, &fs);
     }
-    s = sals_topk_select(ctx, scores, seq_len, idx, n_sel, hip_stream);
+    s = launch_topk(ctx, scores, seq_len, idx, n_sel, static_cast<hipStream_t>(hip_stream),
+                    WindowLists{nullptr, nullptr, nullptr, 0}, ctx->L.tm_chunks > 0);
     if (s != SALS_OK) return s;
     return sals_sparse_attend_qv(ctx, q, q_pos, Kc, Vq, Vmeta, bits, W, idx, n_sel, out, hip_stream);
 }
@@ -1113,11 +1149,11 @@ sals_status sals_decode_step_window(sals_ctx* ctx, sals_ctx* win, const void* q,
     if (!scores) scores = reinterpret_cast<float*>(ctx->ws + ctx->L.scores);
     if (!idx) idx = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.idx);
     if (!n_sel) n_sel = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_sel);
-    s = sals_latent_scores(ctx, q, W, Kc, seq_len, scores, hip_stream);
+    s = step_scores(ctx, q, W, Kc, seq_len, scores, static_cast<hipStream_t>(hip_stream));
     if (s != SALS_OK) return s;
     // the selection kernel also writes the two passes' token lists (they follow from the sequence lengths)
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    s = launch_topk(ctx, scores, seq_len, idx, n_sel, st, window_lists(ctx, win));
+    s = launch_topk(ctx, scores, seq_len, idx, n_sel, st, window_lists(ctx, win), ctx->L.tm_chunks > 0);
     if (s != SALS_OK) return s;
     return window_attend(ctx, win, q, q_pos, Kc, Vc, W, Kw, Vw, W_hi, idx, n_sel, out, st, true);
 }
@@ -1216,10 +1252,10 @@ sals_status sals_decode_step_qv_window(sals_ctx* ctx, sals_ctx* win, const void*
     if (!scores) scores = reinterpret_cast<float*>(ctx->ws + ctx->L.scores);
     if (!idx) idx = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.idx);
     if (!n_sel) n_sel = reinterpret_cast<int32_t*>(ctx->ws + ctx->L.n_sel);
-    s = sals_latent_scores(ctx, q, W, Kc, seq_len, scores, hip_stream);
+    s = step_scores(ctx, q, W, Kc, seq_len, scores, static_cast<hipStream_t>(hip_stream));
     if (s != SALS_OK) return s;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    s = launch_topk(ctx, scores, seq_len, idx, n_sel, st, window_lists(ctx, win));
+    s = launch_topk(ctx, scores, seq_len, idx, n_sel, st, window_lists(ctx, win), ctx->L.tm_chunks > 0);
     if (s != SALS_OK) return s;
     return window_attend_qv(ctx, win, q, q_pos, Kc, Vq, Vmeta, bits, W, Kw, Vqw, Vmeta_w, W_hi, idx, n_sel, out, st, true);
 }
