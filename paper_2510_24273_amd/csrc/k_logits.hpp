@@ -50,7 +50,9 @@ template <int HEADS, int NTG, int NB> struct logits_cfg {
     static constexpr size_t LDS = 3 * (size_t)STAGE > 2 * (size_t)CS_BYTES ? 3 * (size_t)STAGE : 2 * (size_t)CS_BYTES;
 };
 
-template <typename T, int HEADS, int NTG, int NB>
+// GB: query heads of a KV head handled as one block of straight-line code (1, or 4 when the group size is a multiple
+// of 4): the LDS reads and the reductions of a block's heads are in flight together instead of one head after the other.
+template <typename T, int HEADS, int NTG, int NB, int GB>
 __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void attend_logits_kernel(
     const T* __restrict__ Kc, const T* __restrict__ UkP, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ n_sel, const T* __restrict__ q, const int32_t* __restrict__ q_pos,
@@ -63,6 +65,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
     constexpr int ES = (int)sizeof(T);
     static_assert(C::A_BYTES % (16 * NT) == 0 && C::B_BYTES % (16 * NT) == 0 && C::CS_BYTES % (16 * NT) == 0,
                   "tile / thread mismatch");
+    static_assert(kMaxGroup % GB == 0, "head blocks tile the group");
 
     // Workgroup id -> (sequence, token tile, head block).  Consecutive ids are dispatched to
     // different XCDs, each with its own L2, so every XCD gets one contiguous range of the work
@@ -328,14 +331,21 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
                     }
                 }
 #pragma unroll
-                for (int m = 0; m < kMaxGroup; ++m) {
-                    if (m < G) {
-                        const f32x4 q1 = *reinterpret_cast<const f32x4*>(&sQ[hh][m][p0]);
-                        const f32x4 q2 = *reinterpret_cast<const f32x4*>(&sQ[hh][m][kPairs + p0]);
+                for (int m0 = 0; m0 < kMaxGroup; m0 += GB) {
+                    if (m0 < G) {  // uniform; G is a multiple of GB
+                        f32x4 q1[GB], q2[GB];
 #pragma unroll
-                        for (int nb = 0; nb < NB; ++nb)
-                            dot[m][nb] += q1.x * k1[nb][0] + q1.y * k1[nb][1] + q1.z * k1[nb][2] + q1.w * k1[nb][3] +
-                                          q2.x * k2[nb][0] + q2.y * k2[nb][1] + q2.z * k2[nb][2] + q2.w * k2[nb][3];
+                        for (int mi = 0; mi < GB; ++mi) {
+                            q1[mi] = *reinterpret_cast<const f32x4*>(&sQ[hh][m0 + mi][p0]);
+                            q2[mi] = *reinterpret_cast<const f32x4*>(&sQ[hh][m0 + mi][kPairs + p0]);
+                        }
+#pragma unroll
+                        for (int mi = 0; mi < GB; ++mi)
+#pragma unroll
+                            for (int nb = 0; nb < NB; ++nb)
+                                dot[m0 + mi][nb] += q1[mi].x * k1[nb][0] + q1[mi].y * k1[nb][1] + q1[mi].z * k1[nb][2] +
+                                                    q1[mi].w * k1[nb][3] + q2[mi].x * k2[nb][0] + q2[mi].y * k2[nb][1] +
+                                                    q2[mi].z * k2[nb][2] + q2[mi].w * k2[nb][3];
                     }
                 }
             }
@@ -347,31 +357,44 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
 
     bool ok[NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const int slot = tok0 + (tg * NB + nb) * 32 + l32;
-        ok[nb] = slot < n;
+    for (int nb = 0; nb < NB; ++nb) ok[nb] = tok0 + (tg * NB + nb) * 32 + l32 < n;
 #pragma unroll
-        for (int m = 0; m < kMaxGroup; ++m) {
-            if (m < G) {
-                dot[m][nb] += __shfl_xor(dot[m][nb], 32, kWave);
-                if (hi == 0 && slot < lk) logits[((size_t)b * H + g * G + m) * lk + slot] = ok[nb] ? dot[m][nb] : -INFINITY;
+    for (int m0 = 0; m0 < kMaxGroup; m0 += GB) {
+        if (m0 < G) {  // uniform
+#pragma unroll
+            for (int mi = 0; mi < GB; ++mi)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) dot[m0 + mi][nb] += __shfl_xor(dot[m0 + mi][nb], 32, kWave);
+#pragma unroll
+            for (int mi = 0; mi < GB; ++mi)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int slot = tok0 + (tg * NB + nb) * 32 + l32;
+                    if (hi == 0 && slot < lk)
+                        logits[((size_t)b * H + g * G + m0 + mi) * lk + slot] = ok[nb] ? dot[m0 + mi][nb] : -INFINITY;
+                }
+            // softmax statistics of this tile, per head: the waves' (max, sum exp) merged in wave order below
+            float mx[GB], se[GB];
+#pragma unroll
+            for (int mi = 0; mi < GB; ++mi) {
+                mx[mi] = -INFINITY;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) mx[mi] = ok[nb] ? fmaxf(mx[mi], dot[m0 + mi][nb]) : mx[mi];
             }
-        }
-    }
-
-    // softmax statistics of this tile, per head: the waves' (max, sum exp) merged in wave order
 #pragma unroll
-    for (int m = 0; m < kMaxGroup; ++m) {
-        if (m < G) {  // uniform
-            float mx = -INFINITY;
+            for (int mi = 0; mi < GB; ++mi) mx[mi] = wave_max(mx[mi]);
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) mx = ok[nb] ? fmaxf(mx, dot[m][nb]) : mx;
-            mx = wave_max(mx);
-            float se = 0.f;
+            for (int mi = 0; mi < GB; ++mi) {
+                se[mi] = 0.f;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) se += (ok[nb] && hi == 0) ? __expf(dot[m][nb] - mx) : 0.f;
-            se = wave_sum(se);
-            if (lane == 0) sStat[hh][tg][m] = make_float2(mx, se);
+                for (int nb = 0; nb < NB; ++nb) se[mi] += (ok[nb] && hi == 0) ? __expf(dot[m0 + mi][nb] - mx[mi]) : 0.f;
+            }
+#pragma unroll
+            for (int mi = 0; mi < GB; ++mi) se[mi] = wave_sum(se[mi]);
+            if (lane == 0) {
+#pragma unroll
+                for (int mi = 0; mi < GB; ++mi) sStat[hh][tg][m0 + mi] = make_float2(mx[mi], se[mi]);
+            }
         }
     }
     __syncthreads();

@@ -329,14 +329,16 @@ __global__ __launch_bounds__(kTopkThreads) void topk_finish_kernel(const float* 
     __shared__ uint32_t s_sel[kTmCand];
     const int b = blockIdx.x, tid = threadIdx.x;
     write_window_lists(wl, seq_len, b, S_max, top_k + n_sink + n_recent, kTopkThreads);
-    // (requested together with the meta record; slots past the member count hold stale pairs and are masked)
-    const uint2 me_raw = tid < kTmCand ? ws.cand[(size_t)b * kTmCand + tid] : make_uint2(0u, 0u);
+    // (the candidate pair, the length and the meta record are requested together; slots past the member count hold
+    // stale pairs and are masked)
+    const uint2 me_raw = ws.cand[(size_t)b * kTmCand + min(tid, kTmCand - 1)];
+    const int S_v = ld_uniform_i32(seq_len + b);
     const TopkMeta m = ws.meta[b];
     if (m.fallback) {  // uniform
         topk_select_sequence<0>(sh, scores, seq_len, idx, n_sel, b, S_max, top_k, n_sink, n_recent);
         return;
     }
-    const int S = min(seq_len[b], S_max);
+    const int S = min(wave_uniform(S_v), S_max);
     const int k_tot = top_k + n_sink + n_recent;
     int32_t* out = idx + (size_t)b * k_tot;
     for (int t = tid; t < n_sink; t += kTopkThreads) out[t] = t;

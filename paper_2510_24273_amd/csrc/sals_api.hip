@@ -379,12 +379,12 @@ sals_status ensure_rope_table(const sals_ctx* cc, hipStream_t st)
 }
 
 // the logits kernels use more than the default 48 KB of dynamic LDS: raised once per context, on first use
-template <typename T> sals_status allow_logits_lds(const LogitsPlan& P);
+template <typename T> sals_status allow_logits_lds(const LogitsPlan& P, int group);
 template <typename T> sals_status ensure_lds_attr(const sals_ctx* cc)
 {
     sals_ctx* c = const_cast<sals_ctx*>(cc);
     if (c->lds_allowed) return SALS_OK;
-    if (allow_logits_lds<T>(c->plan) != SALS_OK) return SALS_ERR_HIP;
+    if (allow_logits_lds<T>(c->plan, c->d.H_q / c->d.H_kv) != SALS_OK) return SALS_ERR_HIP;
     c->lds_allowed = true;
     return SALS_OK;
 }
@@ -501,15 +501,18 @@ bool fused_selection(const sals_ctx* c)
            d.top_k + d.n_sink + d.n_recent <= kLsFusedMaxK && c->fuse_select;
 }
 
-template <typename T> sals_status allow_logits_lds(const LogitsPlan& P)
+template <typename T> sals_status allow_logits_lds(const LogitsPlan& P, int group)
 {
     auto allow = [](const void* kern, size_t bytes) {
         return bytes <= 48 * 1024 ||
                hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
     };
     bool ok = true;
-    if (P.pick == 1) ok = allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 2, 4, 2>), logits_cfg<2, 4, 2>::LDS);
-    else if (P.pick == 2) ok = allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 1, 4, 2>), logits_cfg<1, 4, 2>::LDS);
+    const bool g4 = group % 4 == 0;  // query heads in blocks of four
+    if (P.pick == 1) ok = g4 ? allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 2, 4, 2, 4>), logits_cfg<2, 4, 2>::LDS)
+                             : allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 2, 4, 2, 1>), logits_cfg<2, 4, 2>::LDS);
+    else if (P.pick == 2) ok = g4 ? allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 1, 4, 2, 4>), logits_cfg<1, 4, 2>::LDS)
+                                  : allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 1, 4, 2, 1>), logits_cfg<1, 4, 2>::LDS);
     else {
         ok = allow(reinterpret_cast<const void*>(SmallLogits<T>::get(P.nst, false)), kLsLds) &&
              allow(reinterpret_cast<const void*>(SmallLogits<T>::get(P.nst, true)), kLsLds);
@@ -546,7 +549,8 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
 #define SALS_LOGITS(HEADS, NTG, NB)                                                                              \
     do {                                                                                                     \
         typedef logits_cfg<HEADS, NTG, NB> LC;                                                               \
-        auto kern = attend_logits_kernel<T, HEADS, NTG, NB>;                                                 \
+        auto kern = (d.H_q / d.H_kv) % 4 == 0 ? attend_logits_kernel<T, HEADS, NTG, NB, 4>                   \
+                                              : attend_logits_kernel<T, HEADS, NTG, NB, 1>;                  \
         hipLaunchKernelGGL(kern, dim3(n_parts * (d.H_kv / HEADS) * d.B), dim3(LC::NT), LC::LDS, st,          \
                            static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,                     \
                            static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats, d.B,                \
