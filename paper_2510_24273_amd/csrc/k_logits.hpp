@@ -52,7 +52,9 @@ template <int HEADS, int NTG, int NB> struct logits_cfg {
 
 // GB: query heads of a KV head handled as one block of straight-line code (1, or 4 when the group size is a multiple
 // of 4): the LDS reads and the reductions of a block's heads are in flight together instead of one head after the other.
-template <typename T, int HEADS, int NTG, int NB, int GB>
+// GFIX: the group size when it is known at compile time (1 and 4, the common ones; 0: read from the arguments), which
+// takes the per-block branches out of the epilogue.
+template <typename T, int HEADS, int NTG, int NB, int GB, int GFIX>
 __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void attend_logits_kernel(
     const T* __restrict__ Kc, const T* __restrict__ UkP, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ n_sel, const T* __restrict__ q, const int32_t* __restrict__ q_pos,
@@ -65,7 +67,8 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
     constexpr int ES = (int)sizeof(T);
     static_assert(C::A_BYTES % (16 * NT) == 0 && C::B_BYTES % (16 * NT) == 0 && C::CS_BYTES % (16 * NT) == 0,
                   "tile / thread mismatch");
-    static_assert(kMaxGroup % GB == 0, "head blocks tile the group");
+    static_assert(kMaxGroup % GB == 0 && (GFIX == 0 || (GFIX % GB == 0 && GFIX <= kMaxGroup)), "head blocks tile the group");
+    constexpr int kGroupEnd = GFIX > 0 ? GFIX : kMaxGroup;
 
     // Workgroup id -> (sequence, token tile, head block).  Consecutive ids are dispatched to
     // different XCDs, each with its own L2, so every XCD gets one contiguous range of the work
@@ -91,7 +94,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
     const int hh = wave / NTG, tg = wave % NTG;   // head of the tile, token group
-    const int G = H / H_kv;
+    const int G = GFIX > 0 ? GFIX : H / H_kv;
     const int g = g0 + hh;
 
     // Everything the prologue needs from memory is requested before anything is waited for, from clamped
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
     int pos_reg[NSP];
 #pragma unroll
     for (int u = 0; u < NSP; ++u) pos_reg[u] = row_of(tok0 + min(tid + u * NT, C::TOK - 1));
-    constexpr int QP = (HEADS * kMaxGroup * kPairs + NT - 1) / NT;
+    constexpr int QP = (HEADS * (GFIX > 0 ? GFIX : kMaxGroup) * kPairs + NT - 1) / NT;
     float qa[QP], qb[QP];
 #pragma unroll
     for (int u = 0; u < QP; ++u) {
@@ -331,8 +334,8 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
                     }
                 }
 #pragma unroll
-                for (int m0 = 0; m0 < kMaxGroup; m0 += GB) {
-                    if (m0 < G) {  // uniform; G is a multiple of GB
+                for (int m0 = 0; m0 < kGroupEnd; m0 += GB) {
+                    if (GFIX > 0 || m0 < G) {  // uniform; G is a multiple of GB
                         f32x4 q1[GB], q2[GB];
 #pragma unroll
                         for (int mi = 0; mi < GB; ++mi) {
@@ -359,8 +362,8 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) ok[nb] = tok0 + (tg * NB + nb) * 32 + l32 < n;
 #pragma unroll
-    for (int m0 = 0; m0 < kMaxGroup; m0 += GB) {
-        if (m0 < G) {  // uniform
+    for (int m0 = 0; m0 < kGroupEnd; m0 += GB) {
+        if (GFIX > 0 || m0 < G) {  // uniform
 #pragma unroll
             for (int mi = 0; mi < GB; ++mi)
 #pragma unroll

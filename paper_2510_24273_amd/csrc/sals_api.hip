@@ -501,6 +501,15 @@ bool fused_selection(const sals_ctx* c)
            d.top_k + d.n_sink + d.n_recent <= kLsFusedMaxK && c->fuse_select;
 }
 
+// the instantiation of the 256-token logits kernel for a group size (query heads per KV head)
+template <typename T, int HEADS, int NTG, int NB> auto logits_kernel_for(int group)
+{
+    if (group == 1) return attend_logits_kernel<T, HEADS, NTG, NB, 1, 1>;
+    if (group == 4) return attend_logits_kernel<T, HEADS, NTG, NB, 4, 4>;
+    if (group % 4 == 0) return attend_logits_kernel<T, HEADS, NTG, NB, 4, 0>;
+    return attend_logits_kernel<T, HEADS, NTG, NB, 1, 0>;
+}
+
 template <typename T> sals_status allow_logits_lds(const LogitsPlan& P, int group)
 {
     auto allow = [](const void* kern, size_t bytes) {
@@ -508,11 +517,8 @@ template <typename T> sals_status allow_logits_lds(const LogitsPlan& P, int grou
                hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
     };
     bool ok = true;
-    const bool g4 = group % 4 == 0;  // query heads in blocks of four
-    if (P.pick == 1) ok = g4 ? allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 2, 4, 2, 4>), logits_cfg<2, 4, 2>::LDS)
-                             : allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 2, 4, 2, 1>), logits_cfg<2, 4, 2>::LDS);
-    else if (P.pick == 2) ok = g4 ? allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 1, 4, 2, 4>), logits_cfg<1, 4, 2>::LDS)
-                                  : allow(reinterpret_cast<const void*>(attend_logits_kernel<T, 1, 4, 2, 1>), logits_cfg<1, 4, 2>::LDS);
+    if (P.pick == 1) ok = allow(reinterpret_cast<const void*>(logits_kernel_for<T, 2, 4, 2>(group)), logits_cfg<2, 4, 2>::LDS);
+    else if (P.pick == 2) ok = allow(reinterpret_cast<const void*>(logits_kernel_for<T, 1, 4, 2>(group)), logits_cfg<1, 4, 2>::LDS);
     else {
         ok = allow(reinterpret_cast<const void*>(SmallLogits<T>::get(P.nst, false)), kLsLds) &&
              allow(reinterpret_cast<const void*>(SmallLogits<T>::get(P.nst, true)), kLsLds);
@@ -549,8 +555,7 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
 #define SALS_LOGITS(HEADS, NTG, NB)                                                                              \
     do {                                                                                                     \
         typedef logits_cfg<HEADS, NTG, NB> LC;                                                               \
-        auto kern = (d.H_q / d.H_kv) % 4 == 0 ? attend_logits_kernel<T, HEADS, NTG, NB, 4>                   \
-                                              : attend_logits_kernel<T, HEADS, NTG, NB, 1>;                  \
+        auto kern = logits_kernel_for<T, HEADS, NTG, NB>(d.H_q / d.H_kv);                                    \
         hipLaunchKernelGGL(kern, dim3(n_parts * (d.H_kv / HEADS) * d.B), dim3(LC::NT), LC::LDS, st,          \
                            static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,                     \
                            static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats, d.B,                \
