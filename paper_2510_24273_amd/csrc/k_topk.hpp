@@ -116,8 +116,23 @@ __device__ __forceinline__ void topk_select_sequence(TopkShared& sh, const float
     const int S_in_v = ld_uniform_i32(seq_len + b);  // (through the vector memory path: in flight with the scores)
     float raw[NREG];
     if (F4 > 0) {
+        if (vec_ok && (S_max & 3) == 0 && S_max >= 4) {  // uniform: every group lies wholly inside or outside the row
+            // all groups requested at once from clamped addresses (a load inside a branch would be waited for at the
+            // end of that branch: one memory round trip per group)
+            f32x4 v[F4 > 0 ? F4 : 1];
 #pragma unroll
-        for (int c = 0; c < (F4 > 0 ? F4 : 1); ++c) load_group(c, raw + 4 * c);
+            for (int c = 0; c < (F4 > 0 ? F4 : 1); ++c)
+                v[c] = *reinterpret_cast<const f32x4*>(s + min(token_of(4 * c), S_max - 4));
+#pragma unroll
+            for (int c = 0; c < (F4 > 0 ? F4 : 1); ++c) {
+                const bool in = token_of(4 * c) < S_max;
+                raw[4 * c] = in ? v[c].x : 0.f; raw[4 * c + 1] = in ? v[c].y : 0.f;
+                raw[4 * c + 2] = in ? v[c].z : 0.f; raw[4 * c + 3] = in ? v[c].w : 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < (F4 > 0 ? F4 : 1); ++c) load_group(c, raw + 4 * c);
+        }
     }
     const int S = min(wave_uniform(S_in_v), S_max);
 

@@ -62,20 +62,37 @@ __device__ __forceinline__ void tm_load_keys(const float* __restrict__ s, int S_
                                             uint32_t* keys)
 {
     const int tid = threadIdx.x;
+    float f[4 * kTmF4];
+    if ((S_max & 3) == 0 && S_max >= 4 && (reinterpret_cast<uintptr_t>(s) & 15) == 0) {  // uniform
+        // both groups requested at once from clamped addresses (no load inside a branch)
+        f32x4 v[kTmF4];
+#pragma unroll
+        for (int c = 0; c < kTmF4; ++c)
+            v[c] = *reinterpret_cast<const f32x4*>(s + min(chunk * kTmChunk + ((c * kTopkThreads + tid) << 2), S_max - 4));
+#pragma unroll
+        for (int c = 0; c < kTmF4; ++c) { f[4 * c] = v[c].x; f[4 * c + 1] = v[c].y; f[4 * c + 2] = v[c].z; f[4 * c + 3] = v[c].w; }
+    } else {
+#pragma unroll
+        for (int c = 0; c < kTmF4; ++c) {
+            const int j = chunk * kTmChunk + ((c * kTopkThreads + tid) << 2);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f[4 * c + e] = 0.f;
+            if (j + 3 < S_max && ((reinterpret_cast<uintptr_t>(s + j) & 15) == 0)) {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(s + j);
+                f[4 * c] = v.x; f[4 * c + 1] = v.y; f[4 * c + 2] = v.z; f[4 * c + 3] = v.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (j + e < S_max) f[4 * c + e] = s[j + e];
+            }
+        }
+    }
+    // (a group past the row read the row's last group: its tokens are at or past S_max >= hi, so their keys are 0)
 #pragma unroll
     for (int c = 0; c < kTmF4; ++c) {
         const int j = chunk * kTmChunk + ((c * kTopkThreads + tid) << 2);
-        float f[4] = {0.f, 0.f, 0.f, 0.f};
-        if (j + 3 < S_max && ((reinterpret_cast<uintptr_t>(s + j) & 15) == 0)) {
-            const f32x4 v = *reinterpret_cast<const f32x4*>(s + j);
-            f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
-        } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (j + e < S_max) f[e] = s[j + e];
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) keys[4 * c + e] = (j + e >= lo && j + e < hi) ? score_key(f[e]) : 0u;
+        for (int e = 0; e < 4; ++e) keys[4 * c + e] = (j + e >= lo && j + e < hi) ? score_key(f[4 * c + e]) : 0u;
     }
 }
 __device__ __forceinline__ int tm_token(int chunk, int i)
