@@ -344,3 +344,19 @@ def make_window(w: Workload, L: dict, layer: int = 0):
                 ring[b, t % n_w, w.r:] = store(extra, w.dtype)
         out[name] = ring
     return out
+
+
+# ---- offline calibration (Sec. 4.2) ----------------------------------------------------------
+
+def make_calibration_keys(seed: int, n_tok: int, D: int, dtype: str = "bf16", decay: float = 0.97, heads: int = 1):
+    """Stand-in for the pre-RoPE keys of a calibration set (the paper collects them from 512 sequences of 4096 C4
+    tokens): n_tok rows of width D = n*d with a planted spectrum.  Row t = sum_c z[t, c] * sigma_c * dir_c with
+    z ~ N(0, 1), sigma_c = decay^(c/2) (eigenvalues of the covariance decay geometrically, so neighbouring
+    eigenvectors are separated by a fixed relative gap) and dir_c the columns of a seeded orthogonal matrix.  With
+    heads > 1 the directions mix the heads' coordinate blocks (a joint basis, the situation of Lemma 1).
+    Storage-rounded; returns the stored array [n_tok, D]."""
+    rng = np.random.default_rng(seed)
+    dirs, _ = np.linalg.qr(rng.standard_normal((D, D)))
+    sigma = decay ** (0.5 * np.arange(D))
+    z = rng.standard_normal((n_tok, D))
+    return store((z * sigma) @ dirs.T, dtype)
