@@ -364,6 +364,51 @@ sals_status sals_overlap_score(sals_ctx* ctx, const void* q, const int32_t* q_po
                                const int32_t* seq_len, const int32_t* idx, const int32_t* n_sel,
                                float* os, void* hip_stream);
 
+/* ---- offline calibration (Sec. 4.2) -------------------------------------------------
+ * The projection into the latent space is found offline from the pre-RoPE keys of a calibration set: with all
+ * heads of a token merged into one row of width D = n*d, the covariance C = K^T K of the stacked keys is
+ * eigen-decomposed and the r leading eigenvectors form U_r.  These two calls need no context.
+ *
+ * sals_calib_accumulate adds the tokens of one call to the covariance:  C += K^T K  (fp64 C; products of the
+ * stored values, summed in fp32 over at most 4096 tokens at a time on the matrix cores, then added in fp64).
+ *   dtype      SALS_BF16 | SALS_F32 (host)
+ *   K          [n_tok, D] T (device)   calibration keys, one token per row
+ *   n_tok      >= 1 (host)
+ *   D          multiple of 128, at most 8192 (host)
+ *   C          [D, D] fp64 (device)    in/out; the caller zeroes it before the first call
+ *   workspace  device, 256-byte aligned, at least sals_calib_accumulate_workspace_bytes(dtype, D) bytes, no contents
+ *              kept between calls (it holds the transposed keys of a chunk)
+ * Asynchronous on hip_stream.  Errors: SALS_ERR_INVALID_ARG (NULL or misaligned pointer, bad size),
+ * SALS_ERR_WORKSPACE, SALS_ERR_HIP.
+ *
+ * sals_calib_eigenvectors computes the eigen-decomposition of C (symmetric, positive semi-definite) by one-sided
+ * Jacobi rotations of its rows in fp64 and returns all eigenvalues in descending order and the r leading eigenvectors:
+ *   C          [D, D] fp64 (device)    in; OVERWRITTEN (its rows become eigenvalue times eigenvector)
+ *   D          multiple of 256, at most 8192;  r  1 .. D
+ *   dtype      storage type T of U
+ *   eigval     [D] fp64 (device)       out, descending: the first r are converged eigenvalues; the others are the
+ *                                      norms their rows had when the leading ones had converged (approximations)
+ *   U          [D, r] T (device)       out: column i is the eigenvector of eigval[i], unit length, signed so that
+ *                                      its largest component is positive, rounded once to T; the layout
+ *                                      sals_pack_weights takes.  Eigenvalues below 1e-13 of the largest are zero to
+ *                                      working precision: their vectors are not resolved (whatever direction the
+ *                                      row was left with).
+ *   workspace  device, 256-byte aligned, at least sals_calib_eigenvectors_workspace_bytes(D) bytes
+ *   max_sweeps at least 1 (host): a sweep rotates every pair of rows once; the call stops after the first sweep in
+ *              which no rotation that involved one of the r largest rows turned by more than 1e-11, or after
+ *              max_sweeps
+ *   sweeps     host int32, out (may be NULL): sweeps run; the negative of that number if the limit was reached
+ *              before convergence (the results are then the current approximation)
+ * BLOCKING: it waits for hip_stream once per sweep to read the convergence measure, so it cannot be captured.
+ * Errors as above. */
+size_t sals_calib_accumulate_workspace_bytes(int32_t dtype, int32_t D);
+sals_status sals_calib_accumulate(int32_t dtype, const void* K, int64_t n_tok, int32_t D, double* C,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t sals_calib_eigenvectors_workspace_bytes(int32_t D);
+sals_status sals_calib_eigenvectors(double* C, int32_t D, int32_t r, int32_t dtype, double* eigval, void* U,
+                                    void* workspace, size_t workspace_bytes, int32_t max_sweeps, int32_t* sweeps,
+                                    void* hip_stream);
+
 /* ---- measurement aid --------------------------------------------------------------
  * Per-stage timing for roofline figures.  While enabled, every stage below (one kernel;
  * for the selection of sequences above 32768 tokens a chain of four, for the logits of very

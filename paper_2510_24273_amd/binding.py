@@ -32,6 +32,8 @@ EXPORTS = (
     "sals_window_append", "sals_sparse_attend_window", "sals_decode_step_window", "sals_overlap_score",
     "sals_latent_scores_noalloc", "sals_compress_prefill",
     "sals_window_append_qv", "sals_sparse_attend_qv_window", "sals_decode_step_qv_window",
+    "sals_calib_accumulate_workspace_bytes", "sals_calib_accumulate",
+    "sals_calib_eigenvectors_workspace_bytes", "sals_calib_eigenvectors",
 )
 N_KERNELS = 9
 
@@ -86,12 +88,19 @@ def load_library() -> ctypes.CDLL:
     lib.sals_decode_step_qv_window.argtypes = [vp, vp, vp, i32p, vp, vp, vp, ctypes.c_int, vp, vp, vp, vp, vp, i32p, vp,
                                                f32p, i32p, i32p, vp]
     lib.sals_overlap_score.argtypes = [vp, vp, i32p, vp, i32p, i32p, i32p, f32p, vp]
+    lib.sals_calib_accumulate_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    lib.sals_calib_accumulate.argtypes = [ctypes.c_int32, vp, ctypes.c_int64, ctypes.c_int32, vp, vp, ctypes.c_size_t, vp]
+    lib.sals_calib_eigenvectors_workspace_bytes.argtypes = [ctypes.c_int32]
+    lib.sals_calib_eigenvectors.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, vp,
+                                            ctypes.c_size_t, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), vp]
     lib.sals_kernel_name.restype = ctypes.c_char_p
     lib.sals_kernel_name.argtypes = [ctypes.c_int]
     lib.sals_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.sals_profile_collect.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
     for name in EXPORTS[1:]:
-        if name not in ("sals_destroy", "sals_kernel_name"):
+        if name.endswith("_workspace_bytes") and name.startswith("sals_calib"):
+            getattr(lib, name).restype = ctypes.c_size_t
+        elif name not in ("sals_destroy", "sals_kernel_name"):
             getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -140,6 +149,44 @@ def latent_scores_noalloc(desc: SalsDesc, q, W, Kc, seq_len, scores):
     st = _lib.sals_latent_scores_noalloc(ctypes.byref(desc), _p(q), _p(W), _p(Kc), _p(seq_len), _p(scores), _stream())
     if st != SALS_OK:
         raise SalsError(st, "sals_latent_scores_noalloc")
+
+
+def _dtype_code(t):
+    return {torch.bfloat16: SALS_BF16, torch.float32: SALS_F32}[t]
+
+
+def calib_accumulate(keys, C):
+    """Offline calibration (Sec. 4.2): C += keys^T keys.  keys [n_tok, D] bf16 | f32, C [D, D] float64, both on the
+    device; the transposed-chunk workspace is a torch tensor allocated here."""
+    n_tok, D = keys.shape
+    dt = _dtype_code(keys.dtype)
+    nbytes = int(_lib.sals_calib_accumulate_workspace_bytes(dt, D))
+    if nbytes == 0:
+        raise SalsError(1, "sals_calib_accumulate_workspace_bytes")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=keys.device)
+    st = _lib.sals_calib_accumulate(dt, _p(keys), int(n_tok), int(D), _p(C), _p(ws), nbytes, _stream())
+    if st != SALS_OK:
+        raise SalsError(st, "sals_calib_accumulate")
+    return ws  # (kept alive by the caller until the stream has run)
+
+
+def calib_eigenvectors(C, r, dtype, max_sweeps=80):
+    """Offline calibration (Sec. 4.2): eigenvalues (descending, float64 [D]) and the r leading eigenvectors
+    (U [D, r] in `dtype`) of the covariance C [D, D] float64, which is overwritten.  Blocking.
+    Returns (eigval, U, sweeps)."""
+    D = C.shape[0]
+    nbytes = int(_lib.sals_calib_eigenvectors_workspace_bytes(D))
+    if nbytes == 0:
+        raise SalsError(1, "sals_calib_eigenvectors_workspace_bytes")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=C.device)
+    eigval = torch.empty(D, dtype=torch.float64, device=C.device)
+    U = torch.empty(D, r, dtype=dtype, device=C.device)
+    sweeps = ctypes.c_int32(0)
+    st = _lib.sals_calib_eigenvectors(_p(C), int(D), int(r), _dtype_code(dtype), _p(eigval), _p(U), _p(ws), nbytes,
+                                      int(max_sweeps), ctypes.byref(sweeps), _stream())
+    if st != SALS_OK:
+        raise SalsError(st, "sals_calib_eigenvectors")
+    return eigval, U, int(sweeps.value)
 
 
 def _p(t):

@@ -29,9 +29,13 @@ struct PrefillArgs {
     const int32_t* seq_len;  // [B] first row to write
     const int32_t* n_new;    // [B] tokens of each sequence (<= n_tok), or nullptr: n_tok everywhere
     int n_tok, D, r, S_max, B, nproj;
+    double* cacc;            // SYRK form only: [n_tok, r] fp64 sums the tile products are added to
 };
 
-template <typename T, int TOK, int NL>
+// SYRK: the same tiles and pipeline as a plain product of two row-major operands, out[t, l] = sum_c X[t, c] UT[l, c],
+// whose fp32 tile sums are added to an fp64 matrix instead of being stored as cache rows (the covariance of the
+// offline calibration, Sec. 4.2, with X = UT = the transposed keys and c running over the calibration tokens).
+template <typename T, int TOK, int NL, bool SYRK = false>
 __global__ __launch_bounds__(kPfThreads, 2) void prefill_compress_kernel(PrefillArgs a)
 {
     static_assert((NL == 128 || NL == 64) && (TOK == 256 || (TOK == 128 && NL == 128)), "tile");
@@ -51,8 +55,8 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_compress_kernel(Prefill
     const int wm = wave / WN, wn = wave % WN;
     const int b = blockIdx.z / a.nproj, proj = blockIdx.z - b * a.nproj;
     const int tok0 = blockIdx.x * kPfTok, lat0 = blockIdx.y * NL;
-    const int n_b = a.n_new ? min(max(ld_uniform_i32(a.n_new + b), 0), a.n_tok) : a.n_tok;
-    const int row0_v = ld_uniform_i32(a.seq_len + b);
+    const int n_b = (!SYRK && a.n_new) ? min(max(ld_uniform_i32(a.n_new + b), 0), a.n_tok) : a.n_tok;
+    const int row0_v = SYRK ? 0 : ld_uniform_i32(a.seq_len + b);
     const T* X = static_cast<const T*>(a.X[proj]) + (size_t)b * a.n_tok * a.D;
     const T* UT = static_cast<const T*>(a.UT[proj]);
 
@@ -135,6 +139,22 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_compress_kernel(Prefill
 
     // acc[mb][nb][4a+c] is token wm*MB*32 + mb*32 + 8a + 4hi + c of the tile, latent coordinate wn*64 + nb*32 + l32:
     // for fixed (a, c) the 32 lanes of a half wave write 32 consecutive elements of one cache row
+    if constexpr (SYRK) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int t = tok0 + (wm * MB + mb) * 32 + (v >> 2) * 8 + hi * 4 + (v & 3);
+                if (t < n_b) {
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb) {
+                        double* dst = a.cacc + (size_t)t * a.r + lat0 + wn * 64 + nb * 32 + l32;
+                        *dst += (double)acc[mb][nb][v];
+                    }
+                }
+            }
+        return;
+    }
     const int row0 = wave_uniform(row0_v);
     T* cache = static_cast<T*>(a.cache[proj]) + (size_t)b * a.S_max * a.r;
 #pragma unroll

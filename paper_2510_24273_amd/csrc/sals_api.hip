@@ -7,12 +7,14 @@
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
+#include <functional>
 #include <mutex>
 #include <new>
 #include <vector>
 
 #include "common.hpp"
 #include "k_attend.hpp"
+#include "k_calib.hpp"
 #include "k_dense.hpp"
 #include "k_logits.hpp"
 #include "k_logits_small.hpp"
@@ -1300,6 +1302,142 @@ sals_status sals_overlap_score(sals_ctx* ctx, const void* q, const int32_t* q_po
     if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     hipLaunchKernelGGL(overlap_merge_kernel, dim3(ceil_div(d.B * d.H_q, 256)), dim3(256), 0, st, part, os,
                        d.B * d.H_q, L.dn_chunks);
+    return launch_status();
+}
+
+
+}  // extern "C"
+
+// ---- offline calibration (Sec. 4.2) ----------------------------------------------------
+namespace {
+constexpr int64_t kCalChunk = 4096;  // tokens whose products are summed in fp32 before they are added to the fp64 matrix
+size_t cal_es(int32_t dtype) { return dtype == SALS_BF16 ? 2 : 4; }
+
+template <typename T>
+sals_status calib_accumulate_t(const void* K, int64_t n_tok, int D, double* C, void* ws, hipStream_t st)
+{
+    const T* X = static_cast<const T*>(K);
+    T* XT = static_cast<T*>(ws);
+    for (int64_t t0 = 0; t0 < n_tok; t0 += kCalChunk) {
+        const int64_t n = std::min(kCalChunk, n_tok - t0);
+        const int64_t n_pad = (n + 63) / 64 * 64;  // whole 64-byte steps of the contraction axis, zero filled
+        hipLaunchKernelGGL((calib_transpose_kernel<T>), dim3((unsigned)(n_pad / kCalTile), (unsigned)ceil_div(D, kCalTile)),
+                           dim3(256), 0, st, X + (size_t)t0 * D, XT, (long long)n, D, (long long)n_pad);
+        PrefillArgs a{};
+        a.X[0] = XT; a.UT[0] = XT; a.cache[0] = nullptr; a.seq_len = nullptr; a.n_new = nullptr;
+        a.n_tok = D; a.D = (int)n_pad; a.r = D; a.S_max = D; a.B = 1; a.nproj = 1; a.cacc = C;
+        if (D % 256 == 0 && D >= 1024) {
+            hipLaunchKernelGGL((prefill_compress_kernel<T, 256, 128, true>), dim3(D / 256, D / 128, 1), dim3(kPfThreads),
+                               prefill_lds_bytes(256, 128), st, a);
+        } else {
+            hipLaunchKernelGGL((prefill_compress_kernel<T, 128, 128, true>), dim3(D / 128, D / 128, 1), dim3(kPfThreads),
+                               prefill_lds_bytes(128, 128), st, a);
+        }
+        if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+    }
+    return SALS_OK;
+}
+
+template <typename T> sals_status calib_lds_attr()
+{
+    static std::mutex m;
+    static bool done[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SALS_ERR_HIP;
+    std::lock_guard<std::mutex> lock(m);
+    if (done[dev]) return SALS_OK;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_compress_kernel<T, 256, 128, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_lds_bytes(256, 128)) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_compress_kernel<T, 128, 128, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_lds_bytes(128, 128)) != hipSuccess)
+        return SALS_ERR_HIP;
+    done[dev] = true;
+    return SALS_OK;
+}
+}  // namespace
+
+extern "C" {
+
+size_t sals_calib_accumulate_workspace_bytes(int32_t dtype, int32_t D)
+{
+    if ((dtype != SALS_BF16 && dtype != SALS_F32) || D < 128 || D % 128 != 0 || D > kCalMaxD) return 0;
+    return align_up((size_t)D * kCalChunk * cal_es(dtype));
+}
+
+sals_status sals_calib_accumulate(int32_t dtype, const void* K, int64_t n_tok, int32_t D, double* C, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream)
+{
+    if ((dtype != SALS_BF16 && dtype != SALS_F32) || bad(K) || bad(C) || n_tok < 1 || D < 128 || D % 128 != 0 || D > kCalMaxD)
+        return SALS_ERR_INVALID_ARG;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 ||
+        workspace_bytes < sals_calib_accumulate_workspace_bytes(dtype, D))
+        return SALS_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (dtype == SALS_BF16) {
+        if (calib_lds_attr<bf16_t>() != SALS_OK) return SALS_ERR_HIP;
+        return calib_accumulate_t<bf16_t>(K, n_tok, D, C, workspace, st);
+    }
+    if (calib_lds_attr<float>() != SALS_OK) return SALS_ERR_HIP;
+    return calib_accumulate_t<float>(K, n_tok, D, C, workspace, st);
+}
+
+size_t sals_calib_eigenvectors_workspace_bytes(int32_t D)
+{
+    if (D < kCalThreads || D % kCalThreads != 0 || D > kCalMaxD) return 0;
+    // convergence slots [D / 2], row norms and signs [D] each
+    return align_up((size_t)(D / 2) * 8) + 2 * align_up((size_t)D * 8);
+}
+
+sals_status sals_calib_eigenvectors(double* C, int32_t D, int32_t r, int32_t dtype, double* eigval, void* U, void* workspace,
+                                    size_t workspace_bytes, int32_t max_sweeps, int32_t* sweeps, void* hip_stream)
+{
+    if ((dtype != SALS_BF16 && dtype != SALS_F32) || bad(C) || !eigval || bad(U) || D < kCalThreads || D % kCalThreads != 0 ||
+        D > kCalMaxD || r < 1 || r > D || max_sweeps < 1)
+        return SALS_ERR_INVALID_ARG;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 ||
+        workspace_bytes < sals_calib_eigenvectors_workspace_bytes(D))
+        return SALS_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    double* conv = reinterpret_cast<double*>(ws);
+    double* lam = reinterpret_cast<double*>(ws + align_up((size_t)(D / 2) * 8));
+    double* sgn = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(lam) + align_up((size_t)D * 8));
+    std::vector<double> h_conv((size_t)D / 2), h_lam((size_t)D);
+    auto row_norms = [&]() -> bool {  // row norms to the host (blocking)
+        hipLaunchKernelGGL(calib_rownorm_kernel, dim3(D), dim3(kCalThreads), 0, st, C, D, lam, sgn);
+        return hipMemcpyAsync(h_lam.data(), lam, (size_t)D * 8, hipMemcpyDeviceToHost, st) == hipSuccess &&
+               hipStreamSynchronize(st) == hipSuccess;
+    };
+    if (!row_norms()) return SALS_ERR_HIP;
+    const double n0 = *std::max_element(h_lam.begin(), h_lam.end());
+    const double floor = 1e-13 * n0;
+    double lead = 0.0;  // first sweep: every rotation counts
+    int done = 0;
+    bool converged = !(n0 > 0.0);  // the zero matrix needs no rotation
+    while (done < max_sweeps && !converged) {
+        if (hipMemsetAsync(conv, 0, (size_t)(D / 2) * 8, st) != hipSuccess) return SALS_ERR_HIP;
+        for (int step = 0; step < D - 1; ++step)
+            hipLaunchKernelGGL(calib_jacobi_step_kernel, dim3(D / 2), dim3(kCalThreads), 0, st, C, D, step, floor, lead, conv);
+        if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+        if (hipMemcpyAsync(h_conv.data(), conv, (size_t)(D / 2) * 8, hipMemcpyDeviceToHost, st) != hipSuccess) return SALS_ERR_HIP;
+        if (!row_norms()) return SALS_ERR_HIP;
+        double worst = 0.0;
+        for (double v : h_conv) worst = std::max(worst, v);
+        ++done;
+        // a rotation by less than 1e-11 no longer moves an eigenvector; only pairs with a row among the r largest
+        // (a little below the r-th largest norm, so that the r-th itself is in) are asked to have converged
+        converged = worst <= 1e-11;
+        std::vector<double> sorted(h_lam);
+        std::nth_element(sorted.begin(), sorted.begin() + (r - 1), sorted.end(), std::greater<double>());
+        lead = 0.999 * sorted[(size_t)r - 1];
+    }
+    if (dtype == SALS_BF16)
+        hipLaunchKernelGGL((calib_select_kernel<bf16_t>), dim3(D), dim3(kCalThreads), 0, st, C, lam, sgn, D, r, eigval,
+                           static_cast<bf16_t*>(U));
+    else
+        hipLaunchKernelGGL((calib_select_kernel<float>), dim3(D), dim3(kCalThreads), 0, st, C, lam, sgn, D, r, eigval,
+                           static_cast<float*>(U));
+    if (sweeps) *sweeps = converged ? done : -done;
     return launch_status();
 }
 
