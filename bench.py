@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer buffer sets (0 = workload default)")
-    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg4_rhalf,cfg2_qv4,cfg4_qv4,cfg2_comp,cfg2_win,cfg3a_win,cfg4_cap2x,cfg2_qvwin,t6_b16_s4096_12,t6w_b16_s4096_12,prefill_cfg2,prefill_cfg3b",
+    ap.add_argument("--extras", default="cfg3a,cfg3b,cfg4,cfg5,cfg4_rhalf,cfg2_qv4,cfg4_qv4,cfg2_comp,cfg2_win,cfg3a_win,cfg4_cap2x,cfg2_qvwin,t6_b16_s4096_12,t6w_b16_s4096_12,prefill_cfg2,prefill_cfg3b,calib_cfg3b",
                     help="other configurations reported under 'extra' (comma list, '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
@@ -207,6 +207,52 @@ def measure_prefill(w, steps, torch, binding, roofline):
     return {"workload": f"prefill_{w.name}", "tokens": w.B * w.S, "us_per_call": round(us, 2), "flops": flops,
             "achieved_TFLOPs": round(flops / (us * 1e-6) / 1e12, 1), "mfma_frac": round(flops / (us * 1e-6) / 1e12 / peak, 4),
             "bytes": byts, "hbm_frac": round(byts / (us * 1e-6) / 1e9 / roofline.HBM_PEAK_GBPS, 4)}
+
+
+def measure_calibration(w, n_tok, steps, torch, binding, roofline):
+    """Offline calibration at the key width of configuration w: covariance of n_tok synthetic calibration keys (timed
+    with events on the launch stream, against the bf16 matrix peak) and the r leading eigenvectors (wall time of the
+    blocking call; every Jacobi step reads and writes the whole fp64 matrix once, so the figure next to it is that
+    stream's bytes per second: a matrix of up to 4096 rows stays in the 256 MB last-level cache, which is why the
+    figure can exceed what HBM delivers)."""
+    dev = "cuda:0"
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    D = w.D_kv
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(10_000 * w.cfg_id + 91)
+    # planted spectrum (eigenvalues decaying like 1/(c+1)) along seeded directions, generated on the device
+    dirs = torch.linalg.qr(torch.randn((D, D), generator=gen, device=dev, dtype=torch.float32))[0]
+    sigma = (torch.arange(1, D + 1, device=dev, dtype=torch.float32)) ** -0.5
+    X = ((torch.randn((n_tok, D), generator=gen, device=dev, dtype=torch.float32) * sigma) @ dirs.T).to(dt)
+    C = torch.zeros((D, D), dtype=torch.float64, device=dev)
+    ws = binding.calib_accumulate(X, C)           # warm-up
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    C.zero_()
+    e0.record()
+    for _ in range(steps):
+        ws = binding.calib_accumulate(X, C)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / steps
+    flops = 2 * n_tok * D * D
+    peak = roofline.MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else roofline.VALU_F32_PEAK_TFLOPS
+    C.div_(steps)
+    t0 = time.perf_counter()
+    lam, U, sweeps = binding.calib_eigenvectors(C, w.r, dt)
+    torch.cuda.synchronize()
+    eig_ms = (time.perf_counter() - t0) * 1e3
+    n_steps = abs(sweeps) * (D - 1)
+    step_bytes = 2 * D * D * 8    # every step reads and writes the whole matrix once
+    del X, ws, dirs
+    torch.cuda.empty_cache()
+    return {"workload": f"calib_{w.name}", "D": D, "r": w.r, "tokens": n_tok, "covariance_us_per_call": round(us, 1),
+            "covariance_flops": flops, "covariance_TFLOPs": round(flops / (us * 1e-6) / 1e12, 1),
+            "covariance_mfma_frac": round(flops / (us * 1e-6) / 1e12 / peak, 4),
+            "eigenvectors_ms": round(eig_ms, 1), "sweeps": sweeps, "jacobi_steps": n_steps,
+            "jacobi_us_per_step": round(eig_ms * 1e3 / max(n_steps, 1), 2),
+            "jacobi_matrix_GBps": round(step_bytes * n_steps / (eig_ms * 1e-3) / 1e9, 1),
+            "lambda_ratio_r": float(lam[w.r - 1] / lam[0])}
 
 
 def timed(torch, fn, steps, warmup):
@@ -388,6 +434,10 @@ def main():
         if name.startswith("prefill_"):   # the prompt of that configuration compressed in one call
             log(f"[bench] extra {name}")
             extra[name] = measure_prefill(synth.lookup(name[len("prefill_"):]), max(5, a.steps // 3), torch, binding, roofline)
+            continue
+        if name.startswith("calib_"):     # offline calibration at that configuration's key width and rank
+            log(f"[bench] extra {name}")
+            extra[name] = measure_calibration(synth.lookup(name[len("calib_"):]), 65536, max(3, a.steps // 6), torch, binding, roofline)
             continue
         we = synth.lookup(name)
         per = roofline.algorithmic_bytes(we) + we.r * we.D_kv * we.esize

@@ -1326,7 +1326,7 @@ sals_status calib_accumulate_t(const void* K, int64_t n_tok, int D, double* C, v
         PrefillArgs a{};
         a.X[0] = XT; a.UT[0] = XT; a.cache[0] = nullptr; a.seq_len = nullptr; a.n_new = nullptr;
         a.n_tok = D; a.D = (int)n_pad; a.r = D; a.S_max = D; a.B = 1; a.nproj = 1; a.cacc = C;
-        if (D % 256 == 0 && D >= 1024) {
+        if (D % 256 == 0 && D >= 2048) {  // (below that the larger tile leaves most of the chip without a workgroup)
             hipLaunchKernelGGL((prefill_compress_kernel<T, 256, 128, true>), dim3(D / 256, D / 128, 1), dim3(kPfThreads),
                                prefill_lds_bytes(256, 128), st, a);
         } else {

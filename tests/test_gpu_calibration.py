@@ -42,7 +42,7 @@ def _check_cov(C_gpu, X_store, chunk_tokens=4096):
 
 
 @pytest.mark.parametrize("dtype,D,n", [("bf16", 256, 1000), ("bf16", 512, 9001), ("f32", 256, 4200),
-                                        ("bf16", 1024, 5000), ("bf16", 128, 64), ("f32", 384, 1)])
+                                        ("bf16", 1024, 5000), ("bf16", 2048, 300), ("bf16", 128, 64), ("f32", 384, 1)])
 def test_covariance_matches_the_oracle(dtype, D, n):
     print(f"[case] covariance {dtype} D={D} n={n}", flush=True)
     X = synth.make_calibration_keys(100 + D + n, n, D, dtype, decay=0.98)
