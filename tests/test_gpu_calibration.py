@@ -202,3 +202,31 @@ def test_bad_arguments_are_refused():
                                               1024, 5, ctypes.byref(n), None)
     assert binding.status_string(st) == "SALS_ERR_WORKSPACE"
     torch.cuda.synchronize()
+
+
+def test_calibrated_projector_feeds_the_decode_path(oracle):
+    """The projector the calibration returns has the layout the rest of the library takes: pack it, compress keys
+    with it and run a decode step; every stage against the oracle with the same projector."""
+    print("[case] calibrated projector in a decode step", flush=True)
+    w = synth.shrink(synth.CONFIGS["cfg2"], B=2, S=600, H=4, H_kv=4, r=128, top_k=64, n_layers=1, plant=2)
+    keys = synth.make_calibration_keys(31, 3000, w.D_kv, w.dtype, decay=0.985)
+    C = _cov_gpu(keys)
+    _, U, sweeps = binding.calib_eigenvectors(C, w.r, torch.bfloat16)
+    torch.cuda.synchronize()
+    assert sweeps > 0
+    L = synth.make_layer(w, 0)
+    U_bits = U.view(torch.int16).cpu().numpy().view(np.uint16)
+    L["Uk"] = U_bits.copy()
+    L["Uv"] = U_bits.copy()
+    ctx = gu.make_ctx(w)
+    G = gu.upload(L, ctx)
+    R = gu.run_stages(ctx, w, G)
+    for b in range(w.B):
+        gu.check_sequence(oracle, w, L, R, b)
+    # compression with the calibrated projector keeps what the spectrum says it keeps
+    x = synth.widen(keys[:64])
+    kt = x @ synth.widen(U_bits)
+    lam_ref, _ = cal.leading_eigenvectors(cal.covariance(synth.widen(keys)), w.r)
+    kept = np.sum(kt * kt) / np.sum(x * x)
+    assert abs(kept - np.sum(lam_ref[: w.r]) / np.sum(lam_ref)) < 0.05
+    ctx.close()
