@@ -370,14 +370,15 @@ sals_status sals_overlap_score(sals_ctx* ctx, const void* q, const int32_t* q_po
  * eigen-decomposed and the r leading eigenvectors form U_r.  These two calls need no context.
  *
  * sals_calib_accumulate adds the tokens of one call to the covariance:  C += K^T K  (fp64 C; products of the
- * stored values, summed in fp32 over at most 4096 tokens at a time on the matrix cores, then added in fp64).
+ * stored values, summed in fp32 over at most 4096 tokens at a time on the matrix cores, then added in fp64; the
+ * upper triangle is computed and mirrored, so C leaves the call exactly symmetric).
  *   dtype      SALS_BF16 | SALS_F32 (host)
  *   K          [n_tok, D] T (device)   calibration keys, one token per row
  *   n_tok      >= 1 (host)
  *   D          multiple of 128, at most 8192 (host)
  *   C          [D, D] fp64 (device)    in/out; the caller zeroes it before the first call
  *   workspace  device, 256-byte aligned, at least sals_calib_accumulate_workspace_bytes(dtype, D) bytes, no contents
- *              kept between calls (it holds the transposed keys of a chunk)
+ *              kept between calls (it holds the transposed keys of a chunk and the fp32 tile sums of its slices)
  * Asynchronous on hip_stream.  Errors: SALS_ERR_INVALID_ARG (NULL or misaligned pointer, bad size),
  * SALS_ERR_WORKSPACE, SALS_ERR_HIP.
  *

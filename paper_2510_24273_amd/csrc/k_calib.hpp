@@ -50,6 +50,40 @@ __global__ __launch_bounds__(256) void calib_transpose_kernel(const T* __restric
     }
 }
 
+// C[i, j] += sum over the slices of P[slice][i, j], for the elements the covariance kernel computed: those of the
+// tiles (tile_rows x tile_cols) that reach the upper triangle.  Slices are added in slice order, in fp64.
+__global__ __launch_bounds__(256) void calib_reduce_kernel(double* __restrict__ C, const float* __restrict__ P, int D,
+                                                           int slices, int tile_rows, int tile_cols)
+{
+    const size_t e = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;  // four consecutive columns
+    if (e >= (size_t)D * D) return;
+    const int i = (int)(e / D), j = (int)(e % D);
+    if (j / tile_cols < (i / tile_rows) * (tile_rows / tile_cols)) return;  // tile not computed (mirrored later)
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    for (int z = 0; z < slices; ++z) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(P + (size_t)z * D * D + e);
+        s0 += (double)v.x; s1 += (double)v.y; s2 += (double)v.z; s3 += (double)v.w;
+    }
+    C[e] += s0; C[e + 1] += s1; C[e + 2] += s2; C[e + 3] += s3;
+}
+
+// C[i, j] = C[j, i] for i > j: the covariance kernel fills the tiles that reach the upper triangle only
+__global__ __launch_bounds__(256) void calib_mirror_kernel(double* __restrict__ C, int D)
+{
+    __shared__ double tile[32][33];
+    const int bi = blockIdx.y, bj = blockIdx.x;   // tile of rows bi*32.., columns bj*32..
+    if (bj > bi) return;                           // (strictly upper tiles are sources only)
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+#pragma unroll
+    for (int k = 0; k < 32; k += 8) tile[ty + k][tx] = C[(size_t)(bj * 32 + ty + k) * D + bi * 32 + tx];  // the upper twin, [col][row]
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 32; k += 8) {
+        const int i = bi * 32 + ty + k, j = bj * 32 + tx;
+        if (i > j) C[(size_t)i * D + j] = tile[tx][ty + k];
+    }
+}
+
 __device__ __forceinline__ double wave_sum_f64(double v)
 {
 #pragma unroll

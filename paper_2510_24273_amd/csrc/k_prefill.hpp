@@ -29,12 +29,15 @@ struct PrefillArgs {
     const int32_t* seq_len;  // [B] first row to write
     const int32_t* n_new;    // [B] tokens of each sequence (<= n_tok), or nullptr: n_tok everywhere
     int n_tok, D, r, S_max, B, nproj;
-    double* cacc;            // SYRK form only: [n_tok, r] fp64 sums the tile products are added to
+    float* pacc;             // SYRK form only: [slices][n_tok, r] fp32 tile sums of each slice of the contraction axis
+    int kslice_steps;        // SYRK form only: 64-byte steps of the contraction axis per slice (blockIdx.y = slice)
 };
 
 // SYRK: the same tiles and pipeline as a plain product of two row-major operands, out[t, l] = sum_c X[t, c] UT[l, c],
-// whose fp32 tile sums are added to an fp64 matrix instead of being stored as cache rows (the covariance of the
-// offline calibration, Sec. 4.2, with X = UT = the transposed keys and c running over the calibration tokens).
+// whose fp32 tile sums are stored as they are instead of becoming cache rows (the covariance of the offline
+// calibration, Sec. 4.2, with X = UT = the transposed keys and c running over the calibration tokens).  The
+// contraction axis is cut into slices (blockIdx.y), each with its own output matrix, so that narrow matrices still
+// fill the chip; a second kernel adds the slices to the fp64 covariance.
 template <typename T, int TOK, int NL, bool SYRK = false>
 __global__ __launch_bounds__(kPfThreads, 2) void prefill_compress_kernel(PrefillArgs a)
 {
@@ -54,7 +57,17 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_compress_kernel(Prefill
     const int l32 = lane & 31, hi = lane >> 5;
     const int wm = wave / WN, wn = wave % WN;
     const int b = blockIdx.z / a.nproj, proj = blockIdx.z - b * a.nproj;
-    const int tok0 = blockIdx.x * kPfTok, lat0 = blockIdx.y * NL;
+    int tile_x = blockIdx.x, tile_y = blockIdx.y;
+    if constexpr (SYRK) {
+        // The result is symmetric: only the tiles that reach the upper triangle (column tile >= row tile, in units of
+        // NL columns) are computed, the rest is mirrored afterwards.  blockIdx.x numbers those tiles row by row.
+        constexpr int RPT = kPfTok / NL;                // column tiles a row tile spans: 2 | 1
+        const int ncol = a.r / NL;
+        int id = blockIdx.x, row = 0;
+        while (id >= ncol - row * RPT) { id -= ncol - row * RPT; ++row; }   // (at most n_tok / TOK rounds, uniform)
+        tile_x = row; tile_y = row * RPT + id;
+    }
+    const int tok0 = tile_x * kPfTok, lat0 = tile_y * NL;
     const int n_b = (!SYRK && a.n_new) ? min(max(ld_uniform_i32(a.n_new + b), 0), a.n_tok) : a.n_tok;
     const int row0_v = SYRK ? 0 : ld_uniform_i32(a.seq_len + b);
     const T* X = static_cast<const T*>(a.X[proj]) + (size_t)b * a.n_tok * a.D;
@@ -85,12 +98,14 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_compress_kernel(Prefill
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
 
-    const int nkc = a.D * ES / kLgStep;
+    const int nkc_all = a.D * ES / kLgStep;
+    const int kc_base = SYRK ? (int)blockIdx.y * a.kslice_steps : 0;
+    const int nkc = SYRK ? min(a.kslice_steps, nkc_all - kc_base) : nkc_all;  // (the host gives every slice >= 1 step)
     struct Regs { u32x4 a[NA]; u32x4 b[NBP]; };
     auto g_load = [&](Regs& R, int kc) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) R.a[i] = ld16(a_src[i] + (size_t)kc * kLgStep);
-        R.b[0] = ld16(b_src + (size_t)kc * kLgStep);
+        for (int i = 0; i < NA; ++i) R.a[i] = ld16(a_src[i] + (size_t)(kc_base + kc) * kLgStep);
+        R.b[0] = ld16(b_src + (size_t)(kc_base + kc) * kLgStep);
     };
     auto l_store = [&](const Regs& R, int buf) {
         unsigned char* base = lds + (size_t)buf * STAGE;
@@ -140,6 +155,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_compress_kernel(Prefill
     // acc[mb][nb][4a+c] is token wm*MB*32 + mb*32 + 8a + 4hi + c of the tile, latent coordinate wn*64 + nb*32 + l32:
     // for fixed (a, c) the 32 lanes of a half wave write 32 consecutive elements of one cache row
     if constexpr (SYRK) {
+        float* pout = a.pacc + (size_t)blockIdx.y * a.n_tok * a.r;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -147,10 +163,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_compress_kernel(Prefill
                 const int t = tok0 + (wm * MB + mb) * 32 + (v >> 2) * 8 + hi * 4 + (v & 3);
                 if (t < n_b) {
 #pragma unroll
-                    for (int nb = 0; nb < 2; ++nb) {
-                        double* dst = a.cacc + (size_t)t * a.r + lat0 + wn * 64 + nb * 32 + l32;
-                        *dst += (double)acc[mb][nb][v];
-                    }
+                    for (int nb = 0; nb < 2; ++nb) pout[(size_t)t * a.r + lat0 + wn * 64 + nb * 32 + l32] = acc[mb][nb][v];
                 }
             }
         return;

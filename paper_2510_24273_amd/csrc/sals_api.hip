@@ -1313,29 +1313,54 @@ namespace {
 constexpr int64_t kCalChunk = 4096;  // tokens whose products are summed in fp32 before they are added to the fp64 matrix
 size_t cal_es(int32_t dtype) { return dtype == SALS_BF16 ? 2 : 4; }
 
+// slices of a chunk's token axis (each a separate fp32 output of the GEMM): as many as bring the launch to about two
+// workgroups per compute unit, at most 8, every slice at least 256 tokens long
+int cal_slices(int D)
+{
+    const bool big = D % 256 == 0 && D >= 2048;
+    const int n = big ? D / 256 : D / 128;
+    const int tiles = big ? n * n + n : n * (n + 1) / 2;
+    int z = 1;
+    while (z < 8 && tiles * z < 512 && kCalChunk / (2 * z) >= 256) z *= 2;
+    return z;
+}
+
 template <typename T>
 sals_status calib_accumulate_t(const void* K, int64_t n_tok, int D, double* C, void* ws, hipStream_t st)
 {
     const T* X = static_cast<const T*>(K);
     T* XT = static_cast<T*>(ws);
+    float* P = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + align_up((size_t)D * kCalChunk * sizeof(T)));
+    const bool big = D % 256 == 0 && D >= 2048;  // (below that the larger tile leaves most of the chip without a workgroup)
+    const int step_tok = kLgStep / (int)sizeof(T);  // tokens per 64-byte step of the contraction axis
     for (int64_t t0 = 0; t0 < n_tok; t0 += kCalChunk) {
         const int64_t n = std::min(kCalChunk, n_tok - t0);
         const int64_t n_pad = (n + 63) / 64 * 64;  // whole 64-byte steps of the contraction axis, zero filled
         hipLaunchKernelGGL((calib_transpose_kernel<T>), dim3((unsigned)(n_pad / kCalTile), (unsigned)ceil_div(D, kCalTile)),
                            dim3(256), 0, st, X + (size_t)t0 * D, XT, (long long)n, D, (long long)n_pad);
+        const int steps = (int)(n_pad / step_tok);
+        const int per = ceil_div(steps, std::min(cal_slices(D), std::max(1, steps / 2)));  // >= 2 steps per slice
+        const int slices = ceil_div(steps, per);
         PrefillArgs a{};
         a.X[0] = XT; a.UT[0] = XT; a.cache[0] = nullptr; a.seq_len = nullptr; a.n_new = nullptr;
-        a.n_tok = D; a.D = (int)n_pad; a.r = D; a.S_max = D; a.B = 1; a.nproj = 1; a.cacc = C;
-        if (D % 256 == 0 && D >= 2048) {  // (below that the larger tile leaves most of the chip without a workgroup)
-            hipLaunchKernelGGL((prefill_compress_kernel<T, 256, 128, true>), dim3(D / 256, D / 128, 1), dim3(kPfThreads),
+        a.n_tok = D; a.D = (int)n_pad; a.r = D; a.S_max = D; a.B = 1; a.nproj = 1; a.pacc = P; a.kslice_steps = per;
+        // tiles that reach the upper triangle only (the kernel numbers them row by row)
+        if (big) {
+            const int nt = D / 256;
+            hipLaunchKernelGGL((prefill_compress_kernel<T, 256, 128, true>), dim3(nt * nt + nt, slices, 1), dim3(kPfThreads),
                                prefill_lds_bytes(256, 128), st, a);
         } else {
-            hipLaunchKernelGGL((prefill_compress_kernel<T, 128, 128, true>), dim3(D / 128, D / 128, 1), dim3(kPfThreads),
-                               prefill_lds_bytes(128, 128), st, a);
+            const int nt = D / 128;
+            hipLaunchKernelGGL((prefill_compress_kernel<T, 128, 128, true>), dim3(nt * (nt + 1) / 2, slices, 1),
+                               dim3(kPfThreads), prefill_lds_bytes(128, 128), st, a);
         }
+        hipLaunchKernelGGL(calib_reduce_kernel, dim3((unsigned)(((size_t)D * D / 4 + 255) / 256)), dim3(256), 0, st, C, P, D,
+                           slices, big ? 256 : 128, 128);
         if (launch_status() != SALS_OK) return SALS_ERR_HIP;
     }
-    return SALS_OK;
+    // the lower triangle from the upper one (which also makes the matrix exactly symmetric)
+    hipLaunchKernelGGL(calib_mirror_kernel, dim3(D / 32, D / 32), dim3(256), 0, st, C, D);
+    return launch_status();
 }
 
 template <typename T> sals_status calib_lds_attr()
@@ -1361,7 +1386,8 @@ extern "C" {
 size_t sals_calib_accumulate_workspace_bytes(int32_t dtype, int32_t D)
 {
     if ((dtype != SALS_BF16 && dtype != SALS_F32) || D < 128 || D % 128 != 0 || D > kCalMaxD) return 0;
-    return align_up((size_t)D * kCalChunk * cal_es(dtype));
+    // the transposed keys of a chunk, then the fp32 tile sums of its slices
+    return align_up((size_t)D * kCalChunk * cal_es(dtype)) + align_up((size_t)cal_slices(D) * D * D * 4);
 }
 
 sals_status sals_calib_accumulate(int32_t dtype, const void* K, int64_t n_tok, int32_t D, double* C, void* workspace,
