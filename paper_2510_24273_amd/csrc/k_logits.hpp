@@ -54,15 +54,23 @@ template <int HEADS, int NTG, int NB> struct logits_cfg {
 // of 4): the LDS reads and the reductions of a block's heads are in flight together instead of one head after the other.
 // GFIX: the group size when it is known at compile time (1 and 4, the common ones; 0: read from the arguments), which
 // takes the per-block branches out of the epilogue.
-template <typename T, int HEADS, int NTG, int NB, int GB, int GFIX>
+// MULTI: a tile of NTG x 64 tokens is made of the (at most 64 token) selections of NTG consecutive SEQUENCES, one per
+// token group, instead of 256 tokens of one sequence: short selections such as a recent window then share one pass
+// over the head's projector among NTG sequences.  Each token group has its own query, count, index list and cache;
+// the latent axis may be cut into `ksplit` slices (the logit is additive over latent coordinates), whose partial
+// logits go to `plogits` for logits_finish_kernel.
+template <typename T, int HEADS, int NTG, int NB, int GB, int GFIX, bool MULTI = false>
 __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void attend_logits_kernel(
     const T* __restrict__ Kc, const T* __restrict__ UkP, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ n_sel, const T* __restrict__ q, const int32_t* __restrict__ q_pos,
     const float2* __restrict__ rope, InvFreq inv,
     float* __restrict__ logits, float2* __restrict__ stats, int B, int S_max, int r, int H, int H_kv,
-    int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale, int ring, int stats_stride)
+    int k_tot, int lk, int n_parts, int heads_fastest, int style, float scale, int ring, int stats_stride,
+    float* __restrict__ plogits, int ksplit)
 {
     typedef logits_cfg<HEADS, NTG, NB> C;
+    static_assert(!MULTI || (HEADS == 1 && NB * 32 == 64), "a token group is one sequence's 64 slots");
+    constexpr int SQ = MULTI ? NTG : 1;   // sequences per tile
     constexpr int NT = C::NT, NA = C::NA, NBP = C::NBP, NCS = C::NCS;
     constexpr int ES = (int)sizeof(T);
     static_assert(C::A_BYTES % (16 * NT) == 0 && C::B_BYTES % (16 * NT) == 0 && C::CS_BYTES % (16 * NT) == 0,
@@ -75,8 +83,17 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
     // list; the list is ordered so that a range shares the larger operand: heads fastest keeps
     // the gathered rows of a few token tiles in that L2 (U_k is re-read per XCD), tiles fastest
     // keeps the U_k panels of a few heads there (the rows are re-read per XCD).
-    int b, g0, part;
-    {
+    int b, g0, part, kz = 0;   // MULTI: b is the first sequence of the tile
+    if constexpr (MULTI) {
+        // list order (head, sequence group, latent slice): an XCD's range keeps a few heads' projector slices
+        const int nb4 = (B + NTG - 1) / NTG, N = nb4 * H_kv * ksplit;
+        const int id = blockIdx.x, xcd = id % kXcds, slot = id / kXcds;
+        const int qn = N / kXcds, rem = N % kXcds;
+        const int w = (xcd < rem ? xcd * (qn + 1) : rem * (qn + 1) + (xcd - rem) * qn) + slot;
+        g0 = w / (nb4 * ksplit);
+        const int rest = w - g0 * (nb4 * ksplit);
+        b = (rest / ksplit) * NTG; kz = rest % ksplit; part = 0;
+    } else {
         const int n_y = H_kv / HEADS, N = n_parts * n_y * B;
         const int id = blockIdx.x, xcd = id % kXcds, slot = id / kXcds;
         const int qn = N / kXcds, rem = N % kXcds;
@@ -90,10 +107,16 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
         }
     }
     const int tok0 = part * C::TOK;
-    const int n_v = ld_uniform_i32(n_sel + b), qpos_v = ld_uniform_i32(q_pos + b);  // in flight with the loads below
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
     const int hh = wave / NTG, tg = wave % NTG;   // head of the tile, token group
+    // sequence of tile token t (MULTI: token group t / 64 is sequence b + t / 64; groups past the batch repeat the last
+    // sequence and get no weight)
+    auto seq_of = [&](int t) { return MULTI ? min(b + (t >> 6), B - 1) : b; };
+    // count and query position: of this wave's sequence (MULTI: wave = token group; the position is needed per thread
+    // for the thread's share of the cos/sin rows, see rotate_query)
+    const int n_v = ld_uniform_i32(n_sel + (MULTI ? seq_of(tg * 64) : b));
+    const int qpos_v = MULTI ? q_pos[seq_of(tid & ~63)] : ld_uniform_i32(q_pos + b);  // in flight with the loads below
     const int G = GFIX > 0 ? GFIX : H / H_kv;
     const int g = g0 + hh;
 
@@ -101,38 +124,48 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
     // addresses so that no load sits in a branch: the tile's token rows (slots at or past the selection count
     // read whatever the index array holds there, clamped to a valid row; they get no weight), the raw query
     // pairs of the tile's heads and the query position.
-    const int32_t* ib = idx + (size_t)b * k_tot;
-    auto row_of = [&](int slot) { return min(max(ib[min(slot, k_tot - 1)], 0), S_max - 1); };
+    const int rows_per_seq = ring > 0 ? ring : S_max;
+    // cache row (= RoPE position) of tile token t: slot t of the one sequence, or slot t % 64 of sequence b + t / 64
+    auto row_of = [&](int t) {
+        const int32_t* ib = idx + (size_t)seq_of(t) * k_tot;
+        return min(max(ib[min(MULTI ? (t & 63) : tok0 + t, k_tot - 1)], 0), S_max - 1);
+    };
     int b_row[NBP];  // gathered rows: piece q = tid + i*NT -> token q/4 of the tile, column q%4
 #pragma unroll
     for (int i = 0; i < NBP; ++i) {
-        b_row[i] = row_of(tok0 + ((tid + i * NT) >> 2));
+        const int t = (tid + i * NT) >> 2;
+        b_row[i] = row_of(t);
         if (ring > 0) b_row[i] %= ring;  // ring cache: token t lies in row t mod ring
+        if (MULTI) b_row[i] += (seq_of(t) - b) * rows_per_seq;  // (rows counted from the tile's first sequence)
     }
     constexpr int NSP = (C::TOK + NT - 1) / NT;
     int pos_reg[NSP];
 #pragma unroll
-    for (int u = 0; u < NSP; ++u) pos_reg[u] = row_of(tok0 + min(tid + u * NT, C::TOK - 1));
-    constexpr int QP = (HEADS * (GFIX > 0 ? GFIX : kMaxGroup) * kPairs + NT - 1) / NT;
+    for (int u = 0; u < NSP; ++u) pos_reg[u] = row_of(min(tid + u * NT, C::TOK - 1));
+    constexpr int QP = (SQ * HEADS * (GFIX > 0 ? GFIX : kMaxGroup) * kPairs + NT - 1) / NT;
     float qa[QP], qb[QP];
 #pragma unroll
     for (int u = 0; u < QP; ++u) {
-        const int t = min(tid + u * NT, HEADS * G * kPairs - 1), p = t & (kPairs - 1);
-        const T* qrow = q + ((size_t)b * H + (size_t)g0 * G + (t >> 6)) * kHeadDim;
+        // query pair t: (sequence of the tile, head of the tile's heads, pair)
+        const int t = min(tid + u * NT, SQ * HEADS * G * kPairs - 1), p = t & (kPairs - 1);
+        const int hq = t >> 6, sq = MULTI ? hq / G : 0, hm = MULTI ? hq - sq * G : hq;
+        const T* qrow = q + ((size_t)seq_of(sq * 64) * H + (size_t)g0 * G + hm) * kHeadDim;
         qa[u] = elem<T>::load(qrow + pair_first(p, style));
         qb[u] = elem<T>::load(qrow + pair_second(p, style));
     }
     asm volatile("" ::: "memory");  // (keeps the loads above ahead of the wait for the count)
-    const int n = wave_uniform(n_v), qpos = wave_uniform(qpos_v);
-    if (tok0 >= n) {  // no selected token in this tile: neutral statistics
+    // MULTI: a token group past the batch has no tokens
+    const int n = (MULTI && b + tg >= B) ? 0 : wave_uniform(n_v);
+    const int qpos = MULTI ? qpos_v : wave_uniform(qpos_v);
+    if (!MULTI && tok0 >= n) {  // no selected token in this tile: neutral statistics
         if (tid < HEADS * G)
             stats[((size_t)b * H + (size_t)g0 * G + tid) * stats_stride + part] = make_float2(-INFINITY, 0.f);
         return;
     }
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // [3][A | B], later [2][cos/sin]
-    __shared__ __attribute__((aligned(16))) float sQ[HEADS][kMaxGroup][kHeadDim];
-    __shared__ float2 sCS[kPairs];
+    __shared__ __attribute__((aligned(16))) float sQ[SQ * HEADS][kMaxGroup][kHeadDim];
+    __shared__ float2 sCS[SQ][kPairs];
     __shared__ float2 sStat[HEADS][NTG][kMaxGroup];
     __shared__ int sPos[C::TOK];  // cache row (= RoPE position) of every token of the tile
 
@@ -140,22 +173,24 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
     for (int u = 0; u < NSP; ++u)
         if (tid + u * NT < C::TOK) sPos[tid + u * NT] = pos_reg[u];
     auto rotate_query = [&]() {
-        if (tid < kPairs) {
+        if (tid < SQ * kPairs) {   // thread -> (sequence tid / 64, pair tid % 64); qpos is that sequence's
+            const int pr = tid & (kPairs - 1);
             if (qpos >= 0 && qpos <= S_max) {  // the table holds exactly these values
-                sCS[tid] = rope[(size_t)qpos * kPairs + tid];
+                sCS[tid >> 6][pr] = rope[(size_t)qpos * kPairs + pr];
             } else {
                 double sn, c;
-                sincos((double)qpos * inv.f[tid], &sn, &c);
-                sCS[tid] = make_float2((float)c, (float)sn);
+                sincos((double)qpos * inv.f[pr], &sn, &c);
+                sCS[tid >> 6][pr] = make_float2((float)c, (float)sn);
             }
         }
         __syncthreads();
 #pragma unroll
         for (int u = 0; u < QP; ++u) {
             const int t = tid + u * NT;
-            if (t < HEADS * G * kPairs) {
+            if (t < SQ * HEADS * G * kPairs) {
+                // (MULTI: t / 64 = sequence * G + head of the group; otherwise head of the tile * G + head of the group)
                 const int p = t & (kPairs - 1), hm = t >> 6;
-                const float2 c = sCS[p];
+                const float2 c = sCS[MULTI ? hm / G : 0][p];
                 float* dst = &sQ[0][0][0] + (size_t)((hm / G) * kMaxGroup + hm % G) * kHeadDim;
                 dst[p] = (qa[u] * c.x - qb[u] * c.y) * scale;
                 dst[kPairs + p] = (qb[u] * c.x + qa[u] * c.y) * scale;
@@ -177,7 +212,7 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
         const int qd = tid + i * NT;
         return (qd >> 9) * 128 * kLgStep + swz64((qd >> 2) & 127, qd & 3);
     };
-    const unsigned char* b_base = reinterpret_cast<const unsigned char*>(Kc + (size_t)b * (ring > 0 ? ring : S_max) * r) + (tid & 3) * 16;
+    const unsigned char* b_base = reinterpret_cast<const unsigned char*>(Kc + (size_t)b * rows_per_seq * r) + (tid & 3) * 16;
     const size_t row_bytes = (size_t)r * ES;
     auto b_dst = [&](int i) { return C::A_BYTES + swz64((tid + i * NT) >> 2, tid & 3); };
 
@@ -189,13 +224,15 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
 
-    const int nkc = r * ES / kLgStep;
+    // steps of the latent axis: all of them, or this workgroup's slice
+    const int nkc = MULTI ? r * ES / kLgStep / ksplit : r * ES / kLgStep;
+    const int kc_base = MULTI ? kz * nkc : 0;
     struct Regs { u32x4 a[NA]; u32x4 b[NBP]; };
     auto g_load = [&](Regs& R, int kc) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) R.a[i] = ld16(a_src(i, kc));
+        for (int i = 0; i < NA; ++i) R.a[i] = ld16(a_src(i, kc_base + kc));
 #pragma unroll
-        for (int i = 0; i < NBP; ++i) R.b[i] = ld16(b_base + (size_t)b_row[i] * row_bytes + (size_t)kc * kLgStep);
+        for (int i = 0; i < NBP; ++i) R.b[i] = ld16(b_base + (size_t)b_row[i] * row_bytes + (size_t)(kc_base + kc) * kLgStep);
     };
     auto l_store = [&](const Regs& R, int buf) {
         unsigned char* base = lds + (size_t)buf * C::STAGE;
@@ -339,8 +376,8 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
                         f32x4 q1[GB], q2[GB];
 #pragma unroll
                         for (int mi = 0; mi < GB; ++mi) {
-                            q1[mi] = *reinterpret_cast<const f32x4*>(&sQ[hh][m0 + mi][p0]);
-                            q2[mi] = *reinterpret_cast<const f32x4*>(&sQ[hh][m0 + mi][kPairs + p0]);
+                            q1[mi] = *reinterpret_cast<const f32x4*>(&sQ[MULTI ? tg : hh][m0 + mi][p0]);
+                            q2[mi] = *reinterpret_cast<const f32x4*>(&sQ[MULTI ? tg : hh][m0 + mi][kPairs + p0]);
                         }
 #pragma unroll
                         for (int mi = 0; mi < GB; ++mi)
@@ -360,7 +397,9 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
 
     bool ok[NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) ok[nb] = tok0 + (tg * NB + nb) * 32 + l32 < n;
+    for (int nb = 0; nb < NB; ++nb) ok[nb] = (MULTI ? nb * 32 + l32 : tok0 + (tg * NB + nb) * 32 + l32) < n;
+    const int bs = MULTI ? seq_of(tg * 64) : b;          // sequence of this wave's tokens
+    const bool seq_real = !MULTI || b + tg < B;          // (a token group past the batch writes nothing)
 #pragma unroll
     for (int m0 = 0; m0 < kGroupEnd; m0 += GB) {
         if (GFIX > 0 || m0 < G) {  // uniform
@@ -372,10 +411,15 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
             for (int mi = 0; mi < GB; ++mi)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    const int slot = tok0 + (tg * NB + nb) * 32 + l32;
-                    if (hi == 0 && slot < lk)
-                        logits[((size_t)b * H + g * G + m0 + mi) * lk + slot] = ok[nb] ? dot[m0 + mi][nb] : -INFINITY;
+                    const int slot = MULTI ? nb * 32 + l32 : tok0 + (tg * NB + nb) * 32 + l32;
+                    const size_t at = ((size_t)bs * H + g * G + m0 + mi) * lk + slot;
+                    if (MULTI && ksplit > 1) {  // uniform: this slice's share of the logit
+                        if (hi == 0 && slot < lk && seq_real) plogits[(size_t)kz * B * H * lk + at] = dot[m0 + mi][nb];
+                    } else if (hi == 0 && slot < lk && seq_real) {
+                        logits[at] = ok[nb] ? dot[m0 + mi][nb] : -INFINITY;
+                    }
                 }
+            if (MULTI && ksplit > 1) continue;  // (statistics are taken when the slices are added up)
             // softmax statistics of this tile, per head: the waves' (max, sum exp) merged in wave order below
             float mx[GB], se[GB];
 #pragma unroll
@@ -396,10 +440,17 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
             for (int mi = 0; mi < GB; ++mi) se[mi] = wave_sum(se[mi]);
             if (lane == 0) {
 #pragma unroll
-                for (int mi = 0; mi < GB; ++mi) sStat[hh][tg][m0 + mi] = make_float2(mx[mi], se[mi]);
+                for (int mi = 0; mi < GB; ++mi) {
+                    if constexpr (MULTI) {  // a token group is the whole (single) tile of its sequence
+                        if (seq_real) stats[((size_t)bs * H + (size_t)g * G + m0 + mi) * stats_stride + part] = make_float2(mx[mi], se[mi]);
+                    } else {
+                        sStat[hh][tg][m0 + mi] = make_float2(mx[mi], se[mi]);
+                    }
+                }
             }
         }
     }
+    if constexpr (MULTI) return;
     __syncthreads();
     if (tid < HEADS * G) {
         const int h2 = tid / G, m = tid - h2 * G;

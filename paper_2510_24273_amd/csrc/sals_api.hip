@@ -168,7 +168,9 @@ Layout make_layout(const sals_desc& d)
     L.n_lo = take((size_t)d.B * 4);                          // recent-window attention: tokens of the low-rank pass
     L.logits = take((size_t)d.B * d.H_q * L.lk * 4);
     // partial logits of the latent slices, for shapes with so few 64-token tiles that the latent axis is split too
-    L.plogits = take(ceil_div(k_tot, kLsTok) * d.H_kv * d.B <= 128 ? (size_t)kLsMaxSplit * d.B * d.H_q * L.lk * 4 : 0);
+    // (also for batches of short selections, whose multi-sequence tiles may split the latent axis)
+    L.plogits = take((ceil_div(k_tot, kLsTok) * d.H_kv * d.B <= 128 || k_tot <= 64)
+                         ? (size_t)kLsMaxSplit * d.B * d.H_q * L.lk * 4 : 0);
     L.max_parts = ceil_div(k_tot, 32) + 2;  // (room for the tiles of a recent-window pass beside the context's own)
     L.stats = take((size_t)d.B * d.H_q * L.max_parts * 8);
     L.rope = take((size_t)(d.S_max + 1) * kPairs * 8);  // positions 0 .. S_max (the query after a full cache)
@@ -465,6 +467,29 @@ template <typename T> LogitsPlan plan_logits(const sals_desc& d)
         if (v == 1 && d.H_kv % 2 == 0) P.pick = 1;
         if (v == 2 || v == 3) P.pick = v;
     }
+    // A selection of at most 64 tokens per sequence (a recent window) in a batch: tiles of four sequences' selections,
+    // 256 tokens against one pass over the head's projector, the latent axis cut until the launch fills the chip.
+    // Estimated like the one-head 256-token tile (0.57 us per step measured at such shapes, 8 us around the loop, 4 us
+    // for the finishing launch of a split).
+    const char* const force = std::getenv("SALS_TUNE_LOGITS");  // tuning aid: "4" asks for these tiles at any batch
+    const bool forced4 = force && std::atoi(force) == 4;
+    if (k_tot <= 64 && ((P.pick == 3 && d.B >= 8) || forced4)) {
+        const int steps = d.r * (int)sizeof(T) / kLgStep;
+        const long long tiles = (long long)ceil_div(d.B, 4) * d.H_kv;
+        int ks = 1;
+        while (ks < kLsMaxSplit && tiles * ks < 256 && steps % (2 * ks) == 0 && steps / (2 * ks) >= 8) ks *= 2;
+        if (const char* e = std::getenv("SALS_TUNE_MULTI_KSPLIT")) {  // tuning aid: any divisor of the step count up to 8
+            const int v = std::atoi(e);
+            if (v >= 1 && v <= kLsMaxSplit && steps % v == 0) ks = v;
+        }
+        const double t4 = (double)((tiles * ks + 255) / 256) * ((double)steps / ks * 0.57 + 8.0) + (ks > 1 ? 4.0 : 0.0);
+        const double bytes3 = (double)(kHeadDim + kLsTok) * d.r * sizeof(T);
+        const double t3 = (double)((n_wg1 + 255) / 256) * (bytes3 / 51e3 + 3.0 + 0.3 * (d.H_q / d.H_kv));
+        if (t4 < t3 || forced4) {
+            P.pick = 4; P.n_parts = 1; P.ksplit = ks;
+            return P;
+        }
+    }
     if (P.pick != 3) {
         P.n_parts = ceil_div(k_tot, 256);
         P.ksplit = 1;
@@ -504,12 +529,12 @@ bool fused_selection(const sals_ctx* c)
 }
 
 // the instantiation of the 256-token logits kernel for a group size (query heads per KV head)
-template <typename T, int HEADS, int NTG, int NB> auto logits_kernel_for(int group)
+template <typename T, int HEADS, int NTG, int NB, bool MULTI = false> auto logits_kernel_for(int group)
 {
-    if (group == 1) return attend_logits_kernel<T, HEADS, NTG, NB, 1, 1>;
-    if (group == 4) return attend_logits_kernel<T, HEADS, NTG, NB, 4, 4>;
-    if (group % 4 == 0) return attend_logits_kernel<T, HEADS, NTG, NB, 4, 0>;
-    return attend_logits_kernel<T, HEADS, NTG, NB, 1, 0>;
+    if (group == 1) return attend_logits_kernel<T, HEADS, NTG, NB, 1, 1, MULTI>;
+    if (group == 4) return attend_logits_kernel<T, HEADS, NTG, NB, 4, 4, MULTI>;
+    if (group % 4 == 0) return attend_logits_kernel<T, HEADS, NTG, NB, 4, 0, MULTI>;
+    return attend_logits_kernel<T, HEADS, NTG, NB, 1, 0, MULTI>;
 }
 
 template <typename T> sals_status allow_logits_lds(const LogitsPlan& P, int group)
@@ -521,6 +546,7 @@ template <typename T> sals_status allow_logits_lds(const LogitsPlan& P, int grou
     bool ok = true;
     if (P.pick == 1) ok = allow(reinterpret_cast<const void*>(logits_kernel_for<T, 2, 4, 2>(group)), logits_cfg<2, 4, 2>::LDS);
     else if (P.pick == 2) ok = allow(reinterpret_cast<const void*>(logits_kernel_for<T, 1, 4, 2>(group)), logits_cfg<1, 4, 2>::LDS);
+    else if (P.pick == 4) ok = allow(reinterpret_cast<const void*>(logits_kernel_for<T, 1, 4, 2, true>(group)), logits_cfg<1, 4, 2>::LDS);
     else {
         ok = allow(reinterpret_cast<const void*>(SmallLogits<T>::get(P.nst, false)), kLsLds) &&
              allow(reinterpret_cast<const void*>(SmallLogits<T>::get(P.nst, true)), kLsLds);
@@ -562,11 +588,25 @@ sals_status launch_attend(const sals_ctx* c, const void* q, const int32_t* q_pos
                            static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel,                     \
                            static_cast<const T*>(q), q_pos, rope, c->inv, logits, stats, d.B,                \
                            d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk, n_parts, heads_fastest, d.rope_style,   \
-                           1.0f / std::sqrt((float)d.d), ring, stats_stride);                                \
+                           1.0f / std::sqrt((float)d.d), ring, stats_stride, static_cast<float*>(nullptr), 1);       \
     } while (0)
         const int pick = P.pick;
         if (pick == 1) SALS_LOGITS(2, 4, 2);        // 2 heads x 256 tokens, 8 waves
         else if (pick == 2) SALS_LOGITS(1, 4, 2);   // 1 head  x 256 tokens
+        else if (pick == 4) {  // four sequences' short selections per 256-token tile, latent axis in P.ksplit slices
+            typedef logits_cfg<1, 4, 2> LC;
+            auto kern = logits_kernel_for<T, 1, 4, 2, true>(d.H_q / d.H_kv);
+            float* plogits = reinterpret_cast<float*>(c->ws + L.plogits);
+            hipLaunchKernelGGL(kern, dim3(ceil_div(d.B, 4) * d.H_kv * P.ksplit), dim3(LC::NT), LC::LDS, st,
+                               static_cast<const T*>(Kc), w_section<T>(c, W, 2), idx, n_sel, static_cast<const T*>(q), q_pos,
+                               rope, c->inv, logits, stats, d.B, d.S_max, d.r, d.H_q, d.H_kv, k_tot, L.lk, 1, heads_fastest,
+                               d.rope_style, 1.0f / std::sqrt((float)d.d), ring, stats_stride, plogits, P.ksplit);
+            if (P.ksplit > 1) {
+                if (launch_status() != SALS_OK) return SALS_ERR_HIP;
+                hipLaunchKernelGGL(logits_finish_kernel, dim3(1, d.B * d.H_q), dim3(64), 0, st, plogits, P.ksplit, n_sel,
+                                   logits, stats, d.B, d.H_q, L.lk, stats_stride);
+            }
+        }
         else {  // few tiles: 1 head x 64 tokens with the whole latent axis loaded ahead
             const int ksplit = P.ksplit, nst = P.nst;
             // fs: idx / n_sel are outputs of this launch (the kernel selects from fs->scores itself)

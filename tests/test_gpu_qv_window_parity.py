@@ -95,6 +95,14 @@ def test_edge_lengths(oracle):
     _case(oracle, w, 4, seq_lens=[0, 1, 39, 40, 41, w.k_tot])
 
 
+def test_windows_of_several_sequences_share_a_tile(oracle, monkeypatch):
+    """The window's logits pass on tiles of four sequences' windows, latent axis in two slices (forced at this size)."""
+    monkeypatch.setenv("SALS_TUNE_LOGITS", "4")
+    monkeypatch.setenv("SALS_TUNE_MULTI_KSPLIT", "2")
+    w = synth.shrink(SMALL, B=9, plant=0)
+    _case(oracle, w, 4, seq_lens=[1000, 0, 1, 39, 40, 41, w.k_tot, 500, 999])
+
+
 def test_gqa_interleaved_rope_and_many_ranges(oracle):
     w = synth.shrink(SMALL, B=2, S=3000, H=32, H_kv=8, top_k=1500, n_sink=16, n_recent=64, rope_style=1, theta=500000.0)
     _case(oracle, w, 2, seq_lens=[3000, 2111], label="gqa, several token ranges")

@@ -99,6 +99,24 @@ def test_gqa_interleaved_rope_and_ring_wrap(oracle):
     _case(oracle, w, seq_lens=[777, 500])
 
 
+@pytest.mark.parametrize("dtype,ks", [("bf16", 1), ("bf16", 2), ("f32", 4)])
+def test_windows_of_several_sequences_share_a_tile(oracle, dtype, ks, monkeypatch):
+    """The window pass on tiles made of four sequences' windows (chosen by itself for batches of eight and more, see
+    the cfg3a case below; forced here at a small rank), unsplit and with the latent axis in slices: a batch that is no
+    multiple of four, with empty sequences, windows that are not full and full ones."""
+    monkeypatch.setenv("SALS_TUNE_LOGITS", "4")
+    monkeypatch.setenv("SALS_TUNE_MULTI_KSPLIT", str(ks))
+    w = synth.shrink(SMALL, B=10, plant=0, dtype=dtype)
+    _case(oracle, w, seq_lens=[1000, 0, 1, 40, 41, 144, 145, 500, 23, 999])
+
+
+def test_shared_tiles_gqa_interleaved_rope_ring_wrap(oracle, monkeypatch):
+    monkeypatch.setenv("SALS_TUNE_LOGITS", "4")
+    monkeypatch.setenv("SALS_TUNE_MULTI_KSPLIT", "2")
+    w = synth.shrink(SMALL, B=9, S=777, H=32, H_kv=8, n_recent=48, rope_style=1, theta=500000.0, plant=0)
+    _case(oracle, w, seq_lens=[777, 500, 48, 49, 47, 0, 600, 100, 776])
+
+
 def test_largest_window_rank(oracle):
     w = synth.shrink(SMALL, B=2, S=600, r=640, r_hi=2048, top_k=200, n_sink=16, n_recent=128, plant=0)
     _case(oracle, w, seq_lens=[600, 345])
