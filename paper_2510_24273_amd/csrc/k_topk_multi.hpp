@@ -10,7 +10,7 @@
 //            counts from the top bin down (entry s = the chunk's scores in bins above s)
 //   place    per chunk: the bin holding the top_k-th score, how many of its members are selected and
 //            where the chunk's output starts (every workgroup of the sequence derives the same
-//            numbers, in two rounds over the chunks' running counts: at every 32nd bin, then at the
+//            numbers, in two passes over the chunks' running counts: at every 32nd bin, then at the
 //            32 bins of the step that holds the threshold); then the indices of the scores in
 //            higher bins go to their final positions (chunk order, then token order) and the
 //            members of the threshold bin to a candidate list
@@ -204,7 +204,7 @@ __device__ __forceinline__ TopkMeta tm_resolve(TmResolveLds& L, const TopkMultiW
     const int tid = threadIdx.x;
     TopkMeta m{};
     const uint32_t* cum = ws.hist + (size_t)b * n_chunk * kTmCum;
-    // round 1: the counts at every 32nd slot, summed over the chunks (four loads per thread and trip in flight, from
+    // first pass: the counts at every 32nd slot, summed over the chunks (four loads per thread and trip in flight, from
     // clamped element numbers: no load in a branch)
     const int n1 = kTmNC * n_chunk;
     for (int t = tid; t < kTmNC + kTmCoarse + 1; t += kTopkThreads) (t < kTmNC ? L.coarse[t] : L.fine[t - kTmNC]) = 0u;
@@ -250,7 +250,7 @@ __device__ __forceinline__ TopkMeta tm_resolve(TmResolveLds& L, const TopkMultiW
         m.fallback = 1u;
         return m;
     }
-    // round 2: the counts at the 33 slot boundaries of coarse step P, per chunk and summed
+    // second pass: the counts at the 33 slot boundaries of coarse step P, per chunk and summed
     const int n2 = (kTmCoarse + 1) * n_chunk;
     for (int e0 = 0; e0 < n2; e0 += 4 * kTopkThreads) {
         uint32_t v[4];
