@@ -172,16 +172,20 @@ __global__ __launch_bounds__(64 * HEADS * NTG, HEADS * NTG >= 8 ? 2 : 1) void at
 #pragma unroll
     for (int u = 0; u < NSP; ++u)
         if (tid + u * NT < C::TOK) sPos[tid + u * NT] = pos_reg[u];
+    // cos/sin of the query position: thread -> (sequence tid / 64, pair tid % 64); qpos is that sequence's.  Requested
+    // here, ahead of the first operand loads, so that the wait for it does not include theirs.
+    const bool q_in_table = qpos >= 0 && qpos <= S_max;  // the table holds exactly these positions
+    float2 qcs = make_float2(1.f, 0.f);
+    if (tid < SQ * kPairs) qcs = rope[(size_t)(q_in_table ? qpos : 0) * kPairs + (tid & (kPairs - 1))];
     auto rotate_query = [&]() {
-        if (tid < SQ * kPairs) {   // thread -> (sequence tid / 64, pair tid % 64); qpos is that sequence's
+        if (tid < SQ * kPairs) {
             const int pr = tid & (kPairs - 1);
-            if (qpos >= 0 && qpos <= S_max) {  // the table holds exactly these values
-                sCS[tid >> 6][pr] = rope[(size_t)qpos * kPairs + pr];
-            } else {
+            if (!q_in_table) {
                 double sn, c;
                 sincos((double)qpos * inv.f[pr], &sn, &c);
-                sCS[tid >> 6][pr] = make_float2((float)c, (float)sn);
+                qcs = make_float2((float)c, (float)sn);
             }
+            sCS[tid >> 6][pr] = qcs;
         }
         __syncthreads();
 #pragma unroll
