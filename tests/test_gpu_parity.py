@@ -380,6 +380,14 @@ def test_repeatable_bit_for_bit(oracle):
 
 # ---- the measured configurations at full size ----------------------------------------
 
+def test_fp32_cache_large_enough_for_the_streaming_loads(oracle):
+    """An fp32 cache of 32 MB and more takes the score kernel's read-once loads (the bf16 form runs at every batch
+    configuration): all stages against the oracle."""
+    w = synth.shrink(C["cfg1"], B=2, S=16384, r=256, top_k=64, plant=2)
+    assert w.B * w.S * w.r * 4 >= 32 << 20
+    _run(oracle, w, seq_lens=[16384, 9000], label="fp32, 33.5 MB cache")
+
+
 def test_cfg2_full(oracle):
     L, R, _ = _run(oracle, C["cfg2"], layer=0)
     sel = set(gu.from_dev(R["idx"][0]).tolist())
