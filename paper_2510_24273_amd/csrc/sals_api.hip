@@ -137,10 +137,12 @@ Layout make_layout(const sals_desc& d)
     const int k_tot = d.top_k + d.n_sink + d.n_recent;
     L.lk = ceil_div(k_tot, 128) * 128;  // whole steps of the value kernel (its last step may read up to the row end)
     L.w_section = (size_t)D * d.r;
-    {   // query projection: slice the D axis until about 256 workgroups stream U_k^T
+    {   // query projection: slice the D axis until at least 160 workgroups stream U_k^T (measured: at r = 640 four
+        // slices = 160 workgroups project as fast as eight, and the score kernel then adds four partial sums, not eight)
         int nks = D / (d.dtype == SALS_BF16 ? 32 : 16);
         int np = 1;
-        while (np < kScoreMaxParts && (d.r / 16) * np < 256 && nks % (np * 2) == 0 && nks / (np * 2) >= 4) np *= 2;
+        while (np < kScoreMaxParts && (d.r / 16) * np < 160 && nks % (np * 2) == 0 && nks / (np * 2) >= 4) np *= 2;
+        if (const char* e = std::getenv("SALS_TUNE_PROJ_NP")) { const int v = std::atoi(e); if (v >= 1 && v <= kScoreMaxParts && nks % v == 0) np = v; }  // tuning aid
         L.proj_np = np;
     }
     // value sum: split the selected tokens into ranges of whole 64-token steps (at least two steps, at
